@@ -1,0 +1,152 @@
+/*
+ * libstree: tree-masked Mamba2 SSD verification pass for AMD MI355X (gfx950).
+ *
+ * One call scores a token tree that is packed into a sequence t_1..t_N (t_1 the
+ * root) and described by a parent-index array, the compact form of the paper's
+ * tree mask L (Sec. 3 "Formalization": L_ij = 1 iff t_j lies on the path from
+ * the root to t_i, the path including t_i itself).
+ *
+ * C ABI, plain pointers and sizes.  Conventions for every entry point:
+ *   - `dims` is HOST memory.  Every other pointer is DEVICE memory owned by the
+ *     caller; the library never allocates, frees or synchronises.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL
+ *     is the default stream).  Outputs are fully overwritten; inputs are never
+ *     written (except where aliasing is explicitly allowed below).
+ *   - Return value: STREE_OK (0) or a host-detected error (> 0), in which case
+ *     nothing was launched.
+ *   - Trees are validated on the device: parent[b,0] == -1 and
+ *     0 <= parent[b,i] < i.  Per sequence, `tree_status[b]` (may be NULL) gets 0,
+ *     or (index of the first bad node) + 1, and that sequence's outputs are
+ *     zero-filled (commit: state copied through unchanged).
+ *   - Layouts are row-major with the last index contiguous.  Head h reads group
+ *     g = h / (nheads / ngroups).  dt, A, D and the SSM state are always fp32;
+ *     `io_dtype` selects fp32 or bf16 for x, B, C, y and the conv tensors.
+ *   - Envelope: 1 <= nnodes <= 256, batch >= 0 (0 is a no-op), nheads % ngroups
+ *     == 0, 1 <= headdim <= 256, 1 <= dstate <= 256, conv_width in {2,3,4}.
+ *     The MFMA kernel is used when io_dtype is bf16, headdim in {32,64,128},
+ *     dstate % 16 == 0 and pointers/strides are 16-byte aligned; every other
+ *     case in the envelope runs a plain fp32-FMA kernel.
+ */
+#ifndef STREE_H
+#define STREE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define STREE_MAX_NODES 256
+
+enum stree_status {
+    STREE_OK = 0,
+    STREE_ERR_NULL_ARG = 1,   /* a required pointer is NULL */
+    STREE_ERR_BAD_SHAPE = 2,  /* a dimension is outside the envelope */
+    STREE_ERR_BAD_DTYPE = 3,  /* unknown io_dtype / unsupported state_dtype */
+    STREE_ERR_BAD_STRIDE = 4, /* a token stride is smaller than its row */
+    STREE_ERR_HIP = 5         /* a HIP launch failed */
+};
+
+enum stree_dtype { STREE_F32 = 0, STREE_BF16 = 1 };
+
+enum stree_flags {
+    STREE_FLAG_CONV_SILU = 1,    /* tree_conv applies z * sigmoid(z) */
+    STREE_FLAG_FORCE_FMA = 256   /* tree_ssd: use the plain fp32-FMA kernel even where MFMA applies */
+};
+
+/* Problem sizes.  POD, host memory. */
+typedef struct stree_dims {
+    int32_t batch;       /* B sequences, each with its own tree of exactly nnodes nodes */
+    int32_t nnodes;      /* N */
+    int32_t nheads;      /* H */
+    int32_t headdim;     /* P */
+    int32_t dstate;      /* S */
+    int32_t ngroups;     /* G */
+    int32_t conv_width;  /* W (ignored by tree_ssd; 0 allowed there) */
+    int32_t io_dtype;    /* enum stree_dtype */
+    int32_t state_dtype; /* STREE_F32 only */
+    int32_t flags;       /* enum stree_flags */
+    /* token strides in ELEMENTS of x, B, C (0 = dense: H*P, G*S, G*S).  They let
+     * x | B | C be column ranges of one conv output buffer [B,N,H*P+2*G*S].  The
+     * batch stride is nnodes * token stride. */
+    int64_t x_stride_n, b_stride_n, c_stride_n;
+} stree_dims;
+
+int stree_version(void);
+const char *stree_status_string(int status);
+
+/*
+ * Tree structure (the tree mask L of Sec. 3 "Formalization", in index form).
+ *   parent     int32 [B,N]
+ *   depth_out  int32 [B,N]               edges from the root            (or NULL)
+ *   ancmask_out uint32 [B,N,ceil(N/32)]  bit j of row i = L_ij          (or NULL)
+ *   anc_out    int32 [B,N,W]             k-th ancestor of i for k < W = conv_width,
+ *                                        k = 0 is i itself; once the walk leaves the
+ *                                        tree the entry is -m, "m rows above the
+ *                                        root" (m = k - depth)          (or NULL)
+ * Results are exact integers.
+ */
+int stree_tree_index(const stree_dims *dims, const int32_t *parent, int32_t *depth_out,
+                     uint32_t *ancmask_out, int32_t *anc_out, int32_t *tree_status,
+                     void *hip_stream);
+
+/*
+ * Depthwise causal conv1d taken along each node's ancestor chain (the Mamba2
+ * block's conv in front of the SSM, applied to the packed tree of Sec. 3):
+ *   out[b,i,c] = act( bias[c] + sum_{k=0}^{W-1} w[c,W-1-k] * src(i,k)[c] )
+ * where src(i,k) is the pre-conv row of the k-th ancestor of i, or, above the
+ * root, row (W-1) - (k - depth(i)) of conv_state.
+ *   xbc_pre    io [B,N,Cc], Cc = H*P + 2*G*S
+ *   conv_state io [B,W-1,Cc]  last W-1 pre-conv rows before the root, oldest first
+ *   conv_w     io [Cc,W]      conv_w[c,W-1] multiplies the node's own row
+ *   conv_b     io [Cc] or NULL
+ *   xbc_out    io [B,N,Cc]    must not alias xbc_pre
+ * Accumulation is fp32.  Cc must be a multiple of 8 (bf16) or 4 (fp32).
+ */
+int stree_tree_conv(const stree_dims *dims, const int32_t *parent, const void *xbc_pre,
+                    const void *conv_state, const void *conv_w, const void *conv_b,
+                    void *xbc_out, int32_t *tree_status, void *hip_stream);
+
+/*
+ * Tree scan (Sec. 3 "Tree decoding with State-space models"; Eq. a_tree and the
+ * matrix form y = M_x x0 + M_u u):
+ *   s_i  = sum_{j on path(i)} dt[j] * A[h]                        (A_tree)
+ *   y_i  = exp(s_i) * h0 C_i
+ *        + sum_{j on path(i)} exp(s_i - s_j) * dt[j] * <C_i,B_j> * x_j
+ *        + D[h] * x_i
+ *   x   io  [B,N,H,P] (token stride x_stride_n)    dt  f32 [B,N,H], already softplus'ed
+ *   A   f32 [H], negative                          Bm, Cm io [B,N,G,S] (strides b/c_stride_n)
+ *   D   f32 [H] or NULL                            h0  f32 [B,H,P,S] or NULL (zero state)
+ *   y   io  [B,N,H,P] dense
+ * bf16 mode: products on the bf16 MFMA units with fp32 accumulation; the state
+ * and the decay-weighted mask are rounded to bf16 as MFMA operands.
+ */
+int stree_tree_ssd(const stree_dims *dims, const int32_t *parent, const void *x, const float *dt,
+                   const float *A, const void *Bm, const void *Cm, const float *D,
+                   const float *h0, void *y, int32_t *tree_status, void *hip_stream);
+
+/*
+ * State commit (the "activation replay" of Sec. 3 "Implementation" / Alg. 1: the
+ * state after the last accepted token is recomputed from the cached x, dt, B of
+ * the tree that was just verified).  For accepted node k = accepted[b]:
+ *   h_out = exp(s_k) * h0 + sum_{j on path(k)} exp(s_k - s_j) * dt[j] * x_j (outer) B_j
+ *   conv_state_out = last W-1 rows of [conv_state ; xbc_pre[path(k)]]
+ * accepted[b] == -1 copies the state through.  An accepted index outside
+ * [-1, N) sets tree_status[b] = -1 and copies the state through.
+ *   accepted int32 [B]; x, dt, A, Bm as in stree_tree_ssd
+ *   h0 f32 [B,H,P,S] or NULL; h_out f32 [B,H,P,S], MAY alias h0
+ *   xbc_pre, conv_state, conv_state_out: all three NULL to skip the conv part;
+ *   conv_state_out MAY alias conv_state.
+ * dstate must be a multiple of 4.
+ */
+int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int32_t *accepted,
+                       const void *x, const float *dt, const float *A, const void *Bm,
+                       const float *h0, float *h_out, const void *xbc_pre,
+                       const void *conv_state, void *conv_state_out, int32_t *tree_status,
+                       void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STREE_H */

@@ -1,0 +1,166 @@
+"""Thin ctypes binding of libstree.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their
+device pointers and the current HIP stream through the C ABI declared in
+``include/stree.h`` and returns the output tensors.  No step of the path is
+computed here, and there is no CPU fallback: if the library is missing,
+``load()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libstree.so")
+
+F32, BF16 = 0, 1
+FLAG_CONV_SILU = 1
+FLAG_FORCE_FMA = 256
+MAX_NODES = 256
+
+
+class StreeDims(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("batch", "nnodes", "nheads", "headdim", "dstate", "ngroups",
+                                         "conv_width", "io_dtype", "state_dtype", "flags")] + \
+               [(n, C.c_int64) for n in ("x_stride_n", "b_stride_n", "c_stride_n")]
+
+
+class StreeError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = load().stree_status_string(code).decode()
+        super().__init__(f"{where}: status {code} ({msg})")
+
+
+_lib = None
+_VP = C.c_void_p
+
+
+def load() -> C.CDLL:
+    """Load libstree.so (build it first with ``python -m paper_2505_14969_amd.build``
+    or ``__graft_entry__.build()``).  Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run paper_2505_14969_amd/build.py")
+        lib = C.CDLL(LIB_PATH)
+        lib.stree_version.restype = C.c_int
+        lib.stree_status_string.restype = C.c_char_p
+        lib.stree_status_string.argtypes = [C.c_int]
+        dp = C.POINTER(StreeDims)
+        lib.stree_tree_index.argtypes = [dp] + [_VP] * 6
+        lib.stree_tree_conv.argtypes = [dp] + [_VP] * 8
+        lib.stree_tree_ssd.argtypes = [dp] + [_VP] * 11
+        lib.stree_commit_state.argtypes = [dp] + [_VP] * 13
+        for f in (lib.stree_tree_index, lib.stree_tree_conv, lib.stree_tree_ssd, lib.stree_commit_state):
+            f.restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else _VP(t.data_ptr())
+
+
+def _stream() -> _VP:
+    return _VP(torch.cuda.current_stream().cuda_stream)
+
+
+def _io_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported io dtype {t.dtype}")
+
+
+def _token_stride(t: torch.Tensor, nnodes: int) -> int:
+    """Element stride between tokens of a [B,N,a,b] view whose last two dims are
+    dense and whose batch stride is N * token stride."""
+    assert t.dim() == 4 and t.stride(3) == 1 and t.stride(2) == t.shape[3], "inner dims must be dense"
+    sn = t.stride(1)
+    assert t.shape[0] == 1 or t.stride(0) == nnodes * sn, "batch stride must be N * token stride"
+    return sn
+
+
+def make_dims(batch, nnodes, nheads, headdim, dstate, ngroups, conv_width=0, io_dtype=BF16, flags=0,
+              x_stride_n=0, b_stride_n=0, c_stride_n=0) -> StreeDims:
+    return StreeDims(batch, nnodes, nheads, headdim, dstate, ngroups, conv_width, io_dtype, F32, flags,
+                     x_stride_n, b_stride_n, c_stride_n)
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise StreeError(rc, where)
+
+
+def stree_tree_index(parent: torch.Tensor, conv_width: int = 4
+                     ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]:
+    """parent int32 [B,N] -> (depth [B,N], ancmask uint32-as-int32 [B,N,ceil(N/32)],
+    anc [B,N,W], status [B])."""
+    B, N = parent.shape
+    dev = parent.device
+    depth = torch.empty((B, N), dtype=torch.int32, device=dev)
+    mask = torch.empty((B, N, (N + 31) // 32), dtype=torch.int32, device=dev)
+    anc = torch.empty((B, N, conv_width), dtype=torch.int32, device=dev)
+    status = torch.empty((B,), dtype=torch.int32, device=dev)
+    d = make_dims(B, N, 1, 1, 1, 1, conv_width, F32)
+    _check(load().stree_tree_index(C.byref(d), _ptr(parent), _ptr(depth), _ptr(mask), _ptr(anc), _ptr(status),
+                                   _stream()), "stree_tree_index")
+    return depth, mask, anc, status
+
+
+def stree_tree_conv(parent, xbc_pre, conv_state, conv_w, conv_b, nheads, headdim, dstate, ngroups,
+                    silu: bool = True, out: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None):
+    """xbc_pre [B,N,Cc], conv_state [B,W-1,Cc], conv_w [Cc,W], conv_b [Cc]|None -> xbc_out [B,N,Cc]."""
+    B, N, Cc = xbc_pre.shape
+    W = conv_w.shape[1]
+    assert Cc == nheads * headdim + 2 * ngroups * dstate
+    assert xbc_pre.is_contiguous() and conv_state.is_contiguous() and conv_w.is_contiguous()
+    if out is None:
+        out = torch.empty_like(xbc_pre)
+    d = make_dims(B, N, nheads, headdim, dstate, ngroups, W, _io_code(xbc_pre), FLAG_CONV_SILU if silu else 0)
+    _check(load().stree_tree_conv(C.byref(d), _ptr(parent), _ptr(xbc_pre), _ptr(conv_state), _ptr(conv_w),
+                                  _ptr(conv_b), _ptr(out), _ptr(status), _stream()), "stree_tree_conv")
+    return out
+
+
+def stree_tree_ssd(parent, x, dt, A, Bm, Cm, D=None, h0=None, out: Optional[torch.Tensor] = None,
+                   status: Optional[torch.Tensor] = None, force_fma: bool = False):
+    """x [B,N,H,P], dt [B,N,H] f32, A [H] f32, Bm/Cm [B,N,G,S], D [H]|None, h0 [B,H,P,S] f32|None
+    -> y [B,N,H,P].  x, Bm, Cm may be column views of one [B,N,Cc] buffer."""
+    B, N, H, P = x.shape
+    G, S = Bm.shape[2], Bm.shape[3]
+    if out is None:
+        out = torch.empty((B, N, H, P), dtype=x.dtype, device=x.device)
+    d = make_dims(B, N, H, P, S, G, 0, _io_code(x), FLAG_FORCE_FMA if force_fma else 0,
+                  _token_stride(x, N), _token_stride(Bm, N), _token_stride(Cm, N))
+    assert dt.is_contiguous() and dt.dtype == torch.float32 and out.is_contiguous()
+    _check(load().stree_tree_ssd(C.byref(d), _ptr(parent), _ptr(x), _ptr(dt), _ptr(A), _ptr(Bm), _ptr(Cm),
+                                 _ptr(D), _ptr(h0), _ptr(out), _ptr(status), _stream()), "stree_tree_ssd")
+    return out
+
+
+def stree_commit_state(parent, accepted, x, dt, A, Bm, h0=None, h_out: Optional[torch.Tensor] = None,
+                       xbc_pre=None, conv_state=None, conv_state_out: Optional[torch.Tensor] = None,
+                       status: Optional[torch.Tensor] = None):
+    """-> (h_out [B,H,P,S] f32, conv_state_out [B,W-1,Cc] | None).  h_out may be h0 itself
+    (in place), conv_state_out may be conv_state itself."""
+    B, N, H, P = x.shape
+    G, S = Bm.shape[2], Bm.shape[3]
+    if h_out is None:
+        h_out = torch.empty((B, H, P, S), dtype=torch.float32, device=x.device)
+    W = 0
+    if xbc_pre is not None:
+        W = conv_state.shape[1] + 1
+        if conv_state_out is None:
+            conv_state_out = torch.empty_like(conv_state)
+    d = make_dims(B, N, H, P, S, G, W, _io_code(x), 0, _token_stride(x, N), _token_stride(Bm, N), 0)
+    _check(load().stree_commit_state(C.byref(d), _ptr(parent), _ptr(accepted), _ptr(x), _ptr(dt), _ptr(A),
+                                     _ptr(Bm), _ptr(h0), _ptr(h_out), _ptr(xbc_pre), _ptr(conv_state),
+                                     _ptr(conv_state_out), _ptr(status), _stream()), "stree_commit_state")
+    return h_out, conv_state_out

@@ -1,0 +1,118 @@
+// C-ABI entry points of libstree: argument validation and kernel dispatch.
+// Nothing here computes; every step of the path runs in the HIP kernels.
+#include <hip/hip_runtime.h>
+
+#include "../../include/stree.h"
+#include "launch.hpp"
+
+namespace {
+
+enum ConvCheck { kNoConv = 0, kConvWidth = 1, kConvChannels = 2 };
+
+int check_dims(const stree_dims *d, int need_conv) {
+    if (!d) return STREE_ERR_NULL_ARG;
+    if (d->io_dtype != STREE_F32 && d->io_dtype != STREE_BF16) return STREE_ERR_BAD_DTYPE;
+    if (d->state_dtype != STREE_F32) return STREE_ERR_BAD_DTYPE;
+    if (d->batch < 0 || d->batch > 65535) return STREE_ERR_BAD_SHAPE;
+    if (d->nnodes < 1 || d->nnodes > STREE_MAX_NODES) return STREE_ERR_BAD_SHAPE;
+    if (d->nheads < 1 || d->nheads > 65535 || d->ngroups < 1 || d->nheads % d->ngroups != 0)
+        return STREE_ERR_BAD_SHAPE;
+    if (d->headdim < 1 || d->headdim > 256 || d->dstate < 1 || d->dstate > 256) return STREE_ERR_BAD_SHAPE;
+    if (need_conv) {
+        if (d->conv_width < 2 || d->conv_width > 4) return STREE_ERR_BAD_SHAPE;
+    }
+    if (need_conv == kConvChannels) {
+        const int cc = d->nheads * d->headdim + 2 * d->ngroups * d->dstate;
+        if (cc % (d->io_dtype == STREE_BF16 ? 8 : 4) != 0) return STREE_ERR_BAD_SHAPE;
+    }
+    return STREE_OK;
+}
+
+// fills in dense strides and checks that rows fit
+int resolve_strides(stree_dims &d) {
+    if (d.x_stride_n == 0) d.x_stride_n = (int64_t)d.nheads * d.headdim;
+    if (d.b_stride_n == 0) d.b_stride_n = (int64_t)d.ngroups * d.dstate;
+    if (d.c_stride_n == 0) d.c_stride_n = (int64_t)d.ngroups * d.dstate;
+    if (d.x_stride_n < (int64_t)d.nheads * d.headdim) return STREE_ERR_BAD_STRIDE;
+    if (d.b_stride_n < (int64_t)d.ngroups * d.dstate) return STREE_ERR_BAD_STRIDE;
+    if (d.c_stride_n < (int64_t)d.ngroups * d.dstate) return STREE_ERR_BAD_STRIDE;
+    return STREE_OK;
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? STREE_OK : STREE_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int stree_version(void) { return 1; }
+
+const char *stree_status_string(int status) {
+    switch (status) {
+        case STREE_OK: return "ok";
+        case STREE_ERR_NULL_ARG: return "a required pointer is NULL";
+        case STREE_ERR_BAD_SHAPE: return "a dimension is outside the supported envelope";
+        case STREE_ERR_BAD_DTYPE: return "unknown io_dtype or unsupported state_dtype";
+        case STREE_ERR_BAD_STRIDE: return "a token stride is smaller than its row";
+        case STREE_ERR_HIP: return "a HIP call failed";
+    }
+    return "unknown status";
+}
+
+int stree_tree_index(const stree_dims *dims, const int32_t *parent, int32_t *depth_out,
+                     uint32_t *ancmask_out, int32_t *anc_out, int32_t *tree_status, void *hip_stream) {
+    int rc = check_dims(dims, anc_out ? kConvWidth : kNoConv);
+    if (rc) return rc;
+    if (!parent) return STREE_ERR_NULL_ARG;
+    if (dims->batch == 0) return STREE_OK;
+    return hip_status(stree::launch_tree_index(*dims, parent, depth_out, ancmask_out, anc_out, tree_status,
+                                               (hipStream_t)hip_stream));
+}
+
+int stree_tree_conv(const stree_dims *dims, const int32_t *parent, const void *xbc_pre,
+                    const void *conv_state, const void *conv_w, const void *conv_b, void *xbc_out,
+                    int32_t *tree_status, void *hip_stream) {
+    int rc = check_dims(dims, kConvChannels);
+    if (rc) return rc;
+    if (!parent || !xbc_pre || !conv_state || !conv_w || !xbc_out) return STREE_ERR_NULL_ARG;
+    if (dims->batch == 0) return STREE_OK;
+    return hip_status(stree::launch_tree_conv(*dims, parent, xbc_pre, conv_state, conv_w, conv_b, xbc_out,
+                                              tree_status, (hipStream_t)hip_stream));
+}
+
+int stree_tree_ssd(const stree_dims *dims, const int32_t *parent, const void *x, const float *dt,
+                   const float *A, const void *Bm, const void *Cm, const float *D, const float *h0, void *y,
+                   int32_t *tree_status, void *hip_stream) {
+    int rc = check_dims(dims, kNoConv);
+    if (rc) return rc;
+    if (!parent || !x || !dt || !A || !Bm || !Cm || !y) return STREE_ERR_NULL_ARG;
+    stree_dims d = *dims;
+    rc = resolve_strides(d);
+    if (rc) return rc;
+    if (d.batch == 0) return STREE_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (!(d.flags & STREE_FLAG_FORCE_FMA) && stree::tree_ssd_mfma_supported(d, x, Bm, Cm, h0, y))
+        return hip_status(stree::launch_tree_ssd_mfma(d, parent, x, dt, A, Bm, Cm, D, h0, y, tree_status, st));
+    return hip_status(stree::launch_tree_ssd_fma(d, parent, x, dt, A, Bm, Cm, D, h0, y, tree_status, st));
+}
+
+int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int32_t *accepted, const void *x,
+                       const float *dt, const float *A, const void *Bm, const float *h0, float *h_out,
+                       const void *xbc_pre, const void *conv_state, void *conv_state_out,
+                       int32_t *tree_status, void *hip_stream) {
+    const bool conv = xbc_pre || conv_state || conv_state_out;
+    int rc = check_dims(dims, conv ? kConvChannels : kNoConv);
+    if (rc) return rc;
+    if (!parent || !accepted || !x || !dt || !A || !Bm || !h_out) return STREE_ERR_NULL_ARG;
+    if (conv && (!xbc_pre || !conv_state || !conv_state_out)) return STREE_ERR_NULL_ARG;
+    if (dims->dstate % 4 != 0) return STREE_ERR_BAD_SHAPE;
+    stree_dims d = *dims;
+    rc = resolve_strides(d);
+    if (rc) return rc;
+    if (d.batch == 0) return STREE_OK;
+    return hip_status(stree::launch_commit_state(d, parent, accepted, x, dt, A, Bm, h0, h_out, xbc_pre,
+                                                 conv_state, conv_state_out, tree_status,
+                                                 (hipStream_t)hip_stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,175 @@
+// stree_commit_state: state of the accepted node, recomputed from the cached
+// activations of the verified tree (activation replay), plus the conv tail.
+//
+//   h_out = exp(s_k) h0 + sum_{j on path(k)} dt_j exp(s_k - s_j) x_j (outer) B_j
+//
+// Streaming kernel: the P x S fp32 state is read once and written once; the
+// rank-(depth+1) update comes from a handful of x / B rows staged in LDS.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace stree {
+
+constexpr int kSlab = 4096;        // state elements per workgroup (4 float4 per thread)
+constexpr int kPathChunk = 16;     // path nodes staged in LDS at a time
+
+// grid (ceil(P*S / kSlab), H, B)
+template <typename T>
+__global__ __launch_bounds__(kThreads) void commit_h_kernel(
+    const int32_t *__restrict__ parent, const int32_t *__restrict__ accepted, int n, int H, int P, int S,
+    int G, const T *__restrict__ x, long x_sn, const float *__restrict__ dt, const float *__restrict__ A,
+    const T *__restrict__ Bm, long b_sn, const float *h0, float *h_out, int32_t *__restrict__ status) {
+    __shared__ TreeLds tree;
+    __shared__ uint32_t mask[kMaxNodes * kMaxWords];
+    __shared__ int path[kMaxNodes];
+    __shared__ float coef[kMaxNodes];
+    __shared__ float xs[kPathChunk][kMaxNodes];
+    __shared__ __align__(16) float bs[kPathChunk][kMaxNodes];
+    const int tid = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int g = h / (H / G);
+    const int words = (n + 31) / 32;
+    const float A_h = A[h];
+    const float dt_i = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
+    const int bad = build_tree_index(tree, mask, parent + (size_t)b * n, n, n, words, dt_i, A_h);
+    const int k = accepted[b];
+    const bool k_bad = (k < -1) || (k >= n);
+    if (status && blockIdx.x == 0 && h == 0 && tid == 0) status[b] = bad ? bad : (k_bad ? -1 : 0);
+
+    const int PS = P * S;
+    const size_t sbase = ((size_t)b * H + h) * PS;
+    const int e0 = blockIdx.x * kSlab + tid * 4;
+    float4 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int e = e0 + q * (kThreads * 4);
+        acc[q] = (h0 && e < PS) ? *reinterpret_cast<const float4 *>(h0 + sbase + e) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (bad || k < 0 || k_bad) {  // pass the state through
+        if (h_out != h0 || !h0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int e = e0 + q * (kThreads * 4);
+                if (e < PS) *reinterpret_cast<float4 *>(h_out + sbase + e) = acc[q];
+            }
+        }
+        return;
+    }
+    // compact path(k) (ancestors have smaller labels, so ascending label = root first)
+    const float s_k = tree.s[k];
+    if (tid < n && mask_bit(mask, words, k, tid)) {
+        int pos = 0;
+        for (int w = 0; w < (tid >> 5); ++w) pos += __popc(mask[k * words + w]);
+        pos += __popc(mask[k * words + (tid >> 5)] & ((1u << (tid & 31)) - 1u));
+        path[pos] = tid;
+        coef[pos] = tree.dt[tid] * __expf(s_k - tree.s[tid]);
+    }
+    const int len = tree.cnt[k];
+    const float decay = __expf(s_k);
+    int pq[4], sq[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int e = e0 + q * (kThreads * 4);
+        pq[q] = e < PS ? e / S : 0;
+        sq[q] = e < PS ? e % S : 0;
+        acc[q].x *= decay; acc[q].y *= decay; acc[q].z *= decay; acc[q].w *= decay;
+    }
+    __syncthreads();
+    const T *xb = x + (size_t)b * n * x_sn + (size_t)h * P;
+    const T *Bb = Bm + (size_t)b * n * b_sn + (size_t)g * S;
+    for (int c0 = 0; c0 < len; c0 += kPathChunk) {
+        const int cn = min(kPathChunk, len - c0);
+        for (int idx = tid; idx < cn * (P + S); idx += kThreads) {
+            const int t = idx / (P + S), col = idx % (P + S);
+            const int node = path[c0 + t];
+            if (col < P) xs[t][col] = to_f32(xb[(size_t)node * x_sn + col]);
+            else bs[t][col - P] = coef[c0 + t] * to_f32(Bb[(size_t)node * b_sn + (col - P)]);
+        }
+        __syncthreads();
+        for (int t = 0; t < cn; ++t) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float xv = xs[t][pq[q]];
+                const float4 bv = *reinterpret_cast<const float4 *>(&bs[t][sq[q]]);
+                acc[q].x = fmaf(xv, bv.x, acc[q].x);
+                acc[q].y = fmaf(xv, bv.y, acc[q].y);
+                acc[q].z = fmaf(xv, bv.z, acc[q].z);
+                acc[q].w = fmaf(xv, bv.w, acc[q].w);
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int e = e0 + q * (kThreads * 4);
+        if (e < PS) *reinterpret_cast<float4 *>(h_out + sbase + e) = acc[q];
+    }
+}
+
+// conv tail: out row r (oldest first) = pre-conv row of the (W-2-r)-th ancestor
+// of k, or the old state row once above the root.  grid (ceil(Cc/(VEC*256)), B)
+template <typename T, int VEC>
+__global__ __launch_bounds__(kThreads) void commit_conv_kernel(
+    const int32_t *__restrict__ parent, const int32_t *__restrict__ accepted, int n, int Cc, int W,
+    const T *__restrict__ xbc_pre, const T *conv_state, T *conv_state_out) {
+    __shared__ int par[kMaxNodes];
+    const int tid = threadIdx.x, b = blockIdx.y;
+    int ok = 1;
+    if (tid < n) {
+        const int p = parent[(size_t)b * n + tid];
+        ok = (tid == 0) ? (p == -1) : (p >= 0 && p < tid);
+        par[tid] = ok ? p : -1;
+    }
+    const int any_bad = __syncthreads_or(!ok);
+    const int k = accepted[b];
+    const int c0 = (blockIdx.x * kThreads + tid) * VEC;
+    if (c0 >= Cc) return;
+    const bool pass = any_bad || k < 0 || k >= n;
+    uint4 rows[3];  // W - 1 <= 3 rows of 16 bytes
+    int v = pass ? -1 : k, above = 0;
+    for (int m = 0; m < W - 1; ++m) {  // m-th ancestor of k feeds out row W-2-m
+        const T *src;
+        if (v >= 0) {
+            src = xbc_pre + ((size_t)b * n + v) * Cc + c0;
+            v = par[v];
+        } else {
+            ++above;
+            src = conv_state + ((size_t)b * (W - 1) + (W - 1 - above)) * Cc + c0;
+        }
+        rows[m] = *reinterpret_cast<const uint4 *>(src);
+    }
+    for (int m = 0; m < W - 1; ++m)
+        *reinterpret_cast<uint4 *>(conv_state_out + ((size_t)b * (W - 1) + (W - 2 - m)) * Cc + c0) = rows[m];
+}
+
+hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const int32_t *accepted,
+                               const void *x, const float *dt, const float *A, const void *Bm,
+                               const float *h0, float *h_out, const void *xbc_pre, const void *conv_state,
+                               void *conv_state_out, int32_t *status, hipStream_t st) {
+    const int PS = d.headdim * d.dstate;
+    const dim3 grid((PS + kSlab - 1) / kSlab, d.nheads, d.batch);
+    if (d.io_dtype == STREE_BF16)
+        hipLaunchKernelGGL(commit_h_kernel<bf16_t>, grid, dim3(kThreads), 0, st, parent, accepted, d.nnodes,
+                           d.nheads, d.headdim, d.dstate, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A,
+                           (const bf16_t *)Bm, (long)d.b_stride_n, h0, h_out, status);
+    else
+        hipLaunchKernelGGL(commit_h_kernel<float>, grid, dim3(kThreads), 0, st, parent, accepted, d.nnodes,
+                           d.nheads, d.headdim, d.dstate, d.ngroups, (const float *)x, (long)d.x_stride_n, dt, A,
+                           (const float *)Bm, (long)d.b_stride_n, h0, h_out, status);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || !conv_state_out) return err;
+    const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
+    if (d.io_dtype == STREE_BF16) {
+        const dim3 cgrid((Cc / 8 + kThreads - 1) / kThreads, d.batch);
+        hipLaunchKernelGGL((commit_conv_kernel<bf16_t, 8>), cgrid, dim3(kThreads), 0, st, parent, accepted,
+                           d.nnodes, Cc, d.conv_width, (const bf16_t *)xbc_pre, (const bf16_t *)conv_state,
+                           (bf16_t *)conv_state_out);
+    } else {
+        const dim3 cgrid((Cc / 4 + kThreads - 1) / kThreads, d.batch);
+        hipLaunchKernelGGL((commit_conv_kernel<float, 4>), cgrid, dim3(kThreads), 0, st, parent, accepted,
+                           d.nnodes, Cc, d.conv_width, (const float *)xbc_pre, (const float *)conv_state,
+                           (float *)conv_state_out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace stree

@@ -1,0 +1,33 @@
+// Host-side launchers, one per kernel family.  Arguments are already validated
+// by the C-ABI layer (api.hip); strides are resolved (never 0).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "../../include/stree.h"
+
+namespace stree {
+
+hipError_t launch_tree_index(const stree_dims &d, const int32_t *parent, int32_t *depth_out,
+                             uint32_t *mask_out, int32_t *anc_out, int32_t *status, hipStream_t st);
+
+hipError_t launch_tree_conv(const stree_dims &d, const int32_t *parent, const void *xbc_pre,
+                            const void *conv_state, const void *conv_w, const void *conv_b, void *xbc_out,
+                            int32_t *status, hipStream_t st);
+
+hipError_t launch_tree_ssd_fma(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
+                               const float *A, const void *Bm, const void *Cm, const float *D,
+                               const float *h0, void *y, int32_t *status, hipStream_t st);
+
+// true when the MFMA kernel covers these dims / alignments
+bool tree_ssd_mfma_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm,
+                             const float *h0, const void *y);
+hipError_t launch_tree_ssd_mfma(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
+                                const float *A, const void *Bm, const void *Cm, const float *D,
+                                const float *h0, void *y, int32_t *status, hipStream_t st);
+
+hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const int32_t *accepted,
+                               const void *x, const float *dt, const float *A, const void *Bm,
+                               const float *h0, float *h_out, const void *xbc_pre, const void *conv_state,
+                               void *conv_state_out, int32_t *status, hipStream_t st);
+
+}  // namespace stree

@@ -1,0 +1,67 @@
+"""Shared helpers for the parity tests: moving seeded numpy inputs to the GPU in
+the library's storage types, reading results back, and the parity metric."""
+from __future__ import annotations
+
+import numpy as np
+
+from paper_2505_14969_amd import synth
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def to_dev(a, io: str = "f32"):
+    """numpy fp32 (already rounded when io == 'bf16') -> cuda tensor in storage type."""
+    import torch
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if a.dtype in (np.int32, np.int64):
+        return torch.from_numpy(a.astype(np.int32)).cuda()
+    if io == "bf16":
+        bits = synth.f32_to_bf16_bits(a.astype(np.float32))
+        assert np.array_equal(synth.bf16_bits_to_f32(bits), a.astype(np.float32)), "input was not bf16-exact"
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(a.astype(np.float32)).cuda()
+
+
+def to_host(t) -> np.ndarray:
+    """cuda tensor (f32 / bf16 / int32) -> numpy (fp32 for floats)."""
+    import torch
+    if t.dtype == torch.bfloat16:
+        return synth.bf16_bits_to_f32(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16))
+    return t.contiguous().cpu().numpy()
+
+
+def parity(got: np.ndarray, want: np.ndarray):
+    """(max-abs error / max-abs reference, l2 error / l2 reference) of one tensor."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (got.shape, want.shape)
+    assert np.isfinite(got).all(), "non-finite values in the result"
+    scale = max(float(np.max(np.abs(want))), 1e-30)
+    l2 = max(float(np.linalg.norm(want.ravel())), 1e-30)
+    return float(np.max(np.abs(got - want))) / scale, float(np.linalg.norm((got - want).ravel())) / l2
+
+
+def assert_parity(got, want, tol: float, what: str = ""):
+    emax, el2 = parity(got, want)
+    assert emax <= tol and el2 <= tol, f"{what}: max-rel {emax:.3e}, l2-rel {el2:.3e} > tol {tol:g}"
+    return emax, el2
+
+
+def split_xbc(xbc: np.ndarray, H: int, P: int, G: int, S: int):
+    """Column ranges x | B | C of a [B,N,Cc] conv output (numpy views)."""
+    B, N, _ = xbc.shape
+    x = xbc[:, :, : H * P].reshape(B, N, H, P)
+    Bm = xbc[:, :, H * P: H * P + G * S].reshape(B, N, G, S)
+    Cm = xbc[:, :, H * P + G * S:].reshape(B, N, G, S)
+    return x, Bm, Cm
+
+
+def split_xbc_dev(xbc, H: int, P: int, G: int, S: int):
+    """Same split on a cuda tensor: strided views, no copies."""
+    B, N, _ = xbc.shape
+    x = xbc[:, :, : H * P].unflatten(2, (H, P))
+    Bm = xbc[:, :, H * P: H * P + G * S].unflatten(2, (G, S))
+    Cm = xbc[:, :, H * P + G * S:].unflatten(2, (G, S))
+    return x, Bm, Cm

@@ -1,0 +1,111 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, and rejects bad arguments before launching
+anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2505_14969_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2505_14969_amd import build
+        build.build()
+    return binding.load()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "stree.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(stree_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = _declared_symbols()
+    assert {"stree_tree_conv", "stree_tree_ssd", "stree_commit_state", "stree_tree_index",
+            "stree_version", "stree_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/stree.h but not exported"
+
+
+def test_dims_struct_matches_header_layout():
+    # 10 int32 + 3 int64, naturally aligned
+    assert C.sizeof(binding.StreeDims) == 10 * 4 + 3 * 8
+    assert binding.StreeDims.x_stride_n.offset == 40
+
+
+def test_version_and_status_strings(lib):
+    assert lib.stree_version() >= 1
+    seen = {lib.stree_status_string(c) for c in range(6)}
+    assert len(seen) == 6 and all(s for s in seen)
+
+
+FAKE = C.c_void_p(0x1000)   # never dereferenced: every call below fails validation first
+
+
+def _ssd(lib, d, parent=FAKE, x=FAKE, dt=FAKE, A=FAKE, Bm=FAKE, Cm=FAKE, y=FAKE):
+    return lib.stree_tree_ssd(C.byref(d), parent, x, dt, A, Bm, Cm, None, None, y, None, None)
+
+
+def test_tree_ssd_rejects_bad_arguments(lib):
+    ok = dict(batch=1, nnodes=64, nheads=8, headdim=64, dstate=128, ngroups=1)
+    assert lib.stree_tree_ssd(None, *([FAKE] * 6), None, None, FAKE, None, None) == 1
+    assert _ssd(lib, binding.make_dims(**ok), x=None) == 1
+    assert _ssd(lib, binding.make_dims(**ok), y=None) == 1
+    assert _ssd(lib, binding.make_dims(**{**ok, "nnodes": 0})) == 2
+    assert _ssd(lib, binding.make_dims(**{**ok, "nnodes": 257})) == 2
+    assert _ssd(lib, binding.make_dims(**{**ok, "ngroups": 3})) == 2
+    assert _ssd(lib, binding.make_dims(**{**ok, "headdim": 0})) == 2
+    assert _ssd(lib, binding.make_dims(**{**ok, "dstate": 512})) == 2
+    assert _ssd(lib, binding.make_dims(**{**ok, "batch": -1})) == 2
+    assert _ssd(lib, binding.make_dims(**ok, io_dtype=7)) == 3
+    d = binding.make_dims(**ok)
+    d.state_dtype = 1
+    assert _ssd(lib, d) == 3
+    assert _ssd(lib, binding.make_dims(**ok, x_stride_n=8)) == 4
+    assert _ssd(lib, binding.make_dims(**ok, b_stride_n=64)) == 4
+    # batch 0 is a valid no-op and launches nothing
+    assert _ssd(lib, binding.make_dims(**{**ok, "batch": 0})) == 0
+
+
+def test_tree_conv_rejects_bad_arguments(lib):
+    ok = dict(batch=1, nnodes=64, nheads=8, headdim=64, dstate=128, ngroups=1, conv_width=4)
+
+    def conv(d, out=FAKE):
+        return lib.stree_tree_conv(C.byref(d), FAKE, FAKE, FAKE, FAKE, None, out, None, None)
+
+    assert conv(binding.make_dims(**ok), out=None) == 1
+    assert conv(binding.make_dims(**{**ok, "conv_width": 1})) == 2
+    assert conv(binding.make_dims(**{**ok, "conv_width": 5})) == 2
+    assert conv(binding.make_dims(**{**ok, "headdim": 3, "dstate": 1})) == 2   # Cc not a vector multiple
+    assert conv(binding.make_dims(**{**ok, "batch": 0})) == 0
+
+
+def test_commit_rejects_bad_arguments(lib):
+    ok = dict(batch=1, nnodes=64, nheads=8, headdim=64, dstate=128, ngroups=1, conv_width=4)
+
+    def commit(d, accepted=FAKE, h_out=FAKE, xbc=None, cs=None, cso=None):
+        return lib.stree_commit_state(C.byref(d), FAKE, accepted, FAKE, FAKE, FAKE, FAKE, None, h_out,
+                                      xbc, cs, cso, None, None)
+
+    assert commit(binding.make_dims(**ok), accepted=None) == 1
+    assert commit(binding.make_dims(**ok), h_out=None) == 1
+    assert commit(binding.make_dims(**ok), xbc=FAKE) == 1            # conv part needs all three
+    assert commit(binding.make_dims(**{**ok, "dstate": 30})) == 2
+    assert commit(binding.make_dims(**{**ok, "conv_width": 7}), xbc=FAKE, cs=FAKE, cso=FAKE) == 2
+    assert commit(binding.make_dims(**{**ok, "batch": 0})) == 0
+
+
+def test_tree_index_rejects_bad_arguments(lib):
+    d = binding.make_dims(1, 300, 1, 1, 1, 1, 4, binding.F32)
+    assert lib.stree_tree_index(C.byref(d), FAKE, FAKE, None, None, None, None) == 2
+    d = binding.make_dims(1, 30, 1, 1, 1, 1, 9, binding.F32)
+    assert lib.stree_tree_index(C.byref(d), FAKE, None, None, FAKE, None, None) == 2
+    d = binding.make_dims(1, 30, 1, 1, 1, 1, 4, binding.F32)
+    assert lib.stree_tree_index(C.byref(d), None, FAKE, None, None, None, None) == 1

@@ -1,0 +1,120 @@
+"""GPU parity on the five benchmark configurations at full size, through the
+C ABI, in the same call sequence the benchmark times (conv -> tree scan on
+column views of the conv output -> commit)."""
+import numpy as np
+import pytest
+
+from paper_2505_14969_amd import synth
+from helpers import TOL, assert_parity, split_xbc, split_xbc_dev, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def st():
+    import torch
+    from paper_2505_14969_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()
+    return binding
+
+
+def _pipeline(st, oracle, wl, h0_dev, h0_ref, check_commit=True):
+    """conv -> ssd -> commit on both sides; returns nothing, asserts parity."""
+    import torch
+    H, P, S, G = wl.nheads, wl.headdim, wl.dstate, wl.ngroups
+    io = wl.io_dtype
+    par_d = to_dev(wl.parent)
+    xbc_pre_d, cs_d = to_dev(wl.xbc_pre, io), to_dev(wl.conv_state, io)
+    status = torch.full((wl.batch,), -7, dtype=torch.int32, device="cuda")
+    # ---- conv
+    want_conv = oracle.tree_conv(wl.parent, wl.xbc_pre, wl.conv_state, wl.conv_w, wl.conv_b, True)
+    xbc_d = st.stree_tree_conv(par_d, xbc_pre_d, cs_d, to_dev(wl.conv_w, io), to_dev(wl.conv_b, io), H, P, S, G,
+                               silu=True, status=status)
+    assert not to_host(status).any()
+    got_conv = to_host(xbc_d)
+    assert_parity(got_conv, want_conv, 4e-3, f"{wl.name} conv")
+    assert np.all(np.abs(got_conv - want_conv) <= 2.0 ** -8 * np.abs(want_conv) + 1e-5)
+    # ---- tree scan, stage-isolated: GPU scan on the oracle's (rounded) conv output
+    ref_xbc = synth.round_to_bf16(want_conv.astype(np.float32))
+    rx, rB, rC = split_xbc(ref_xbc, H, P, G, S)
+    want_y = oracle.ssd_paths(wl.parent, rx, wl.dt, wl.A, rB, rC, wl.D, h0_ref)
+    dt_d, A_d, D_d = to_dev(wl.dt), to_dev(wl.A), to_dev(wl.D)
+    ox, oB, oC = split_xbc_dev(to_dev(ref_xbc, io), H, P, G, S)
+    y_iso = st.stree_tree_ssd(par_d, ox, dt_d, A_d, oB, oC, D_d, to_dev(h0_ref.astype(np.float32)))
+    assert_parity(to_host(y_iso), want_y, TOL[io], f"{wl.name} y (scan alone)")
+    # ---- tree scan, end to end: views of the GPU's own conv output and the GPU's own h0
+    gx, gB, gC = split_xbc_dev(xbc_d, H, P, G, S)
+    y_d = st.stree_tree_ssd(par_d, gx, dt_d, A_d, gB, gC, D_d, h0_dev, status=status)
+    assert not to_host(status).any()
+    assert_parity(to_host(y_d), want_y, TOL[io], f"{wl.name} y (conv + scan)")
+    if not check_commit:
+        return
+    # ---- commit
+    acc_d = to_dev(wl.accepted)
+    want_h, want_cs = oracle.commit(wl.parent, wl.accepted, rx, wl.dt, wl.A, rB, h0_ref, wl.xbc_pre, wl.conv_state)
+    h_iso, cs_out = st.stree_commit_state(par_d, acc_d, ox, dt_d, A_d, oB, to_dev(h0_ref.astype(np.float32)),
+                                          xbc_pre=xbc_pre_d, conv_state=cs_d, status=status)
+    assert not to_host(status).any()
+    assert_parity(to_host(h_iso), want_h, 1e-4, f"{wl.name} committed state (commit alone)")
+    assert np.array_equal(to_host(cs_out), want_cs.astype(np.float32)), "conv state rows are copies: exact"
+    h_e2e, _ = st.stree_commit_state(par_d, acc_d, gx, dt_d, A_d, gB, h0_dev)
+    assert_parity(to_host(h_e2e), want_h, TOL[io], f"{wl.name} committed state (end to end)")
+
+
+def test_config1_tree64_batch1(st, oracle):
+    wl = synth.config(1)
+    _pipeline(st, oracle, wl, to_dev(wl.h0), wl.h0.astype(np.float64), check_commit=False)
+
+
+def test_config2_tree64_batch16_with_commit(st, oracle):
+    wl = synth.config(2)
+    assert wl.batch == 16 and wl.nheads == 80 and len({tuple(p) for p in wl.parent}) == 16
+    _pipeline(st, oracle, wl, to_dev(wl.h0), wl.h0.astype(np.float64))
+
+
+def test_config2_direct_inputs_scan_only(st, oracle):
+    """The variant the benchmark's roofline is quoted on: x,B,C ~ N(0,1) directly."""
+    wl = synth.direct_xbc(synth.config(2))
+    want = oracle.ssd_paths(wl.parent, wl.x, wl.dt, wl.A, wl.Bm, wl.Cm, wl.D, wl.h0)
+    y = st.stree_tree_ssd(to_dev(wl.parent), to_dev(wl.x, "bf16"), to_dev(wl.dt), to_dev(wl.A),
+                          to_dev(wl.Bm, "bf16"), to_dev(wl.Cm, "bf16"), to_dev(wl.D), to_dev(wl.h0))
+    assert_parity(to_host(y), want, TOL["bf16"], "cfg2 direct")
+
+
+def test_config3_wide_deep_256_groups8(st, oracle):
+    wl = synth.config(3)
+    assert wl.nnodes == 256 and wl.ngroups == 8 and wl.nheads == 128
+    assert synth.tree_depths(wl.parent[0]).max() == 10
+    want = oracle.ssd_paths(wl.parent, wl.x, wl.dt, wl.A, wl.Bm, wl.Cm, wl.D, wl.h0)
+    # last sequence is a chain: the tree result must be the ordinary causal scan
+    lin, _ = oracle.linear_scan(wl.x[3:], wl.dt[3:], wl.A, wl.Bm[3:], wl.Cm[3:], wl.D, wl.h0[3:])
+    assert np.array_equal(want[3:], lin)
+    y = st.stree_tree_ssd(to_dev(wl.parent), to_dev(wl.x, "bf16"), to_dev(wl.dt), to_dev(wl.A),
+                          to_dev(wl.Bm, "bf16"), to_dev(wl.Cm, "bf16"), to_dev(wl.D), to_dev(wl.h0))
+    got = to_host(y)
+    for b in range(wl.batch):
+        assert_parity(got[b], want[b], TOL["bf16"], f"cfg3 b={b}")
+
+
+def test_config4_prefix_then_tree(st, oracle):
+    import torch
+    wl = synth.config(4)
+    e = wl.extras
+    T = e["prefix_x"].shape[1]
+    B, H, P, S = wl.batch, wl.nheads, wl.headdim, wl.dstate
+    # oracle: one linear scan over the 4096-token prefix
+    _, h_ref = oracle.linear_scan(e["prefix_x"], e["prefix_dt"], wl.A, e["prefix_B"], e["prefix_C"], None, None)
+    # GPU: 16 x (256-node chain, commit at its last node), state updated in place
+    chunk = 256
+    chain = to_dev(np.stack([synth.chain_tree(chunk)] * B))
+    last = to_dev(np.full(B, chunk - 1, dtype=np.int32))
+    px, pB, pdt = to_dev(e["prefix_x"], "bf16"), to_dev(e["prefix_B"], "bf16"), to_dev(e["prefix_dt"])
+    A_d = to_dev(wl.A)
+    h = torch.zeros((B, H, P, S), dtype=torch.float32, device="cuda")
+    for c in range(T // chunk):
+        sl = slice(c * chunk, (c + 1) * chunk)
+        st.stree_commit_state(chain, last, px[:, sl].contiguous(), pdt[:, sl].contiguous(), A_d,
+                              pB[:, sl].contiguous(), h, h_out=h)
+    assert_parity(to_host(h), h_ref, 1e-4, "cfg4 prefix state")
+    _pipeline(st, oracle, wl, h, h_ref)
