@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-masked SSD verification pass on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+  stree_tree_conv -> stree_tree_ssd (on column views of the conv output) ->
+  stree_commit_state
+on the 64-node / 80-head configuration at batch 16 (Mamba2-2.7B layer shape,
+bf16 io, fp32 state).  Inputs are resident in HBM before the timed region; the
+step rotates over several buffer sets so that the working set exceeds the
+256 MB Infinity Cache and the scan really streams from HBM.
+
+Prints ONE JSON line on stdout (metric = tree-nodes/s per SSD layer).  Details
+(per-kernel times, cache-warm numbers) go to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
+N_SETS = 6                # rotating buffer sets (about 117 MB each)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes_tree_ssd(B, N, H, P, S, G):
+    """Each operand once: x, y (bf16), B, C (bf16), dt (f32), h0 (f32), parent."""
+    per_seq = N * H * P * 2 * 2 + 2 * N * G * S * 2 + N * H * 4 + H * P * S * 4 + N * 4
+    return B * per_seq + 2 * H * 4
+
+
+def algorithmic_flops_tree_ssd(B, N, H, P, S, G):
+    """C B^T once per group, (L o CB^T) X and C h0^T per head, dense-masked."""
+    return B * (G * 2 * N * N * S + H * (2 * N * N * P + 2 * N * S * P))
+
+
+def read_traffic(kernel_tag):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=600)
+    ap.add_argument("--warmup", type=int, default=60)
+    ap.add_argument("--no-graph", action="store_true", help="launch each kernel from Python instead of HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-ssd", type=int, default=0, metavar="K",
+                    help="profiling aid: run K tree-scan launches and exit")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU; run with --gpus 1 (no collectives or sharding are built)")
+
+    import torch
+    from paper_2505_14969_amd import binding as st
+    from paper_2505_14969_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    st.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = synth.config(2)
+    B, N, H, P, S, G, W = wl.batch, wl.nnodes, wl.nheads, wl.headdim, wl.dstate, wl.ngroups, wl.conv_width
+    Cc = wl.conv_channels
+
+    def bf16(a):
+        return torch.from_numpy(synth.f32_to_bf16_bits(a).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    base = dict(parent=torch.from_numpy(wl.parent).to(dev), xbc_pre=bf16(wl.xbc_pre), conv_state=bf16(wl.conv_state),
+                dt=torch.from_numpy(wl.dt).to(dev), h0=torch.from_numpy(wl.h0).to(dev),
+                accepted=torch.from_numpy(wl.accepted).to(dev))
+    conv_w, conv_b = bf16(wl.conv_w), bf16(wl.conv_b)
+    A, D = torch.from_numpy(wl.A).to(dev), torch.from_numpy(wl.D).to(dev)
+
+    # rotating sets: the same seeded sequences rolled along the batch (distinct memory)
+    sets = []
+    for r in range(N_SETS):
+        s = {k: torch.roll(v, r, 0).contiguous() for k, v in base.items()}
+        s["xbc"] = torch.empty((B, N, Cc), dtype=torch.bfloat16, device=dev)
+        s["y"] = torch.empty((B, N, H, P), dtype=torch.bfloat16, device=dev)
+        s["h_out"] = torch.empty((B, H, P, S), dtype=torch.float32, device=dev)
+        s["cs_out"] = torch.empty_like(s["conv_state"])
+        s["x"] = s["xbc"][:, :, : H * P].unflatten(2, (H, P))
+        s["Bm"] = s["xbc"][:, :, H * P: H * P + G * S].unflatten(2, (G, S))
+        s["Cm"] = s["xbc"][:, :, H * P + G * S:].unflatten(2, (G, S))
+        sets.append(s)
+
+    def conv(s):
+        st.stree_tree_conv(s["parent"], s["xbc_pre"], s["conv_state"], conv_w, conv_b, H, P, S, G, silu=True,
+                           out=s["xbc"])
+
+    def ssd(s):
+        st.stree_tree_ssd(s["parent"], s["x"], s["dt"], A, s["Bm"], s["Cm"], D, s["h0"], out=s["y"])
+
+    def commit(s):
+        st.stree_commit_state(s["parent"], s["accepted"], s["x"], s["dt"], A, s["Bm"], s["h0"], h_out=s["h_out"],
+                              xbc_pre=s["xbc_pre"], conv_state=s["conv_state"], conv_state_out=s["cs_out"])
+
+    def step(s):
+        conv(s)
+        ssd(s)
+        commit(s)
+
+    for s in sets:           # first launches (also sets the kernel's LDS attribute) outside any capture
+        step(s)
+    torch.cuda.synchronize()
+
+    if args.only_ssd:
+        for k in range(args.only_ssd):
+            ssd(sets[k % N_SETS])
+        torch.cuda.synchronize()
+        return
+
+    def make_graphs(fn):
+        graphs = []
+        for s in sets:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                fn(s)
+            graphs.append(g)
+        torch.cuda.synchronize()
+        return [g.replay for g in graphs]
+
+    use_graph = not args.no_graph
+    if use_graph:
+        try:
+            run_step = make_graphs(step)
+            run_ssd = make_graphs(ssd)
+            run_conv = make_graphs(conv)
+            run_commit = make_graphs(commit)
+        except Exception as exc:  # pragma: no cover
+            log(f"[bench] HIP graph capture failed ({exc}); falling back to direct launches")
+            use_graph = False
+    if not use_graph:
+        run_step = [lambda s=s: step(s) for s in sets]
+        run_ssd = [lambda s=s: ssd(s) for s in sets]
+        run_conv = [lambda s=s: conv(s) for s in sets]
+        run_commit = [lambda s=s: commit(s) for s in sets]
+
+    def timed(runs, k, warm):
+        """Wall-clock and HIP-event time of k launches on the current stream."""
+        for i in range(warm):
+            runs[i % len(runs)]()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(k):
+            runs[i % len(runs)]()
+        e1.record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / k, e0.elapsed_time(e1) / k
+
+    K, Wm = args.steps, args.warmup
+    ms_step, ms_step_ev = timed(run_step, K, Wm)
+    # dominant kernel alone, same rotation (HBM-cold), HIP events on the launch stream
+    _, ms_ssd = timed(run_ssd, K, Wm)
+    _, ms_conv = timed(run_conv, K, Wm)
+    _, ms_commit = timed(run_commit, K, Wm)
+    _, ms_ssd_warm = timed(run_ssd[:1], K, Wm)   # one buffer set: inputs stay in the Infinity Cache
+
+    nodes = B * N
+    alg_bytes = algorithmic_bytes_tree_ssd(B, N, H, P, S, G)
+    alg_flops = algorithmic_flops_tree_ssd(B, N, H, P, S, G)
+    achieved = alg_bytes / (ms_ssd * 1e-3) / 1e9
+    log(f"[bench] step {ms_step*1e3:.1f} us wall ({ms_step_ev*1e3:.1f} us events)  graph={use_graph}")
+    log(f"[bench] tree_conv {ms_conv*1e3:.2f} us | tree_ssd {ms_ssd*1e3:.2f} us (warm {ms_ssd_warm*1e3:.2f} us) | "
+        f"commit {ms_commit*1e3:.2f} us")
+    log(f"[bench] tree_ssd: {alg_bytes/1e6:.2f} MB algorithmic -> {achieved:.0f} GB/s "
+        f"({achieved/HBM_PEAK_GBS*100:.1f}% of 8 TB/s); {alg_flops/ (ms_ssd*1e-3)/1e12:.1f} TFLOP/s bf16 MFMA "
+        f"(dense-masked count); scan-only {nodes/(ms_ssd*1e-3)/1e6:.1f} M nodes/s")
+
+    out = {
+        "metric": "tree-nodes/sec per SSD layer at 1 MI355X; % of MFMA/HBM roofline",
+        "value": nodes / (ms_step * 1e-3),
+        "unit": "tree-nodes/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg2: batch 16 x 64-node random trees (depth 4-8), 80 heads x headdim 64, "
+                               "dstate 128, ngroups 1, conv width 4; step = tree_conv + tree_ssd + commit_state",
+                   "batch": B, "nnodes": N, "hip_graph": use_graph, "buffer_sets": N_SETS},
+        "roofline": {"bound": "hbm", "kernel": "tree_ssd_mfma_kernel<64>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": read_traffic("tree_ssd_mfma_cfg2"),
+                     "algorithmic_bytes": alg_bytes, "avg_launch_us": ms_ssd * 1e3,
+                     "cache_warm_us": ms_ssd_warm * 1e3,
+                     "mfma_tflops": alg_flops / (ms_ssd * 1e-3) / 1e12},
+        "kernels_us": {"tree_conv": ms_conv * 1e3, "tree_ssd": ms_ssd * 1e3, "commit_state": ms_commit * 1e3},
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(wl):
+    """The oracle as it stands (fp64 C, OpenMP over batch x head), timed on the
+    host: full-size steps of the same workload, repeated to about 10-20 s."""
+    from oracle import ref
+    from paper_2505_14969_amd import synth
+    H, P, S, G = wl.nheads, wl.headdim, wl.dstate, wl.ngroups
+    f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    xbc_pre, cs, w, b, dt, A, D, h0 = map(f64, (wl.xbc_pre, wl.conv_state, wl.conv_w, wl.conv_b, wl.dt, wl.A, wl.D,
+                                                wl.h0))
+
+    def one():
+        conv = ref.tree_conv(wl.parent, xbc_pre, cs, w, b, True)
+        xbc = synth.round_to_bf16(conv.astype(np.float32)).astype(np.float64)
+        Bn, N, _ = xbc.shape
+        x = np.ascontiguousarray(xbc[:, :, : H * P].reshape(Bn, N, H, P))
+        Bm = np.ascontiguousarray(xbc[:, :, H * P: H * P + G * S].reshape(Bn, N, G, S))
+        Cm = np.ascontiguousarray(xbc[:, :, H * P + G * S:].reshape(Bn, N, G, S))
+        ref.ssd_paths(wl.parent, x, dt, A, Bm, Cm, D, h0)
+        ref.commit(wl.parent, wl.accepted, x, dt, A, Bm, h0, xbc_pre, cs)
+
+    one()
+    t0 = time.perf_counter()
+    reps = 0
+    while reps < 3 or (time.perf_counter() - t0 < 12.0 and reps < 200):
+        one()
+        reps += 1
+    dt_s = (time.perf_counter() - t0) / reps
+    return {"value": wl.batch * wl.nnodes / dt_s, "unit": "tree-nodes/s", "cores": ref.num_threads(),
+            "kind": "oracle", "sample": f"{reps} full-size steps of the same cfg2 batch (conv + path-unrolled "
+                                       f"fp64 scan + commit), {dt_s*1e3:.0f} ms each"}
+
+
+if __name__ == "__main__":
+    main()
