@@ -25,6 +25,12 @@ hipError_t launch_tree_ssd_mfma(const stree_dims &d, const int32_t *parent, cons
                                 const float *A, const void *Bm, const void *Cm, const float *D,
                                 const float *h0, void *y, int32_t *status, hipStream_t st);
 
+// single node block (n <= 64), persistent and software-pipelined
+bool tree_ssd_mfma64_supported(const stree_dims &d);
+hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
+                                  const float *A, const void *Bm, const void *Cm, const float *D,
+                                  const float *h0, void *y, int32_t *status, hipStream_t st);
+
 hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const int32_t *accepted,
                                const void *x, const float *dt, const float *A, const void *Bm,
                                const float *h0, float *h_out, const void *xbc_pre, const void *conv_state,

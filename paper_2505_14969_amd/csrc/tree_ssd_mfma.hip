@@ -21,6 +21,10 @@
 #include "common.hpp"
 #include "launch.hpp"
 
+#ifndef STREE_PHASE_CLOCK
+#define STREE_PHASE_CLOCK(k)
+#endif
+
 namespace stree {
 
 constexpr int kBlk = 64;         // node block
@@ -73,6 +77,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
     bf16_t *sM = reinterpret_cast<bf16_t *>(lds + pl.off_m);
     uint32_t *mask = reinterpret_cast<uint32_t *>(lds + pl.off_mask);
 
+    STREE_PHASE_CLOCK(0);
     // ---- initial state -> bf16 MFMA operand rows sH[p][s] -------------------------------
     if (h0) {
         const float *hb = h0 + ((size_t)b * H + h) * P * S;
@@ -84,11 +89,13 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
             *reinterpret_cast<bf16x4 *>(&sH[p * SP + s]) = o;
         }
     }
+    STREE_PHASE_CLOCK(1);
     // ---- tree index: depth, mask rows L_i, s_i = (A_tree)_i ---------------------------
     const float A_h = A[h];
     const float dt_i = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
     const int bad = build_tree_index(tree, mask, parent + (size_t)b * n, n, npad, words, dt_i, A_h);
     if (status && h == 0 && tid == 0) status[b] = bad;
+    STREE_PHASE_CLOCK(2);
     bf16_t *yb = y + (size_t)b * n * H * P + (size_t)h * P;
     if (bad) {
         for (int idx = tid; idx < n * (P / 8); idx += kThreads) {
@@ -112,6 +119,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
             *reinterpret_cast<uint4 *>(&sC[r * SP + c * 8]) = v;
         }
         __syncthreads();
+        STREE_PHASE_CLOCK(3);
 
         floatx16 acc[YQ];
 #pragma unroll
@@ -140,6 +148,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
             }
         }
 
+        STREE_PHASE_CLOCK(4);
         for (int j0 = 0; j0 <= i0; j0 += kBlk) {
             // ---- skip column blocks that hold no ancestor of this row block ------------
             if (j0 < i0) {
@@ -170,6 +179,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
                 }
             }
             __syncthreads();
+            STREE_PHASE_CLOCK(5);
 
             // ---- phase 2: Gt = B * C^T; mask and decay -> M[i][j] as bf16 ----------------
             {
@@ -206,6 +216,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
                 }
             }
             __syncthreads();
+            STREE_PHASE_CLOCK(6);
 
             // ---- phase 3: Yt += Xt * M^T ---------------------------------------------------
 #pragma unroll
@@ -225,6 +236,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
             }
             __syncthreads();
         }
+        STREE_PHASE_CLOCK(7);
 
         // ---- epilogue: stage fp32 Y rows (over the dead B tile), add D*x, store bf16 -----
 #pragma unroll
@@ -260,6 +272,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
         }
         // the next block's C load and its barrier separate these sY reads from the next B load
     }
+    STREE_PHASE_CLOCK(8);
 }
 
 bool tree_ssd_mfma_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm,
@@ -297,6 +310,8 @@ static hipError_t launch_p(const stree_dims &d, const int32_t *parent, const voi
 hipError_t launch_tree_ssd_mfma(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                 const float *A, const void *Bm, const void *Cm, const float *D,
                                 const float *h0, void *y, int32_t *status, hipStream_t st) {
+    if (tree_ssd_mfma64_supported(d))
+        return launch_tree_ssd_mfma64(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
     switch (d.headdim) {
         case 32: return launch_p<32>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
         case 64: return launch_p<64>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
