@@ -10,12 +10,11 @@
 // B / C rows that the heads of a group share.
 //
 // Per unit:   regs -> LDS (C, B, X^T, h0 as bf16), wave 0 builds the tree index
-//             barrier; issue next unit's loads
-//             phase 1  Yt = h0b C^T, *= exp(s_i)     phase 2  Gt = B C^T -> M (mask, decay) -> LDS
+//             barrier; issue next unit's loads; store the previous unit's y rows from LDS
+//             phases 1+2 in one sweep over the state index (shared C fragment):
+//                      Yt = h0b C^T, *= exp(s_i);  Gt = B C^T -> M (mask, decay) -> LDS
 //             barrier
-//             phase 3  Yt += Xt M^T ;  Yt -> LDS staging (over the dead B tile)
-//             barrier
-//             y = Yt + D x, coalesced bf16 stores
+//             phase 3  Yt += Xt M^T ;  y = Yt + D x -> bf16 rows in LDS
 //             barrier
 #include "common.hpp"
 #include "launch.hpp"
@@ -34,16 +33,15 @@ constexpr int kNP64 = kB64 + 8;
 template <int P, int S>
 struct Lds64 {
     static constexpr int SP = S + 8;
-    static constexpr int YP = P + 4;
+    static constexpr int YOP = P + 8;   // padded bf16 output row
     static constexpr size_t c_bytes = (size_t)kB64 * SP * 2;
-    static constexpr size_t y_bytes = (size_t)kB64 * YP * 4;
-    static constexpr size_t b_bytes = c_bytes > y_bytes ? c_bytes : y_bytes;
     static constexpr size_t off_c = 0;
     static constexpr size_t off_b = off_c + c_bytes;
-    static constexpr size_t off_h = off_b + b_bytes;
+    static constexpr size_t off_h = off_b + c_bytes;
     static constexpr size_t off_xt = off_h + (size_t)P * SP * 2;
     static constexpr size_t off_m = off_xt + (size_t)P * kNP64 * 2;
-    static constexpr size_t off_s = off_m + (size_t)kB64 * kNP64 * 2;   // float s[64]
+    static constexpr size_t off_yo = off_m + (size_t)kB64 * kNP64 * 2;
+    static constexpr size_t off_s = off_yo + (size_t)kB64 * YOP * 2;     // float s[64]
     static constexpr size_t off_dt = off_s + 256;                       // float dt[64]
     static constexpr size_t off_mask = off_dt + 256;                    // uint32 mask[64][2]
     static constexpr size_t off_bad = off_mask + 512;                   // int
@@ -93,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
     const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
     bf16_t *__restrict__ y, int32_t *__restrict__ status) {
     using L = Lds64<P, S>;
-    constexpr int SP = L::SP, YP = L::YP;
+    constexpr int SP = L::SP, YOP = L::YOP;
     constexpr int NC = kB64 * (S / 8) / kThreads;   // 16-byte chunks of C (and B) per thread
     constexpr int NX = kB64 * (P / 8) / kThreads;   // of x
     constexpr int NH = P * S / 4 / kThreads;        // float4 chunks of h0 per thread
@@ -102,7 +100,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
     extern __shared__ __align__(16) unsigned char lds[];
     bf16_t *sC = reinterpret_cast<bf16_t *>(lds + L::off_c);
     bf16_t *sB = reinterpret_cast<bf16_t *>(lds + L::off_b);
-    float *sY = reinterpret_cast<float *>(lds + L::off_b);
+    bf16_t *sYo = reinterpret_cast<bf16_t *>(lds + L::off_yo);
     bf16_t *sH = reinterpret_cast<bf16_t *>(lds + L::off_h);
     unsigned short *sXT = reinterpret_cast<unsigned short *>(lds + L::off_xt);
     bf16_t *sM = reinterpret_cast<bf16_t *>(lds + L::off_m);
@@ -170,6 +168,22 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
     bool have = decode(r, b, h);
     if (have) issue_loads(b, h);
 
+    // y rows of the previous unit wait in sYo and are stored while the next unit computes, so
+    // that no store is outstanding when the loop top waits for its loads (on gfx9 loads and
+    // stores share one counter and complete out of order with respect to each other)
+    bf16_t *y_pending = nullptr;
+    auto flush_y = [&]() {
+        if (y_pending) {
+#pragma unroll
+            for (int q = 0; q < NX; ++q) {
+                const int idx = tid + q * kThreads, rr = idx / (P / 8), c = idx % (P / 8);
+                if (rr < n)
+                    *reinterpret_cast<uint4 *>(y_pending + (size_t)rr * H * P + c * 8) =
+                        *reinterpret_cast<const uint4 *>(&sYo[rr * YOP + c * 8]);
+            }
+        }
+    };
+
     while (have) {
         [[maybe_unused]] const int prof_unit = b * H + h;  // only read by probe builds
         STREE_PHASE_CLOCK(0);
@@ -179,6 +193,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
             const int bad = wave_tree_index(lane, n, rpar, rdt, A_h, sS, sDt, sMask);
             if (lane == 0) *sBad = bad;
         }
+        STREE_PHASE_CLOCK(1);
 #pragma unroll
         for (int q = 0; q < NC; ++q) {
             const int idx = tid + q * kThreads, rr = idx / (S / 8), c = idx % (S / 8);
@@ -205,74 +220,71 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
                 *reinterpret_cast<bf16x4 *>(&sH[p * SP + s]) = o;
             }
         }
+        STREE_PHASE_CLOCK(2);
         __syncthreads();
-        STREE_PHASE_CLOCK(1);
+        STREE_PHASE_CLOCK(3);
 
-        // ---- next unit's loads go out now and fly during the compute below -------------------
+        // ---- next unit's loads go out now and fly during the compute below; so do the
+        //      previous unit's y rows ---------------------------------------------------------
         const int cb = b, ch = h;
         r += rstep;
         have = decode(r, b, h);
         if (have) issue_loads(b, h);
+        flush_y();
+        y_pending = y + (size_t)cb * n * H * P + (size_t)ch * P;
+        STREE_PHASE_CLOCK(4);
 
         const int bad = *sBad;
         if (status && ch == 0 && tid == 0) status[cb] = bad;
-        bf16_t *yb = y + (size_t)cb * n * H * P + (size_t)ch * P;
-        if (bad) {
-            for (int idx = tid; idx < n * (P / 8); idx += kThreads) {
-                const int rr = idx / (P / 8), c = idx % (P / 8);
-                *reinterpret_cast<uint4 *>(yb + (size_t)rr * H * P + c * 8) = make_uint4(0, 0, 0, 0);
-            }
-            __syncthreads();
-            continue;
-        }
 
         floatx16 acc[YQ];
 #pragma unroll
         for (int q = 0; q < YQ; ++q)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+        const int it = wave & 1;            // node half of every tile this wave owns
+        const int il = it * 32 + l32;       // this lane's node
 
-        // ---- phase 1: Yt = h0b * C^T, scaled by exp(s_i) ---------------------------------------
-        if (h0) {
-#pragma unroll
-            for (int q = 0; q < YQ; ++q) {
-                const int t = wave + 4 * q;
-                if (t < YT) {
-                    const int it = t & 1, pt = t >> 1;
-                    const bf16_t *ap = &sH[(pt * 32 + l32) * SP + 8 * lh];
-                    const bf16_t *bp = &sC[(it * 32 + l32) * SP + 8 * lh];
-#pragma unroll
-                    for (int k0 = 0; k0 < S; k0 += 16) {
-                        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ap + k0);
-                        const bf16x8 bb = *reinterpret_cast<const bf16x8 *>(bp + k0);
-                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[q], 0, 0, 0);
-                    }
-                    const float e = __expf(sS[it * 32 + l32]);
-#pragma unroll
-                    for (int rg = 0; rg < 16; ++rg) acc[q][rg] *= e;
-                }
-            }
-        }
-        STREE_PHASE_CLOCK(2);
-        // ---- phase 2: Gt = B * C^T; mask and decay -> M[i][j] as bf16 ---------------------------
-        {
-            const int it = wave & 1, jt = wave >> 1;
+        if (!bad) {
+            // ---- phases 1 and 2 in one sweep over the state index: the C fragment feeds both
+            //      Yt = h0b C^T and Gt = B C^T -----------------------------------------------------
+            const int jt = wave >> 1;
+            const bool gt_live = !(jt == 1 && it == 0);   // j > i everywhere in that tile
             floatx16 gt;
 #pragma unroll
             for (int e = 0; e < 16; ++e) gt[e] = 0.f;
-            if (!(jt == 1 && it == 0)) {  // j > i everywhere in that tile: stays zero
-                const bf16_t *ap = &sB[(jt * 32 + l32) * SP + 8 * lh];
-                const bf16_t *bp = &sC[(it * 32 + l32) * SP + 8 * lh];
+            const bf16_t *cp = &sC[il * SP + 8 * lh];
+            const bf16_t *bp = &sB[(jt * 32 + l32) * SP + 8 * lh];
 #pragma unroll
-                for (int k0 = 0; k0 < S; k0 += 16) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ap + k0);
-                    const bf16x8 bb = *reinterpret_cast<const bf16x8 *>(bp + k0);
-                    gt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, gt, 0, 0, 0);
+            for (int k0 = 0; k0 < S; k0 += 16) {
+                const bf16x8 cf = *reinterpret_cast<const bf16x8 *>(cp + k0);
+                if (h0) {
+#pragma unroll
+                    for (int q = 0; q < YQ; ++q) {
+                        const int t = wave + 4 * q;
+                        if (t < YT) {
+                            const bf16x8 hf = *reinterpret_cast<const bf16x8 *>(&sH[((t >> 1) * 32 + l32) * SP + 8 * lh + k0]);
+                            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf, cf, acc[q], 0, 0, 0);
+                        }
+                    }
+                }
+                if (gt_live) {
+                    const bf16x8 bf = *reinterpret_cast<const bf16x8 *>(bp + k0);
+                    gt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, cf, gt, 0, 0, 0);
                 }
             }
-            const int il = it * 32 + l32;
-            const uint32_t mrow = sMask[il * 2 + jt];
+            STREE_PHASE_CLOCK(5);
             const float s_i = sS[il];
+            if (h0) {
+                const float e = __expf(s_i);
+#pragma unroll
+                for (int q = 0; q < YQ; ++q)
+#pragma unroll
+                    for (int rg = 0; rg < 16; ++rg) acc[q][rg] *= e;
+            }
+            STREE_PHASE_CLOCK(6);
+            // ---- mask and decay: M[i][j] = L_ij ? Gt[j][i] exp(s_i - s_j) dt_j : 0 (select) -----
+            const uint32_t mrow = sMask[il * 2 + jt];
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 const int jl = jt * 32 + 8 * rg + 4 * lh;
@@ -290,54 +302,44 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
                 *reinterpret_cast<bf16x4 *>(&sM[il * kNP64 + jl]) = o;
             }
         }
+        STREE_PHASE_CLOCK(7);
         __syncthreads();
-        STREE_PHASE_CLOCK(3);
+        STREE_PHASE_CLOCK(8);
 
-        // ---- phase 3: Yt += Xt * M^T; stage fp32 rows over the dead B tile -----------------------
+        // ---- phase 3: Yt += Xt M^T; y = Yt + D x as bf16 into the output staging rows -----------
 #pragma unroll
         for (int q = 0; q < YQ; ++q) {
             const int t = wave + 4 * q;
             if (t < YT) {
-                const int it = t & 1, pt = t >> 1;
-                const bf16_t *ap = reinterpret_cast<const bf16_t *>(sXT) + (pt * 32 + l32) * kNP64 + 8 * lh;
-                const bf16_t *bp = &sM[(it * 32 + l32) * kNP64 + 8 * lh];
+                const int pt = t >> 1;
+                if (!bad) {
+                    const bf16_t *ap = reinterpret_cast<const bf16_t *>(sXT) + (pt * 32 + l32) * kNP64 + 8 * lh;
+                    const bf16_t *bp = &sM[il * kNP64 + 8 * lh];
 #pragma unroll
-                for (int k0 = 0; k0 < kB64; k0 += 16) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ap + k0);
-                    const bf16x8 bb = *reinterpret_cast<const bf16x8 *>(bp + k0);
-                    acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[q], 0, 0, 0);
+                    for (int k0 = 0; k0 < kB64; k0 += 16) {
+                        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ap + k0);
+                        const bf16x8 bb = *reinterpret_cast<const bf16x8 *>(bp + k0);
+                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[q], 0, 0, 0);
+                    }
                 }
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg) {
-                    const float4 v = make_float4(acc[q][4 * rg], acc[q][4 * rg + 1], acc[q][4 * rg + 2], acc[q][4 * rg + 3]);
-                    *reinterpret_cast<float4 *>(&sY[(it * 32 + l32) * YP + pt * 32 + 8 * rg + 4 * lh]) = v;
+                    const int p0 = pt * 32 + 8 * rg + 4 * lh;
+                    bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float xv = __uint_as_float((uint32_t)sXT[(p0 + e) * kNP64 + il] << 16);
+                        o[e] = bad ? (bf16_t)0.f : (bf16_t)fmaf(D_h, xv, acc[q][4 * rg + e]);
+                    }
+                    *reinterpret_cast<bf16x4 *>(&sYo[il * YOP + p0]) = o;
                 }
             }
         }
+        STREE_PHASE_CLOCK(9);
         __syncthreads();
-        STREE_PHASE_CLOCK(4);
-
-        // ---- epilogue: y = Yt + D x (x from the transposed tile), 16-byte bf16 stores -----------
-#pragma unroll
-        for (int q = 0; q < NX; ++q) {
-            const int idx = tid + q * kThreads, rr = idx / (P / 8), c = idx % (P / 8);
-            if (rr < n) {
-                const float4 a0 = *reinterpret_cast<const float4 *>(&sY[rr * YP + c * 8]);
-                const float4 a1 = *reinterpret_cast<const float4 *>(&sY[rr * YP + c * 8 + 4]);
-                const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-                const unsigned short *xs = sXT + (c * 8) * kNP64 + rr;
-                bf16x8 o;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float xv = __uint_as_float((uint32_t)xs[e * kNP64] << 16);
-                    o[e] = (bf16_t)fmaf(D_h, xv, av[e]);
-                }
-                *reinterpret_cast<bf16x8 *>(yb + (size_t)rr * H * P + c * 8) = o;
-            }
-        }
-        __syncthreads();
-        STREE_PHASE_CLOCK(5);
+        STREE_PHASE_CLOCK(10);
     }
+    flush_y();
 }
 
 template <int P, int S>
