@@ -11,16 +11,19 @@
 //
 // Per unit:   regs -> LDS (C, B, X^T, h0 as bf16), wave 0 builds the tree index
 //             barrier; issue next unit's loads; store the previous unit's y rows from LDS
-//             phases 1+2 in one sweep over the state index (shared C fragment):
-//                      Yt = h0b C^T, *= exp(s_i);  Gt = B C^T -> M (mask, decay) -> LDS
+//             waves 0-3: phase 1  Yt = h0b C^T, *= exp(s_i)
+//             waves 4-7: phase 2  Gt = B C^T -> M (mask, decay) -> LDS      (concurrently)
 //             barrier
-//             phase 3  Yt += Xt M^T ;  y = Yt + D x -> bf16 rows in LDS
+//             waves 0-3: phase 3  Yt += Xt M^T ;  y = Yt + D x -> bf16 rows in LDS
 //             barrier
 #include "common.hpp"
 #include "launch.hpp"
 
 #ifndef STREE_PHASE_CLOCK
 #define STREE_PHASE_CLOCK(k)
+#endif
+#ifndef STREE_PHASE_CLOCK_G
+#define STREE_PHASE_CLOCK_G(k)
 #endif
 
 namespace stree {
@@ -29,6 +32,7 @@ namespace {
 
 constexpr int kB64 = 64;
 constexpr int kNP64 = kB64 + 8;
+constexpr int kT64 = 512;   // 8 waves: 4 own Yt tiles, 3 own Gt tiles, 1 builds the tree index
 
 template <int P, int S>
 struct Lds64 {
@@ -84,19 +88,20 @@ __device__ __forceinline__ int wave_tree_index(int lane, int n, int parent_i, fl
     return 0;
 }
 
-template <int P, int S>
-__global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
+// WPE = waves per SIMD the register budget is sized for: 4 when two workgroups fit a CU's LDS
+template <int P, int S, int WPE>
+__global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void tree_ssd_mfma64_kernel(
     const int32_t *__restrict__ parent, int n, int nbatch, int H, int G, const bf16_t *__restrict__ x, long x_sn,
     const float *__restrict__ dt, const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn,
     const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
     bf16_t *__restrict__ y, int32_t *__restrict__ status) {
     using L = Lds64<P, S>;
     constexpr int SP = L::SP, YOP = L::YOP;
-    constexpr int NC = kB64 * (S / 8) / kThreads;   // 16-byte chunks of C (and B) per thread
-    constexpr int NX = kB64 * (P / 8) / kThreads;   // of x
-    constexpr int NH = P * S / 4 / kThreads;        // float4 chunks of h0 per thread
-    constexpr int YT = (P / 32) * 2, YQ = (YT + 3) / 4;
-    static_assert(NC >= 1 && NX >= 1 && NH >= 1, "tile too small for 256 threads");
+    constexpr int NC = kB64 * (S / 8) / kT64;   // 16-byte chunks of C (and B) per thread
+    constexpr int NX = kB64 * (P / 8) / kT64;   // of x
+    constexpr int NH = P * S / 4 / kT64;        // float4 chunks of h0 per thread
+    constexpr int YT = (P / 32) * 2, YQ = YT / 4;   // Yt tiles, tiles per Y wave
+    static_assert(NC >= 1 && NX >= 1 && NH >= 1 && YQ >= 1, "tile too small for 512 threads");
     extern __shared__ __align__(16) unsigned char lds[];
     bf16_t *sC = reinterpret_cast<bf16_t *>(lds + L::off_c);
     bf16_t *sB = reinterpret_cast<bf16_t *>(lds + L::off_b);
@@ -109,7 +114,13 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
     uint32_t *sMask = reinterpret_cast<uint32_t *>(lds + L::off_mask);
     int *sBad = reinterpret_cast<int *>(lds + L::off_bad);
 
+    // Waves 0-3 own the Yt tiles (phases 1 and 3), waves 4-7 the Gt tiles (phase 2).  The
+    // Gt tile of wave 6 is (j >= 32, i < 32): all zero since j > i, so wave 6 builds the
+    // tree index instead and its lanes carry parent[] and dt[].
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
+    constexpr int kTreeWave = 6;
+    const int it = wave & 1;             // node half of the tiles this wave owns
+    const int il = it * 32 + l32;        // this lane's node in accumulators
     const int n_units = nbatch * H;
     const int per_xcd = (n_units + 7) >> 3;
     const int xcd = blockIdx.x & 7;
@@ -130,37 +141,45 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
     int rpar = -1;
     float rdt = 0.f, rA = 0.f, rD = 0.f;
 
+    // per-thread offsets of the 16-byte chunks never change from unit to unit: one 32-bit
+    // offset per tensor, the unit's base pointer and the per-chunk row step are uniform.
+    // Rows >= n are read from row n-1 (valid memory) and zeroed afterwards: no branches.
+    constexpr int kRowsC = kT64 / (S / 8), kRowsX = kT64 / (P / 8);
+    const int rc0 = tid / (S / 8), cc0 = tid % (S / 8), rx0 = tid / (P / 8), cx0 = tid % (P / 8);
+    uint32_t offC[NC], offB[NC], offX[NX];
+#pragma unroll
+    for (int q = 0; q < NC; ++q) {
+        const int rr = min(rc0 + q * kRowsC, n - 1);
+        offC[q] = (uint32_t)(rr * (int)c_sn + cc0 * 8) * 2u;
+        offB[q] = (uint32_t)(rr * (int)b_sn + cc0 * 8) * 2u;
+    }
+#pragma unroll
+    for (int q = 0; q < NX; ++q) offX[q] = (uint32_t)(min(rx0 + q * kRowsX, n - 1) * (int)x_sn + cx0 * 8) * 2u;
+
     auto issue_loads = [&](int b, int h) {
         const int g = h / hpg;
-        const bf16_t *Cb = Cm + (size_t)b * n * c_sn + (size_t)g * S;
-        const bf16_t *Bb = Bm + (size_t)b * n * b_sn + (size_t)g * S;
-        const bf16_t *xb = x + (size_t)b * n * x_sn + (size_t)h * P;
-        if (tid < n) {
-            rpar = parent[(size_t)b * n + tid];
-            rdt = dt[((size_t)b * n + tid) * H + h];
+        const char *Cb = reinterpret_cast<const char *>(Cm + (size_t)b * n * c_sn + (size_t)g * S);
+        const char *Bb = reinterpret_cast<const char *>(Bm + (size_t)b * n * b_sn + (size_t)g * S);
+        const char *xb = reinterpret_cast<const char *>(x + (size_t)b * n * x_sn + (size_t)h * P);
+        if (wave == kTreeWave) {
+            const int node = min(lane, n - 1);
+            rpar = parent[(size_t)b * n + node];
+            rdt = dt[((size_t)b * n + node) * H + h];
         }
         rA = A[h];
         rD = D ? D[h] : 0.f;
 #pragma unroll
         for (int q = 0; q < NC; ++q) {
-            const int idx = tid + q * kThreads, r = idx / (S / 8), c = idx % (S / 8);
-            rC[q] = make_uint4(0, 0, 0, 0);
-            rB[q] = make_uint4(0, 0, 0, 0);
-            if (r < n) {
-                rC[q] = *reinterpret_cast<const uint4 *>(Cb + (size_t)r * c_sn + c * 8);
-                rB[q] = *reinterpret_cast<const uint4 *>(Bb + (size_t)r * b_sn + c * 8);
-            }
+            rC[q] = *reinterpret_cast<const uint4 *>(Cb + offC[q]);
+            rB[q] = *reinterpret_cast<const uint4 *>(Bb + offB[q]);
         }
 #pragma unroll
-        for (int q = 0; q < NX; ++q) {
-            const int idx = tid + q * kThreads, r = idx / (P / 8), c = idx % (P / 8);
-            rX[q] = make_uint4(0, 0, 0, 0);
-            if (r < n) rX[q] = *reinterpret_cast<const uint4 *>(xb + (size_t)r * x_sn + c * 8);
-        }
+        for (int q = 0; q < NX; ++q) rX[q] = *reinterpret_cast<const uint4 *>(xb + offX[q]);
         if (h0) {
-            const float *hb = h0 + ((size_t)b * H + h) * P * S;
+            const char *hb = reinterpret_cast<const char *>(h0 + ((size_t)b * H + h) * P * S);
 #pragma unroll
-            for (int q = 0; q < NH; ++q) rH[q] = *reinterpret_cast<const float4 *>(hb + (size_t)(tid + q * kThreads) * 4);
+            for (int q = 0; q < NH; ++q)
+                rH[q] = *reinterpret_cast<const float4 *>(hb + (uint32_t)(tid + q * kT64) * 16u);
         }
     };
 
@@ -176,7 +195,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
         if (y_pending) {
 #pragma unroll
             for (int q = 0; q < NX; ++q) {
-                const int idx = tid + q * kThreads, rr = idx / (P / 8), c = idx % (P / 8);
+                const int idx = tid + q * kT64, rr = idx / (P / 8), c = idx % (P / 8);
                 if (rr < n)
                     *reinterpret_cast<uint4 *>(y_pending + (size_t)rr * H * P + c * 8) =
                         *reinterpret_cast<const uint4 *>(&sYo[rr * YOP + c * 8]);
@@ -188,22 +207,26 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
         [[maybe_unused]] const int prof_unit = b * H + h;  // only read by probe builds
         STREE_PHASE_CLOCK(0);
         const float A_h = rA, D_h = rD;
-        // ---- registers -> LDS -----------------------------------------------------------------
-        if (wave == 0) {
+        // ---- registers -> LDS; the tree wave builds the index first ------------------------------
+        if (wave == kTreeWave) {
             const int bad = wave_tree_index(lane, n, rpar, rdt, A_h, sS, sDt, sMask);
             if (lane == 0) *sBad = bad;
         }
         STREE_PHASE_CLOCK(1);
 #pragma unroll
         for (int q = 0; q < NC; ++q) {
-            const int idx = tid + q * kThreads, rr = idx / (S / 8), c = idx % (S / 8);
-            *reinterpret_cast<uint4 *>(&sC[rr * SP + c * 8]) = rC[q];
-            *reinterpret_cast<uint4 *>(&sB[rr * SP + c * 8]) = rB[q];
+            const int rr = rc0 + q * kRowsC;
+            const uint32_t keep = rr < n ? 0xffffffffu : 0u;   // zero the rows beyond the tree
+            *reinterpret_cast<uint4 *>(&sC[rr * SP + cc0 * 8]) =
+                make_uint4(rC[q].x & keep, rC[q].y & keep, rC[q].z & keep, rC[q].w & keep);
+            *reinterpret_cast<uint4 *>(&sB[rr * SP + cc0 * 8]) =
+                make_uint4(rB[q].x & keep, rB[q].y & keep, rB[q].z & keep, rB[q].w & keep);
         }
 #pragma unroll
         for (int q = 0; q < NX; ++q) {
-            const int idx = tid + q * kThreads, rr = idx / (P / 8), c = idx % (P / 8);
-            const uint32_t wv[4] = {rX[q].x, rX[q].y, rX[q].z, rX[q].w};
+            const int rr = rx0 + q * kRowsX, c = cx0;
+            const uint32_t keep = rr < n ? 0xffffffffu : 0u;
+            const uint32_t wv[4] = {rX[q].x & keep, rX[q].y & keep, rX[q].z & keep, rX[q].w & keep};
             unsigned short *dst = sXT + (c * 8) * kNP64 + rr;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -214,7 +237,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
         if (h0) {
 #pragma unroll
             for (int q = 0; q < NH; ++q) {
-                const int e = (tid + q * kThreads) * 4, p = e / S, s = e % S;
+                const int e = (tid + q * kT64) * 4, p = e / S, s = e % S;
                 bf16x4 o;
                 o[0] = (bf16_t)rH[q].x; o[1] = (bf16_t)rH[q].y; o[2] = (bf16_t)rH[q].z; o[3] = (bf16_t)rH[q].w;
                 *reinterpret_cast<bf16x4 *>(&sH[p * SP + s]) = o;
@@ -242,81 +265,95 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
         for (int q = 0; q < YQ; ++q)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
-        const int it = wave & 1;            // node half of every tile this wave owns
-        const int il = it * 32 + l32;       // this lane's node
 
         if (!bad) {
-            // ---- phases 1 and 2 in one sweep over the state index: the C fragment feeds both
-            //      Yt = h0b C^T and Gt = B C^T -----------------------------------------------------
-            const int jt = wave >> 1;
-            const bool gt_live = !(jt == 1 && it == 0);   // j > i everywhere in that tile
-            floatx16 gt;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) gt[e] = 0.f;
             const bf16_t *cp = &sC[il * SP + 8 * lh];
-            const bf16_t *bp = &sB[(jt * 32 + l32) * SP + 8 * lh];
-#pragma unroll
-            for (int k0 = 0; k0 < S; k0 += 16) {
-                const bf16x8 cf = *reinterpret_cast<const bf16x8 *>(cp + k0);
+            if (wave < 4) {
+                // ---- phase 1 (Y waves): Yt = h0b C^T, then *= exp(s_i) ----------------------------
                 if (h0) {
+                    // fragments of half the state index are read in one batch, then consumed
 #pragma unroll
-                    for (int q = 0; q < YQ; ++q) {
-                        const int t = wave + 4 * q;
-                        if (t < YT) {
-                            const bf16x8 hf = *reinterpret_cast<const bf16x8 *>(&sH[((t >> 1) * 32 + l32) * SP + 8 * lh + k0]);
-                            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf, cf, acc[q], 0, 0, 0);
+                    for (int kb = 0; kb < S; kb += S / 2) {
+                        bf16x8 cf[S / 32], hf[YQ][S / 32];
+#pragma unroll
+                        for (int j = 0; j < S / 32; ++j) {
+                            cf[j] = *reinterpret_cast<const bf16x8 *>(cp + kb + 16 * j);
+#pragma unroll
+                            for (int q = 0; q < YQ; ++q)
+                                hf[q][j] = *reinterpret_cast<const bf16x8 *>(
+                                    &sH[(((wave + 4 * q) >> 1) * 32 + l32) * SP + 8 * lh + kb + 16 * j]);
                         }
+#pragma unroll
+                        for (int j = 0; j < S / 32; ++j)
+#pragma unroll
+                            for (int q = 0; q < YQ; ++q)
+                                acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf[q][j], cf[j], acc[q], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);   // keep the two batches apart: register budget
                     }
+                    const float e = __expf(sS[il]);
+#pragma unroll
+                    for (int q = 0; q < YQ; ++q)
+#pragma unroll
+                        for (int rg = 0; rg < 16; ++rg) acc[q][rg] *= e;
                 }
-                if (gt_live) {
-                    const bf16x8 bf = *reinterpret_cast<const bf16x8 *>(bp + k0);
-                    gt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, cf, gt, 0, 0, 0);
+            } else if (wave != kTreeWave) {
+                // ---- phase 2 (G waves): Gt = B C^T, mask and decay -> M[i][j] as bf16 --------------
+                const int jt = (wave - 4) >> 1;
+                STREE_PHASE_CLOCK_G(9);
+                floatx16 gt;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) gt[e] = 0.f;
+                const bf16_t *bp = &sB[(jt * 32 + l32) * SP + 8 * lh];
+#pragma unroll
+                for (int kb = 0; kb < S; kb += S / 2) {
+                    bf16x8 cf[S / 32], bf[S / 32];
+#pragma unroll
+                    for (int j = 0; j < S / 32; ++j) {
+                        cf[j] = *reinterpret_cast<const bf16x8 *>(cp + kb + 16 * j);
+                        bf[j] = *reinterpret_cast<const bf16x8 *>(bp + kb + 16 * j);
+                    }
+#pragma unroll
+                    for (int j = 0; j < S / 32; ++j)
+                        gt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], cf[j], gt, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-            }
-            STREE_PHASE_CLOCK(5);
-            const float s_i = sS[il];
-            if (h0) {
-                const float e = __expf(s_i);
+                STREE_PHASE_CLOCK_G(10);
+                const float s_i = sS[il];
+                const uint32_t mrow = sMask[il * 2 + jt] >> (4 * lh);   // bit 8*rg + e <-> j = jl + e
 #pragma unroll
-                for (int q = 0; q < YQ; ++q)
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int jl = jt * 32 + 8 * rg + 4 * lh;
+                    const float4 sj = *reinterpret_cast<const float4 *>(&sS[jl]);
+                    const float4 dj = *reinterpret_cast<const float4 *>(&sDt[jl]);
+                    const float sjv[4] = {sj.x, sj.y, sj.z, sj.w};
+                    const float djv[4] = {dj.x, dj.y, dj.z, dj.w};
+                    bf16x4 o;
 #pragma unroll
-                    for (int rg = 0; rg < 16; ++rg) acc[q][rg] *= e;
-            }
-            STREE_PHASE_CLOCK(6);
-            // ---- mask and decay: M[i][j] = L_ij ? Gt[j][i] exp(s_i - s_j) dt_j : 0 (select) -----
-            const uint32_t mrow = sMask[il * 2 + jt];
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                const int jl = jt * 32 + 8 * rg + 4 * lh;
-                const float4 sj = *reinterpret_cast<const float4 *>(&sS[jl]);
-                const float4 dj = *reinterpret_cast<const float4 *>(&sDt[jl]);
-                const float sjv[4] = {sj.x, sj.y, sj.z, sj.w};
-                const float djv[4] = {dj.x, dj.y, dj.z, dj.w};
-                bf16x4 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const bool on = (mrow >> (8 * rg + 4 * lh + e)) & 1u;
-                    const float v = on ? gt[4 * rg + e] * __expf(s_i - sjv[e]) * djv[e] : 0.f;
-                    o[e] = (bf16_t)v;
+                    for (int e = 0; e < 4; ++e) {
+                        const bool on = (mrow >> (8 * rg + e)) & 1u;
+                        const float v = on ? gt[4 * rg + e] * __expf(s_i - sjv[e]) * djv[e] : 0.f;
+                        o[e] = (bf16_t)v;
+                    }
+                    *reinterpret_cast<bf16x4 *>(&sM[il * kNP64 + jl]) = o;
                 }
-                *reinterpret_cast<bf16x4 *>(&sM[il * kNP64 + jl]) = o;
+                STREE_PHASE_CLOCK_G(11);
             }
         }
-        STREE_PHASE_CLOCK(7);
+        STREE_PHASE_CLOCK(5);
         __syncthreads();
-        STREE_PHASE_CLOCK(8);
+        STREE_PHASE_CLOCK(6);
 
-        // ---- phase 3: Yt += Xt M^T; y = Yt + D x as bf16 into the output staging rows -----------
+        // ---- phase 3 (Y waves): Yt += Xt M^T over j <= i only (nodes i < 32 have no ancestor
+        //      j >= 32, that quadrant of M is never written or read); y = Yt + D x -> bf16 rows ---
+        if (wave < 4) {
 #pragma unroll
-        for (int q = 0; q < YQ; ++q) {
-            const int t = wave + 4 * q;
-            if (t < YT) {
-                const int pt = t >> 1;
+            for (int q = 0; q < YQ; ++q) {
+                const int pt = (wave + 4 * q) >> 1;
                 if (!bad) {
                     const bf16_t *ap = reinterpret_cast<const bf16_t *>(sXT) + (pt * 32 + l32) * kNP64 + 8 * lh;
                     const bf16_t *bp = &sM[il * kNP64 + 8 * lh];
-#pragma unroll
-                    for (int k0 = 0; k0 < kB64; k0 += 16) {
+                    const int kend = it ? kB64 : 32;
+                    for (int k0 = 0; k0 < kend; k0 += 16) {
                         const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ap + k0);
                         const bf16x8 bb = *reinterpret_cast<const bf16x8 *>(bp + k0);
                         acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[q], 0, 0, 0);
@@ -335,9 +372,9 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma64_kernel(
                 }
             }
         }
-        STREE_PHASE_CLOCK(9);
+        STREE_PHASE_CLOCK(7);
         __syncthreads();
-        STREE_PHASE_CLOCK(10);
+        STREE_PHASE_CLOCK(8);
     }
     flush_y();
 }
@@ -347,9 +384,10 @@ hipError_t launch64_ps(const stree_dims &d, const int32_t *parent, const void *x
                        const void *Bm, const void *Cm, const float *D, const float *h0, void *y,
                        int32_t *status, hipStream_t st) {
     constexpr size_t lds = Lds64<P, S>::total;
+    constexpr int WPE = (2 * (lds + 64) <= 160 * 1024) ? 4 : 2;
     static bool attr_set = false;  // dynamic LDS above 64 KB needs the attribute once
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_mfma64_kernel<P, S>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_mfma64_kernel<P, S, WPE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -359,7 +397,7 @@ hipError_t launch64_ps(const stree_dims &d, const int32_t *parent, const void *x
     int grid = (n_units + 7) / 8 * 8;
     const int cap = 256 * (per_cu < 1 ? 1 : per_cu);
     if (grid > cap) grid = cap;
-    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S>), dim3(grid), dim3(kThreads), lds, st, parent, d.nnodes,
+    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE>), dim3(grid), dim3(kT64), lds, st, parent, d.nnodes,
                        d.batch, d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A,
                        (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,
                        (bf16_t *)y, status);
@@ -371,7 +409,7 @@ hipError_t launch64_ps(const stree_dims &d, const int32_t *parent, const void *x
 bool tree_ssd_mfma64_supported(const stree_dims &d) {
     if (d.nnodes > kB64) return false;
     const int P = d.headdim, S = d.dstate;
-    return (P == 64 && (S == 128 || S == 64)) || (P == 128 && S == 128) || (P == 32 && S == 128);
+    return (P == 64 && (S == 128 || S == 64)) || (P == 128 && S == 128);
 }
 
 hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
@@ -381,7 +419,6 @@ hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, co
     if (P == 64 && S == 128) return launch64_ps<64, 128>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
     if (P == 64 && S == 64) return launch64_ps<64, 64>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
     if (P == 128 && S == 128) return launch64_ps<128, 128>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
-    if (P == 32 && S == 128) return launch64_ps<32, 128>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
     return hipErrorInvalidValue;
 }
 
