@@ -1,21 +1,31 @@
 // Tree scan for trees of at most 64 nodes (one node block), the shape of a
-// speculative-decoding step: persistent, software-pipelined variant of the MFMA
-// kernel in tree_ssd_mfma.hip (same products, same accumulator layouts).
+// speculative-decoding step: persistent, software-pipelined, wave-specialised
+// variant of the MFMA kernel in tree_ssd_mfma.hip (same products, same
+// accumulator layouts).
 //
-// A workgroup walks a list of (batch, head) units.  While it computes unit u
-// from LDS, the global loads of its next unit (h0 32 KB, x, B, C, parent, dt)
-// are already in flight into registers, so HBM latency is paid once per
-// workgroup, not once per unit.  Units are dealt out so that all heads of one
-// sequence land on the same XCD (workgroup id % 8), whose L2 then serves the
-// B / C rows that the heads of a group share.
+// A workgroup of 8 waves walks a list of (batch, head) units.  Units are dealt
+// out so that all heads of one sequence land on the same XCD (workgroup id % 8),
+// whose L2 then serves the B / C rows that the heads of a group share.
 //
-// Per unit:   regs -> LDS (C, B, X^T, h0 as bf16), wave 0 builds the tree index
-//             barrier; issue next unit's loads; store the previous unit's y rows from LDS
-//             waves 0-3: phase 1  Yt = h0b C^T, *= exp(s_i)
-//             waves 4-7: phase 2  Gt = B C^T -> M (mask, decay) -> LDS      (concurrently)
-//             barrier
-//             waves 0-3: phase 3  Yt += Xt M^T ;  y = Yt + D x -> bf16 rows in LDS
-//             barrier
+//   Y waves 0-3   own the four 32x32 tiles of Yt[p][i]; carry the h0 prefetch
+//   G waves 4,5,7 own the three live tiles of Gt[j][i]; carry the C, B, x prefetch
+//   T wave  6     (its Gt tile has j > i everywhere) builds the tree index
+//
+// Steady state for unit k, with the registers already holding unit k+1:
+//   barrier 1
+//     Y: store y(k-1) from LDS; phase 1  Yt = h0b C^T, *= exp(s_i)
+//     G: phase 2  Gt = B C^T, M = L ? Gt exp(s_i - s_j) dt_j : 0 -> LDS (bf16)
+//   barrier 2   (C, B, h0b tiles and the tree arrays are dead from here on)
+//     Y: phase 3  Yt += Xt M^T; y = Yt + D x -> bf16 rows in LDS;
+//        then h0(k+1) regs -> LDS as bf16, issue h0(k+2) loads
+//     G: C, B (k+1) regs -> LDS, issue C, B (k+2) loads
+//     T: tree index of unit k+1, issue parent/dt (k+2) loads
+//   barrier 3   (X^T tile is dead)
+//     G: x(k+1) regs -> LDS transposed, issue x(k+2) loads
+// so global loads are in flight for a whole unit period and HBM latency is paid
+// once per workgroup.  y rows are stored one unit late, from LDS, so that no
+// store is outstanding when a wave waits for its loads (on gfx9 loads and stores
+// share one counter and complete out of order with respect to each other).
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -32,7 +42,7 @@ namespace {
 
 constexpr int kB64 = 64;
 constexpr int kNP64 = kB64 + 8;
-constexpr int kT64 = 512;   // 8 waves: 4 own Yt tiles, 3 own Gt tiles, 1 builds the tree index
+constexpr int kT64 = 512;   // 8 waves: 4 Y waves, 3 G waves, 1 tree wave
 
 template <int P, int S>
 struct Lds64 {
@@ -46,7 +56,7 @@ struct Lds64 {
     static constexpr size_t off_m = off_xt + (size_t)P * kNP64 * 2;
     static constexpr size_t off_yo = off_m + (size_t)kB64 * kNP64 * 2;
     static constexpr size_t off_s = off_yo + (size_t)kB64 * YOP * 2;     // float s[64]
-    static constexpr size_t off_dt = off_s + 256;                       // float dt[64]
+    static constexpr size_t off_dt = off_s + 256;                       // float u[64]
     static constexpr size_t off_mask = off_dt + 256;                    // uint32 mask[64][2]
     static constexpr size_t off_bad = off_mask + 512;                   // int
     static constexpr size_t total = off_bad + 16;
@@ -54,8 +64,11 @@ struct Lds64 {
 
 // Wave-level tree index for n <= 64: lane i owns node i; pointer doubling with
 // cross-lane reads (ds_bpermute), no barriers.  Returns the status (uniform).
-__device__ __forceinline__ int wave_tree_index(int lane, int n, int parent_i, float dt_i, float A_h, float *s_out,
-                                               float *dt_out, uint32_t *mask_out) {
+// Outputs are in log2 units so that the decay is one v_exp_f32 per element:
+//   s2[i] = log2(e) * s_i          u[j] = s2[j] - log2(dt_j)
+//   exp(s_i - s_j) * dt_j = exp2(s2[i] - u[j])      (dt_j = 0 -> u = +inf -> 0)
+__device__ __forceinline__ int wave_tree_index(int lane, int n, int parent_i, float dt_i, float A_h, float *s2_out,
+                                               float *u_out, uint32_t *mask_out) {
     int p = -1;
     bool ok = true;
     if (lane < n) {
@@ -81,8 +94,9 @@ __device__ __forceinline__ int wave_tree_index(int lane, int n, int parent_i, fl
             p = rp;
         }
     }
-    s_out[lane] = s;
-    dt_out[lane] = lane < n ? dt_i : 0.f;
+    const float s2 = s * 1.44269504088896340736f;
+    s2_out[lane] = s2;
+    u_out[lane] = s2 - __log2f(lane < n ? dt_i : 0.f);
     mask_out[lane * 2] = mlo;
     mask_out[lane * 2 + 1] = mhi;
     return 0;
@@ -97,11 +111,13 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     bf16_t *__restrict__ y, int32_t *__restrict__ status) {
     using L = Lds64<P, S>;
     constexpr int SP = L::SP, YOP = L::YOP;
-    constexpr int NC = kB64 * (S / 8) / kT64;   // 16-byte chunks of C (and B) per thread
-    constexpr int NX = kB64 * (P / 8) / kT64;   // of x
-    constexpr int NH = P * S / 4 / kT64;        // float4 chunks of h0 per thread
+    constexpr int kHalf = kT64 / 2;                 // threads per role group
+    constexpr int NC = kB64 * (S / 8) / kHalf;      // 16-byte chunks of C (and of B) per G thread
+    constexpr int NX = kB64 * (P / 8) / kHalf;      // of x per G thread; of y per Y thread
+    constexpr int NH = P * S / 4 / kHalf;           // float4 chunks of h0 per Y thread
     constexpr int YT = (P / 32) * 2, YQ = YT / 4;   // Yt tiles, tiles per Y wave
-    static_assert(NC >= 1 && NX >= 1 && NH >= 1 && YQ >= 1, "tile too small for 512 threads");
+    constexpr int kRowsC = kHalf / (S / 8), kRowsX = kHalf / (P / 8);
+    static_assert(NC >= 1 && NX >= 1 && NH >= 1 && YQ >= 1, "tile too small for this thread count");
     extern __shared__ __align__(16) unsigned char lds[];
     bf16_t *sC = reinterpret_cast<bf16_t *>(lds + L::off_c);
     bf16_t *sB = reinterpret_cast<bf16_t *>(lds + L::off_b);
@@ -109,154 +125,177 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     bf16_t *sH = reinterpret_cast<bf16_t *>(lds + L::off_h);
     unsigned short *sXT = reinterpret_cast<unsigned short *>(lds + L::off_xt);
     bf16_t *sM = reinterpret_cast<bf16_t *>(lds + L::off_m);
-    float *sS = reinterpret_cast<float *>(lds + L::off_s);
-    float *sDt = reinterpret_cast<float *>(lds + L::off_dt);
+    float *sS2 = reinterpret_cast<float *>(lds + L::off_s);
+    float *sU = reinterpret_cast<float *>(lds + L::off_dt);
     uint32_t *sMask = reinterpret_cast<uint32_t *>(lds + L::off_mask);
     int *sBad = reinterpret_cast<int *>(lds + L::off_bad);
 
-    // Waves 0-3 own the Yt tiles (phases 1 and 3), waves 4-7 the Gt tiles (phase 2).  The
-    // Gt tile of wave 6 is (j >= 32, i < 32): all zero since j > i, so wave 6 builds the
-    // tree index instead and its lanes carry parent[] and dt[].
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
     constexpr int kTreeWave = 6;
+    const bool isY = wave < 4;
+    const int rt = tid & (kHalf - 1);    // thread index within its role group
     const int it = wave & 1;             // node half of the tiles this wave owns
     const int il = it * 32 + l32;        // this lane's node in accumulators
     const int n_units = nbatch * H;
     const int per_xcd = (n_units + 7) >> 3;
     const int xcd = blockIdx.x & 7;
-    const int rstep = gridDim.x >> 3;
+    const int r0 = blockIdx.x >> 3, rstep = gridDim.x >> 3;
     const int hpg = H / G;
-
-    // unit r of this XCD -> (b, h); false when past the end
-    auto decode = [&](int r, int &b, int &h) -> bool {
-        const int logical = xcd * per_xcd + r;
-        if (r >= per_xcd || logical >= n_units) return false;
+    // this workgroup's units: k-th is number r0 + k*rstep of its XCD's contiguous range
+    const int r_end = min(per_xcd, n_units - xcd * per_xcd);
+    const int nU = r0 < r_end ? (r_end - r0 + rstep - 1) / rstep : 0;
+    auto unit = [&](int k, int &b, int &h) {
+        const int logical = xcd * per_xcd + r0 + k * rstep;
         b = logical / H;
         h = logical - b * H;
-        return true;
     };
 
-    uint4 rC[NC], rB[NC], rX[NX];
-    float4 rH[NH];
+    // ---- prefetch registers and their loaders ---------------------------------------------------
+    // per-thread chunk offsets never change from unit to unit; the unit's base pointer is uniform.
+    // Rows >= n are read from row n-1 (valid memory) and zeroed when staged: no branches.
+    // one register array serves both roles (a thread is either Y or G for its whole life):
+    //   Y: pre[0..NH)  = h0 chunks (fp32 bits)      G: pre[0..NC) = C, pre[NC..2NC) = B, then NX of x
+    constexpr int NPRE = NH > 2 * NC + NX ? NH : 2 * NC + NX;
+    uint4 pre[NPRE];
     int rpar = -1;
-    float rdt = 0.f, rA = 0.f, rD = 0.f;
+    float rdt = 0.f, rA = 0.f;
+    // The chunk coordinates of a thread are loop invariants; keeping them all in registers
+    // across the unit loop would cost more registers than the budget of 128 allows, so every
+    // helper below re-derives them from an opaque copy of the thread index (a few VALU ops).
+    auto opaque = [](int v) {
+        asm volatile("" : "+v"(v));
+        return v;
+    };
 
-    // per-thread offsets of the 16-byte chunks never change from unit to unit: one 32-bit
-    // offset per tensor, the unit's base pointer and the per-chunk row step are uniform.
-    // Rows >= n are read from row n-1 (valid memory) and zeroed afterwards: no branches.
-    constexpr int kRowsC = kT64 / (S / 8), kRowsX = kT64 / (P / 8);
-    const int rc0 = tid / (S / 8), cc0 = tid % (S / 8), rx0 = tid / (P / 8), cx0 = tid % (P / 8);
-    uint32_t offC[NC], offB[NC], offX[NX];
+    auto load_H = [&](int k) {       // Y threads
+        int b, h;
+        unit(k, b, h);
+        const char *hb = reinterpret_cast<const char *>(h0 + ((size_t)b * H + h) * P * S);
+        const uint32_t off = (uint32_t)opaque(rt) * 16u;
 #pragma unroll
-    for (int q = 0; q < NC; ++q) {
-        const int rr = min(rc0 + q * kRowsC, n - 1);
-        offC[q] = (uint32_t)(rr * (int)c_sn + cc0 * 8) * 2u;
-        offB[q] = (uint32_t)(rr * (int)b_sn + cc0 * 8) * 2u;
-    }
-#pragma unroll
-    for (int q = 0; q < NX; ++q) offX[q] = (uint32_t)(min(rx0 + q * kRowsX, n - 1) * (int)x_sn + cx0 * 8) * 2u;
-
-    auto issue_loads = [&](int b, int h) {
+        for (int q = 0; q < NH; ++q) pre[q] = *reinterpret_cast<const uint4 *>(hb + q * (kHalf * 16) + off);
+    };
+    auto load_CB = [&](int k) {      // G threads
+        int b, h;
+        unit(k, b, h);
         const int g = h / hpg;
         const char *Cb = reinterpret_cast<const char *>(Cm + (size_t)b * n * c_sn + (size_t)g * S);
         const char *Bb = reinterpret_cast<const char *>(Bm + (size_t)b * n * b_sn + (size_t)g * S);
-        const char *xb = reinterpret_cast<const char *>(x + (size_t)b * n * x_sn + (size_t)h * P);
-        if (wave == kTreeWave) {
-            const int node = min(lane, n - 1);
-            rpar = parent[(size_t)b * n + node];
-            rdt = dt[((size_t)b * n + node) * H + h];
-        }
-        rA = A[h];
-        rD = D ? D[h] : 0.f;
+        const int t = opaque(rt), rc0 = t / (S / 8), cc0 = t % (S / 8);
 #pragma unroll
         for (int q = 0; q < NC; ++q) {
-            rC[q] = *reinterpret_cast<const uint4 *>(Cb + offC[q]);
-            rB[q] = *reinterpret_cast<const uint4 *>(Bb + offB[q]);
-        }
-#pragma unroll
-        for (int q = 0; q < NX; ++q) rX[q] = *reinterpret_cast<const uint4 *>(xb + offX[q]);
-        if (h0) {
-            const char *hb = reinterpret_cast<const char *>(h0 + ((size_t)b * H + h) * P * S);
-#pragma unroll
-            for (int q = 0; q < NH; ++q)
-                rH[q] = *reinterpret_cast<const float4 *>(hb + (uint32_t)(tid + q * kT64) * 16u);
+            const int rr = min(rc0 + q * kRowsC, n - 1);
+            pre[q] = *reinterpret_cast<const uint4 *>(Cb + (uint32_t)(rr * (int)c_sn + cc0 * 8) * 2u);
+            pre[NC + q] = *reinterpret_cast<const uint4 *>(Bb + (uint32_t)(rr * (int)b_sn + cc0 * 8) * 2u);
         }
     };
-
-    int r = blockIdx.x >> 3, b = 0, h = 0;
-    bool have = decode(r, b, h);
-    if (have) issue_loads(b, h);
-
-    // y rows of the previous unit wait in sYo and are stored while the next unit computes, so
-    // that no store is outstanding when the loop top waits for its loads (on gfx9 loads and
-    // stores share one counter and complete out of order with respect to each other)
-    bf16_t *y_pending = nullptr;
-    auto flush_y = [&]() {
-        if (y_pending) {
+    auto load_X = [&](int k) {       // G threads
+        int b, h;
+        unit(k, b, h);
+        const char *xb = reinterpret_cast<const char *>(x + (size_t)b * n * x_sn + (size_t)h * P);
+        const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
 #pragma unroll
-            for (int q = 0; q < NX; ++q) {
-                const int idx = tid + q * kT64, rr = idx / (P / 8), c = idx % (P / 8);
-                if (rr < n)
-                    *reinterpret_cast<uint4 *>(y_pending + (size_t)rr * H * P + c * 8) =
-                        *reinterpret_cast<const uint4 *>(&sYo[rr * YOP + c * 8]);
-            }
+        for (int q = 0; q < NX; ++q)
+            pre[2 * NC + q] = *reinterpret_cast<const uint4 *>(
+                xb + (uint32_t)(min(rx0 + q * kRowsX, n - 1) * (int)x_sn + cx0 * 8) * 2u);
+    };
+    auto load_T = [&](int k) {       // tree wave
+        int b, h;
+        unit(k, b, h);
+        const int node = min(lane, n - 1);
+        rpar = parent[(size_t)b * n + node];
+        rdt = dt[((size_t)b * n + node) * H + h];
+        rA = A[h];
+    };
+    // ---- registers -> LDS -------------------------------------------------------------------------
+    auto stage_H = [&]() {
+        const int t = opaque(rt);
+#pragma unroll
+        for (int q = 0; q < NH; ++q) {
+            const int e = (t + q * kHalf) * 4, p = e / S, sidx = e % S;
+            bf16x4 o;
+            o[0] = (bf16_t)__uint_as_float(pre[q].x); o[1] = (bf16_t)__uint_as_float(pre[q].y);
+            o[2] = (bf16_t)__uint_as_float(pre[q].z); o[3] = (bf16_t)__uint_as_float(pre[q].w);
+            *reinterpret_cast<bf16x4 *>(&sH[p * SP + sidx]) = o;
         }
     };
-
-    while (have) {
-        [[maybe_unused]] const int prof_unit = b * H + h;  // only read by probe builds
-        STREE_PHASE_CLOCK(0);
-        const float A_h = rA, D_h = rD;
-        // ---- registers -> LDS; the tree wave builds the index first ------------------------------
-        if (wave == kTreeWave) {
-            const int bad = wave_tree_index(lane, n, rpar, rdt, A_h, sS, sDt, sMask);
-            if (lane == 0) *sBad = bad;
-        }
-        STREE_PHASE_CLOCK(1);
+    auto stage_CB = [&]() {
+        const int t = opaque(rt), rc0 = t / (S / 8), cc0 = t % (S / 8);
 #pragma unroll
         for (int q = 0; q < NC; ++q) {
             const int rr = rc0 + q * kRowsC;
             const uint32_t keep = rr < n ? 0xffffffffu : 0u;   // zero the rows beyond the tree
-            *reinterpret_cast<uint4 *>(&sC[rr * SP + cc0 * 8]) =
-                make_uint4(rC[q].x & keep, rC[q].y & keep, rC[q].z & keep, rC[q].w & keep);
-            *reinterpret_cast<uint4 *>(&sB[rr * SP + cc0 * 8]) =
-                make_uint4(rB[q].x & keep, rB[q].y & keep, rB[q].z & keep, rB[q].w & keep);
+            const uint4 c = pre[q], bq = pre[NC + q];
+            *reinterpret_cast<uint4 *>(&sC[rr * SP + cc0 * 8]) = make_uint4(c.x & keep, c.y & keep, c.z & keep, c.w & keep);
+            *reinterpret_cast<uint4 *>(&sB[rr * SP + cc0 * 8]) = make_uint4(bq.x & keep, bq.y & keep, bq.z & keep, bq.w & keep);
         }
+    };
+    auto stage_X = [&]() {
+        const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
 #pragma unroll
         for (int q = 0; q < NX; ++q) {
-            const int rr = rx0 + q * kRowsX, c = cx0;
+            const int rr = rx0 + q * kRowsX;
             const uint32_t keep = rr < n ? 0xffffffffu : 0u;
-            const uint32_t wv[4] = {rX[q].x & keep, rX[q].y & keep, rX[q].z & keep, rX[q].w & keep};
-            unsigned short *dst = sXT + (c * 8) * kNP64 + rr;
+            const uint4 xq = pre[2 * NC + q];
+            const uint32_t wv[4] = {xq.x & keep, xq.y & keep, xq.z & keep, xq.w & keep};
+            unsigned short *dst = sXT + (cx0 * 8) * kNP64 + rr;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 dst[(2 * e) * kNP64] = (unsigned short)(wv[e] & 0xffffu);
                 dst[(2 * e + 1) * kNP64] = (unsigned short)(wv[e] >> 16);
             }
         }
+    };
+    auto stage_T = [&]() {
+        const int bad = wave_tree_index(lane, n, rpar, rdt, rA, sS2, sU, sMask);
+        if (lane == 0) *sBad = bad;
+    };
+
+    if (nU == 0) return;
+    // ---- prologue: unit 0 into LDS, unit 1 into registers ---------------------------------------
+    if (isY) {
         if (h0) {
+            load_H(0);
+            stage_H();
+            if (nU > 1) load_H(1);
+        }
+    } else {
+        load_CB(0);
+        load_X(0);
+        if (wave == kTreeWave) {
+            load_T(0);
+            stage_T();
+            if (nU > 1) load_T(1);
+        }
+        stage_CB();
+        stage_X();
+        if (nU > 1) {
+            load_CB(1);
+            load_X(1);
+        }
+    }
+
+    bf16_t *y_pending = nullptr;     // rows of the previous unit waiting in sYo (Y threads store them)
+    auto flush_y = [&]() {
+        if (y_pending) {
+            const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
+            char *yb = reinterpret_cast<char *>(y_pending);
 #pragma unroll
-            for (int q = 0; q < NH; ++q) {
-                const int e = (tid + q * kT64) * 4, p = e / S, s = e % S;
-                bf16x4 o;
-                o[0] = (bf16_t)rH[q].x; o[1] = (bf16_t)rH[q].y; o[2] = (bf16_t)rH[q].z; o[3] = (bf16_t)rH[q].w;
-                *reinterpret_cast<bf16x4 *>(&sH[p * SP + s]) = o;
+            for (int q = 0; q < NX; ++q) {
+                const int rr = rx0 + q * kRowsX;
+                if (rr < n)
+                    *reinterpret_cast<uint4 *>(yb + (uint32_t)(rr * H * P + cx0 * 8) * 2u) =
+                        *reinterpret_cast<const uint4 *>(&sYo[rr * YOP + cx0 * 8]);
             }
         }
-        STREE_PHASE_CLOCK(2);
-        __syncthreads();
-        STREE_PHASE_CLOCK(3);
+    };
 
-        // ---- next unit's loads go out now and fly during the compute below; so do the
-        //      previous unit's y rows ---------------------------------------------------------
-        const int cb = b, ch = h;
-        r += rstep;
-        have = decode(r, b, h);
-        if (have) issue_loads(b, h);
-        flush_y();
-        y_pending = y + (size_t)cb * n * H * P + (size_t)ch * P;
-        STREE_PHASE_CLOCK(4);
-
+    for (int k = 0; k < nU; ++k) {
+        int cb, ch;
+        unit(k, cb, ch);
+        [[maybe_unused]] const int prof_unit = cb * H + ch;  // only read by probe builds
+        __syncthreads();                                      // barrier 1: unit k is staged
+        STREE_PHASE_CLOCK(0);
         const int bad = *sBad;
         if (status && ch == 0 && tid == 0) status[cb] = bad;
 
@@ -265,87 +304,96 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         for (int q = 0; q < YQ; ++q)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+        float D_h = 0.f;
 
-        if (!bad) {
-            const bf16_t *cp = &sC[il * SP + 8 * lh];
-            if (wave < 4) {
-                // ---- phase 1 (Y waves): Yt = h0b C^T, then *= exp(s_i) ----------------------------
-                if (h0) {
-                    // fragments of half the state index are read in one batch, then consumed
+        if (isY) {
+            D_h = D ? D[ch] : 0.f;
+            flush_y();
+            y_pending = y + (size_t)cb * n * H * P + (size_t)ch * P;
+            STREE_PHASE_CLOCK(1);
+            // ---- phase 1: Yt = h0b C^T, then *= exp(s_i) -------------------------------------------
+            if (h0 && !bad) {
+                const bf16_t *cp = &sC[il * SP + 8 * lh];
 #pragma unroll
-                    for (int kb = 0; kb < S; kb += S / 2) {
-                        bf16x8 cf[S / 32], hf[YQ][S / 32];
-#pragma unroll
-                        for (int j = 0; j < S / 32; ++j) {
-                            cf[j] = *reinterpret_cast<const bf16x8 *>(cp + kb + 16 * j);
-#pragma unroll
-                            for (int q = 0; q < YQ; ++q)
-                                hf[q][j] = *reinterpret_cast<const bf16x8 *>(
-                                    &sH[(((wave + 4 * q) >> 1) * 32 + l32) * SP + 8 * lh + kb + 16 * j]);
-                        }
-#pragma unroll
-                        for (int j = 0; j < S / 32; ++j)
-#pragma unroll
-                            for (int q = 0; q < YQ; ++q)
-                                acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf[q][j], cf[j], acc[q], 0, 0, 0);
-                        __builtin_amdgcn_sched_barrier(0);   // keep the two batches apart: register budget
-                    }
-                    const float e = __expf(sS[il]);
-#pragma unroll
-                    for (int q = 0; q < YQ; ++q)
-#pragma unroll
-                        for (int rg = 0; rg < 16; ++rg) acc[q][rg] *= e;
-                }
-            } else if (wave != kTreeWave) {
-                // ---- phase 2 (G waves): Gt = B C^T, mask and decay -> M[i][j] as bf16 --------------
-                const int jt = (wave - 4) >> 1;
-                STREE_PHASE_CLOCK_G(9);
-                floatx16 gt;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) gt[e] = 0.f;
-                const bf16_t *bp = &sB[(jt * 32 + l32) * SP + 8 * lh];
-#pragma unroll
-                for (int kb = 0; kb < S; kb += S / 2) {
-                    bf16x8 cf[S / 32], bf[S / 32];
+                for (int kb = 0; kb < S; kb += S / 2) {   // fragments of half the state index per batch
+                    __builtin_amdgcn_sched_barrier(0);
+                    bf16x8 cf[S / 32], hf[YQ][S / 32];
 #pragma unroll
                     for (int j = 0; j < S / 32; ++j) {
                         cf[j] = *reinterpret_cast<const bf16x8 *>(cp + kb + 16 * j);
-                        bf[j] = *reinterpret_cast<const bf16x8 *>(bp + kb + 16 * j);
+#pragma unroll
+                        for (int q = 0; q < YQ; ++q)
+                            hf[q][j] = *reinterpret_cast<const bf16x8 *>(
+                                &sH[(((wave + 4 * q) >> 1) * 32 + l32) * SP + 8 * lh + kb + 16 * j]);
                     }
 #pragma unroll
                     for (int j = 0; j < S / 32; ++j)
-                        gt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], cf[j], gt, 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                STREE_PHASE_CLOCK_G(10);
-                const float s_i = sS[il];
-                const uint32_t mrow = sMask[il * 2 + jt] >> (4 * lh);   // bit 8*rg + e <-> j = jl + e
 #pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    const int jl = jt * 32 + 8 * rg + 4 * lh;
-                    const float4 sj = *reinterpret_cast<const float4 *>(&sS[jl]);
-                    const float4 dj = *reinterpret_cast<const float4 *>(&sDt[jl]);
-                    const float sjv[4] = {sj.x, sj.y, sj.z, sj.w};
-                    const float djv[4] = {dj.x, dj.y, dj.z, dj.w};
-                    bf16x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const bool on = (mrow >> (8 * rg + e)) & 1u;
-                        const float v = on ? gt[4 * rg + e] * __expf(s_i - sjv[e]) * djv[e] : 0.f;
-                        o[e] = (bf16_t)v;
-                    }
-                    *reinterpret_cast<bf16x4 *>(&sM[il * kNP64 + jl]) = o;
+                        for (int q = 0; q < YQ; ++q)
+                            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf[q][j], cf[j], acc[q], 0, 0, 0);
                 }
-                STREE_PHASE_CLOCK_G(11);
+                const float e = __builtin_amdgcn_exp2f(sS2[il]);
+#pragma unroll
+                for (int q = 0; q < YQ; ++q)
+#pragma unroll
+                    for (int rg = 0; rg < 16; ++rg) acc[q][rg] *= e;
             }
+            STREE_PHASE_CLOCK(2);
+        } else if (wave != kTreeWave && !bad) {
+            // ---- phase 2: Gt = B C^T, mask and decay -> M[i][j] as bf16 ------------------------------
+            const int jt = (wave - 4) >> 1;
+            STREE_PHASE_CLOCK_G(9);
+            floatx16 gt;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) gt[e] = 0.f;
+            const bf16_t *cp = &sC[il * SP + 8 * lh];
+            const bf16_t *bp = &sB[(jt * 32 + l32) * SP + 8 * lh];
+            {   // all fragments of the state index are requested before the first MFMA issues
+                bf16x8 cf[S / 16], bf[S / 16];
+#pragma unroll
+                for (int j = 0; j < S / 16; ++j) {
+                    cf[j] = *reinterpret_cast<const bf16x8 *>(cp + 16 * j);
+                    bf[j] = *reinterpret_cast<const bf16x8 *>(bp + 16 * j);
+                }
+#pragma unroll
+                for (int j = 0; j < S / 16; ++j)
+                    gt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], cf[j], gt, 0, 0, 0);
+                // issue order: half of the reads, then reads of one more step per pair of MFMAs
+                __builtin_amdgcn_sched_group_barrier(0x100, S / 16, 0);
+#pragma unroll
+                for (int j = 0; j < S / 64; ++j) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, S / 16 - 2 * (S / 64), 0);
+            }
+            STREE_PHASE_CLOCK_G(10);
+            const float s2_i = sS2[il];
+            const uint32_t mrow = sMask[il * 2 + jt] >> (4 * lh);   // bit 8*rg + e <-> j = jl + e
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int jl = jt * 32 + 8 * rg + 4 * lh;
+                const float4 uj = *reinterpret_cast<const float4 *>(&sU[jl]);
+                const float ujv[4] = {uj.x, uj.y, uj.z, uj.w};
+                bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // bitwise select: an overflowed exp2 under a cleared mask bit never reaches M
+                    const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)mrow, 8 * rg + e, 1);
+                    const float v = gt[4 * rg + e] * __builtin_amdgcn_exp2f(s2_i - ujv[e]);
+                    o[e] = (bf16_t)__uint_as_float(__float_as_uint(v) & keep);
+                }
+                *reinterpret_cast<bf16x4 *>(&sM[il * kNP64 + jl]) = o;
+            }
+            STREE_PHASE_CLOCK_G(11);
         }
-        STREE_PHASE_CLOCK(5);
-        __syncthreads();
-        STREE_PHASE_CLOCK(6);
+        __syncthreads();                                      // barrier 2: M is ready; C, B, h0b dead
+        STREE_PHASE_CLOCK(3);
 
-        // ---- phase 3 (Y waves): Yt += Xt M^T over j <= i only (nodes i < 32 have no ancestor
-        //      j >= 32, that quadrant of M is never written or read); y = Yt + D x -> bf16 rows ---
-        if (wave < 4) {
+        const bool more = k + 1 < nU, more2 = k + 2 < nU;
+        if (isY) {
+            // ---- phase 3: Yt += Xt M^T over j <= i only (nodes i < 32 have no ancestor j >= 32:
+            //      that quadrant of M is never written or read); y = Yt + D x -> bf16 rows -------------
 #pragma unroll
             for (int q = 0; q < YQ; ++q) {
                 const int pt = (wave + 4 * q) >> 1;
@@ -371,12 +419,32 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                     *reinterpret_cast<bf16x4 *>(&sYo[il * YOP + p0]) = o;
                 }
             }
+            STREE_PHASE_CLOCK(4);
+            if (h0) {
+                if (more) stage_H();
+                if (more2) load_H(k + 2);
+            }
+            STREE_PHASE_CLOCK(5);
+        } else {
+            if (more) {
+                if (wave == kTreeWave) {
+                    stage_T();
+                    if (more2) load_T(k + 2);
+                }
+                stage_CB();
+                if (more2) load_CB(k + 2);
+            }
+        }
+        __syncthreads();                                      // barrier 3: X^T is dead
+        STREE_PHASE_CLOCK(6);
+        if (!isY && more) {
+            stage_X();
+            if (more2) load_X(k + 2);
         }
         STREE_PHASE_CLOCK(7);
-        __syncthreads();
-        STREE_PHASE_CLOCK(8);
     }
-    flush_y();
+    __syncthreads();
+    if (isY) flush_y();
 }
 
 template <int P, int S>
