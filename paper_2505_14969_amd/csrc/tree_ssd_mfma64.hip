@@ -11,21 +11,22 @@
 //   G waves 4,5,7 own the three live tiles of Gt[j][i]; carry the C, B, x prefetch
 //   T wave  6     (its Gt tile has j > i everywhere) builds the tree index
 //
+// A workgroup's units are consecutive, so mostly heads of one sequence and
+// group: C, B and Gt = B C^T are staged / computed once per run of such heads
+// (CB^T once per group), only the decay weighting is redone per head.
+//
 // Steady state for unit k, with the registers already holding unit k+1:
 //   barrier 1
-//     Y: store y(k-1) from LDS; phase 1  Yt = h0b C^T, *= exp(s_i)
-//     G: phase 2  Gt = B C^T, M = L ? Gt exp(s_i - s_j) dt_j : 0 -> LDS (bf16)
-//   barrier 2   (C, B, h0b tiles and the tree arrays are dead from here on)
-//     Y: phase 3  Yt += Xt M^T; y = Yt + D x -> bf16 rows in LDS;
-//        then h0(k+1) regs -> LDS as bf16, issue h0(k+2) loads
-//     G: C, B (k+1) regs -> LDS, issue C, B (k+2) loads
+//     Y: phase 1  Yt = h0b C^T, *= exp(s_i)
+//     G: phase 2  (Gt = B C^T if the tiles are new) M = L ? Gt exp(s_i - s_j) dt_j : 0 -> LDS
+//   barrier 2   (h0b tile and the tree arrays are dead from here on)
+//     Y: phase 3  Yt += Xt M^T; y = Yt + D x -> bf16 rows in LDS; h0(k+1) regs -> LDS as
+//        bf16; store own y rows from LDS (16 B per lane); issue h0(k+2) loads
+//     G: new C, B tiles if unit k+1 starts another sequence or group
 //     T: tree index of unit k+1, issue parent/dt (k+2) loads
 //   barrier 3   (X^T tile is dead)
 //     G: x(k+1) regs -> LDS transposed, issue x(k+2) loads
-// so global loads are in flight for a whole unit period and HBM latency is paid
-// once per workgroup.  y rows are stored one unit late, from LDS, so that no
-// store is outstanding when a wave waits for its loads (on gfx9 loads and stores
-// share one counter and complete out of order with respect to each other).
+// so the big global loads (h0, x) are in flight for a whole unit period.
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -139,23 +140,32 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     const int n_units = nbatch * H;
     const int per_xcd = (n_units + 7) >> 3;
     const int xcd = blockIdx.x & 7;
-    const int r0 = blockIdx.x >> 3, rstep = gridDim.x >> 3;
+    const int wg = blockIdx.x >> 3, nwg = gridDim.x >> 3;   // this workgroup among its XCD's
     const int hpg = H / G;
-    // this workgroup's units: k-th is number r0 + k*rstep of its XCD's contiguous range
-    const int r_end = min(per_xcd, n_units - xcd * per_xcd);
-    const int nU = r0 < r_end ? (r_end - r0 + rstep - 1) / rstep : 0;
-    auto unit = [&](int k, int &b, int &h) {
-        const int logical = xcd * per_xcd + r0 + k * rstep;
-        b = logical / H;
-        h = logical - b * H;
+    // XCD x owns the contiguous unit range [x*per_xcd, ...); its workgroups split that range
+    // into contiguous runs, so a workgroup mostly sees consecutive heads of one sequence and
+    // group: their C, B tiles, the tree mask and Gt = B C^T are then reused, not redone.
+    const int cnt = max(0, min(per_xcd, n_units - xcd * per_xcd));
+    const int u0 = xcd * per_xcd + (int)((long)wg * cnt / nwg);
+    const int nU = xcd * per_xcd + (int)((long)(wg + 1) * cnt / nwg) - u0;
+    // (b, h) of unit k by stepping from unit 0 (k is 0, 1 or 2 units ahead of a known one):
+    // scalar adds and compares only, no division inside the unit loop
+    const int ub0 = __builtin_amdgcn_readfirstlane(u0 / H), uh0 = __builtin_amdgcn_readfirstlane(u0 % H);
+    auto step = [&](int &b, int &h) {
+        if (++h == H) {
+            h = 0;
+            ++b;
+        }
     };
+    // a unit needs new C/B tiles when it is the first one or starts another sequence or group
+    auto fresh_at = [&](int k, int h) -> bool { return k == 0 || h % hpg == 0; };
 
     // ---- prefetch registers and their loaders ---------------------------------------------------
     // per-thread chunk offsets never change from unit to unit; the unit's base pointer is uniform.
     // Rows >= n are read from row n-1 (valid memory) and zeroed when staged: no branches.
     // one register array serves both roles (a thread is either Y or G for its whole life):
-    //   Y: pre[0..NH)  = h0 chunks (fp32 bits)      G: pre[0..NC) = C, pre[NC..2NC) = B, then NX of x
-    constexpr int NPRE = NH > 2 * NC + NX ? NH : 2 * NC + NX;
+    //   Y: pre[0..NH) = h0 chunks (fp32 bits)      G: pre[0..NX) = x chunks
+    constexpr int NPRE = NH > NX ? NH : NX;
     uint4 pre[NPRE];
     int rpar = -1;
     float rdt = 0.f, rA = 0.f;
@@ -167,41 +177,49 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         return v;
     };
 
-    auto load_H = [&](int k) {       // Y threads
-        int b, h;
-        unit(k, b, h);
+    float rD = 0.f;                  // D[h] of the unit whose h0 is in pre[]
+    auto load_H = [&](int b, int h) {       // Y threads
+        // the lane-dependent zero keeps this a vector load: it then sits in the same in-order
+        // queue as the h0 chunks instead of forcing a scalar-cache wait in the hot window
+        if (D) rD = D[h + (opaque(lane) & 0)];
         const char *hb = reinterpret_cast<const char *>(h0 + ((size_t)b * H + h) * P * S);
         const uint32_t off = (uint32_t)opaque(rt) * 16u;
 #pragma unroll
         for (int q = 0; q < NH; ++q) pre[q] = *reinterpret_cast<const uint4 *>(hb + q * (kHalf * 16) + off);
     };
-    auto load_CB = [&](int k) {      // G threads
-        int b, h;
-        unit(k, b, h);
+    // C and B tiles of unit k: global -> registers -> LDS in one go (G threads).  Runs only when
+    // the (sequence, group) changes, i.e. about once per workgroup.
+    auto restage_CB = [&](int b, int h) {
         const int g = h / hpg;
         const char *Cb = reinterpret_cast<const char *>(Cm + (size_t)b * n * c_sn + (size_t)g * S);
         const char *Bb = reinterpret_cast<const char *>(Bm + (size_t)b * n * b_sn + (size_t)g * S);
         const int t = opaque(rt), rc0 = t / (S / 8), cc0 = t % (S / 8);
+        uint4 c[NC], bq[NC];
 #pragma unroll
         for (int q = 0; q < NC; ++q) {
             const int rr = min(rc0 + q * kRowsC, n - 1);
-            pre[q] = *reinterpret_cast<const uint4 *>(Cb + (uint32_t)(rr * (int)c_sn + cc0 * 8) * 2u);
-            pre[NC + q] = *reinterpret_cast<const uint4 *>(Bb + (uint32_t)(rr * (int)b_sn + cc0 * 8) * 2u);
+            c[q] = *reinterpret_cast<const uint4 *>(Cb + (uint32_t)(rr * (int)c_sn + cc0 * 8) * 2u);
+            bq[q] = *reinterpret_cast<const uint4 *>(Bb + (uint32_t)(rr * (int)b_sn + cc0 * 8) * 2u);
+        }
+#pragma unroll
+        for (int q = 0; q < NC; ++q) {
+            const int rr = rc0 + q * kRowsC;
+            const uint32_t keep = rr < n ? 0xffffffffu : 0u;   // zero the rows beyond the tree
+            *reinterpret_cast<uint4 *>(&sC[rr * SP + cc0 * 8]) =
+                make_uint4(c[q].x & keep, c[q].y & keep, c[q].z & keep, c[q].w & keep);
+            *reinterpret_cast<uint4 *>(&sB[rr * SP + cc0 * 8]) =
+                make_uint4(bq[q].x & keep, bq[q].y & keep, bq[q].z & keep, bq[q].w & keep);
         }
     };
-    auto load_X = [&](int k) {       // G threads
-        int b, h;
-        unit(k, b, h);
+    auto load_X = [&](int b, int h) {       // G threads
         const char *xb = reinterpret_cast<const char *>(x + (size_t)b * n * x_sn + (size_t)h * P);
         const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
 #pragma unroll
         for (int q = 0; q < NX; ++q)
-            pre[2 * NC + q] = *reinterpret_cast<const uint4 *>(
+            pre[q] = *reinterpret_cast<const uint4 *>(
                 xb + (uint32_t)(min(rx0 + q * kRowsX, n - 1) * (int)x_sn + cx0 * 8) * 2u);
     };
-    auto load_T = [&](int k) {       // tree wave
-        int b, h;
-        unit(k, b, h);
+    auto load_T = [&](int b, int h) {       // tree wave
         const int node = min(lane, n - 1);
         rpar = parent[(size_t)b * n + node];
         rdt = dt[((size_t)b * n + node) * H + h];
@@ -219,24 +237,13 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             *reinterpret_cast<bf16x4 *>(&sH[p * SP + sidx]) = o;
         }
     };
-    auto stage_CB = [&]() {
-        const int t = opaque(rt), rc0 = t / (S / 8), cc0 = t % (S / 8);
-#pragma unroll
-        for (int q = 0; q < NC; ++q) {
-            const int rr = rc0 + q * kRowsC;
-            const uint32_t keep = rr < n ? 0xffffffffu : 0u;   // zero the rows beyond the tree
-            const uint4 c = pre[q], bq = pre[NC + q];
-            *reinterpret_cast<uint4 *>(&sC[rr * SP + cc0 * 8]) = make_uint4(c.x & keep, c.y & keep, c.z & keep, c.w & keep);
-            *reinterpret_cast<uint4 *>(&sB[rr * SP + cc0 * 8]) = make_uint4(bq.x & keep, bq.y & keep, bq.z & keep, bq.w & keep);
-        }
-    };
     auto stage_X = [&]() {
         const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
 #pragma unroll
         for (int q = 0; q < NX; ++q) {
             const int rr = rx0 + q * kRowsX;
             const uint32_t keep = rr < n ? 0xffffffffu : 0u;
-            const uint4 xq = pre[2 * NC + q];
+            const uint4 xq = pre[q];
             const uint32_t wv[4] = {xq.x & keep, xq.y & keep, xq.z & keep, xq.w & keep};
             unsigned short *dst = sXT + (cx0 * 8) * kNP64 + rr;
 #pragma unroll
@@ -251,48 +258,40 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         if (lane == 0) *sBad = bad;
     };
 
-    if (nU == 0) return;
+    if (nU <= 0) return;
+    // (b, h) of the current unit and of the next two
+    int cb = ub0, ch = uh0, b1 = ub0, h1 = uh0;
+    step(b1, h1);
+    int b2 = b1, h2 = h1;
+    step(b2, h2);
     // ---- prologue: unit 0 into LDS, unit 1 into registers ---------------------------------------
+    float D_h = 0.f;                 // D of the current unit (Y threads)
     if (isY) {
         if (h0) {
-            load_H(0);
+            load_H(cb, ch);
             stage_H();
-            if (nU > 1) load_H(1);
+            D_h = rD;
+            if (nU > 1) load_H(b1, h1);
+        } else if (D) {
+            D_h = D[ch];
         }
     } else {
-        load_CB(0);
-        load_X(0);
+        load_X(cb, ch);
         if (wave == kTreeWave) {
-            load_T(0);
+            load_T(cb, ch);
             stage_T();
-            if (nU > 1) load_T(1);
+            if (nU > 1) load_T(b1, h1);
         }
-        stage_CB();
+        restage_CB(cb, ch);
         stage_X();
-        if (nU > 1) {
-            load_CB(1);
-            load_X(1);
-        }
+        if (nU > 1) load_X(b1, h1);
     }
 
-    bf16_t *y_pending = nullptr;     // rows of the previous unit waiting in sYo (Y threads store them)
-    auto flush_y = [&]() {
-        if (y_pending) {
-            const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
-            char *yb = reinterpret_cast<char *>(y_pending);
+    floatx16 gt;     // G waves: Gt tile of the current (sequence, group), kept across its heads
 #pragma unroll
-            for (int q = 0; q < NX; ++q) {
-                const int rr = rx0 + q * kRowsX;
-                if (rr < n)
-                    *reinterpret_cast<uint4 *>(yb + (uint32_t)(rr * H * P + cx0 * 8) * 2u) =
-                        *reinterpret_cast<const uint4 *>(&sYo[rr * YOP + cx0 * 8]);
-            }
-        }
-    };
+    for (int e = 0; e < 16; ++e) gt[e] = 0.f;
 
     for (int k = 0; k < nU; ++k) {
-        int cb, ch;
-        unit(k, cb, ch);
         [[maybe_unused]] const int prof_unit = cb * H + ch;  // only read by probe builds
         __syncthreads();                                      // barrier 1: unit k is staged
         STREE_PHASE_CLOCK(0);
@@ -304,19 +303,13 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         for (int q = 0; q < YQ; ++q)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
-        float D_h = 0.f;
 
         if (isY) {
-            D_h = D ? D[ch] : 0.f;
-            flush_y();
-            y_pending = y + (size_t)cb * n * H * P + (size_t)ch * P;
-            STREE_PHASE_CLOCK(1);
             // ---- phase 1: Yt = h0b C^T, then *= exp(s_i) -------------------------------------------
             if (h0 && !bad) {
                 const bf16_t *cp = &sC[il * SP + 8 * lh];
 #pragma unroll
                 for (int kb = 0; kb < S; kb += S / 2) {   // fragments of half the state index per batch
-                    __builtin_amdgcn_sched_barrier(0);
                     bf16x8 cf[S / 32], hf[YQ][S / 32];
 #pragma unroll
                     for (int j = 0; j < S / 32; ++j) {
@@ -338,34 +331,28 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
 #pragma unroll
                     for (int rg = 0; rg < 16; ++rg) acc[q][rg] *= e;
             }
-            STREE_PHASE_CLOCK(2);
+            STREE_PHASE_CLOCK(1);
         } else if (wave != kTreeWave && !bad) {
-            // ---- phase 2: Gt = B C^T, mask and decay -> M[i][j] as bf16 ------------------------------
+            // ---- phase 2: Gt = B C^T (only when the C/B tiles are new), mask and decay -> M ----------
             const int jt = (wave - 4) >> 1;
             STREE_PHASE_CLOCK_G(9);
-            floatx16 gt;
+            if (fresh_at(k, ch)) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) gt[e] = 0.f;
-            const bf16_t *cp = &sC[il * SP + 8 * lh];
-            const bf16_t *bp = &sB[(jt * 32 + l32) * SP + 8 * lh];
-            {   // all fragments of the state index are requested before the first MFMA issues
-                bf16x8 cf[S / 16], bf[S / 16];
+                for (int e = 0; e < 16; ++e) gt[e] = 0.f;
+                const bf16_t *cp = &sC[il * SP + 8 * lh];
+                const bf16_t *bp = &sB[(jt * 32 + l32) * SP + 8 * lh];
 #pragma unroll
-                for (int j = 0; j < S / 16; ++j) {
-                    cf[j] = *reinterpret_cast<const bf16x8 *>(cp + 16 * j);
-                    bf[j] = *reinterpret_cast<const bf16x8 *>(bp + 16 * j);
+                for (int kb = 0; kb < S; kb += S / 2) {
+                    bf16x8 cf[S / 32], bf[S / 32];
+#pragma unroll
+                    for (int j = 0; j < S / 32; ++j) {
+                        cf[j] = *reinterpret_cast<const bf16x8 *>(cp + kb + 16 * j);
+                        bf[j] = *reinterpret_cast<const bf16x8 *>(bp + kb + 16 * j);
+                    }
+#pragma unroll
+                    for (int j = 0; j < S / 32; ++j)
+                        gt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], cf[j], gt, 0, 0, 0);
                 }
-#pragma unroll
-                for (int j = 0; j < S / 16; ++j)
-                    gt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], cf[j], gt, 0, 0, 0);
-                // issue order: half of the reads, then reads of one more step per pair of MFMAs
-                __builtin_amdgcn_sched_group_barrier(0x100, S / 16, 0);
-#pragma unroll
-                for (int j = 0; j < S / 64; ++j) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, S / 16 - 2 * (S / 64), 0);
             }
             STREE_PHASE_CLOCK_G(10);
             const float s2_i = sS2[il];
@@ -387,13 +374,14 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
             STREE_PHASE_CLOCK_G(11);
         }
-        __syncthreads();                                      // barrier 2: M is ready; C, B, h0b dead
-        STREE_PHASE_CLOCK(3);
+        __syncthreads();                                      // barrier 2: M is ready; h0b (and B) dead
+        STREE_PHASE_CLOCK(2);
 
         const bool more = k + 1 < nU, more2 = k + 2 < nU;
         if (isY) {
             // ---- phase 3: Yt += Xt M^T over j <= i only (nodes i < 32 have no ancestor j >= 32:
-            //      that quadrant of M is never written or read); y = Yt + D x -> bf16 rows -------------
+            //      that quadrant of M is never written or read); y = Yt + D x -> own 32x32 block
+            //      of the bf16 staging rows ------------------------------------------------------------
 #pragma unroll
             for (int q = 0; q < YQ; ++q) {
                 const int pt = (wave + 4 * q) >> 1;
@@ -419,32 +407,57 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                     *reinterpret_cast<bf16x4 *>(&sYo[il * YOP + p0]) = o;
                 }
             }
+            STREE_PHASE_CLOCK(3);
+            // next unit's state tile (its loads have been in flight for a whole unit period)
+            float D_next = 0.f;
+            if (h0 && more) {
+                stage_H();
+                D_next = rD;
+            } else if (D && more) {
+                D_next = D[h1];
+            }
             STREE_PHASE_CLOCK(4);
-            if (h0) {
-                if (more) stage_H();
-                if (more2) load_H(k + 2);
-            }
-            STREE_PHASE_CLOCK(5);
-        } else {
-            if (more) {
-                if (wave == kTreeWave) {
-                    stage_T();
-                    if (more2) load_T(k + 2);
+            // y rows: each wave stores the 32x32 blocks it has just written itself (LDS executes a
+            // wave's accesses in order, no barrier needed), 16 bytes per lane.  The stores go out
+            // after the wait for the h0 loads above and are long complete at the next such wait:
+            // on gfx9 loads and stores share one counter and complete out of order with respect
+            // to each other, so a store in flight would turn that wait into a wait for everything.
+            {
+                char *yb = reinterpret_cast<char *>(y + (size_t)cb * n * H * P + (size_t)ch * P);
+                const int ln = opaque(lane);
+#pragma unroll
+                for (int q = 0; q < YQ; ++q) {
+                    const int pt = (wave + 4 * q) >> 1;
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        const int row = it * 32 + half * 16 + (ln >> 2), col = pt * 32 + (ln & 3) * 8;
+                        if (row < n)
+                            *reinterpret_cast<uint4 *>(yb + (uint32_t)(row * H * P + col) * 2u) =
+                                *reinterpret_cast<const uint4 *>(&sYo[row * YOP + col]);
+                    }
                 }
-                stage_CB();
-                if (more2) load_CB(k + 2);
             }
+            if (h0 && more2) load_H(b2, h2);
+            D_h = D_next;
+            STREE_PHASE_CLOCK(5);
+        } else if (more) {
+            if (wave == kTreeWave) {
+                stage_T();
+                if (more2) load_T(b2, h2);
+            }
+            if (fresh_at(k + 1, h1)) restage_CB(b1, h1);   // C is dead too: phase 1 of unit k is done
         }
         __syncthreads();                                      // barrier 3: X^T is dead
         STREE_PHASE_CLOCK(6);
         if (!isY && more) {
             stage_X();
-            if (more2) load_X(k + 2);
+            if (more2) load_X(b2, h2);
         }
         STREE_PHASE_CLOCK(7);
+        cb = b1; ch = h1;
+        b1 = b2; h1 = h2;
+        step(b2, h2);
     }
-    __syncthreads();
-    if (isY) flush_y();
 }
 
 template <int P, int S>
