@@ -7,9 +7,10 @@
 // out so that all heads of one sequence land on the same XCD (workgroup id % 8),
 // whose L2 then serves the B / C rows that the heads of a group share.
 //
-//   Y waves 0-3   own the four 32x32 tiles of Yt[p][i]; carry the h0 prefetch
-//   G waves 4,5,7 own the three live tiles of Gt[j][i]; carry the C, B, x prefetch
-//   T wave  6     (its Gt tile has j > i everywhere) builds the tree index
+//   Y waves 0-3   own the four 32x32 tiles of Yt[p][i]; carry the h0 prefetch of even units
+//   G waves 4,5,7 own the three live tiles of Gt[j][i]; carry the x prefetch and, with the
+//   T wave  6     (its Gt tile has j > i everywhere; builds the tree index), the h0 prefetch
+//                 of odd units: the h0 tiles of two future units are always in flight
 //
 // A workgroup's units are consecutive, so mostly heads of one sequence and
 // group: C, B and Gt = B C^T are staged / computed once per run of such heads
@@ -20,8 +21,8 @@
 //     Y: phase 1  Yt = h0b C^T, *= exp(s_i)
 //     G: phase 2  (Gt = B C^T if the tiles are new) M = L ? Gt exp(s_i - s_j) dt_j : 0 -> LDS
 //   barrier 2   (h0b tile and the tree arrays are dead from here on)
-//     Y: phase 3  Yt += Xt M^T; y = Yt + D x -> bf16 rows in LDS; h0(k+1) regs -> LDS as
-//        bf16; store own y rows from LDS (16 B per lane); issue h0(k+2) loads
+//     Y: phase 3  Yt += Xt M^T; y = Yt + D x -> bf16 rows in LDS; store own y rows from LDS
+//     Y or G (whoever carries unit k+1): h0(k+1) regs -> LDS as bf16; issue h0(k+3) loads
 //     G: new C, B tiles if unit k+1 starts another sequence or group
 //     T: tree index of unit k+1, issue parent/dt (k+2) loads
 //   barrier 3   (X^T tile is dead)
@@ -119,17 +120,19 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     constexpr int YT = (P / 32) * 2, YQ = YT / 4;   // Yt tiles, tiles per Y wave
     constexpr int kRowsC = kHalf / (S / 8), kRowsX = kHalf / (P / 8);
     static_assert(NC >= 1 && NX >= 1 && NH >= 1 && YQ >= 1, "tile too small for this thread count");
-    extern __shared__ __align__(16) unsigned char lds[];
-    bf16_t *sC = reinterpret_cast<bf16_t *>(lds + L::off_c);
-    bf16_t *sB = reinterpret_cast<bf16_t *>(lds + L::off_b);
-    bf16_t *sYo = reinterpret_cast<bf16_t *>(lds + L::off_yo);
-    bf16_t *sH = reinterpret_cast<bf16_t *>(lds + L::off_h);
-    unsigned short *sXT = reinterpret_cast<unsigned short *>(lds + L::off_xt);
-    bf16_t *sM = reinterpret_cast<bf16_t *>(lds + L::off_m);
-    float *sS2 = reinterpret_cast<float *>(lds + L::off_s);
-    float *sU = reinterpret_cast<float *>(lds + L::off_dt);
-    uint32_t *sMask = reinterpret_cast<uint32_t *>(lds + L::off_mask);
-    int *sBad = reinterpret_cast<int *>(lds + L::off_bad);
+    // separate LDS objects (not slices of one array), so that the compiler knows that a write to
+    // one tile cannot alias a read of another and does not serialise them
+    __shared__ __align__(16) bf16_t sC[kB64 * SP];
+    __shared__ __align__(16) bf16_t sB[kB64 * SP];
+    __shared__ __align__(16) bf16_t sH[P * SP];
+    __shared__ __align__(16) unsigned short sXT[P * kNP64];
+    __shared__ __align__(16) bf16_t sM[kB64 * kNP64];
+    __shared__ __align__(16) bf16_t sYo[kB64 * YOP];
+    __shared__ __align__(16) float sS2[kB64];
+    __shared__ __align__(16) float sU[kB64];
+    __shared__ uint32_t sMask[kB64 * 2];
+    __shared__ int sBad[1];
+    __shared__ float sDh[1];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
     constexpr int kTreeWave = 6;
@@ -164,8 +167,10 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     // per-thread chunk offsets never change from unit to unit; the unit's base pointer is uniform.
     // Rows >= n are read from row n-1 (valid memory) and zeroed when staged: no branches.
     // one register array serves both roles (a thread is either Y or G for its whole life):
-    //   Y: pre[0..NH) = h0 chunks (fp32 bits)      G: pre[0..NX) = x chunks
-    constexpr int NPRE = NH > NX ? NH : NX;
+    //   pre[0..NH)  h0 chunks (fp32 bits) of a future unit: the Y threads carry the even units
+    //               of the run, the G threads the odd ones, so two units' h0 are in flight
+    //   pre[NH..)   x chunks of the next unit (G threads)
+    constexpr int NPRE = NH + NX;
     uint4 pre[NPRE];
     int rpar = -1;
     float rdt = 0.f, rA = 0.f;
@@ -178,7 +183,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     };
 
     float rD = 0.f;                  // D[h] of the unit whose h0 is in pre[]
-    auto load_H = [&](int b, int h) {       // Y threads
+    auto load_H = [&](int b, int h) {       // the role group that carries this unit
         // the lane-dependent zero keeps this a vector load: it then sits in the same in-order
         // queue as the h0 chunks instead of forcing a scalar-cache wait in the hot window
         if (D) rD = D[h + (opaque(lane) & 0)];
@@ -216,7 +221,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
 #pragma unroll
         for (int q = 0; q < NX; ++q)
-            pre[q] = *reinterpret_cast<const uint4 *>(
+            pre[NH + q] = *reinterpret_cast<const uint4 *>(
                 xb + (uint32_t)(min(rx0 + q * kRowsX, n - 1) * (int)x_sn + cx0 * 8) * 2u);
     };
     auto load_T = [&](int b, int h) {       // tree wave
@@ -236,6 +241,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             o[2] = (bf16_t)__uint_as_float(pre[q].z); o[3] = (bf16_t)__uint_as_float(pre[q].w);
             *reinterpret_cast<bf16x4 *>(&sH[p * SP + sidx]) = o;
         }
+        if (rt == 0) *sDh = rD;      // D of that unit, for the Y waves
     };
     auto stage_X = [&]() {
         const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
@@ -243,7 +249,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         for (int q = 0; q < NX; ++q) {
             const int rr = rx0 + q * kRowsX;
             const uint32_t keep = rr < n ? 0xffffffffu : 0u;
-            const uint4 xq = pre[q];
+            const uint4 xq = pre[NH + q];
             const uint32_t wv[4] = {xq.x & keep, xq.y & keep, xq.z & keep, xq.w & keep};
             unsigned short *dst = sXT + (cx0 * 8) * kNP64 + rr;
 #pragma unroll
@@ -259,52 +265,59 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     };
 
     if (nU <= 0) return;
-    // (b, h) of the current unit and of the next two
+    // (b, h) of the current unit and of the next three
     int cb = ub0, ch = uh0, b1 = ub0, h1 = uh0;
     step(b1, h1);
     int b2 = b1, h2 = h1;
     step(b2, h2);
-    // ---- prologue: unit 0 into LDS, unit 1 into registers ---------------------------------------
-    float D_h = 0.f;                 // D of the current unit (Y threads)
+    int b3 = b2, h3 = h2;
+    step(b3, h3);
+    // ---- prologue: unit 0 into LDS; h0 of units 1 (G threads) and 2 (Y threads), x of unit 1
+    //      into registers.  All first loads are issued before anything is waited for. -------------
     if (isY) {
         if (h0) {
             load_H(cb, ch);
             stage_H();
-            D_h = rD;
-            if (nU > 1) load_H(b1, h1);
-        } else if (D) {
-            D_h = D[ch];
+            if (nU > 2) load_H(b2, h2);
+        } else if (rt == 0) {
+            *sDh = D ? D[ch] : 0.f;
         }
     } else {
         load_X(cb, ch);
+        if (wave == kTreeWave) load_T(cb, ch);
+        restage_CB(cb, ch);                     // waits for its own loads only (in-order return)
         if (wave == kTreeWave) {
-            load_T(cb, ch);
             stage_T();
             if (nU > 1) load_T(b1, h1);
         }
-        restage_CB(cb, ch);
         stage_X();
-        if (nU > 1) load_X(b1, h1);
+        if (nU > 1) {
+            load_X(b1, h1);
+            if (h0) load_H(b1, h1);
+        }
     }
 
-    floatx16 gt;     // G waves: Gt tile of the current (sequence, group), kept across its heads
+    // One accumulator set serves both roles: the Y waves' Yt tiles of the current unit, or
+    // (acc[0]) the G waves' Gt tile of the current (sequence, group), kept across its heads.
+    floatx16 acc[YQ];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) gt[e] = 0.f;
+    for (int q = 0; q < YQ; ++q)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
 
     for (int k = 0; k < nU; ++k) {
         [[maybe_unused]] const int prof_unit = cb * H + ch;  // only read by probe builds
         __syncthreads();                                      // barrier 1: unit k is staged
         STREE_PHASE_CLOCK(0);
         const int bad = *sBad;
+        const float D_h = *sDh;
         if (status && ch == 0 && tid == 0) status[cb] = bad;
 
-        floatx16 acc[YQ];
-#pragma unroll
-        for (int q = 0; q < YQ; ++q)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
-
         if (isY) {
+#pragma unroll
+            for (int q = 0; q < YQ; ++q)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
             // ---- phase 1: Yt = h0b C^T, then *= exp(s_i) -------------------------------------------
             if (h0 && !bad) {
                 const bf16_t *cp = &sC[il * SP + 8 * lh];
@@ -324,6 +337,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
 #pragma unroll
                         for (int q = 0; q < YQ; ++q)
                             acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf[q][j], cf[j], acc[q], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);   // keep the batches apart: register budget
                 }
                 const float e = __builtin_amdgcn_exp2f(sS2[il]);
 #pragma unroll
@@ -336,6 +350,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             // ---- phase 2: Gt = B C^T (only when the C/B tiles are new), mask and decay -> M ----------
             const int jt = (wave - 4) >> 1;
             STREE_PHASE_CLOCK_G(9);
+            floatx16 &gt = acc[0];
             if (fresh_at(k, ch)) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) gt[e] = 0.f;
@@ -357,11 +372,13 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             STREE_PHASE_CLOCK_G(10);
             const float s2_i = sS2[il];
             const uint32_t mrow = sMask[il * 2 + jt] >> (4 * lh);   // bit 8*rg + e <-> j = jl + e
+            float4 uj[4];
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) uj[rg] = *reinterpret_cast<const float4 *>(&sU[jt * 32 + 8 * rg + 4 * lh]);
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 const int jl = jt * 32 + 8 * rg + 4 * lh;
-                const float4 uj = *reinterpret_cast<const float4 *>(&sU[jl]);
-                const float ujv[4] = {uj.x, uj.y, uj.z, uj.w};
+                const float ujv[4] = {uj[rg].x, uj[rg].y, uj[rg].z, uj[rg].w};
                 bf16x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -377,7 +394,8 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         __syncthreads();                                      // barrier 2: M is ready; h0b (and B) dead
         STREE_PHASE_CLOCK(2);
 
-        const bool more = k + 1 < nU, more2 = k + 2 < nU;
+        const bool more = k + 1 < nU, more2 = k + 2 < nU, more3 = k + 3 < nU;
+        const bool y_stages = (k & 1) != 0;    // unit k+1 is even: its h0 sits in the Y threads
         if (isY) {
             // ---- phase 3: Yt += Xt M^T over j <= i only (nodes i < 32 have no ancestor j >= 32:
             //      that quadrant of M is never written or read); y = Yt + D x -> own 32x32 block
@@ -385,14 +403,36 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
 #pragma unroll
             for (int q = 0; q < YQ; ++q) {
                 const int pt = (wave + 4 * q) >> 1;
+                float xv[16];   // x[i][p] of this lane's node for the 16 p of its accumulator
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        xv[4 * rg + e] =
+                            __uint_as_float((uint32_t)sXT[(pt * 32 + 8 * rg + 4 * lh + e) * kNP64 + il] << 16);
                 if (!bad) {
                     const bf16_t *ap = reinterpret_cast<const bf16_t *>(sXT) + (pt * 32 + l32) * kNP64 + 8 * lh;
                     const bf16_t *bp = &sM[il * kNP64 + 8 * lh];
-                    const int kend = it ? kB64 : 32;
-                    for (int k0 = 0; k0 < kend; k0 += 16) {
-                        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ap + k0);
-                        const bf16x8 bb = *reinterpret_cast<const bf16x8 *>(bp + k0);
-                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[q], 0, 0, 0);
+                    if (it) {
+                        bf16x8 a[4], bb[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            a[j] = *reinterpret_cast<const bf16x8 *>(ap + 16 * j);
+                            bb[j] = *reinterpret_cast<const bf16x8 *>(bp + 16 * j);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], bb[j], acc[q], 0, 0, 0);
+                    } else {
+                        bf16x8 a[2], bb[2];
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            a[j] = *reinterpret_cast<const bf16x8 *>(ap + 16 * j);
+                            bb[j] = *reinterpret_cast<const bf16x8 *>(bp + 16 * j);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], bb[j], acc[q], 0, 0, 0);
                     }
                 }
 #pragma unroll
@@ -400,21 +440,19 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                     const int p0 = pt * 32 + 8 * rg + 4 * lh;
                     bf16x4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float xv = __uint_as_float((uint32_t)sXT[(p0 + e) * kNP64 + il] << 16);
-                        o[e] = bad ? (bf16_t)0.f : (bf16_t)fmaf(D_h, xv, acc[q][4 * rg + e]);
-                    }
+                    for (int e = 0; e < 4; ++e)
+                        o[e] = bad ? (bf16_t)0.f : (bf16_t)fmaf(D_h, xv[4 * rg + e], acc[q][4 * rg + e]);
                     *reinterpret_cast<bf16x4 *>(&sYo[il * YOP + p0]) = o;
                 }
             }
             STREE_PHASE_CLOCK(3);
             // next unit's state tile (its loads have been in flight for a whole unit period)
-            float D_next = 0.f;
-            if (h0 && more) {
-                stage_H();
-                D_next = rD;
-            } else if (D && more) {
-                D_next = D[h1];
+            if (more) {
+                if (h0) {
+                    if (y_stages) stage_H();
+                } else if (rt == 0) {
+                    *sDh = D ? D[h1] : 0.f;
+                }
             }
             STREE_PHASE_CLOCK(4);
             // y rows: each wave stores the 32x32 blocks it has just written itself (LDS executes a
@@ -437,10 +475,13 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                     }
                 }
             }
-            if (h0 && more2) load_H(b2, h2);
-            D_h = D_next;
+            if (h0 && more3 && y_stages) load_H(b3, h3);
             STREE_PHASE_CLOCK(5);
         } else if (more) {
+            if (h0 && !y_stages) {
+                stage_H();
+                if (more3) load_H(b3, h3);
+            }
             if (wave == kTreeWave) {
                 stage_T();
                 if (more2) load_T(b2, h2);
@@ -456,7 +497,8 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         STREE_PHASE_CLOCK(7);
         cb = b1; ch = h1;
         b1 = b2; h1 = h2;
-        step(b2, h2);
+        b2 = b3; h2 = h3;
+        step(b3, h3);
     }
 }
 
@@ -464,21 +506,14 @@ template <int P, int S>
 hipError_t launch64_ps(const stree_dims &d, const int32_t *parent, const void *x, const float *dt, const float *A,
                        const void *Bm, const void *Cm, const float *D, const float *h0, void *y,
                        int32_t *status, hipStream_t st) {
-    constexpr size_t lds = Lds64<P, S>::total;
+    constexpr size_t lds = Lds64<P, S>::total;   // static LDS of the kernel (upper bound)
     constexpr int WPE = (2 * (lds + 64) <= 160 * 1024) ? 4 : 2;
-    static bool attr_set = false;  // dynamic LDS above 64 KB needs the attribute once
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_mfma64_kernel<P, S, WPE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int n_units = d.batch * d.nheads;
     const int per_cu = (int)((160 * 1024) / (lds + 64));      // resident workgroups per CU by LDS
     int grid = (n_units + 7) / 8 * 8;
     const int cap = 256 * (per_cu < 1 ? 1 : per_cu);
     if (grid > cap) grid = cap;
-    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE>), dim3(grid), dim3(kT64), lds, st, parent, d.nnodes,
+    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE>), dim3(grid), dim3(kT64), 0, st, parent, d.nnodes,
                        d.batch, d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A,
                        (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,
                        (bf16_t *)y, status);
