@@ -13,28 +13,63 @@ namespace stree {
 constexpr int kSlab = 4096;        // state elements per workgroup (4 float4 per thread)
 constexpr int kPathChunk = 16;     // path nodes staged in LDS at a time
 
-// grid (ceil(P*S / kSlab), H, B)
-template <typename T>
+// Path of the accepted node k for trees of at most 64 nodes, by one wave with no LDS and no
+// barrier: lane j owns node j; pointer doubling over the parent array with cross-lane reads
+// gives every lane s_j (the paper's A_tree) and its ancestor bit row; lane k's values are then
+// broadcast.  Returns the tree status (uniform).  On success lane j holds in `coef` the weight
+// dt_j * exp(s_k - s_j) of node j if it lies on path(k) and its position on the path (root
+// first) in `pos`, else pos = -1; `len` = nodes on the path, `decay` = exp(s_k).
+__device__ __forceinline__ int wave_path(int lane, int n, int k, int parent_j, float dt_j, float A_h, int &pos,
+                                         float &coef, int &len, float &decay) {
+    int p = -1;
+    bool ok = true;
+    if (lane < n) {
+        p = parent_j;
+        ok = (lane == 0) ? (p == -1) : (p >= 0 && p < lane);
+        if (!ok) p = -1;
+    }
+    const unsigned long long badmask = __ballot(!ok);
+    if (badmask) return __ffsll((long long)badmask);
+    float s = lane < n ? dt_j * A_h : 0.f;
+    unsigned long long m = lane < n ? (1ull << lane) : 0ull;
+    for (int round = 0; round < 6; ++round) {
+        if (!__any(p >= 0)) break;
+        const int q = p >= 0 ? p : lane;
+        const float rs = __shfl(s, q);
+        const int rp = __shfl(p, q);
+        const unsigned long long rm = __shfl(m, q);
+        if (p >= 0) {
+            s += rs;
+            m |= rm;
+            p = rp;
+        }
+    }
+    const float s_k = __shfl(s, k);
+    const unsigned long long m_k = __shfl(m, k);
+    const bool on = (m_k >> lane) & 1ull;
+    pos = on ? __popcll(m_k & ((1ull << lane) - 1ull)) : -1;   // ancestors have smaller labels
+    coef = on ? dt_j * __expf(s_k - s) : 0.f;
+    len = __popcll(m_k);
+    decay = __expf(s_k);
+    return 0;
+}
+
+// grid (ceil(P*S / kSlab), H, B); dynamic LDS = kPathChunk * (P + S) floats
+template <typename T, bool WAVE>
 __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     const int32_t *__restrict__ parent, const int32_t *__restrict__ accepted, int n, int H, int P, int S,
     int G, const T *__restrict__ x, long x_sn, const float *__restrict__ dt, const float *__restrict__ A,
     const T *__restrict__ Bm, long b_sn, const float *h0, float *h_out, int32_t *__restrict__ status) {
-    __shared__ TreeLds tree;
-    __shared__ uint32_t mask[kMaxNodes * kMaxWords];
+    extern __shared__ __align__(16) float rows[];     // xs[kPathChunk][P] then bs[kPathChunk][S]
     __shared__ int path[kMaxNodes];
     __shared__ float coef[kMaxNodes];
-    __shared__ float xs[kPathChunk][kMaxNodes];
-    __shared__ __align__(16) float bs[kPathChunk][kMaxNodes];
-    const int tid = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+    __shared__ float scal[2];                          // decay, then path length (as int bits)
+    __shared__ int bad_s;
+    float *xs = rows, *bs = rows + kPathChunk * P;
+    const int tid = threadIdx.x, lane = tid & 63, h = blockIdx.y, b = blockIdx.z;
     const int g = h / (H / G);
-    const int words = (n + 31) / 32;
-    const float A_h = A[h];
-    const float dt_i = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
-    const int bad = build_tree_index(tree, mask, parent + (size_t)b * n, n, n, words, dt_i, A_h);
-    const int k = accepted[b];
-    const bool k_bad = (k < -1) || (k >= n);
-    if (status && blockIdx.x == 0 && h == 0 && tid == 0) status[b] = bad ? bad : (k_bad ? -1 : 0);
 
+    // the state slab first: these loads fly while the path is worked out
     const int PS = P * S;
     const size_t sbase = ((size_t)b * H + h) * PS;
     const int e0 = blockIdx.x * kSlab + tid * 4;
@@ -44,6 +79,60 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
         const int e = e0 + q * (kThreads * 4);
         acc[q] = (h0 && e < PS) ? *reinterpret_cast<const float4 *>(h0 + sbase + e) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+
+    const int k = accepted[b];
+    const bool k_bad = (k < -1) || (k >= n);
+    const float A_h = A[h];
+    int bad, len;
+    float decay;
+    if constexpr (WAVE) {
+        // n <= 64: wave 0 finds the path in registers and publishes it
+        if (tid < 64) {
+            const int node = min(lane, n - 1);
+            const int par_j = parent[(size_t)b * n + node];
+            const float dt_j = dt[((size_t)b * n + node) * H + h];
+            int pos, ln;
+            float cf, dc;
+            const int st = wave_path(lane, n, (k >= 0 && !k_bad) ? k : 0, par_j, dt_j, A_h, pos, cf, ln, dc);
+            if (st == 0 && pos >= 0) {
+                path[pos] = lane;
+                coef[pos] = cf;
+            }
+            if (lane == 0) {
+                bad_s = st;
+                scal[0] = dc;
+                scal[1] = __int_as_float(ln);
+            }
+        }
+        __syncthreads();
+        bad = bad_s;
+        decay = scal[0];
+        len = __float_as_int(scal[1]);
+    } else {
+        __shared__ TreeLds tree;
+        __shared__ uint32_t mask[kMaxNodes * kMaxWords];
+        const int words = (n + 31) / 32;
+        const float dt_i = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
+        bad = build_tree_index(tree, mask, parent + (size_t)b * n, n, n, words, dt_i, A_h);
+        len = 0;
+        decay = 1.f;
+        if (!bad && k >= 0 && !k_bad) {
+            // compact path(k) (ancestors have smaller labels, so ascending label = root first)
+            const float s_k = tree.s[k];
+            if (tid < n && mask_bit(mask, words, k, tid)) {
+                int pos = 0;
+                for (int w = 0; w < (tid >> 5); ++w) pos += __popc(mask[k * words + w]);
+                pos += __popc(mask[k * words + (tid >> 5)] & ((1u << (tid & 31)) - 1u));
+                path[pos] = tid;
+                coef[pos] = tree.dt[tid] * __expf(s_k - tree.s[tid]);
+            }
+            len = tree.cnt[k];
+            decay = __expf(s_k);
+        }
+        __syncthreads();
+    }
+    if (status && blockIdx.x == 0 && h == 0 && tid == 0) status[b] = bad ? bad : (k_bad ? -1 : 0);
+
     if (bad || k < 0 || k_bad) {  // pass the state through
         if (h_out != h0 || !h0) {
 #pragma unroll
@@ -54,42 +143,37 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
         }
         return;
     }
-    // compact path(k) (ancestors have smaller labels, so ascending label = root first)
-    const float s_k = tree.s[k];
-    if (tid < n && mask_bit(mask, words, k, tid)) {
-        int pos = 0;
-        for (int w = 0; w < (tid >> 5); ++w) pos += __popc(mask[k * words + w]);
-        pos += __popc(mask[k * words + (tid >> 5)] & ((1u << (tid & 31)) - 1u));
-        path[pos] = tid;
-        coef[pos] = tree.dt[tid] * __expf(s_k - tree.s[tid]);
-    }
-    const int len = tree.cnt[k];
-    const float decay = __expf(s_k);
     int pq[4], sq[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int e = e0 + q * (kThreads * 4);
         pq[q] = e < PS ? e / S : 0;
         sq[q] = e < PS ? e % S : 0;
-        acc[q].x *= decay; acc[q].y *= decay; acc[q].z *= decay; acc[q].w *= decay;
     }
-    __syncthreads();
     const T *xb = x + (size_t)b * n * x_sn + (size_t)h * P;
     const T *Bb = Bm + (size_t)b * n * b_sn + (size_t)g * S;
+    bool scaled = false;
     for (int c0 = 0; c0 < len; c0 += kPathChunk) {
         const int cn = min(kPathChunk, len - c0);
         for (int idx = tid; idx < cn * (P + S); idx += kThreads) {
             const int t = idx / (P + S), col = idx % (P + S);
             const int node = path[c0 + t];
-            if (col < P) xs[t][col] = to_f32(xb[(size_t)node * x_sn + col]);
-            else bs[t][col - P] = coef[c0 + t] * to_f32(Bb[(size_t)node * b_sn + (col - P)]);
+            if (col < P) xs[t * P + col] = to_f32(xb[(size_t)node * x_sn + col]);
+            else bs[t * S + col - P] = coef[c0 + t] * to_f32(Bb[(size_t)node * b_sn + (col - P)]);
+        }
+        if (!scaled) {   // the state loads are first needed here
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                acc[q].x *= decay; acc[q].y *= decay; acc[q].z *= decay; acc[q].w *= decay;
+            }
+            scaled = true;
         }
         __syncthreads();
         for (int t = 0; t < cn; ++t) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float xv = xs[t][pq[q]];
-                const float4 bv = *reinterpret_cast<const float4 *>(&bs[t][sq[q]]);
+                const float xv = xs[t * P + pq[q]];
+                const float4 bv = *reinterpret_cast<const float4 *>(&bs[t * S + sq[q]]);
                 acc[q].x = fmaf(xv, bv.x, acc[q].x);
                 acc[q].y = fmaf(xv, bv.y, acc[q].y);
                 acc[q].z = fmaf(xv, bv.z, acc[q].z);
@@ -147,14 +231,20 @@ hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const
                                void *conv_state_out, int32_t *status, hipStream_t st) {
     const int PS = d.headdim * d.dstate;
     const dim3 grid((PS + kSlab - 1) / kSlab, d.nheads, d.batch);
-    if (d.io_dtype == STREE_BF16)
-        hipLaunchKernelGGL(commit_h_kernel<bf16_t>, grid, dim3(kThreads), 0, st, parent, accepted, d.nnodes,
-                           d.nheads, d.headdim, d.dstate, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A,
-                           (const bf16_t *)Bm, (long)d.b_stride_n, h0, h_out, status);
-    else
-        hipLaunchKernelGGL(commit_h_kernel<float>, grid, dim3(kThreads), 0, st, parent, accepted, d.nnodes,
-                           d.nheads, d.headdim, d.dstate, d.ngroups, (const float *)x, (long)d.x_stride_n, dt, A,
-                           (const float *)Bm, (long)d.b_stride_n, h0, h_out, status);
+    const size_t lds = (size_t)kPathChunk * (d.headdim + d.dstate) * sizeof(float);
+#define STREE_COMMIT_LAUNCH(TT, WV)                                                                           \
+    hipLaunchKernelGGL((commit_h_kernel<TT, WV>), grid, dim3(kThreads), lds, st, parent, accepted, d.nnodes,     \
+                       d.nheads, d.headdim, d.dstate, d.ngroups, (const TT *)x, (long)d.x_stride_n, dt, A,      \
+                       (const TT *)Bm, (long)d.b_stride_n, h0, h_out, status)
+    const bool wave = d.nnodes <= 64;
+    if (d.io_dtype == STREE_BF16) {
+        if (wave) STREE_COMMIT_LAUNCH(bf16_t, true);
+        else STREE_COMMIT_LAUNCH(bf16_t, false);
+    } else {
+        if (wave) STREE_COMMIT_LAUNCH(float, true);
+        else STREE_COMMIT_LAUNCH(float, false);
+    }
+#undef STREE_COMMIT_LAUNCH
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || !conv_state_out) return err;
     const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;

@@ -35,7 +35,9 @@ struct Vec16<bf16_t> {
     }
 };
 
-// grid (ceil(Cc / (VEC*256)), N, B)
+constexpr int kConvNodes = 4;   // nodes per workgroup: weights and the tree check are shared
+
+// grid (ceil(Cc / (VEC*256)), ceil(N / kConvNodes), B)
 template <typename T, int W>
 __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
     const int32_t *__restrict__ parent, int n, int Cc, int silu, const T *__restrict__ xbc_pre,
@@ -44,7 +46,7 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
     constexpr int VEC = Vec16<T>::N;
     __shared__ int par[kMaxNodes];
     __shared__ int bad_s;
-    const int tid = threadIdx.x, i = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, i0 = blockIdx.y * kConvNodes, b = blockIdx.z;
     if (tid == 0) bad_s = 0x7fffffff;
     __syncthreads();
     if (tid < n) {
@@ -55,53 +57,61 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
     }
     __syncthreads();
     const int bad = bad_s == 0x7fffffff ? 0 : bad_s;
-    if (status && blockIdx.x == 0 && i == 0 && tid == 0) status[b] = bad;
+    if (status && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) status[b] = bad;
     const int c0 = (blockIdx.x * kThreads + tid) * VEC;
     if (c0 >= Cc) return;
-    T *dst = out + ((size_t)b * n + i) * Cc + c0;
-    float acc[VEC];
     if (bad) {
+        float z[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-        Vec16<T>::store(dst, acc);
+        for (int e = 0; e < VEC; ++e) z[e] = 0.f;
+        for (int i = i0; i < min(i0 + kConvNodes, n); ++i) Vec16<T>::store(out + ((size_t)b * n + i) * Cc + c0, z);
         return;
-    }
-    // rows feeding node i: k-th ancestor, or conv_state once above the root
-    const T *rows[W];
-    int v = i, above = 0;
-#pragma unroll
-    for (int k = 0; k < W; ++k) {
-        if (v >= 0) {
-            rows[k] = xbc_pre + ((size_t)b * n + v) * Cc + c0;
-            v = par[v];
-        } else {
-            ++above;  // `above` rows over the root: state row (W-1) - above
-            rows[k] = conv_state + ((size_t)b * (W - 1) + (W - 1 - above)) * Cc + c0;
-        }
     }
     float wv[W][VEC];  // flat [e*W + j] = w[c0+e][j]
 #pragma unroll
     for (int q = 0; q < W; ++q) Vec16<T>::load(w + (size_t)c0 * W + q * VEC, wv[q]);
-    if (bias) Vec16<T>::load(bias + c0, acc);
+    float bv[VEC];
+    if (bias) Vec16<T>::load(bias + c0, bv);
     else {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+        for (int e = 0; e < VEC; ++e) bv[e] = 0.f;
     }
+    // all gathered rows of the workgroup's nodes are requested before any is used
+    float r[kConvNodes][W][VEC];
 #pragma unroll
-    for (int k = 0; k < W; ++k) {
-        float r[VEC];
-        Vec16<T>::load(rows[k], r);
+    for (int m = 0; m < kConvNodes; ++m) {
+        const int i = min(i0 + m, n - 1);
+        int v = i, above = 0;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            const int f = e * W + (W - 1 - k);
-            acc[e] = fmaf((&wv[0][0])[f], r[e], acc[e]);
+        for (int k = 0; k < W; ++k) {   // k-th ancestor, or conv_state once above the root
+            const T *src;
+            if (v >= 0) {
+                src = xbc_pre + ((size_t)b * n + v) * Cc + c0;
+                v = par[v];
+            } else {
+                ++above;  // `above` rows over the root: state row (W-1) - above
+                src = conv_state + ((size_t)b * (W - 1) + (W - 1 - above)) * Cc + c0;
+            }
+            Vec16<T>::load(src, r[m][k]);
         }
     }
-    if (silu) {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = acc[e] / (1.f + __expf(-acc[e]));
+    for (int m = 0; m < kConvNodes; ++m) {
+        if (i0 + m < n) {
+            float acc[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = bv[e];
+#pragma unroll
+            for (int k = 0; k < W; ++k)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] = fmaf((&wv[0][0])[e * W + (W - 1 - k)], r[m][k][e], acc[e]);
+            if (silu) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] = acc[e] / (1.f + __expf(-acc[e]));
+            }
+            Vec16<T>::store(out + ((size_t)b * n + i0 + m) * Cc + c0, acc);
+        }
     }
-    Vec16<T>::store(dst, acc);
 }
 
 template <typename T>
@@ -110,7 +120,7 @@ static hipError_t launch_conv_t(const stree_dims &d, const int32_t *parent, cons
                                 void *xbc_out, int32_t *status, hipStream_t st) {
     constexpr int VEC = Vec16<T>::N;
     const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
-    const dim3 grid((Cc / VEC + kThreads - 1) / kThreads, d.nnodes, d.batch);
+    const dim3 grid((Cc / VEC + kThreads - 1) / kThreads, (d.nnodes + kConvNodes - 1) / kConvNodes, d.batch);
     const int silu = (d.flags & STREE_FLAG_CONV_SILU) ? 1 : 0;
 #define STREE_CONV_CASE(WW)                                                                             \
     case WW:                                                                                            \
