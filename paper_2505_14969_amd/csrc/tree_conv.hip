@@ -37,16 +37,24 @@ struct Vec16<bf16_t> {
 
 constexpr int kConvNodes = 4;   // nodes per workgroup: weights and the tree check are shared
 
-// grid (ceil(Cc / (VEC*256)), ceil(N / kConvNodes), B)
+// 1-D grid of ceil8(B * cblocks * nblocks) workgroups.  Workgroup ids are dealt to the 8 XCDs
+// round-robin by the hardware; the id is remapped so that each XCD gets a contiguous range of
+// (sequence, channel block, node block) with the node block fastest: the ancestors' rows that the
+// node blocks of one (sequence, channel block) share are then fetched into one L2 only.
 template <typename T, int W>
 __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
-    const int32_t *__restrict__ parent, int n, int Cc, int silu, const T *__restrict__ xbc_pre,
+    const int32_t *__restrict__ parent, int nbatch, int n, int Cc, int silu, const T *__restrict__ xbc_pre,
     const T *__restrict__ conv_state, const T *__restrict__ w, const T *__restrict__ bias,
     T *__restrict__ out, int32_t *__restrict__ status) {
     constexpr int VEC = Vec16<T>::N;
     __shared__ int par[kMaxNodes];
     __shared__ int bad_s;
-    const int tid = threadIdx.x, i0 = blockIdx.y * kConvNodes, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const int cblocks = (Cc / VEC + kThreads - 1) / kThreads, nblocks = (n + kConvNodes - 1) / kConvNodes;
+    const int logical = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    if (logical >= nbatch * cblocks * nblocks) return;
+    const int nb = logical % nblocks, cblk = (logical / nblocks) % cblocks, b = logical / (nblocks * cblocks);
+    const int i0 = nb * kConvNodes;
     if (tid == 0) bad_s = 0x7fffffff;
     __syncthreads();
     if (tid < n) {
@@ -57,8 +65,8 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
     }
     __syncthreads();
     const int bad = bad_s == 0x7fffffff ? 0 : bad_s;
-    if (status && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) status[b] = bad;
-    const int c0 = (blockIdx.x * kThreads + tid) * VEC;
+    if (status && cblk == 0 && nb == 0 && tid == 0) status[b] = bad;
+    const int c0 = (cblk * kThreads + tid) * VEC;
     if (c0 >= Cc) return;
     if (bad) {
         float z[VEC];
@@ -120,11 +128,12 @@ static hipError_t launch_conv_t(const stree_dims &d, const int32_t *parent, cons
                                 void *xbc_out, int32_t *status, hipStream_t st) {
     constexpr int VEC = Vec16<T>::N;
     const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
-    const dim3 grid((Cc / VEC + kThreads - 1) / kThreads, (d.nnodes + kConvNodes - 1) / kConvNodes, d.batch);
+    const int total = ((Cc / VEC + kThreads - 1) / kThreads) * ((d.nnodes + kConvNodes - 1) / kConvNodes) * d.batch;
+    const dim3 grid((total + 7) / 8 * 8);
     const int silu = (d.flags & STREE_FLAG_CONV_SILU) ? 1 : 0;
 #define STREE_CONV_CASE(WW)                                                                             \
     case WW:                                                                                            \
-        hipLaunchKernelGGL((tree_conv_kernel<T, WW>), grid, dim3(kThreads), 0, st, parent, d.nnodes, Cc, \
+        hipLaunchKernelGGL((tree_conv_kernel<T, WW>), grid, dim3(kThreads), 0, st, parent, d.batch, d.nnodes, Cc, \
                            silu, (const T *)xbc_pre, (const T *)conv_state, (const T *)conv_w,          \
                            (const T *)conv_b, (T *)xbc_out, status);                                    \
         break;
