@@ -21,12 +21,11 @@
 //     Y: phase 1  Yt = h0b C^T, *= exp(s_i)
 //     G: phase 2  (Gt = B C^T if the tiles are new) M = L ? Gt exp(s_i - s_j) dt_j : 0 -> LDS
 //   barrier 2   (h0b tile and the tree arrays are dead from here on)
-//     Y: phase 3  Yt += Xt M^T; y = Yt + D x -> bf16 rows in LDS; store own y rows from LDS
+//     Y: phase 3  Yt += Xt M^T; y = Yt + D x -> bf16, stored straight from the accumulators
 //     Y or G (whoever carries unit k+1): h0(k+1) regs -> LDS as bf16; issue h0(k+3) loads
-//     G: new C, B tiles if unit k+1 starts another sequence or group
+//     G: new C tile if unit k+1 starts another sequence or group
 //     T: tree index of unit k+1, issue parent/dt (k+2) loads
-//   barrier 3   (X^T tile is dead)
-//     G: x(k+1) regs -> LDS transposed, issue x(k+2) loads
+//     G: x(k+1) regs -> the other X^T tile in LDS, issue x(k+2) loads
 // so the big global loads (h0, x) are in flight for a whole unit period.
 #include "common.hpp"
 #include "launch.hpp"
@@ -46,22 +45,12 @@ constexpr int kB64 = 64;
 constexpr int kNP64 = kB64 + 8;
 constexpr int kT64 = 512;   // 8 waves: 4 Y waves, 3 G waves, 1 tree wave
 
+// static LDS of the kernel below (C, B, h0b tiles, two X^T tiles, M, tree arrays)
 template <int P, int S>
 struct Lds64 {
     static constexpr int SP = S + 8;
-    static constexpr int YOP = P + 8;   // padded bf16 output row
-    static constexpr size_t c_bytes = (size_t)kB64 * SP * 2;
-    static constexpr size_t off_c = 0;
-    static constexpr size_t off_b = off_c + c_bytes;
-    static constexpr size_t off_h = off_b + c_bytes;
-    static constexpr size_t off_xt = off_h + (size_t)P * SP * 2;
-    static constexpr size_t off_m = off_xt + (size_t)P * kNP64 * 2;
-    static constexpr size_t off_yo = off_m + (size_t)kB64 * kNP64 * 2;
-    static constexpr size_t off_s = off_yo + (size_t)kB64 * YOP * 2;     // float s[64]
-    static constexpr size_t off_dt = off_s + 256;                       // float u[64]
-    static constexpr size_t off_mask = off_dt + 256;                    // uint32 mask[64][2]
-    static constexpr size_t off_bad = off_mask + 512;                   // int
-    static constexpr size_t total = off_bad + 16;
+    static constexpr size_t total = (size_t)2 * kB64 * SP * 2 + (size_t)P * SP * 2 + (size_t)2 * P * kNP64 * 2 +
+                                    (size_t)kB64 * kNP64 * 2 + 1040;
 };
 
 // Wave-level tree index for n <= 64: lane i owns node i; pointer doubling with
@@ -112,7 +101,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
     bf16_t *__restrict__ y, int32_t *__restrict__ status) {
     using L = Lds64<P, S>;
-    constexpr int SP = L::SP, YOP = L::YOP;
+    constexpr int SP = L::SP;
     constexpr int kHalf = kT64 / 2;                 // threads per role group
     constexpr int NC = kB64 * (S / 8) / kHalf;      // 16-byte chunks of C (and of B) per G thread
     constexpr int NX = kB64 * (P / 8) / kHalf;      // of x per G thread; of y per Y thread
@@ -125,9 +114,8 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     __shared__ __align__(16) bf16_t sC[kB64 * SP];
     __shared__ __align__(16) bf16_t sB[kB64 * SP];
     __shared__ __align__(16) bf16_t sH[P * SP];
-    __shared__ __align__(16) unsigned short sXT[P * kNP64];
+    __shared__ __align__(16) unsigned short sXT2[2][P * kNP64];   // X^T of units k and k+1
     __shared__ __align__(16) bf16_t sM[kB64 * kNP64];
-    __shared__ __align__(16) bf16_t sYo[kB64 * YOP];
     __shared__ __align__(16) float sS2[kB64];
     __shared__ __align__(16) float sU[kB64];
     __shared__ uint32_t sMask[kB64 * 2];
@@ -192,7 +180,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
 #pragma unroll
         for (int q = 0; q < NH; ++q) pre[q] = *reinterpret_cast<const uint4 *>(hb + q * (kHalf * 16) + off);
     };
-    // C and B tiles of unit k: global -> registers -> LDS in one go (G threads).  Runs only when
+    // C and B tiles of a unit: global -> registers -> LDS in one go (G threads).  Runs only when
     // the (sequence, group) changes, i.e. about once per workgroup.
     auto restage_CB = [&](int b, int h) {
         const int g = h / hpg;
@@ -225,9 +213,9 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 xb + (uint32_t)(min(rx0 + q * kRowsX, n - 1) * (int)x_sn + cx0 * 8) * 2u);
     };
     auto load_T = [&](int b, int h) {       // tree wave
-        const int node = min(lane, n - 1);
-        rpar = parent[(size_t)b * n + node];
-        rdt = dt[((size_t)b * n + node) * H + h];
+        const int node = min(opaque(lane), n - 1);
+        rpar = parent[(uint32_t)(b * n + node)];
+        rdt = dt[(uint32_t)((b * n + node) * H + h)];
         rA = A[h];
     };
     // ---- registers -> LDS -------------------------------------------------------------------------
@@ -243,7 +231,8 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         }
         if (rt == 0) *sDh = rD;      // D of that unit, for the Y waves
     };
-    auto stage_X = [&]() {
+    auto stage_X = [&](int buf) {
+        unsigned short *sXT = sXT2[buf];
         const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
 #pragma unroll
         for (int q = 0; q < NX; ++q) {
@@ -290,7 +279,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             stage_T();
             if (nU > 1) load_T(b1, h1);
         }
-        stage_X();
+        stage_X(0);
         if (nU > 1) {
             load_X(b1, h1);
             if (h0) load_H(b1, h1);
@@ -309,6 +298,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         [[maybe_unused]] const int prof_unit = cb * H + ch;  // only read by probe builds
         __syncthreads();                                      // barrier 1: unit k is staged
         STREE_PHASE_CLOCK(0);
+        const unsigned short *sXT = sXT2[k & 1];
         const int bad = *sBad;
         const float D_h = *sDh;
         if (status && ch == 0 && tid == 0) status[cb] = bad;
@@ -391,7 +381,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
             STREE_PHASE_CLOCK_G(11);
         }
-        __syncthreads();                                      // barrier 2: M is ready; h0b (and B) dead
+        __syncthreads();                                      // barrier 2: M is ready; h0b, C and the tree arrays are dead
         STREE_PHASE_CLOCK(2);
 
         const bool more = k + 1 < nU, more2 = k + 2 < nU, more3 = k + 3 < nU;
@@ -400,6 +390,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             // ---- phase 3: Yt += Xt M^T over j <= i only (nodes i < 32 have no ancestor j >= 32:
             //      that quadrant of M is never written or read); y = Yt + D x -> own 32x32 block
             //      of the bf16 staging rows ------------------------------------------------------------
+            bf16x4 yreg[YQ][4];
 #pragma unroll
             for (int q = 0; q < YQ; ++q) {
                 const int pt = (wave + 4 * q) >> 1;
@@ -435,14 +426,14 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                             acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], bb[j], acc[q], 0, 0, 0);
                     }
                 }
+                // y = Yt + D x; kept in registers as bf16 until the stores further down
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg) {
-                    const int p0 = pt * 32 + 8 * rg + 4 * lh;
                     bf16x4 o;
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         o[e] = bad ? (bf16_t)0.f : (bf16_t)fmaf(D_h, xv[4 * rg + e], acc[q][4 * rg + e]);
-                    *reinterpret_cast<bf16x4 *>(&sYo[il * YOP + p0]) = o;
+                    yreg[q][rg] = o;
                 }
             }
             STREE_PHASE_CLOCK(3);
@@ -455,24 +446,22 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 }
             }
             STREE_PHASE_CLOCK(4);
-            // y rows: each wave stores the 32x32 blocks it has just written itself (LDS executes a
-            // wave's accesses in order, no barrier needed), 16 bytes per lane.  The stores go out
-            // after the wait for the h0 loads above and are long complete at the next such wait:
-            // on gfx9 loads and stores share one counter and complete out of order with respect
-            // to each other, so a store in flight would turn that wait into a wait for everything.
-            {
+            // y: a lane owns node il and 4 consecutive p per register group: 8-byte stores, the two
+            // lane halves completing 16 contiguous bytes of a row (L2 merges the pieces of a line).
+            // The stores go out after the wait for the h0 loads above and are long complete at
+            // the next such wait: on gfx9 loads and stores share one counter and complete out of
+            // order with respect to each other, so a store in flight would turn that wait into a
+            // wait for everything.
+            if (il < n) {
                 char *yb = reinterpret_cast<char *>(y + (size_t)cb * n * H * P + (size_t)ch * P);
-                const int ln = opaque(lane);
+                const int row = opaque(il);
 #pragma unroll
                 for (int q = 0; q < YQ; ++q) {
                     const int pt = (wave + 4 * q) >> 1;
 #pragma unroll
-                    for (int half = 0; half < 2; ++half) {
-                        const int row = it * 32 + half * 16 + (ln >> 2), col = pt * 32 + (ln & 3) * 8;
-                        if (row < n)
-                            *reinterpret_cast<uint4 *>(yb + (uint32_t)(row * H * P + col) * 2u) =
-                                *reinterpret_cast<const uint4 *>(&sYo[row * YOP + col]);
-                    }
+                    for (int rg = 0; rg < 4; ++rg)
+                        *reinterpret_cast<bf16x4 *>(yb + (uint32_t)(row * H * P + pt * 32 + 8 * rg + 4 * lh) * 2u) =
+                            yreg[q][rg];
                 }
             }
             if (h0 && more3 && y_stages) load_H(b3, h3);
@@ -486,14 +475,11 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 stage_T();
                 if (more2) load_T(b2, h2);
             }
-            if (fresh_at(k + 1, h1)) restage_CB(b1, h1);   // C is dead too: phase 1 of unit k is done
-        }
-        __syncthreads();                                      // barrier 3: X^T is dead
-        STREE_PHASE_CLOCK(6);
-        if (!isY && more) {
-            stage_X();
+            if (fresh_at(k + 1, h1)) restage_CB(b1, h1);
+            stage_X((k + 1) & 1);                          // the other X^T tile: unit k still reads its own
             if (more2) load_X(b2, h2);
         }
+        STREE_PHASE_CLOCK(6);
         STREE_PHASE_CLOCK(7);
         cb = b1; ch = h1;
         b1 = b2; h1 = h2;
