@@ -128,7 +128,7 @@ def linear_scan(x, dt, A, Bm, Cm, D=None, h0=None):
     x, dt, A, Bm, Cm, D, h0 = map(_f64, (x, dt, A, Bm, Cm, D, h0))
     B, T, H, P = x.shape
     G, S = Bm.shape[2], Bm.shape[3]
-    assert dt.shape == (B, T, H) and Bm.shape == (B, T, G, S) and Cm.shape == (B, T, G, S)
+    assert dt.shape == (B, T, H) and Bm.shape == (B, T, G, S) and Cm.shape == (B, T, G, S) and H % G == 0
     y = np.full((B, T, H, P), np.nan)
     hf = np.full((B, H, P, S), np.nan)
     lib().orc_linear_scan(*(C.c_int(v) for v in (B, T, H, P, S, G)), _p(x), _p(dt), _p(A), _p(Bm), _p(Cm),
@@ -162,6 +162,7 @@ def commit(parent, accepted, x, dt, A, Bm, h0=None, xbc_pre=None, conv_state=Non
     B, N = parent.shape
     _, _, H, P = x.shape
     G, S = Bm.shape[2], Bm.shape[3]
+    assert H % G == 0
     h_out = np.full((B, H, P, S), np.nan)
     W = Cc = 0
     cs_out = None

@@ -54,12 +54,64 @@ __device__ __forceinline__ int wave_path(int lane, int n, int k, int parent_j, f
     return 0;
 }
 
-// grid (ceil(P*S / kSlab), H, B); dynamic LDS = kPathChunk * (P + S) floats
+// conv tail: out row r (oldest first) = pre-conv row of the (W-2-r)-th ancestor of k, or the old
+// state row once above the root.  One workgroup covers VEC*256 channels of one sequence.
+template <typename T, int VEC>
+__device__ __forceinline__ void conv_tail(int b, int cblk, const int32_t *__restrict__ parent,
+                                          const int32_t *__restrict__ accepted, int n, int Cc, int W,
+                                          const T *__restrict__ xbc_pre, const T *conv_state, T *conv_state_out) {
+    __shared__ int par[kMaxNodes];
+    const int tid = threadIdx.x;
+    int ok = 1;
+    if (tid < n) {
+        const int p = parent[(size_t)b * n + tid];
+        ok = (tid == 0) ? (p == -1) : (p >= 0 && p < tid);
+        par[tid] = ok ? p : -1;
+    }
+    const int any_bad = __syncthreads_or(!ok);
+    const int k = accepted[b];
+    const int c0 = (cblk * kThreads + tid) * VEC;
+    if (c0 >= Cc) return;
+    const bool pass = any_bad || k < 0 || k >= n;
+    uint4 rows[3];  // W - 1 <= 3 rows of 16 bytes
+    int v = pass ? -1 : k, above = 0;
+    for (int m = 0; m < W - 1; ++m) {  // m-th ancestor of k feeds out row W-2-m
+        const T *src;
+        if (v >= 0) {
+            src = xbc_pre + ((size_t)b * n + v) * Cc + c0;
+            v = par[v];
+        } else {
+            ++above;
+            src = conv_state + ((size_t)b * (W - 1) + (W - 1 - above)) * Cc + c0;
+        }
+        rows[m] = *reinterpret_cast<const uint4 *>(src);
+    }
+    for (int m = 0; m < W - 1; ++m)
+        *reinterpret_cast<uint4 *>(conv_state_out + ((size_t)b * (W - 1) + (W - 2 - m)) * Cc + c0) = rows[m];
+}
+
+struct ConvTailArgs {      // conv part folded into the state kernel's grid (cblocks = 0: none)
+    const void *xbc_pre, *conv_state;
+    void *conv_state_out;
+    int Cc, W, cblocks;
+};
+
+// grid (slabs [+ 1], H, B), slabs = ceil(P*S / kSlab); dynamic LDS = kPathChunk * (P + S) floats.
+// The extra x index, when present, carries the conv tail: its workgroups with h < cblocks each copy
+// one channel block, so that the whole commit is one launch.
 template <typename T, bool WAVE>
 __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     const int32_t *__restrict__ parent, const int32_t *__restrict__ accepted, int n, int H, int P, int S,
     int G, const T *__restrict__ x, long x_sn, const float *__restrict__ dt, const float *__restrict__ A,
-    const T *__restrict__ Bm, long b_sn, const float *h0, float *h_out, int32_t *__restrict__ status) {
+    const T *__restrict__ Bm, long b_sn, const float *h0, float *h_out, int32_t *__restrict__ status,
+    ConvTailArgs ct) {
+    if ((int)blockIdx.x * kSlab >= P * S) {            // the conv-tail slot of the grid
+        if ((int)blockIdx.y < ct.cblocks)
+            conv_tail<T, 16 / (int)sizeof(T)>(blockIdx.z, blockIdx.y, parent, accepted, n, ct.Cc, ct.W,
+                                              (const T *)ct.xbc_pre, (const T *)ct.conv_state,
+                                              (T *)ct.conv_state_out);
+        return;
+    }
     extern __shared__ __align__(16) float rows[];     // xs[kPathChunk][P] then bs[kPathChunk][S]
     __shared__ int path[kMaxNodes];
     __shared__ float coef[kMaxNodes];
@@ -189,53 +241,25 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     }
 }
 
-// conv tail: out row r (oldest first) = pre-conv row of the (W-2-r)-th ancestor
-// of k, or the old state row once above the root.  grid (ceil(Cc/(VEC*256)), B)
-template <typename T, int VEC>
-__global__ __launch_bounds__(kThreads) void commit_conv_kernel(
-    const int32_t *__restrict__ parent, const int32_t *__restrict__ accepted, int n, int Cc, int W,
-    const T *__restrict__ xbc_pre, const T *conv_state, T *conv_state_out) {
-    __shared__ int par[kMaxNodes];
-    const int tid = threadIdx.x, b = blockIdx.y;
-    int ok = 1;
-    if (tid < n) {
-        const int p = parent[(size_t)b * n + tid];
-        ok = (tid == 0) ? (p == -1) : (p >= 0 && p < tid);
-        par[tid] = ok ? p : -1;
-    }
-    const int any_bad = __syncthreads_or(!ok);
-    const int k = accepted[b];
-    const int c0 = (blockIdx.x * kThreads + tid) * VEC;
-    if (c0 >= Cc) return;
-    const bool pass = any_bad || k < 0 || k >= n;
-    uint4 rows[3];  // W - 1 <= 3 rows of 16 bytes
-    int v = pass ? -1 : k, above = 0;
-    for (int m = 0; m < W - 1; ++m) {  // m-th ancestor of k feeds out row W-2-m
-        const T *src;
-        if (v >= 0) {
-            src = xbc_pre + ((size_t)b * n + v) * Cc + c0;
-            v = par[v];
-        } else {
-            ++above;
-            src = conv_state + ((size_t)b * (W - 1) + (W - 1 - above)) * Cc + c0;
-        }
-        rows[m] = *reinterpret_cast<const uint4 *>(src);
-    }
-    for (int m = 0; m < W - 1; ++m)
-        *reinterpret_cast<uint4 *>(conv_state_out + ((size_t)b * (W - 1) + (W - 2 - m)) * Cc + c0) = rows[m];
-}
-
 hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const int32_t *accepted,
                                const void *x, const float *dt, const float *A, const void *Bm,
                                const float *h0, float *h_out, const void *xbc_pre, const void *conv_state,
                                void *conv_state_out, int32_t *status, hipStream_t st) {
     const int PS = d.headdim * d.dstate;
-    const dim3 grid((PS + kSlab - 1) / kSlab, d.nheads, d.batch);
+    const int slabs = (PS + kSlab - 1) / kSlab;
+    const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
+    const int vec = d.io_dtype == STREE_BF16 ? 8 : 4;
+    // channel blocks of the conv tail; never more than heads: Cc = H*P + 2*G*S <= H*(P + 2*S) and
+    // P, S <= 256 give Cc / (vec*256) <= 0.75 * H
+    const int cblocks = conv_state_out ? (Cc / vec + kThreads - 1) / kThreads : 0;
+    if (cblocks > d.nheads) return hipErrorInvalidValue;
+    ConvTailArgs ct = {xbc_pre, conv_state, conv_state_out, Cc, d.conv_width, cblocks};
+    const dim3 grid(slabs + (cblocks ? 1 : 0), d.nheads, d.batch);
     const size_t lds = (size_t)kPathChunk * (d.headdim + d.dstate) * sizeof(float);
 #define STREE_COMMIT_LAUNCH(TT, WV)                                                                           \
     hipLaunchKernelGGL((commit_h_kernel<TT, WV>), grid, dim3(kThreads), lds, st, parent, accepted, d.nnodes,     \
                        d.nheads, d.headdim, d.dstate, d.ngroups, (const TT *)x, (long)d.x_stride_n, dt, A,      \
-                       (const TT *)Bm, (long)d.b_stride_n, h0, h_out, status)
+                       (const TT *)Bm, (long)d.b_stride_n, h0, h_out, status, ct)
     const bool wave = d.nnodes <= 64;
     if (d.io_dtype == STREE_BF16) {
         if (wave) STREE_COMMIT_LAUNCH(bf16_t, true);
@@ -245,20 +269,6 @@ hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const
         else STREE_COMMIT_LAUNCH(float, false);
     }
 #undef STREE_COMMIT_LAUNCH
-    hipError_t err = hipGetLastError();
-    if (err != hipSuccess || !conv_state_out) return err;
-    const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
-    if (d.io_dtype == STREE_BF16) {
-        const dim3 cgrid((Cc / 8 + kThreads - 1) / kThreads, d.batch);
-        hipLaunchKernelGGL((commit_conv_kernel<bf16_t, 8>), cgrid, dim3(kThreads), 0, st, parent, accepted,
-                           d.nnodes, Cc, d.conv_width, (const bf16_t *)xbc_pre, (const bf16_t *)conv_state,
-                           (bf16_t *)conv_state_out);
-    } else {
-        const dim3 cgrid((Cc / 4 + kThreads - 1) / kThreads, d.batch);
-        hipLaunchKernelGGL((commit_conv_kernel<float, 4>), cgrid, dim3(kThreads), 0, st, parent, accepted,
-                           d.nnodes, Cc, d.conv_width, (const float *)xbc_pre, (const float *)conv_state,
-                           (float *)conv_state_out);
-    }
     return hipGetLastError();
 }
 

@@ -270,3 +270,4 @@ def test_commit_then_continue_on_gpu(st, oracle):
     y2 = st.stree_tree_ssd(to_dev(p2[None]), to_dev(x[:, n1:], "bf16"), to_dev(dt[:, n1:]), to_dev(A),
                            to_dev(Bm[:, n1:], "bf16"), to_dev(Cm[:, n1:], "bf16"), to_dev(D), hk)
     assert_parity(to_host(y2), want, TOL["bf16"], "commit then continue")
+
