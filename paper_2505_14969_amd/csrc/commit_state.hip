@@ -10,7 +10,7 @@
 
 namespace stree {
 
-constexpr int kSlab = 4096;        // state elements per workgroup (4 float4 per thread)
+constexpr int kQ = 8;               // state rows per thread (one float4 of each)
 constexpr int kPathChunk = 16;     // path nodes staged in LDS at a time
 
 // Path of the accepted node k for trees of at most 64 nodes, by one wave with no LDS and no
@@ -96,7 +96,10 @@ struct ConvTailArgs {      // conv part folded into the state kernel's grid (cbl
     int Cc, W, cblocks;
 };
 
-// grid (slabs [+ 1], H, B), slabs = ceil(P*S / kSlab); dynamic LDS = kPathChunk * (P + S) floats.
+// grid (slabs [+ 1], H, B); dynamic LDS = kPathChunk * (P + S) floats.
+// A thread owns one 4-wide piece s4 of the state index and kQ consecutive rows p, so that per
+// path node it needs one B piece and kQ x values: three 16-byte LDS reads for 4*kQ FMAs.  A
+// workgroup covers rows_wg = kQ * (256 / (S/4)) rows; slabs = ceil(P / rows_wg).
 // The extra x index, when present, carries the conv tail: its workgroups with h < cblocks each copy
 // one channel block, so that the whole commit is one launch.
 template <typename T, bool WAVE>
@@ -104,8 +107,8 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     const int32_t *__restrict__ parent, const int32_t *__restrict__ accepted, int n, int H, int P, int S,
     int G, const T *__restrict__ x, long x_sn, const float *__restrict__ dt, const float *__restrict__ A,
     const T *__restrict__ Bm, long b_sn, const float *h0, float *h_out, int32_t *__restrict__ status,
-    ConvTailArgs ct) {
-    if ((int)blockIdx.x * kSlab >= P * S) {            // the conv-tail slot of the grid
+    int slabs, ConvTailArgs ct) {
+    if ((int)blockIdx.x >= slabs) {                    // the conv-tail slot of the grid
         if ((int)blockIdx.y < ct.cblocks)
             conv_tail<T, 16 / (int)sizeof(T)>(blockIdx.z, blockIdx.y, parent, accepted, n, ct.Cc, ct.W,
                                               (const T *)ct.xbc_pre, (const T *)ct.conv_state,
@@ -121,15 +124,17 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     const int tid = threadIdx.x, lane = tid & 63, h = blockIdx.y, b = blockIdx.z;
     const int g = h / (H / G);
 
-    // the state slab first: these loads fly while the path is worked out
-    const int PS = P * S;
-    const size_t sbase = ((size_t)b * H + h) * PS;
-    const int e0 = blockIdx.x * kSlab + tid * 4;
-    float4 acc[4];
+    // the state rows first: these loads fly while the path is worked out
+    const int S4 = S >> 2, RP = kThreads / S4;
+    const int s4 = tid % S4, p0 = (blockIdx.x * RP + tid / S4) * kQ;   // rows p0 .. p0 + kQ - 1
+    const bool owner = tid < RP * S4;                  // S/4 need not divide the thread count
+    const size_t sbase = ((size_t)b * H + h) * P * S + (size_t)s4 * 4;
+    float4 acc[kQ];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int e = e0 + q * (kThreads * 4);
-        acc[q] = (h0 && e < PS) ? *reinterpret_cast<const float4 *>(h0 + sbase + e) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int q = 0; q < kQ; ++q) {
+        const int p = p0 + q;
+        acc[q] = (h0 && owner && p < P) ? *reinterpret_cast<const float4 *>(h0 + sbase + (size_t)p * S)
+                                        : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 
     const int k = accepted[b];
@@ -185,27 +190,12 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     }
     if (status && blockIdx.x == 0 && h == 0 && tid == 0) status[b] = bad ? bad : (k_bad ? -1 : 0);
 
-    if (bad || k < 0 || k_bad) {  // pass the state through
-        if (h_out != h0 || !h0) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int e = e0 + q * (kThreads * 4);
-                if (e < PS) *reinterpret_cast<float4 *>(h_out + sbase + e) = acc[q];
-            }
-        }
-        return;
-    }
-    int pq[4], sq[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int e = e0 + q * (kThreads * 4);
-        pq[q] = e < PS ? e / S : 0;
-        sq[q] = e < PS ? e % S : 0;
-    }
+    const bool pass = bad || k < 0 || k_bad;          // the state goes through unchanged
+    if (pass && h_out == h0 && h0) return;
     const T *xb = x + (size_t)b * n * x_sn + (size_t)h * P;
     const T *Bb = Bm + (size_t)b * n * b_sn + (size_t)g * S;
     bool scaled = false;
-    for (int c0 = 0; c0 < len; c0 += kPathChunk) {
+    for (int c0 = 0; !pass && c0 < len; c0 += kPathChunk) {
         const int cn = min(kPathChunk, len - c0);
         for (int idx = tid; idx < cn * (P + S); idx += kThreads) {
             const int t = idx / (P + S), col = idx % (P + S);
@@ -215,29 +205,43 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
         }
         if (!scaled) {   // the state loads are first needed here
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kQ; ++q) {
                 acc[q].x *= decay; acc[q].y *= decay; acc[q].z *= decay; acc[q].w *= decay;
             }
             scaled = true;
         }
         __syncthreads();
-        for (int t = 0; t < cn; ++t) {
+        if (owner && p0 < P) {
+            for (int t = 0; t < cn; ++t) {
+                const float4 bv = *reinterpret_cast<const float4 *>(&bs[t * S + s4 * 4]);
+                float xv[kQ];
+                if (P % kQ == 0) {   // kQ consecutive rows, 16-byte aligned: p0 is a multiple of kQ
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float xv = xs[t * P + pq[q]];
-                const float4 bv = *reinterpret_cast<const float4 *>(&bs[t * S + sq[q]]);
-                acc[q].x = fmaf(xv, bv.x, acc[q].x);
-                acc[q].y = fmaf(xv, bv.y, acc[q].y);
-                acc[q].z = fmaf(xv, bv.z, acc[q].z);
-                acc[q].w = fmaf(xv, bv.w, acc[q].w);
+                    for (int q = 0; q < kQ; q += 4) {
+                        const float4 v = *reinterpret_cast<const float4 *>(&xs[t * P + p0 + q]);
+                        xv[q] = v.x; xv[q + 1] = v.y; xv[q + 2] = v.z; xv[q + 3] = v.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < kQ; ++q) xv[q] = xs[t * P + min(p0 + q, P - 1)];
+                }
+#pragma unroll
+                for (int q = 0; q < kQ; ++q) {
+                    acc[q].x = fmaf(xv[q], bv.x, acc[q].x);
+                    acc[q].y = fmaf(xv[q], bv.y, acc[q].y);
+                    acc[q].z = fmaf(xv[q], bv.z, acc[q].z);
+                    acc[q].w = fmaf(xv[q], bv.w, acc[q].w);
+                }
             }
         }
         __syncthreads();
     }
+    if (owner) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int e = e0 + q * (kThreads * 4);
-        if (e < PS) *reinterpret_cast<float4 *>(h_out + sbase + e) = acc[q];
+        for (int q = 0; q < kQ; ++q) {
+            const int p = p0 + q;
+            if (p < P) *reinterpret_cast<float4 *>(h_out + sbase + (size_t)p * S) = acc[q];
+        }
     }
 }
 
@@ -245,8 +249,8 @@ hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const
                                const void *x, const float *dt, const float *A, const void *Bm,
                                const float *h0, float *h_out, const void *xbc_pre, const void *conv_state,
                                void *conv_state_out, int32_t *status, hipStream_t st) {
-    const int PS = d.headdim * d.dstate;
-    const int slabs = (PS + kSlab - 1) / kSlab;
+    const int rows_wg = kQ * (kThreads / (d.dstate / 4));   // state rows per workgroup
+    const int slabs = (d.headdim + rows_wg - 1) / rows_wg;
     const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
     const int vec = d.io_dtype == STREE_BF16 ? 8 : 4;
     // channel blocks of the conv tail; never more than heads: Cc = H*P + 2*G*S <= H*(P + 2*S) and
@@ -259,7 +263,7 @@ hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const
 #define STREE_COMMIT_LAUNCH(TT, WV)                                                                           \
     hipLaunchKernelGGL((commit_h_kernel<TT, WV>), grid, dim3(kThreads), lds, st, parent, accepted, d.nnodes,     \
                        d.nheads, d.headdim, d.dstate, d.ngroups, (const TT *)x, (long)d.x_stride_n, dt, A,      \
-                       (const TT *)Bm, (long)d.b_stride_n, h0, h_out, status, ct)
+                       (const TT *)Bm, (long)d.b_stride_n, h0, h_out, status, slabs, ct)
     const bool wave = d.nnodes <= 64;
     if (d.io_dtype == STREE_BF16) {
         if (wave) STREE_COMMIT_LAUNCH(bf16_t, true);

@@ -36,6 +36,15 @@
 #ifndef STREE_PHASE_CLOCK_G
 #define STREE_PHASE_CLOCK_G(k)
 #endif
+#ifndef STREE_PHASE_ENTRY
+#define STREE_PHASE_ENTRY(u)
+#define STREE_PHASE_PRO(slot, t)
+#endif
+#ifndef STREE_EXIT_POINT
+#define STREE_EXIT_INIT
+#define STREE_EXIT_POINT(n)
+#endif
+
 
 namespace stree {
 
@@ -52,6 +61,14 @@ struct Lds64 {
     static constexpr size_t total = (size_t)2 * kB64 * SP * 2 + (size_t)P * SP * 2 + (size_t)2 * P * kNP64 * 2 +
                                     (size_t)kB64 * kNP64 * 2 + 1040;
 };
+
+// Output stores that write through L2 (system scope): y is never read again by this kernel, and
+// lines left dirty in the eight L2s would all be written back at once when the kernel ends.
+__device__ __forceinline__ void store_through16(void *p, uint4 v) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 vv = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(vv) : "memory");
+}
 
 // Wave-level tree index for n <= 64: lane i owns node i; pointer doubling with
 // cross-lane reads (ds_bpermute), no barriers.  Returns the status (uniform).
@@ -249,42 +266,35 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         }
     };
     auto stage_T = [&]() {
-        const int bad = wave_tree_index(lane, n, rpar, rdt, rA, sS2, sU, sMask);
-        if (lane == 0) *sBad = bad;
+        const int ln = opaque(lane);   // LDS addresses re-derived here, not carried across the loop
+        const int bad = wave_tree_index(ln, n, rpar, rdt, rA, sS2, sU, sMask);
+        if (ln == 0) *sBad = bad;
     };
 
     if (nU <= 0) return;
-    // (b, h) of the current unit and of the next three
+    STREE_EXIT_INIT;
+    STREE_EXIT_POINT(1);
+    STREE_PHASE_PRO(23, 0);
+    STREE_PHASE_ENTRY(u0);
+    // (b, h) of the current unit and of the next three.  The loop starts one unit early (k = -1):
+    // that pass has no unit to compute and only runs the staging half, which brings unit 0 into
+    // LDS and issues the loads of units 1 and 2 -- the same code as in the steady state, so the
+    // instruction cache sees each part of the loop body once.
     int cb = ub0, ch = uh0, b1 = ub0, h1 = uh0;
-    step(b1, h1);
     int b2 = b1, h2 = h1;
     step(b2, h2);
     int b3 = b2, h3 = h2;
     step(b3, h3);
-    // ---- prologue: unit 0 into LDS; h0 of units 1 (G threads) and 2 (Y threads), x of unit 1
-    //      into registers.  All first loads are issued before anything is waited for. -------------
+    // the first loads of every role, before anything is waited for
     if (isY) {
-        if (h0) {
-            load_H(cb, ch);
-            stage_H();
-            if (nU > 2) load_H(b2, h2);
-        } else if (rt == 0) {
-            *sDh = D ? D[ch] : 0.f;
-        }
+        if (h0) load_H(b1, h1);
+        STREE_PHASE_PRO(16, 0);
     } else {
-        load_X(cb, ch);
-        if (wave == kTreeWave) load_T(cb, ch);
-        restage_CB(cb, ch);                     // waits for its own loads only (in-order return)
-        if (wave == kTreeWave) {
-            stage_T();
-            if (nU > 1) load_T(b1, h1);
-        }
-        stage_X(0);
-        if (nU > 1) {
-            load_X(b1, h1);
-            if (h0) load_H(b1, h1);
-        }
+        load_X(b1, h1);
+        if (wave == kTreeWave) load_T(b1, h1);
+        STREE_PHASE_PRO(18, 256);
     }
+    STREE_EXIT_POINT(2);
 
     // One accumulator set serves both roles: the Y waves' Yt tiles of the current unit, or
     // (acc[0]) the G waves' Gt tile of the current (sequence, group), kept across its heads.
@@ -294,16 +304,23 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
 
-    for (int k = 0; k < nU; ++k) {
+    for (int k = -1; k < nU; ++k) {
         [[maybe_unused]] const int prof_unit = cb * H + ch;  // only read by probe builds
-        __syncthreads();                                      // barrier 1: unit k is staged
-        STREE_PHASE_CLOCK(0);
+        const bool live = k >= 0;                             // false in the staging-only first pass
+        int bad = 0;
+        float D_h = 0.f;
+        if (live) {
+            __syncthreads();                                  // barrier 1: unit k is staged
+            STREE_PHASE_CLOCK(0);
+            bad = *sBad;
+            D_h = *sDh;
+            if (status && ch == 0 && tid == 0) status[cb] = bad;
+            STREE_EXIT_POINT(10 + 10 * k);
+        }
         const unsigned short *sXT = sXT2[k & 1];
-        const int bad = *sBad;
-        const float D_h = *sDh;
-        if (status && ch == 0 && tid == 0) status[cb] = bad;
 
-        if (isY) {
+        if (!live) {
+        } else if (isY) {
 #pragma unroll
             for (int q = 0; q < YQ; ++q)
 #pragma unroll
@@ -381,7 +398,9 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
             STREE_PHASE_CLOCK_G(11);
         }
-        __syncthreads();                                      // barrier 2: M is ready; h0b, C and the tree arrays are dead
+        if (live) STREE_EXIT_POINT(11 + 10 * k);
+        if (live) __syncthreads();                            // barrier 2: M is ready; h0b, C and the tree arrays are dead
+        if (live) STREE_EXIT_POINT(12 + 10 * k);
         STREE_PHASE_CLOCK(2);
 
         const bool more = k + 1 < nU, more2 = k + 2 < nU, more3 = k + 3 < nU;
@@ -393,6 +412,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             bf16x4 yreg[YQ][4];
 #pragma unroll
             for (int q = 0; q < YQ; ++q) {
+                if (!live) break;
                 const int pt = (wave + 4 * q) >> 1;
                 float xv[16];   // x[i][p] of this lane's node for the 16 p of its accumulator
 #pragma unroll
@@ -437,31 +457,61 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 }
             }
             STREE_PHASE_CLOCK(3);
+            if (live) STREE_EXIT_POINT(13 + 10 * k);
             // next unit's state tile (its loads have been in flight for a whole unit period)
             if (more) {
                 if (h0) {
                     if (y_stages) stage_H();
+                    if (!live) STREE_PHASE_PRO(17, 0);
                 } else if (rt == 0) {
                     *sDh = D ? D[h1] : 0.f;
                 }
             }
             STREE_PHASE_CLOCK(4);
-            // y: a lane owns node il and 4 consecutive p per register group: 8-byte stores, the two
-            // lane halves completing 16 contiguous bytes of a row (L2 merges the pieces of a line).
+            // y leaves as 64-byte row pieces: the accumulators give a lane 4 consecutive p of one
+            // node, which as direct stores would be 16-byte pieces of 32 different lines per
+            // instruction.  Each wave therefore turns its 32x32 tile around in a private 2 KB of LDS
+            // (a wave's LDS operations complete in order: no barrier) and stores 16 bytes per lane,
+            // four lanes to a row.  The LDS used is the B tile's, idle except while the next unit
+            // brings new C / B tiles; that pass stores straight from the accumulators instead.
             // The stores go out after the wait for the h0 loads above and are long complete at
             // the next such wait: on gfx9 loads and stores share one counter and complete out of
             // order with respect to each other, so a store in flight would turn that wait into a
             // wait for everything.
-            if (il < n) {
+            if (live) {
                 char *yb = reinterpret_cast<char *>(y + (size_t)cb * n * H * P + (size_t)ch * P);
-                const int row = opaque(il);
+                if (!(more && fresh_at(k + 1, h1))) {
+                    char *ys = reinterpret_cast<char *>(sB) + opaque(wave) * 2048;
+                    const int ln = opaque(lane), wr = ln & 31, wh = ln >> 5;
+                    const int rr = ln >> 2, rc = ln & 3;
 #pragma unroll
-                for (int q = 0; q < YQ; ++q) {
-                    const int pt = (wave + 4 * q) >> 1;
+                    for (int q = 0; q < YQ; ++q) {
+                        const int pt = (wave + 4 * q) >> 1;
+                        // row r keeps its 16-byte chunk c at slot c ^ ((r >> 2) & 3)
 #pragma unroll
-                    for (int rg = 0; rg < 4; ++rg)
-                        *reinterpret_cast<bf16x4 *>(yb + (uint32_t)(row * H * P + pt * 32 + 8 * rg + 4 * lh) * 2u) =
-                            yreg[q][rg];
+                        for (int rg = 0; rg < 4; ++rg)
+                            *reinterpret_cast<bf16x4 *>(ys + wr * 64 + ((rg ^ ((wr >> 2) & 3)) * 16) + wh * 8) =
+                                yreg[q][rg];
+#pragma unroll
+                        for (int half = 0; half < 2; ++half) {
+                            const int row = half * 16 + rr;
+                            const uint4 v =
+                                *reinterpret_cast<const uint4 *>(ys + row * 64 + ((rc ^ ((row >> 2) & 3)) * 16));
+                            const int node = it * 32 + row;
+                            if (node < n)
+                                store_through16(yb + (uint32_t)(node * H * P + pt * 32 + rc * 8) * 2u, v);
+                        }
+                    }
+                } else if (il < n) {
+                    const int row = opaque(il), lh = opaque(lane) >> 5;   // re-derived: not carried across the loop
+#pragma unroll
+                    for (int q = 0; q < YQ; ++q) {
+                        const int pt = (wave + 4 * q) >> 1;
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg)
+                            *reinterpret_cast<bf16x4 *>(yb + (uint32_t)(row * H * P + pt * 32 + 8 * rg + 4 * lh) * 2u) =
+                                yreg[q][rg];   // 8-byte pieces: left to L2 to merge, not written through
+                    }
                 }
             }
             if (h0 && more3 && y_stages) load_H(b3, h3);
@@ -473,14 +523,22 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
             if (wave == kTreeWave) {
                 stage_T();
+                if (!live) STREE_PHASE_PRO(20, 384);
                 if (more2) load_T(b2, h2);
             }
             if (fresh_at(k + 1, h1)) restage_CB(b1, h1);
+            if (!live) STREE_PHASE_PRO(19, 256);
             stage_X((k + 1) & 1);                          // the other X^T tile: unit k still reads its own
-            if (more2) load_X(b2, h2);
+            if (!live) STREE_PHASE_PRO(21, 256);
+            if (more2) {
+                load_X(b2, h2);
+                if (!live && h0) load_H(b2, h2);           // unit 1: the first odd unit
+            }
+            if (!live) STREE_PHASE_PRO(22, 256);
         }
         STREE_PHASE_CLOCK(6);
         STREE_PHASE_CLOCK(7);
+        STREE_EXIT_POINT(4 + k);
         cb = b1; ch = h1;
         b1 = b2; h1 = h2;
         b2 = b3; h2 = h3;

@@ -255,6 +255,19 @@ def test_commit_edge_cases(st, oracle):
     assert_parity(to_host(h3), want3, 1e-4, "commit without h0")
 
 
+@pytest.mark.parametrize("N,H,P,S,G", [(13, 3, 24, 20, 1), (30, 2, 12, 48, 2), (64, 2, 256, 256, 1), (7, 4, 1, 4, 4)])
+def test_commit_ragged_shapes(st, oracle, N, H, P, S, G):
+    """State tiles that do not divide evenly over the threads of a workgroup."""
+    B = 2
+    parent = _trees(61, B, N)
+    x, dt, A, Bm, Cm, D, h0 = _rand(62, "f32", B, N, H, P, S, G)
+    acc = np.array([N - 1, N // 2], dtype=np.int32)
+    want, _ = oracle.commit(parent, acc, x, dt, A, Bm, h0)
+    h, _ = st.stree_commit_state(to_dev(parent), to_dev(acc), to_dev(x, "f32"), to_dev(dt), to_dev(A),
+                                 to_dev(Bm, "f32"), to_dev(h0))
+    assert_parity(to_host(h), want, 1e-4, f"commit P={P} S={S}")
+
+
 def test_commit_then_continue_on_gpu(st, oracle):
     """Verify a second tree from the committed state: equals the grafted big tree."""
     n1, n2, H, P, S, G = 40, 30, 2, 64, 128, 1
