@@ -138,6 +138,8 @@ int stree_tree_ssd(const stree_dims *dims, const int32_t *parent, const void *x,
  *   h0 f32 [B,H,P,S] or NULL; h_out f32 [B,H,P,S], MAY alias h0
  *   xbc_pre, conv_state, conv_state_out: all three NULL to skip the conv part;
  *   conv_state_out MAY alias conv_state.
+ *   x, dt, A, Bm, h0, h_out: all six NULL to skip the state part (conv tail only,
+ *   as used in front of stree_tree_ssd_replay).
  * dstate must be a multiple of 4.
  */
 int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int32_t *accepted,
@@ -145,6 +147,45 @@ int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int3
                        const float *h0, float *h_out, const void *xbc_pre,
                        const void *conv_state, void *conv_state_out, int32_t *tree_status,
                        void *hip_stream);
+
+/*
+ * The previous iteration's tree and its cached activations: what Alg. 1 keeps so
+ * that the state can be replayed at the start of the next iteration.  POD, host
+ * memory; the pointers in it are device memory.  Batch, heads, headdim, dstate,
+ * groups and io_dtype are those of the `dims` it is passed with.
+ */
+typedef struct stree_replay {
+    int32_t nnodes;           /* nodes of the previous tree, 1..STREE_MAX_NODES */
+    int32_t reserved;         /* 0 */
+    const int32_t *parent;    /* int32 [B,nnodes] */
+    const int32_t *accepted;  /* int32 [B]: accepted node of the previous tree, -1 = none */
+    const void *x;            /* io [B,nnodes,H,P], token stride x_stride_n */
+    const float *dt;          /* f32 [B,nnodes,H] */
+    const void *Bm;           /* io [B,nnodes,G,S], token stride b_stride_n */
+    int64_t x_stride_n, b_stride_n; /* elements; 0 = dense */
+} stree_replay;
+
+/*
+ * Fused activation replay and tree scan (Alg. 1, "replay at the start of the next
+ * iteration"; Sec. 3 "Implementation"): one pass over the state that does what
+ * stree_commit_state on the previous tree followed by stree_tree_ssd on the
+ * current tree would do, reading the state once instead of twice:
+ *   h_out = state after the accepted path of `prev` starting from h0   (commit formula)
+ *   y     = tree scan of the current tree starting from h_out          (scan formula)
+ *   h0    f32 [B,H,P,S], required; h_out f32 [B,H,P,S], required, MAY alias h0
+ *   replay_status int32 [B] or NULL: 0, (first bad node of the previous tree) + 1,
+ *                 or -1 for an accepted index outside [-1, prev->nnodes); in the
+ *                 last two cases the state passes through unchanged
+ *   every other argument as in stree_tree_ssd; A is shared by both trees.
+ * The single-pass kernel covers the shapes of a decoding step (both trees of at
+ * most 64 nodes, bf16, the MFMA head shapes); every other shape in the envelope
+ * runs the two separate kernels back to back on the stream, with the same result.
+ * dstate must be a multiple of 4.
+ */
+int stree_tree_ssd_replay(const stree_dims *dims, const stree_replay *prev, const int32_t *parent,
+                          const void *x, const float *dt, const float *A, const void *Bm,
+                          const void *Cm, const float *D, const float *h0, float *h_out, void *y,
+                          int32_t *tree_status, int32_t *replay_status, void *hip_stream);
 
 #ifdef __cplusplus
 }

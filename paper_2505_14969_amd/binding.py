@@ -29,6 +29,12 @@ class StreeDims(C.Structure):
                [(n, C.c_int64) for n in ("x_stride_n", "b_stride_n", "c_stride_n")]
 
 
+class StreeReplay(C.Structure):
+    _fields_ = [("nnodes", C.c_int32), ("reserved", C.c_int32), ("parent", C.c_void_p), ("accepted", C.c_void_p),
+                ("x", C.c_void_p), ("dt", C.c_void_p), ("Bm", C.c_void_p),
+                ("x_stride_n", C.c_int64), ("b_stride_n", C.c_int64)]
+
+
 class StreeError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -56,7 +62,9 @@ def load() -> C.CDLL:
         lib.stree_tree_conv.argtypes = [dp] + [_VP] * 8
         lib.stree_tree_ssd.argtypes = [dp] + [_VP] * 11
         lib.stree_commit_state.argtypes = [dp] + [_VP] * 13
-        for f in (lib.stree_tree_index, lib.stree_tree_conv, lib.stree_tree_ssd, lib.stree_commit_state):
+        lib.stree_tree_ssd_replay.argtypes = [dp, C.POINTER(StreeReplay)] + [_VP] * 13
+        for f in (lib.stree_tree_index, lib.stree_tree_conv, lib.stree_tree_ssd, lib.stree_commit_state,
+                  lib.stree_tree_ssd_replay):
             f.restype = C.c_int
         _lib = lib
     return _lib
@@ -147,9 +155,21 @@ def stree_tree_ssd(parent, x, dt, A, Bm, Cm, D=None, h0=None, out: Optional[torc
 
 def stree_commit_state(parent, accepted, x, dt, A, Bm, h0=None, h_out: Optional[torch.Tensor] = None,
                        xbc_pre=None, conv_state=None, conv_state_out: Optional[torch.Tensor] = None,
-                       status: Optional[torch.Tensor] = None):
+                       status: Optional[torch.Tensor] = None, dims: Optional[tuple] = None):
     """-> (h_out [B,H,P,S] f32, conv_state_out [B,W-1,Cc] | None).  h_out may be h0 itself
-    (in place), conv_state_out may be conv_state itself."""
+    (in place), conv_state_out may be conv_state itself.  With x, dt, A, Bm all None only the conv
+    tail is updated; `dims` = (H, P, S, G) then names the head shapes."""
+    if x is None:
+        B, N = parent.shape
+        H, P, S, G = dims
+        W = conv_state.shape[1] + 1
+        if conv_state_out is None:
+            conv_state_out = torch.empty_like(conv_state)
+        d = make_dims(B, N, H, P, S, G, W, _io_code(xbc_pre))
+        _check(load().stree_commit_state(C.byref(d), _ptr(parent), _ptr(accepted), None, None, None, None, None,
+                                         None, _ptr(xbc_pre), _ptr(conv_state), _ptr(conv_state_out),
+                                         _ptr(status), _stream()), "stree_commit_state")
+        return None, conv_state_out
     B, N, H, P = x.shape
     G, S = Bm.shape[2], Bm.shape[3]
     if h_out is None:
@@ -164,3 +184,29 @@ def stree_commit_state(parent, accepted, x, dt, A, Bm, h0=None, h_out: Optional[
                                      _ptr(Bm), _ptr(h0), _ptr(h_out), _ptr(xbc_pre), _ptr(conv_state),
                                      _ptr(conv_state_out), _ptr(status), _stream()), "stree_commit_state")
     return h_out, conv_state_out
+
+
+def stree_tree_ssd_replay(prev_parent, prev_accepted, prev_x, prev_dt, prev_Bm, parent, x, dt, A, Bm, Cm, D, h0,
+                          h_out: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                          status: Optional[torch.Tensor] = None, replay_status: Optional[torch.Tensor] = None,
+                          force_fma: bool = False):
+    """Commit of the previous tree's accepted path fused with the scan of the current tree.
+    -> (y [B,N,H,P], h_out [B,H,P,S] f32).  h_out may be h0 itself (in place)."""
+    B, N, H, P = x.shape
+    G, S = Bm.shape[2], Bm.shape[3]
+    Np = prev_x.shape[1]
+    assert prev_x.shape == (B, Np, H, P) and prev_Bm.shape == (B, Np, G, S) and prev_x.dtype == x.dtype
+    assert prev_dt.is_contiguous() and prev_dt.dtype == torch.float32 and prev_dt.shape == (B, Np, H)
+    assert dt.is_contiguous() and dt.dtype == torch.float32 and h0.is_contiguous()
+    if out is None:
+        out = torch.empty((B, N, H, P), dtype=x.dtype, device=x.device)
+    if h_out is None:
+        h_out = torch.empty_like(h0)
+    d = make_dims(B, N, H, P, S, G, 0, _io_code(x), FLAG_FORCE_FMA if force_fma else 0,
+                  _token_stride(x, N), _token_stride(Bm, N), _token_stride(Cm, N))
+    r = StreeReplay(Np, 0, prev_parent.data_ptr(), prev_accepted.data_ptr(), prev_x.data_ptr(), prev_dt.data_ptr(),
+                    prev_Bm.data_ptr(), _token_stride(prev_x, Np), _token_stride(prev_Bm, Np))
+    _check(load().stree_tree_ssd_replay(C.byref(d), C.byref(r), _ptr(parent), _ptr(x), _ptr(dt), _ptr(A), _ptr(Bm),
+                                        _ptr(Cm), _ptr(D), _ptr(h0), _ptr(h_out), _ptr(out), _ptr(status),
+                                        _ptr(replay_status), _stream()), "stree_tree_ssd_replay")
+    return out, h_out

@@ -103,7 +103,10 @@ int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int3
     const bool conv = xbc_pre || conv_state || conv_state_out;
     int rc = check_dims(dims, conv ? kConvChannels : kNoConv);
     if (rc) return rc;
-    if (!parent || !accepted || !x || !dt || !A || !Bm || !h_out) return STREE_ERR_NULL_ARG;
+    const bool no_state = !x && !dt && !A && !Bm && !h0 && !h_out;   // conv tail only
+    if (!parent || !accepted) return STREE_ERR_NULL_ARG;
+    if (!no_state && (!x || !dt || !A || !Bm || !h_out)) return STREE_ERR_NULL_ARG;
+    if (no_state && !conv) return STREE_ERR_NULL_ARG;
     if (conv && (!xbc_pre || !conv_state || !conv_state_out)) return STREE_ERR_NULL_ARG;
     if (dims->dstate % 4 != 0) return STREE_ERR_BAD_SHAPE;
     stree_dims d = *dims;
@@ -113,6 +116,40 @@ int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int3
     return hip_status(stree::launch_commit_state(d, parent, accepted, x, dt, A, Bm, h0, h_out, xbc_pre,
                                                  conv_state, conv_state_out, tree_status,
                                                  (hipStream_t)hip_stream));
+}
+
+int stree_tree_ssd_replay(const stree_dims *dims, const stree_replay *prev, const int32_t *parent,
+                          const void *x, const float *dt, const float *A, const void *Bm, const void *Cm,
+                          const float *D, const float *h0, float *h_out, void *y, int32_t *tree_status,
+                          int32_t *replay_status, void *hip_stream) {
+    int rc = check_dims(dims, kNoConv);
+    if (rc) return rc;
+    if (!prev || !prev->parent || !prev->accepted || !prev->x || !prev->dt || !prev->Bm) return STREE_ERR_NULL_ARG;
+    if (!parent || !x || !dt || !A || !Bm || !Cm || !y || !h0 || !h_out) return STREE_ERR_NULL_ARG;
+    if (prev->nnodes < 1 || prev->nnodes > STREE_MAX_NODES || dims->dstate % 4 != 0) return STREE_ERR_BAD_SHAPE;
+    stree_dims d = *dims;
+    rc = resolve_strides(d);
+    if (rc) return rc;
+    // the previous tree as a problem of its own: same heads and dtypes, its own node count and strides
+    stree_dims dp = *dims;
+    dp.nnodes = prev->nnodes;
+    dp.x_stride_n = prev->x_stride_n;
+    dp.b_stride_n = prev->b_stride_n;
+    dp.c_stride_n = 0;
+    rc = resolve_strides(dp);
+    if (rc) return rc;
+    if (d.batch == 0) return STREE_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (!(d.flags & STREE_FLAG_FORCE_FMA) && stree::tree_ssd_replay_fused_supported(d, dp, prev->x, prev->Bm, x, Bm, Cm, y))
+        return hip_status(stree::launch_tree_ssd_replay_fused(d, dp, prev->parent, prev->accepted, prev->x, prev->dt,
+                                                              prev->Bm, parent, x, dt, A, Bm, Cm, D, h0, h_out, y,
+                                                              tree_status, replay_status, st));
+    hipError_t e = stree::launch_commit_state(dp, prev->parent, prev->accepted, prev->x, prev->dt, A, prev->Bm, h0,
+                                              h_out, nullptr, nullptr, nullptr, replay_status, st);
+    if (e != hipSuccess) return STREE_ERR_HIP;
+    if (stree::tree_ssd_mfma_supported(d, x, Bm, Cm, h_out, y) && !(d.flags & STREE_FLAG_FORCE_FMA))
+        return hip_status(stree::launch_tree_ssd_mfma(d, parent, x, dt, A, Bm, Cm, D, h_out, y, tree_status, st));
+    return hip_status(stree::launch_tree_ssd_fma(d, parent, x, dt, A, Bm, Cm, D, h_out, y, tree_status, st));
 }
 
 }  // extern "C"

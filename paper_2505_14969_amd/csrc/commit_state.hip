@@ -250,7 +250,7 @@ hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const
                                const float *h0, float *h_out, const void *xbc_pre, const void *conv_state,
                                void *conv_state_out, int32_t *status, hipStream_t st) {
     const int rows_wg = kQ * (kThreads / (d.dstate / 4));   // state rows per workgroup
-    const int slabs = (d.headdim + rows_wg - 1) / rows_wg;
+    const int slabs = h_out ? (d.headdim + rows_wg - 1) / rows_wg : 0;
     const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
     const int vec = d.io_dtype == STREE_BF16 ? 8 : 4;
     // channel blocks of the conv tail; never more than heads: Cc = H*P + 2*G*S <= H*(P + 2*S) and
@@ -258,7 +258,8 @@ hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const
     const int cblocks = conv_state_out ? (Cc / vec + kThreads - 1) / kThreads : 0;
     if (cblocks > d.nheads) return hipErrorInvalidValue;
     ConvTailArgs ct = {xbc_pre, conv_state, conv_state_out, Cc, d.conv_width, cblocks};
-    const dim3 grid(slabs + (cblocks ? 1 : 0), d.nheads, d.batch);
+    if (slabs + cblocks == 0) return hipSuccess;
+    const dim3 grid(slabs + (cblocks ? 1 : 0), slabs ? d.nheads : cblocks, d.batch);
     const size_t lds = (size_t)kPathChunk * (d.headdim + d.dstate) * sizeof(float);
 #define STREE_COMMIT_LAUNCH(TT, WV)                                                                           \
     hipLaunchKernelGGL((commit_h_kernel<TT, WV>), grid, dim3(kThreads), lds, st, parent, accepted, d.nnodes,     \

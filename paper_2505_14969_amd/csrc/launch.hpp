@@ -31,6 +31,16 @@ hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, co
                                   const float *A, const void *Bm, const void *Cm, const float *D,
                                   const float *h0, void *y, int32_t *status, hipStream_t st);
 
+// fused replay + scan: `dp` describes the previous tree (its node count and strides)
+bool tree_ssd_replay_fused_supported(const stree_dims &d, const stree_dims &dp, const void *px, const void *pB,
+                                     const void *x, const void *Bm, const void *Cm, const void *y);
+hipError_t launch_tree_ssd_replay_fused(const stree_dims &d, const stree_dims &dp, const int32_t *pparent,
+                                        const int32_t *paccepted, const void *px, const float *pdt, const void *pB,
+                                        const int32_t *parent, const void *x, const float *dt, const float *A,
+                                        const void *Bm, const void *Cm, const float *D, const float *h0,
+                                        float *h_out, void *y, int32_t *status, int32_t *rstatus, hipStream_t st);
+
+// h_out == NULL: conv tail only
 hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const int32_t *accepted,
                                const void *x, const float *dt, const float *A, const void *Bm,
                                const float *h0, float *h_out, const void *xbc_pre, const void *conv_state,

@@ -572,6 +572,17 @@ bool tree_ssd_mfma64_supported(const stree_dims &d) {
     return (P == 64 && (S == 128 || S == 64)) || (P == 128 && S == 128);
 }
 
+bool tree_ssd_replay_fused_supported(const stree_dims &, const stree_dims &, const void *, const void *, const void *,
+                                     const void *, const void *, const void *) {
+    return false;
+}
+hipError_t launch_tree_ssd_replay_fused(const stree_dims &, const stree_dims &, const int32_t *, const int32_t *,
+                                        const void *, const float *, const void *, const int32_t *, const void *,
+                                        const float *, const float *, const void *, const void *, const float *,
+                                        const float *, float *, void *, int32_t *, int32_t *, hipStream_t) {
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                   const float *A, const void *Bm, const void *Cm, const float *D,
                                   const float *h0, void *y, int32_t *status, hipStream_t st) {

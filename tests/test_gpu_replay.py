@@ -1,0 +1,141 @@
+"""GPU parity of the fused activation replay + tree scan (Alg. 1: the state is
+advanced along the previous tree's accepted path at the start of the next
+iteration).  The oracle has no fused routine: the expected values are its commit
+followed by its path-unrolled scan from the committed state."""
+import numpy as np
+import pytest
+
+from paper_2505_14969_amd import synth
+from helpers import TOL, assert_parity, to_dev, to_host
+from test_gpu_parity import _rand, _trees, st  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(seed, io, B, Np, N, H, P, S, G):
+    prev = _rand(seed, io, B, Np, H, P, S, G)
+    cur = _rand(seed + 1, io, B, N, H, P, S, G, h0=False)
+    pp, p = _trees(seed + 2, B, Np), _trees(seed + 3, B, N)
+    return prev, cur, pp, p
+
+
+def _expect(oracle, pp, acc, prev, p, cur, A, D):
+    px, pdt, _, pB, _, _, h0 = prev
+    x, dt, _, Bm, Cm, _, _ = cur
+    h_star, _ = oracle.commit(pp, acc, px, pdt, A, pB, h0)
+    y = oracle.ssd_paths(p, x, dt, A, Bm, Cm, D, h_star)
+    return h_star, y
+
+
+def _run(st, io, pp, acc, prev, p, cur, A, D, h_io=None, **kw):
+    px, pdt, _, pB, _, _, h0 = prev
+    x, dt, _, Bm, Cm, _, _ = cur
+    h_in = to_dev(h0) if h_io is None else h_io
+    y, h = st.stree_tree_ssd_replay(to_dev(pp), to_dev(acc), to_dev(px, io), to_dev(pdt), to_dev(pB, io),
+                                    to_dev(p), to_dev(x, io), to_dev(dt), to_dev(A), to_dev(Bm, io),
+                                    to_dev(Cm, io), to_dev(D), h_in, **kw)
+    return to_host(y), to_host(h)
+
+
+# single-pass kernel shapes (both trees of at most 64 nodes, bf16, MFMA head shapes), several
+# units per workgroup, and shapes that take the two-kernel route
+SHAPES = [("bf16", 5, 40, 64, 6, 64, 128, 2), ("bf16", 3, 64, 30, 4, 64, 64, 1), ("bf16", 2, 20, 64, 3, 128, 128, 1),
+          ("bf16", 16, 33, 57, 80, 64, 128, 1), ("bf16", 2, 100, 64, 4, 64, 128, 1), ("bf16", 2, 30, 130, 4, 64, 128, 2),
+          ("f32", 2, 25, 31, 3, 24, 20, 1)]
+
+
+@pytest.mark.parametrize("io,B,Np,N,H,P,S,G", SHAPES)
+def test_replay_matches_commit_then_scan(st, oracle, io, B, Np, N, H, P, S, G):
+    import torch
+    prev, cur, pp, p = _case(700 + B + N, io, B, Np, N, H, P, S, G)
+    A, D = prev[2], prev[5]
+    rng = np.random.default_rng(7)
+    acc = rng.integers(0, Np, B).astype(np.int32)
+    acc[0] = Np - 1
+    if B > 2:
+        acc[2] = -1                                   # nothing accepted: state passes through
+        pp[1] = synth.chain_tree(Np)                  # longest possible path
+        acc[1] = Np - 1
+    want_h, want_y = _expect(oracle, pp, acc, prev, p, cur, A, D)
+    status = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    rstatus = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    y, h = _run(st, io, pp, acc, prev, p, cur, A, D, status=status, replay_status=rstatus)
+    assert not to_host(status).any() and not to_host(rstatus).any()
+    for b in range(B):
+        assert_parity(h[b], want_h[b], 1e-4, f"replayed state b={b}")
+        assert_parity(y[b], want_y[b], TOL[io], f"scan after replay b={b}")
+    if B > 2:
+        assert np.array_equal(h[2], prev[6][2])       # bit-exact pass-through
+    # in place: same bits
+    h_io = to_dev(prev[6])
+    y2, h2 = _run(st, io, pp, acc, prev, p, cur, A, D, h_io=h_io, h_out=h_io)
+    assert np.array_equal(h2, h) and np.array_equal(y2, y)
+
+
+def test_replay_edge_cases(st, oracle):
+    """Bad previous tree, accepted index out of range, bad current tree: the state passes
+    through (or is still replayed) and the scan of the other sequences is untouched."""
+    import torch
+    io, B, Np, N, H, P, S, G = "bf16", 4, 20, 24, 4, 64, 128, 1
+    prev, cur, pp, p = _case(900, io, B, Np, N, H, P, S, G)
+    A, D = prev[2], prev[5]
+    acc = np.array([Np + 5, 7, 3, 11], dtype=np.int32)          # b=0 out of range
+    pp[1, 6] = 9                                                 # b=1 bad previous tree
+    p[2, 4] = 4                                                  # b=2 bad current tree
+    status = torch.zeros((B,), dtype=torch.int32, device="cuda")
+    rstatus = torch.zeros((B,), dtype=torch.int32, device="cuda")
+    y, h = _run(st, io, pp, acc, prev, p, cur, A, D, status=status, replay_status=rstatus)
+    assert list(to_host(rstatus)) == [-1, 7, 0, 0]
+    assert list(to_host(status)) == [0, 0, 5, 0]
+    h0 = prev[6]
+    assert np.array_equal(h[0], h0[0]) and np.array_equal(h[1], h0[1])
+    assert not y[2].any()
+    # expected values sequence by sequence (the oracle rejects bad trees as a whole)
+    x, dt, _, Bm, Cm, _, _ = cur
+    for b in (0, 1):
+        want = oracle.ssd_paths(p[b:b + 1], x[b:b + 1], dt[b:b + 1], A, Bm[b:b + 1], Cm[b:b + 1], D, h0[b:b + 1])
+        assert_parity(y[b], want[0], TOL[io], f"scan from the untouched state b={b}")
+    px, pdt, _, pB, _, _, _ = prev
+    for b in (2, 3):
+        want_h, _ = oracle.commit(pp[b:b + 1], acc[b:b + 1], px[b:b + 1], pdt[b:b + 1], A, pB[b:b + 1], h0[b:b + 1])
+        assert_parity(h[b], want_h[0], 1e-4, f"replayed state b={b}")
+    want = oracle.ssd_paths(p[3:4], x[3:4], dt[3:4], A, Bm[3:4], Cm[3:4], D, want_h)
+    assert_parity(y[3], want[0], TOL[io], "scan after replay b=3")
+
+
+def test_replay_chain_of_iterations(st, oracle):
+    """Three decoding iterations through the fused call, the state carried in place, against one
+    oracle scan of the concatenated accepted paths (the linear-sequence special case)."""
+    io, B, H, P, S, G, N = "bf16", 2, 4, 64, 128, 1, 48
+    rng = np.random.default_rng(77)
+    steps = [(_rand(950 + i, io, B, N, H, P, S, G), _trees(960 + i, B, N)) for i in range(4)]
+    A, D = steps[0][0][2], steps[0][0][5]
+    h0 = steps[0][0][6]
+    accs = [rng.integers(0, N, B).astype(np.int32) for _ in range(3)]
+    h_dev = to_dev(h0)
+    for i in range(3):
+        prev, pp = steps[i]
+        cur, p = steps[i + 1]
+        y, _ = st.stree_tree_ssd_replay(to_dev(pp), to_dev(accs[i]), to_dev(prev[0], io), to_dev(prev[1]),
+                                        to_dev(prev[3], io), to_dev(p), to_dev(cur[0], io), to_dev(cur[1]),
+                                        to_dev(A), to_dev(cur[3], io), to_dev(cur[4], io), to_dev(D), h_dev,
+                                        h_out=h_dev)
+    # oracle: accepted paths of the three trees as one sequence, then the last tree from that state
+    want_h = np.empty_like(h0, dtype=np.float64)
+    for b in range(B):
+        xs, dts, Bs = [], [], []
+        for i in range(3):
+            prev, pp = steps[i]
+            path, v = [], int(accs[i][b])
+            while v >= 0:
+                path.append(v)
+                v = int(pp[b, v])
+            path.reverse()
+            xs.append(prev[0][b, path]); dts.append(prev[1][b, path]); Bs.append(prev[3][b, path])
+        xs, dts, Bs = np.concatenate(xs)[None], np.concatenate(dts)[None], np.concatenate(Bs)[None]
+        _, hf = oracle.linear_scan(xs, dts, A, Bs, np.zeros_like(Bs), None, h0[b:b + 1])
+        want_h[b] = hf[0]
+    assert_parity(to_host(h_dev), want_h, 1e-4, "state after three fused iterations")
+    cur, p = steps[3]
+    want_y = oracle.ssd_paths(p, cur[0], cur[1], A, cur[3], cur[4], D, want_h)
+    assert_parity(to_host(y), want_y, TOL[io], "scan of the fourth tree")
