@@ -13,47 +13,6 @@ namespace stree {
 constexpr int kQ = 8;               // state rows per thread (one float4 of each)
 constexpr int kPathChunk = 16;     // path nodes staged in LDS at a time
 
-// Path of the accepted node k for trees of at most 64 nodes, by one wave with no LDS and no
-// barrier: lane j owns node j; pointer doubling over the parent array with cross-lane reads
-// gives every lane s_j (the paper's A_tree) and its ancestor bit row; lane k's values are then
-// broadcast.  Returns the tree status (uniform).  On success lane j holds in `coef` the weight
-// dt_j * exp(s_k - s_j) of node j if it lies on path(k) and its position on the path (root
-// first) in `pos`, else pos = -1; `len` = nodes on the path, `decay` = exp(s_k).
-__device__ __forceinline__ int wave_path(int lane, int n, int k, int parent_j, float dt_j, float A_h, int &pos,
-                                         float &coef, int &len, float &decay) {
-    int p = -1;
-    bool ok = true;
-    if (lane < n) {
-        p = parent_j;
-        ok = (lane == 0) ? (p == -1) : (p >= 0 && p < lane);
-        if (!ok) p = -1;
-    }
-    const unsigned long long badmask = __ballot(!ok);
-    if (badmask) return __ffsll((long long)badmask);
-    float s = lane < n ? dt_j * A_h : 0.f;
-    unsigned long long m = lane < n ? (1ull << lane) : 0ull;
-    for (int round = 0; round < 6; ++round) {
-        if (!__any(p >= 0)) break;
-        const int q = p >= 0 ? p : lane;
-        const float rs = __shfl(s, q);
-        const int rp = __shfl(p, q);
-        const unsigned long long rm = __shfl(m, q);
-        if (p >= 0) {
-            s += rs;
-            m |= rm;
-            p = rp;
-        }
-    }
-    const float s_k = __shfl(s, k);
-    const unsigned long long m_k = __shfl(m, k);
-    const bool on = (m_k >> lane) & 1ull;
-    pos = on ? __popcll(m_k & ((1ull << lane) - 1ull)) : -1;   // ancestors have smaller labels
-    coef = on ? dt_j * __expf(s_k - s) : 0.f;
-    len = __popcll(m_k);
-    decay = __expf(s_k);
-    return 0;
-}
-
 // conv tail: out row r (oldest first) = pre-conv row of the (W-2-r)-th ancestor of k, or the old
 // state row once above the root.  One workgroup covers VEC*256 channels of one sequence.
 template <typename T, int VEC>

@@ -123,4 +123,59 @@ __device__ __forceinline__ bool mask_bit(const uint32_t *mask, int words, int i,
     return (mask[i * words + (j >> 5)] >> (j & 31)) & 1u;
 }
 
+// Cross-lane read within a wave of 64: value `v` of lane `src` (0..63).  Unlike __shfl this
+// needs no lane id of the caller, so nothing lane-derived stays live around it.
+__device__ __forceinline__ int wave_read(int v, int src) { return __builtin_amdgcn_ds_bpermute(src << 2, v); }
+__device__ __forceinline__ uint32_t wave_read(uint32_t v, int src) {
+    return (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)v);
+}
+__device__ __forceinline__ float wave_read(float v, int src) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(src << 2, __float_as_int(v)));
+}
+__device__ __forceinline__ unsigned long long wave_read(unsigned long long v, int src) {
+    const uint32_t lo = wave_read((uint32_t)v, src), hi = wave_read((uint32_t)(v >> 32), src);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// Path of the accepted node k for trees of at most 64 nodes, by one wave with no LDS and no
+// barrier: lane j owns node j; pointer doubling over the parent array with cross-lane reads
+// gives every lane s_j (the paper's A_tree) and its ancestor bit row; lane k's values are then
+// broadcast.  Returns the tree status (uniform).  On success lane j holds in `coef` the weight
+// dt_j * exp(s_k - s_j) of node j if it lies on path(k) and its position on the path (root
+// first) in `pos`, else pos = -1; `len` = nodes on the path, `decay` = exp(s_k).
+__device__ __forceinline__ int wave_path(int lane, int n, int k, int parent_j, float dt_j, float A_h, int &pos,
+                                         float &coef, int &len, float &decay) {
+    int p = -1;
+    bool ok = true;
+    if (lane < n) {
+        p = parent_j;
+        ok = (lane == 0) ? (p == -1) : (p >= 0 && p < lane);
+        if (!ok) p = -1;
+    }
+    const unsigned long long badmask = __ballot(!ok);
+    if (badmask) return __ffsll((long long)badmask);
+    float s = lane < n ? dt_j * A_h : 0.f;
+    unsigned long long m = lane < n ? (1ull << lane) : 0ull;
+    for (int round = 0; round < 6; ++round) {
+        if (!__any(p >= 0)) break;
+        const int q = p >= 0 ? p : lane;
+        const float rs = wave_read(s, q);
+        const int rp = wave_read(p, q);
+        const unsigned long long rm = wave_read(m, q);
+        if (p >= 0) {
+            s += rs;
+            m |= rm;
+            p = rp;
+        }
+    }
+    const float s_k = wave_read(s, k);
+    const unsigned long long m_k = wave_read(m, k);
+    const bool on = (m_k >> lane) & 1ull;
+    pos = on ? __popcll(m_k & ((1ull << lane) - 1ull)) : -1;   // ancestors have smaller labels
+    coef = on ? dt_j * __expf(s_k - s) : 0.f;
+    len = __popcll(m_k);
+    decay = __expf(s_k);
+    return 0;
+}
+
 }  // namespace stree

@@ -54,20 +54,41 @@ constexpr int kB64 = 64;
 constexpr int kNP64 = kB64 + 8;
 constexpr int kT64 = 512;   // 8 waves: 4 Y waves, 3 G waves, 1 tree wave
 
-// static LDS of the kernel below (C, B, h0b tiles, two X^T tiles, M, tree arrays)
+constexpr int kRC = 8;      // path nodes of the previous tree whose x / B rows are staged in LDS per unit
+constexpr int kYStage = 4 * 2048;   // bytes at the start of the B tile's LDS that the Y waves turn y around in
+
+// static LDS of the kernel below (C, B, h0b tiles, two X^T tiles, M, tree arrays; with replay
+// the path arrays and, where the B tile has no room behind the y staging area, the path rows)
 template <int P, int S>
 struct Lds64 {
     static constexpr int SP = S + 8;
+    static constexpr size_t replay_rows = (size_t)kRC * (P + S) * 2;
+    static constexpr bool rows_in_b = (size_t)kB64 * SP * 2 >= kYStage + replay_rows;
     static constexpr size_t total = (size_t)2 * kB64 * SP * 2 + (size_t)P * SP * 2 + (size_t)2 * P * kNP64 * 2 +
                                     (size_t)kB64 * kNP64 * 2 + 1040;
+    static constexpr size_t total_replay = total + 336 + (rows_in_b ? 0 : replay_rows);
 };
 
-// Output stores that write through L2 (system scope): y is never read again by this kernel, and
-// lines left dirty in the eight L2s would all be written back at once when the kernel ends.
+// The previous iteration's tree and cached activations (fused replay variant only).
+struct ReplayArgs {
+    const int32_t *parent, *accepted;   // [B, pn], [B]
+    const bf16_t *x, *Bm;               // [B, pn, H, P], [B, pn, G, S] with token strides x_sn, b_sn
+    const float *dt;                    // [B, pn, H]
+    long x_sn, b_sn;
+    int pn;
+    float *h_out;                       // [B, H, P, S]: the replayed state
+    int32_t *status;                    // [B] or null
+};
+
+// Output stores that write through L2 (system scope): y and the replayed state are never read
+// again by this kernel, and lines left dirty in the eight L2s would all be written back at once
+// when the kernel ends.  The store is inline assembly, so the compiler does not know that it reads
+// four data registers after issue: the trailing s_nop keeps the next instruction from overwriting
+// them in that window (the wait states a store of more than 8 bytes needs).
 __device__ __forceinline__ void store_through16(void *p, uint4 v) {
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
     const u32x4 vv = {v.x, v.y, v.z, v.w};
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(vv) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(vv) : "memory");
 }
 
 // Wave-level tree index for n <= 64: lane i owns node i; pointer doubling with
@@ -92,9 +113,9 @@ __device__ __forceinline__ int wave_tree_index(int lane, int n, int parent_i, fl
     for (int round = 0; round < 6; ++round) {
         if (!__any(p >= 0)) break;
         const int q = p >= 0 ? p : lane;
-        const float rs = __shfl(s, q);
-        const int rp = __shfl(p, q);
-        const uint32_t rlo = __shfl(mlo, q), rhi = __shfl(mhi, q);
+        const float rs = wave_read(s, q);
+        const int rp = wave_read(p, q);
+        const uint32_t rlo = wave_read(mlo, q), rhi = wave_read(mhi, q);
         if (p >= 0) {
             s += rs;
             mlo |= rlo;
@@ -110,13 +131,23 @@ __device__ __forceinline__ int wave_tree_index(int lane, int n, int parent_i, fl
     return 0;
 }
 
-// WPE = waves per SIMD the register budget is sized for: 4 when two workgroups fit a CU's LDS
-template <int P, int S, int WPE>
+// WPE = waves per SIMD the register budget is sized for: 4 when two workgroups fit a CU's LDS.
+//
+// RP = fused activation replay (Alg. 1): the state loaded for a unit is first advanced along the
+// accepted path of the previous tree,
+//   h* = exp(s_k) h0 + sum_{j on path(k)} dt_j exp(s_k - s_j) x_j (outer) B_j,
+// in the fp32 registers it arrives in, written back once to h_out, and only then rounded to the
+// bf16 MFMA operand.  The tree wave works the path out one unit ahead (same pointer doubling as
+// the tree index, on the previous tree), fetches the x / B rows of its first kRC nodes and puts
+// them into LDS at the start of the staging half; one more barrier per unit (c) separates that
+// from the FMAs of the threads that carry the unit.  Longer paths read the remaining rows from
+// global memory.  Each thread owns one 4-wide piece of the state index and NH consecutive rows.
+template <int P, int S, int WPE, bool RP>
 __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void tree_ssd_mfma64_kernel(
     const int32_t *__restrict__ parent, int n, int nbatch, int H, int G, const bf16_t *__restrict__ x, long x_sn,
     const float *__restrict__ dt, const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn,
     const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
-    bf16_t *__restrict__ y, int32_t *__restrict__ status) {
+    bf16_t *__restrict__ y, int32_t *__restrict__ status, ReplayArgs R) {
     using L = Lds64<P, S>;
     constexpr int SP = L::SP;
     constexpr int kHalf = kT64 / 2;                 // threads per role group
@@ -126,6 +157,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     constexpr int YT = (P / 32) * 2, YQ = YT / 4;   // Yt tiles, tiles per Y wave
     constexpr int kRowsC = kHalf / (S / 8), kRowsX = kHalf / (P / 8);
     static_assert(NC >= 1 && NX >= 1 && NH >= 1 && YQ >= 1, "tile too small for this thread count");
+    static_assert(!RP || NH % 4 == 0, "replay reads a thread's x values four at a time");
     // separate LDS objects (not slices of one array), so that the compiler knows that a write to
     // one tile cannot alias a read of another and does not serialise them
     __shared__ __align__(16) bf16_t sC[kB64 * SP];
@@ -138,13 +170,19 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     __shared__ uint32_t sMask[kB64 * 2];
     __shared__ int sBad[1];
     __shared__ float sDh[1];
+    // replay: path of the accepted node (position -> node, weight), its length and exp(s_k)
+    __shared__ float sRcoef[RP ? kB64 : 1];
+    __shared__ unsigned char sRnode[RP ? kB64 : 4];
+    __shared__ int sRlen[1];
+    __shared__ float sRdec[1];
+    __shared__ __align__(16) bf16_t sRrows[(RP && !L::rows_in_b) ? kRC * (P + S) : 8];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = tid >> 6;
     constexpr int kTreeWave = 6;
     const bool isY = wave < 4;
     const int rt = tid & (kHalf - 1);    // thread index within its role group
     const int it = wave & 1;             // node half of the tiles this wave owns
-    const int il = it * 32 + l32;        // this lane's node in accumulators
     const int n_units = nbatch * H;
     const int per_xcd = (n_units + 7) >> 3;
     const int xcd = blockIdx.x & 7;
@@ -178,7 +216,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     constexpr int NPRE = NH + NX;
     uint4 pre[NPRE];
     int rpar = -1;
-    float rdt = 0.f, rA = 0.f;
+    float rdt = 0.f;
     // The chunk coordinates of a thread are loop invariants; keeping them all in registers
     // across the unit loop would cost more registers than the budget of 128 allows, so every
     // helper below re-derives them from an opaque copy of the thread index (a few VALU ops).
@@ -188,14 +226,24 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     };
 
     float rD = 0.f;                  // D[h] of the unit whose h0 is in pre[]
+    // chunk q of a thread: without replay element (t + q*kHalf)*4 of the P x S tile; with replay
+    // row (t / S4) * NH + q, piece t % S4, so that a thread's rows are consecutive
+    constexpr int S4 = S / 4;
     auto load_H = [&](int b, int h) {       // the role group that carries this unit
         // the lane-dependent zero keeps this a vector load: it then sits in the same in-order
         // queue as the h0 chunks instead of forcing a scalar-cache wait in the hot window
         if (D) rD = D[h + (opaque(lane) & 0)];
         const char *hb = reinterpret_cast<const char *>(h0 + ((size_t)b * H + h) * P * S);
-        const uint32_t off = (uint32_t)opaque(rt) * 16u;
+        if constexpr (RP) {
+            const int t = opaque(rt);
+            const uint32_t off = (uint32_t)(((t / S4) * NH) * S + (t % S4) * 4) * 4u;
 #pragma unroll
-        for (int q = 0; q < NH; ++q) pre[q] = *reinterpret_cast<const uint4 *>(hb + q * (kHalf * 16) + off);
+            for (int q = 0; q < NH; ++q) pre[q] = *reinterpret_cast<const uint4 *>(hb + off + q * (S * 4));
+        } else {
+            const uint32_t off = (uint32_t)opaque(rt) * 16u;
+#pragma unroll
+            for (int q = 0; q < NH; ++q) pre[q] = *reinterpret_cast<const uint4 *>(hb + q * (kHalf * 16) + off);
+        }
     };
     // C and B tiles of a unit: global -> registers -> LDS in one go (G threads).  Runs only when
     // the (sequence, group) changes, i.e. about once per workgroup.
@@ -233,18 +281,79 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         const int node = min(opaque(lane), n - 1);
         rpar = parent[(uint32_t)(b * n + node)];
         rdt = dt[(uint32_t)((b * n + node) * H + h)];
-        rA = A[h];
     };
     // ---- registers -> LDS -------------------------------------------------------------------------
-    auto stage_H = [&]() {
+    // rbuf: the LDS rows of the replayed path (x rows [kRC][P], then B rows [kRC][S]); b, h: the unit
+    auto stage_H = [&]([[maybe_unused]] const char *rbuf, [[maybe_unused]] int b, [[maybe_unused]] int h) {
         const int t = opaque(rt);
+        if constexpr (RP) {
+            const int prow = (t / S4) * NH, s4 = t % S4;
+            const int len = *sRlen;
+            const float dec = *sRdec;
+            float hv[NH][4];
 #pragma unroll
-        for (int q = 0; q < NH; ++q) {
-            const int e = (t + q * kHalf) * 4, p = e / S, sidx = e % S;
-            bf16x4 o;
-            o[0] = (bf16_t)__uint_as_float(pre[q].x); o[1] = (bf16_t)__uint_as_float(pre[q].y);
-            o[2] = (bf16_t)__uint_as_float(pre[q].z); o[3] = (bf16_t)__uint_as_float(pre[q].w);
-            *reinterpret_cast<bf16x4 *>(&sH[p * SP + sidx]) = o;
+            for (int q = 0; q < NH; ++q) {
+                hv[q][0] = dec * __uint_as_float(pre[q].x); hv[q][1] = dec * __uint_as_float(pre[q].y);
+                hv[q][2] = dec * __uint_as_float(pre[q].z); hv[q][3] = dec * __uint_as_float(pre[q].w);
+            }
+            auto rank1 = [&](float cf, uint2 b4, const uint32_t (&xw)[NH / 2]) {
+                const float bv[4] = {cf * bf16_lo(b4.x), cf * bf16_hi(b4.x), cf * bf16_lo(b4.y), cf * bf16_hi(b4.y)};
+#pragma unroll
+                for (int q = 0; q < NH; ++q) {
+                    const float xv = (q & 1) ? bf16_hi(xw[q >> 1]) : bf16_lo(xw[q >> 1]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) hv[q][e] = fmaf(xv, bv[e], hv[q][e]);
+                }
+            };
+            const int nl = min(len, kRC);
+            for (int j = 0; j < nl; ++j) {
+                const uint2 b4 = *reinterpret_cast<const uint2 *>(rbuf + (kRC * P + j * S + s4 * 4) * 2);
+                uint32_t xw[NH / 2];
+#pragma unroll
+                for (int w = 0; w < NH / 2; w += 2) {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(rbuf + (j * P + prow + 2 * w) * 2);
+                    xw[w] = v.x;
+                    xw[w + 1] = v.y;
+                }
+                rank1(sRcoef[j], b4, xw);
+            }
+            if (len > kRC) {   // the rest of a long path: rows straight from global memory
+                const int g = h / hpg;
+                const char *xb = reinterpret_cast<const char *>(R.x + (size_t)b * R.pn * R.x_sn + (size_t)h * P + prow);
+                const char *Bb = reinterpret_cast<const char *>(R.Bm + (size_t)b * R.pn * R.b_sn + (size_t)g * S + s4 * 4);
+                for (int j = kRC; j < len; ++j) {
+                    const int node = sRnode[j];
+                    const uint2 b4 = *reinterpret_cast<const uint2 *>(Bb + (size_t)node * R.b_sn * 2);
+                    uint32_t xw[NH / 2];
+#pragma unroll
+                    for (int w = 0; w < NH / 2; w += 2) {
+                        const uint2 v = *reinterpret_cast<const uint2 *>(xb + ((size_t)node * R.x_sn + 2 * w) * 2);
+                        xw[w] = v.x;
+                        xw[w + 1] = v.y;
+                    }
+                    rank1(sRcoef[j], b4, xw);
+                }
+            }
+            // the replayed state: written once, through L2 (never read again by this kernel)
+            char *ob = reinterpret_cast<char *>(R.h_out + ((size_t)b * H + h) * P * S);
+#pragma unroll
+            for (int q = 0; q < NH; ++q) {
+                store_through16(ob + (uint32_t)((prow + q) * S + s4 * 4) * 4u,
+                                make_uint4(__float_as_uint(hv[q][0]), __float_as_uint(hv[q][1]),
+                                           __float_as_uint(hv[q][2]), __float_as_uint(hv[q][3])));
+                bf16x4 o;
+                o[0] = (bf16_t)hv[q][0]; o[1] = (bf16_t)hv[q][1]; o[2] = (bf16_t)hv[q][2]; o[3] = (bf16_t)hv[q][3];
+                *reinterpret_cast<bf16x4 *>(&sH[(prow + q) * SP + s4 * 4]) = o;
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < NH; ++q) {
+                const int e = (t + q * kHalf) * 4, p = e / S, sidx = e % S;
+                bf16x4 o;
+                o[0] = (bf16_t)__uint_as_float(pre[q].x); o[1] = (bf16_t)__uint_as_float(pre[q].y);
+                o[2] = (bf16_t)__uint_as_float(pre[q].z); o[3] = (bf16_t)__uint_as_float(pre[q].w);
+                *reinterpret_cast<bf16x4 *>(&sH[p * SP + sidx]) = o;
+            }
         }
         if (rt == 0) *sDh = rD;      // D of that unit, for the Y waves
     };
@@ -265,11 +374,128 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
         }
     };
-    auto stage_T = [&]() {
+    auto stage_T = [&](int h) {
         const int ln = opaque(lane);   // LDS addresses re-derived here, not carried across the loop
-        const int bad = wave_tree_index(ln, n, rpar, rdt, rA, sS2, sU, sMask);
+        const int bad = wave_tree_index(ln, n, rpar, rdt, A[h], sS2, sU, sMask);
         if (ln == 0) *sBad = bad;
     };
+
+    // ---- replay (tree wave): previous tree's path one unit ahead ----------------------------------
+    // Registers that only the tree wave needs live in its copy of acc[0], which it never uses
+    // as an accumulator: 0-3 x row pieces, 4-11 B row pieces, 12 position on the path, 13 weight,
+    // 14 path length, 15 exp(s_k).
+    constexpr int PX = P / 8, PB = S / 8;                     // 16-byte pieces per x row, per B row
+    constexpr int NXG = (kRC * PX + 63) / 64, NBG = (kRC * PB + 63) / 64;   // pieces per lane
+    static_assert(!RP || (NXG <= 1 && NBG <= 2) || WPE < 4, "tree-wave registers exceed its accumulator copy");
+    int rpp = -1;
+    float rpdt = 0.f;
+    uint4 gxw[(RP && WPE < 4) ? NXG : 1], gbw[(RP && WPE < 4) ? NBG : 1];   // roomy variants: plain registers
+    int wpos = -1, wlen = 0;
+    float wcf = 0.f, wdec = 1.f;
+    auto load_R = [&](int b, int h) {
+        const int node = min(opaque(lane), R.pn - 1);
+        rpp = R.parent[(uint32_t)(b * R.pn + node)];
+        rpdt = R.dt[(uint32_t)((b * R.pn + node) * H + h)];
+    };
+    auto path_R = [&](floatx16 &tw, int b, int h) {
+        const int ln = opaque(lane);
+        const int pn = R.pn;
+        const int rk = R.accepted[b];      // uniform: scalar loads, this wave is not in a hot window
+        const float rRA = A[h];
+        const bool kbad = rk < -1 || rk >= pn;
+        int pos = -1, len = 0;
+        float cf = 0.f, dc = 1.f;
+        const int st = wave_path(ln, pn, (rk >= 0 && !kbad) ? rk : 0, rpp, rpdt, rRA, pos, cf, len, dc);
+        if (st != 0 || rk < 0 || kbad) {   // nothing to replay: the state passes through
+            pos = -1;
+            len = 0;
+            cf = 0.f;
+            dc = 1.f;
+        }
+        if (R.status && h == 0 && ln == 0) R.status[b] = st ? st : (kbad ? -1 : 0);
+        // x / B rows of the first kRC path nodes: 16-byte pieces dealt over the lanes
+        const int g = h / hpg;
+        const char *xb = reinterpret_cast<const char *>(R.x + (size_t)b * pn * R.x_sn + (size_t)h * P);
+        const char *Bb = reinterpret_cast<const char *>(R.Bm + (size_t)b * pn * R.b_sn + (size_t)g * S);
+        int nx[NXG], nb[NBG];      // node of the path position each of this lane's pieces belongs to
+#pragma unroll
+        for (int i = 0; i < NXG; ++i) nx[i] = 0;
+#pragma unroll
+        for (int i = 0; i < NBG; ++i) nb[i] = 0;
+#pragma unroll
+        for (int sl = 0; sl < kRC; ++sl) {
+            const unsigned long long m = __ballot(pos == sl);
+            const int nd = m ? (int)__ffsll((long long)m) - 1 : 0;
+#pragma unroll
+            for (int i = 0; i < NXG; ++i) nx[i] = ((ln + 64 * i) / PX == sl) ? nd : nx[i];
+#pragma unroll
+            for (int i = 0; i < NBG; ++i) nb[i] = ((ln + 64 * i) / PB == sl) ? nd : nb[i];
+        }
+        uint4 gx[NXG], gb[NBG];
+#pragma unroll
+        for (int i = 0; i < NXG; ++i)
+            gx[i] = *reinterpret_cast<const uint4 *>(xb + (uint32_t)(nx[i] * (int)R.x_sn + ((ln + 64 * i) % PX) * 8) * 2u);
+#pragma unroll
+        for (int i = 0; i < NBG; ++i)
+            gb[i] = *reinterpret_cast<const uint4 *>(Bb + (uint32_t)(nb[i] * (int)R.b_sn + ((ln + 64 * i) % PB) * 8) * 2u);
+        if constexpr (WPE < 4) {
+#pragma unroll
+            for (int i = 0; i < NXG; ++i) gxw[i] = gx[i];
+#pragma unroll
+            for (int i = 0; i < NBG; ++i) gbw[i] = gb[i];
+            wpos = pos; wcf = cf; wlen = len; wdec = dc;
+        } else {
+            tw[0] = __uint_as_float(gx[0].x); tw[1] = __uint_as_float(gx[0].y);
+            tw[2] = __uint_as_float(gx[0].z); tw[3] = __uint_as_float(gx[0].w);
+#pragma unroll
+            for (int i = 0; i < NBG; ++i) {
+                tw[4 + 4 * i] = __uint_as_float(gb[i].x); tw[5 + 4 * i] = __uint_as_float(gb[i].y);
+                tw[6 + 4 * i] = __uint_as_float(gb[i].z); tw[7 + 4 * i] = __uint_as_float(gb[i].w);
+            }
+            tw[12] = __int_as_float(pos); tw[13] = cf; tw[14] = __int_as_float(len); tw[15] = dc;
+        }
+    };
+    auto write_R = [&](const floatx16 &tw, char *rbuf) {
+        const int ln = opaque(lane);
+        uint4 gx[NXG], gb[NBG];
+        int pos, len;
+        float cf, dc;
+        if constexpr (WPE < 4) {
+#pragma unroll
+            for (int i = 0; i < NXG; ++i) gx[i] = gxw[i];
+#pragma unroll
+            for (int i = 0; i < NBG; ++i) gb[i] = gbw[i];
+            pos = wpos; cf = wcf; len = wlen; dc = wdec;
+        } else {
+            gx[0] = make_uint4(__float_as_uint(tw[0]), __float_as_uint(tw[1]), __float_as_uint(tw[2]), __float_as_uint(tw[3]));
+#pragma unroll
+            for (int i = 0; i < NBG; ++i)
+                gb[i] = make_uint4(__float_as_uint(tw[4 + 4 * i]), __float_as_uint(tw[5 + 4 * i]),
+                                   __float_as_uint(tw[6 + 4 * i]), __float_as_uint(tw[7 + 4 * i]));
+            pos = __float_as_int(tw[12]); cf = tw[13]; len = __float_as_int(tw[14]); dc = tw[15];
+        }
+#pragma unroll
+        for (int i = 0; i < NXG; ++i) {
+            const int idx = ln + 64 * i;
+            if (idx < kRC * PX) *reinterpret_cast<uint4 *>(rbuf + ((idx / PX) * P + (idx % PX) * 8) * 2) = gx[i];
+        }
+#pragma unroll
+        for (int i = 0; i < NBG; ++i) {
+            const int idx = ln + 64 * i;
+            if (idx < kRC * PB)
+                *reinterpret_cast<uint4 *>(rbuf + (kRC * P + (idx / PB) * S + (idx % PB) * 8) * 2) = gb[i];
+        }
+        if (pos >= 0) {
+            sRnode[pos] = (unsigned char)ln;
+            sRcoef[pos] = cf;
+        }
+        if (ln == 0) {
+            *sRlen = len;
+            *sRdec = dc;
+        }
+    };
+    // LDS rows of the replayed path: behind the y staging area of the idle B tile, or their own array
+    char *const rrows = L::rows_in_b ? reinterpret_cast<char *>(sB) + kYStage : reinterpret_cast<char *>(sRrows);
 
     if (nU <= 0) return;
     STREE_EXIT_INIT;
@@ -291,7 +517,10 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         STREE_PHASE_PRO(16, 0);
     } else {
         load_X(b1, h1);
-        if (wave == kTreeWave) load_T(b1, h1);
+        if (wave == kTreeWave) {
+            load_T(b1, h1);
+            if constexpr (RP) load_R(b1, h1);
+        }
         STREE_PHASE_PRO(18, 256);
     }
     STREE_EXIT_POINT(2);
@@ -327,6 +556,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
             // ---- phase 1: Yt = h0b C^T, then *= exp(s_i) -------------------------------------------
             if (h0 && !bad) {
+                const int lnp = opaque(lane), l32 = lnp & 31, lh = lnp >> 5, il = it * 32 + l32;   // re-derived per phase
                 const bf16_t *cp = &sC[il * SP + 8 * lh];
 #pragma unroll
                 for (int kb = 0; kb < S; kb += S / 2) {   // fragments of half the state index per batch
@@ -356,6 +586,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         } else if (wave != kTreeWave && !bad) {
             // ---- phase 2: Gt = B C^T (only when the C/B tiles are new), mask and decay -> M ----------
             const int jt = (wave - 4) >> 1;
+            const int lnp = opaque(lane), l32 = lnp & 31, lh = lnp >> 5, il = it * 32 + l32;   // re-derived per phase
             STREE_PHASE_CLOCK_G(9);
             floatx16 &gt = acc[0];
             if (fresh_at(k, ch)) {
@@ -405,11 +636,19 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
 
         const bool more = k + 1 < nU, more2 = k + 2 < nU, more3 = k + 3 < nU;
         const bool y_stages = (k & 1) != 0;    // unit k+1 is even: its h0 sits in the Y threads
+        // new C / B tiles for unit k+1 overwrite the B tile's LDS, which this half uses as scratch
+        // (y staging, replayed path rows): they wait for one more barrier (a).  Not in the first
+        // pass, which has no such use and wants the tiles early.
+        const bool fresh_next = more && fresh_at(k + 1, h1);
+        const bool late_tiles = live && fresh_next;
+        // replayed path rows of unit k+1: in the first pass the M tile's LDS (the B tile is being
+        // written), later the B tile's
+        [[maybe_unused]] char *rbuf = (L::rows_in_b && !live) ? reinterpret_cast<char *>(sM) : rrows;
         if (isY) {
             // ---- phase 3: Yt += Xt M^T over j <= i only (nodes i < 32 have no ancestor j >= 32:
-            //      that quadrant of M is never written or read); y = Yt + D x -> own 32x32 block
-            //      of the bf16 staging rows ------------------------------------------------------------
+            //      that quadrant of M is never written or read); y = Yt + D x ---------------------------
             bf16x4 yreg[YQ][4];
+            const int lnp = opaque(lane), l32 = lnp & 31, lh = lnp >> 5, il = it * 32 + l32;   // re-derived per phase
 #pragma unroll
             for (int q = 0; q < YQ; ++q) {
                 if (!live) break;
@@ -458,10 +697,11 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
             STREE_PHASE_CLOCK(3);
             if (live) STREE_EXIT_POINT(13 + 10 * k);
+            if (RP && more) __syncthreads();                  // barrier (c): path rows of unit k+1 are in LDS
             // next unit's state tile (its loads have been in flight for a whole unit period)
             if (more) {
                 if (h0) {
-                    if (y_stages) stage_H();
+                    if (y_stages) stage_H(rbuf, b1, h1);
                     if (!live) STREE_PHASE_PRO(17, 0);
                 } else if (rt == 0) {
                     *sDh = D ? D[h1] : 0.f;
@@ -472,69 +712,77 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             // node, which as direct stores would be 16-byte pieces of 32 different lines per
             // instruction.  Each wave therefore turns its 32x32 tile around in a private 2 KB of LDS
             // (a wave's LDS operations complete in order: no barrier) and stores 16 bytes per lane,
-            // four lanes to a row.  The LDS used is the B tile's, idle except while the next unit
-            // brings new C / B tiles; that pass stores straight from the accumulators instead.
+            // four lanes to a row.  The LDS used is the B tile's, which is idle in this half.
             // The stores go out after the wait for the h0 loads above and are long complete at
             // the next such wait: on gfx9 loads and stores share one counter and complete out of
             // order with respect to each other, so a store in flight would turn that wait into a
             // wait for everything.
             if (live) {
                 char *yb = reinterpret_cast<char *>(y + (size_t)cb * n * H * P + (size_t)ch * P);
-                if (!(more && fresh_at(k + 1, h1))) {
-                    char *ys = reinterpret_cast<char *>(sB) + opaque(wave) * 2048;
-                    const int ln = opaque(lane), wr = ln & 31, wh = ln >> 5;
-                    const int rr = ln >> 2, rc = ln & 3;
+                char *ys = reinterpret_cast<char *>(sB) + opaque(wave) * 2048;
+                const int ln = opaque(lane), wr = ln & 31, wh = ln >> 5;
+                const int rr = ln >> 2, rc = ln & 3;
 #pragma unroll
-                    for (int q = 0; q < YQ; ++q) {
-                        const int pt = (wave + 4 * q) >> 1;
-                        // row r keeps its 16-byte chunk c at slot c ^ ((r >> 2) & 3)
+                for (int q = 0; q < YQ; ++q) {
+                    const int pt = (wave + 4 * q) >> 1;
+                    // row r keeps its 16-byte chunk c at slot c ^ ((r >> 2) & 3)
 #pragma unroll
-                        for (int rg = 0; rg < 4; ++rg)
-                            *reinterpret_cast<bf16x4 *>(ys + wr * 64 + ((rg ^ ((wr >> 2) & 3)) * 16) + wh * 8) =
-                                yreg[q][rg];
+                    for (int rg = 0; rg < 4; ++rg)
+                        *reinterpret_cast<bf16x4 *>(ys + wr * 64 + ((rg ^ ((wr >> 2) & 3)) * 16) + wh * 8) =
+                            yreg[q][rg];
 #pragma unroll
-                        for (int half = 0; half < 2; ++half) {
-                            const int row = half * 16 + rr;
-                            const uint4 v =
-                                *reinterpret_cast<const uint4 *>(ys + row * 64 + ((rc ^ ((row >> 2) & 3)) * 16));
-                            const int node = it * 32 + row;
-                            if (node < n)
-                                store_through16(yb + (uint32_t)(node * H * P + pt * 32 + rc * 8) * 2u, v);
-                        }
-                    }
-                } else if (il < n) {
-                    const int row = opaque(il), lh = opaque(lane) >> 5;   // re-derived: not carried across the loop
-#pragma unroll
-                    for (int q = 0; q < YQ; ++q) {
-                        const int pt = (wave + 4 * q) >> 1;
-#pragma unroll
-                        for (int rg = 0; rg < 4; ++rg)
-                            *reinterpret_cast<bf16x4 *>(yb + (uint32_t)(row * H * P + pt * 32 + 8 * rg + 4 * lh) * 2u) =
-                                yreg[q][rg];   // 8-byte pieces: left to L2 to merge, not written through
+                    for (int half = 0; half < 2; ++half) {
+                        const int row = half * 16 + rr;
+                        const uint4 v =
+                            *reinterpret_cast<const uint4 *>(ys + row * 64 + ((rc ^ ((row >> 2) & 3)) * 16));
+                        const int node = it * 32 + row;
+                        if (node < n)
+                            store_through16(yb + (uint32_t)(node * H * P + pt * 32 + rc * 8) * 2u, v);
                     }
                 }
             }
             if (h0 && more3 && y_stages) load_H(b3, h3);
             STREE_PHASE_CLOCK(5);
+            if (late_tiles) __syncthreads();                  // barrier (a): scratch use of the B tile is over
         } else if (more) {
-            if (h0 && !y_stages) {
-                stage_H();
-                if (more3) load_H(b3, h3);
-            }
             if (wave == kTreeWave) {
-                stage_T();
+                stage_T(h1);
                 if (!live) STREE_PHASE_PRO(20, 384);
                 if (more2) load_T(b2, h2);
             }
-            if (fresh_at(k + 1, h1)) restage_CB(b1, h1);
+            if (fresh_next && !live) restage_CB(b1, h1);
             if (!live) STREE_PHASE_PRO(19, 256);
             stage_X((k + 1) & 1);                          // the other X^T tile: unit k still reads its own
             if (!live) STREE_PHASE_PRO(21, 256);
+            if constexpr (RP) {
+                if (wave == kTreeWave) {
+                    if (!live) {                           // unit 0: path and rows within this pass
+                        path_R(acc[0], b1, h1);
+                        if (more2) load_R(b2, h2);
+                    }
+                    write_R(acc[0], rbuf);
+                }
+                __syncthreads();                           // barrier (c)
+            }
+            if (h0 && !y_stages) {
+                stage_H(rbuf, b1, h1);
+                if (more3) load_H(b3, h3);
+            }
             if (more2) {
                 load_X(b2, h2);
                 if (!live && h0) load_H(b2, h2);           // unit 1: the first odd unit
             }
+            if constexpr (RP) {
+                if (wave == kTreeWave && more2) {          // path of unit k+2, rows into registers
+                    path_R(acc[0], b2, h2);
+                    if (more3) load_R(b3, h3);
+                }
+            }
             if (!live) STREE_PHASE_PRO(22, 256);
+            if (late_tiles) {
+                __syncthreads();                           // barrier (a)
+                restage_CB(b1, h1);
+            }
         }
         STREE_PHASE_CLOCK(6);
         STREE_PHASE_CLOCK(7);
@@ -546,22 +794,33 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     }
 }
 
-template <int P, int S>
+template <int P, int S, bool RP>
 hipError_t launch64_ps(const stree_dims &d, const int32_t *parent, const void *x, const float *dt, const float *A,
                        const void *Bm, const void *Cm, const float *D, const float *h0, void *y,
-                       int32_t *status, hipStream_t st) {
-    constexpr size_t lds = Lds64<P, S>::total;   // static LDS of the kernel (upper bound)
+                       int32_t *status, const ReplayArgs &R, hipStream_t st) {
+    constexpr size_t lds = RP ? Lds64<P, S>::total_replay : Lds64<P, S>::total;   // static LDS (upper bound)
     constexpr int WPE = (2 * (lds + 64) <= 160 * 1024) ? 4 : 2;
     const int n_units = d.batch * d.nheads;
     const int per_cu = (int)((160 * 1024) / (lds + 64));      // resident workgroups per CU by LDS
     int grid = (n_units + 7) / 8 * 8;
-    const int cap = 256 * (per_cu < 1 ? 1 : per_cu);
+    const int cap = 256 * (per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu));
     if (grid > cap) grid = cap;
-    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE>), dim3(grid), dim3(kT64), 0, st, parent, d.nnodes,
+    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE, RP>), dim3(grid), dim3(kT64), 0, st, parent, d.nnodes,
                        d.batch, d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A,
                        (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,
-                       (bf16_t *)y, status);
+                       (bf16_t *)y, status, R);
     return hipGetLastError();
+}
+
+template <bool RP>
+hipError_t launch64(const stree_dims &d, const int32_t *parent, const void *x, const float *dt, const float *A,
+                    const void *Bm, const void *Cm, const float *D, const float *h0, void *y, int32_t *status,
+                    const ReplayArgs &R, hipStream_t st) {
+    const int P = d.headdim, S = d.dstate;
+    if (P == 64 && S == 128) return launch64_ps<64, 128, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
+    if (P == 64 && S == 64) return launch64_ps<64, 64, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
+    if (P == 128 && S == 128) return launch64_ps<128, 128, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -572,25 +831,28 @@ bool tree_ssd_mfma64_supported(const stree_dims &d) {
     return (P == 64 && (S == 128 || S == 64)) || (P == 128 && S == 128);
 }
 
-bool tree_ssd_replay_fused_supported(const stree_dims &, const stree_dims &, const void *, const void *, const void *,
-                                     const void *, const void *, const void *) {
-    return false;
+bool tree_ssd_replay_fused_supported(const stree_dims &d, const stree_dims &dp, const void *px, const void *pB,
+                                     const void *x, const void *Bm, const void *Cm, const void *y) {
+    if (d.io_dtype != STREE_BF16 || !tree_ssd_mfma64_supported(d) || dp.nnodes > kB64) return false;
+    if ((d.x_stride_n | d.b_stride_n | d.c_stride_n | dp.x_stride_n | dp.b_stride_n) % 8 != 0) return false;
+    const uintptr_t bits = (uintptr_t)x | (uintptr_t)Bm | (uintptr_t)Cm | (uintptr_t)y | (uintptr_t)px | (uintptr_t)pB;
+    return bits % 16 == 0;
 }
-hipError_t launch_tree_ssd_replay_fused(const stree_dims &, const stree_dims &, const int32_t *, const int32_t *,
-                                        const void *, const float *, const void *, const int32_t *, const void *,
-                                        const float *, const float *, const void *, const void *, const float *,
-                                        const float *, float *, void *, int32_t *, int32_t *, hipStream_t) {
-    return hipErrorInvalidValue;
+
+hipError_t launch_tree_ssd_replay_fused(const stree_dims &d, const stree_dims &dp, const int32_t *pparent,
+                                        const int32_t *paccepted, const void *px, const float *pdt, const void *pB,
+                                        const int32_t *parent, const void *x, const float *dt, const float *A,
+                                        const void *Bm, const void *Cm, const float *D, const float *h0,
+                                        float *h_out, void *y, int32_t *status, int32_t *rstatus, hipStream_t st) {
+    const ReplayArgs R = {pparent, paccepted, (const bf16_t *)px, (const bf16_t *)pB, pdt,
+                          (long)dp.x_stride_n, (long)dp.b_stride_n, dp.nnodes, h_out, rstatus};
+    return launch64<true>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
 }
 
 hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                   const float *A, const void *Bm, const void *Cm, const float *D,
                                   const float *h0, void *y, int32_t *status, hipStream_t st) {
-    const int P = d.headdim, S = d.dstate;
-    if (P == 64 && S == 128) return launch64_ps<64, 128>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
-    if (P == 64 && S == 64) return launch64_ps<64, 64>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
-    if (P == 128 && S == 128) return launch64_ps<128, 128>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
-    return hipErrorInvalidValue;
+    return launch64<false>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, ReplayArgs{}, st);
 }
 
 }  // namespace stree
