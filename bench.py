@@ -1,11 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the tree-masked SSD verification pass on one MI355X.
 
-A step is one pass of the whole hot path over one batch of synthetic input:
-  stree_tree_conv -> stree_tree_ssd (on column views of the conv output) ->
-  stree_commit_state
-on the 64-node / 80-head configuration at batch 16 (Mamba2-2.7B layer shape,
-bf16 io, fp32 state).  Inputs are resident in HBM before the timed region; the
+A step is one pass of the whole hot path (tree index, tree conv, tree scan,
+state commit) over one batch of synthetic input, on the 64-node / 80-head
+configuration at batch 16 (Mamba2-2.7B layer shape, bf16 io, fp32 state).  Two
+call sequences do that work and both are timed:
+  separate: stree_tree_conv -> stree_tree_ssd -> stree_commit_state
+            (the tree is committed right after it is scanned)
+  fused:    stree_commit_state (conv tail only) -> stree_tree_conv ->
+            stree_tree_ssd_replay
+            (the previous iteration's tree is committed while the state is
+            loaded for this iteration's scan, as in Alg. 1: one pass over the
+            state per iteration instead of two)
+`value` is the faster of the two; both are in the JSON line.  Inputs are resident in HBM before the timed region; the
 step rotates over several buffer sets so that the working set exceeds the
 256 MB Infinity Cache and the scan really streams from HBM.
 
@@ -40,6 +47,13 @@ def algorithmic_bytes_tree_ssd(B, N, H, P, S, G):
     return B * per_seq + 2 * H * 4
 
 
+def algorithmic_bytes_replay(B, N, Np, H, P, S, G, path_nodes):
+    """The scan's operands plus the replayed state written once, the previous tree's parent /
+    accepted / dt, and the x and B rows of the accepted paths (path_nodes = their total length)."""
+    extra = B * H * P * S * 4 + B * (Np * 4 + 4 + Np * H * 4) + path_nodes * (H * P + G * S) * 2
+    return algorithmic_bytes_tree_ssd(B, N, H, P, S, G) + extra
+
+
 def algorithmic_flops_tree_ssd(B, N, H, P, S, G):
     """C B^T once per group, (L o CB^T) X and C h0^T per head, dense-masked."""
     return B * (G * 2 * N * N * S + H * (2 * N * N * P + 2 * N * S * P))
@@ -63,6 +77,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-ssd", type=int, default=0, metavar="K",
                     help="profiling aid: run K tree-scan launches and exit")
+    ap.add_argument("--only-fused", type=int, default=0, metavar="K",
+                    help="profiling aid: run K fused replay + scan launches and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU; run with --gpus 1 (no collectives or sharding are built)")
@@ -118,13 +134,41 @@ def main():
         ssd(s)
         commit(s)
 
+    # fused sequence: the "previous tree" of a set is the tree of the set before it in the
+    # rotation, with the activations that set's conv left in its buffer
+    for r, s in enumerate(sets):
+        s["prev"] = sets[r - 1]
+
+    def conv_tail(s):
+        q = s["prev"]
+        st.stree_commit_state(q["parent"], q["accepted"], None, None, None, None, xbc_pre=q["xbc_pre"],
+                              conv_state=s["conv_state"], conv_state_out=s["cs_out"], dims=(H, P, S, G))
+
+    def conv_after_tail(s):
+        st.stree_tree_conv(s["parent"], s["xbc_pre"], s["cs_out"], conv_w, conv_b, H, P, S, G, silu=True,
+                           out=s["xbc"])
+
+    def fused(s):
+        q = s["prev"]
+        st.stree_tree_ssd_replay(q["parent"], q["accepted"], q["x"], q["dt"], q["Bm"], s["parent"], s["x"], s["dt"],
+                                 A, s["Bm"], s["Cm"], D, s["h0"], h_out=s["h_out"], out=s["y"])
+
+    def step_fused(s):
+        conv_tail(s)
+        conv_after_tail(s)
+        fused(s)
+
     for s in sets:           # first launches (also sets the kernel's LDS attribute) outside any capture
         step(s)
+    for s in sets:
+        step_fused(s)
     torch.cuda.synchronize()
 
-    if args.only_ssd:
+    if args.only_ssd or args.only_fused:
         for k in range(args.only_ssd):
             ssd(sets[k % N_SETS])
+        for k in range(args.only_fused):
+            fused(sets[k % N_SETS])
         torch.cuda.synchronize()
         return
 
@@ -145,6 +189,9 @@ def main():
             run_ssd = make_graphs(ssd)
             run_conv = make_graphs(conv)
             run_commit = make_graphs(commit)
+            run_step_fused = make_graphs(step_fused)
+            run_fused = make_graphs(fused)
+            run_tail = make_graphs(conv_tail)
         except Exception as exc:  # pragma: no cover
             log(f"[bench] HIP graph capture failed ({exc}); falling back to direct launches")
             use_graph = False
@@ -155,6 +202,7 @@ def main():
                     fn(s)
             return run
         run_step, run_ssd, run_conv, run_commit = all_sets(step), all_sets(ssd), all_sets(conv), all_sets(commit)
+        run_step_fused, run_fused, run_tail = all_sets(step_fused), all_sets(fused), all_sets(conv_tail)
 
     def timed(run, k, warm, per_run=N_SETS):
         """Wall-clock and HIP-event time per launch of k launches on the current stream
@@ -180,6 +228,9 @@ def main():
     _, ms_ssd = timed(run_ssd, K, Wm)
     _, ms_conv = timed(run_conv, K, Wm)
     _, ms_commit = timed(run_commit, K, Wm)
+    ms_fstep, ms_fstep_ev = timed(run_step_fused, K, Wm)
+    _, ms_fused = timed(run_fused, K, Wm)
+    _, ms_tail = timed(run_tail, K, Wm)
     # one buffer set only: inputs stay in the 256 MB Infinity Cache
     warm_fn = (lambda: ssd(sets[0]))
     if use_graph:
@@ -196,30 +247,54 @@ def main():
     alg_bytes = algorithmic_bytes_tree_ssd(B, N, H, P, S, G)
     alg_flops = algorithmic_flops_tree_ssd(B, N, H, P, S, G)
     achieved = alg_bytes / (ms_ssd * 1e-3) / 1e9
-    log(f"[bench] step {ms_step*1e3:.1f} us wall ({ms_step_ev*1e3:.1f} us events)  graph={use_graph}")
-    log(f"[bench] tree_conv {ms_conv*1e3:.2f} us | tree_ssd {ms_ssd*1e3:.2f} us (warm {ms_ssd_warm*1e3:.2f} us) | "
+    # nodes on the accepted paths (integer bookkeeping on the inputs, for the byte count only)
+    depth = np.stack([synth.tree_depths(wl.parent[b]) for b in range(B)])
+    path_nodes = int(sum(depth[b, wl.accepted[b]] + 1 for b in range(B) if wl.accepted[b] >= 0))
+    alg_bytes_f = algorithmic_bytes_replay(B, N, N, H, P, S, G, path_nodes)
+    achieved_f = alg_bytes_f / (ms_fused * 1e-3) / 1e9
+    log(f"[bench] separate: step {ms_step*1e3:.1f} us wall ({ms_step_ev*1e3:.1f} us events)  graph={use_graph}")
+    log(f"[bench]   tree_conv {ms_conv*1e3:.2f} us | tree_ssd {ms_ssd*1e3:.2f} us (warm {ms_ssd_warm*1e3:.2f} us) | "
         f"commit {ms_commit*1e3:.2f} us")
-    log(f"[bench] tree_ssd: {alg_bytes/1e6:.2f} MB algorithmic -> {achieved:.0f} GB/s "
+    log(f"[bench]   tree_ssd: {alg_bytes/1e6:.2f} MB algorithmic -> {achieved:.0f} GB/s "
         f"({achieved/HBM_PEAK_GBS*100:.1f}% of 8 TB/s); {alg_flops/ (ms_ssd*1e-3)/1e12:.1f} TFLOP/s bf16 MFMA "
         f"(dense-masked count); scan-only {nodes/(ms_ssd*1e-3)/1e6:.1f} M nodes/s")
+    log(f"[bench] fused:    step {ms_fstep*1e3:.1f} us wall ({ms_fstep_ev*1e3:.1f} us events)")
+    log(f"[bench]   conv tail {ms_tail*1e3:.2f} us | tree_conv {ms_conv*1e3:.2f} us | replay+scan {ms_fused*1e3:.2f} us")
+    log(f"[bench]   replay+scan: {alg_bytes_f/1e6:.2f} MB algorithmic -> {achieved_f:.0f} GB/s "
+        f"({achieved_f/HBM_PEAK_GBS*100:.1f}% of 8 TB/s)")
 
+    fused_wins = ms_fstep < ms_step
+    ms_best = ms_fstep if fused_wins else ms_step
+    roof_scan = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,false>", "achieved": achieved,
+                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                 "traffic": read_traffic("tree_ssd_mfma_cfg2"),
+                 "algorithmic_bytes": alg_bytes, "avg_launch_us": ms_ssd * 1e3,
+                 "cache_warm_us": ms_ssd_warm * 1e3,
+                 "mfma_tflops": alg_flops / (ms_ssd * 1e-3) / 1e12}
+    roof_fused = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,true>", "achieved": achieved_f,
+                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_f / HBM_PEAK_GBS,
+                  "traffic": read_traffic("tree_ssd_replay_cfg2"),
+                  "algorithmic_bytes": alg_bytes_f, "avg_launch_us": ms_fused * 1e3}
     out = {
         "metric": "tree-nodes/sec per SSD layer at 1 MI355X; % of MFMA/HBM roofline",
-        "value": nodes / (ms_step * 1e-3),
+        "value": nodes / (ms_best * 1e-3),
         "unit": "tree-nodes/s",
-        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": ms_step,
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": ms_best,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "cfg2: batch 16 x 64-node random trees (depth 4-8), 80 heads x headdim 64, "
-                               "dstate 128, ngroups 1, conv width 4; step = tree_conv + tree_ssd + commit_state",
+                               "dstate 128, ngroups 1, conv width 4; step = "
+                               + ("commit_state (conv tail) + tree_conv + tree_ssd_replay (previous tree committed "
+                                  "while the state is loaded for the scan)" if fused_wins
+                                  else "tree_conv + tree_ssd + commit_state"),
+                   "sequence": "fused" if fused_wins else "separate",
                    "batch": B, "nnodes": N, "hip_graph": use_graph, "buffer_sets": N_SETS},
-        "roofline": {"bound": "hbm", "kernel": "tree_ssd_mfma_kernel<64>", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": read_traffic("tree_ssd_mfma_cfg2"),
-                     "algorithmic_bytes": alg_bytes, "avg_launch_us": ms_ssd * 1e3,
-                     "cache_warm_us": ms_ssd_warm * 1e3,
-                     "mfma_tflops": alg_flops / (ms_ssd * 1e-3) / 1e12},
-        "kernels_us": {"tree_conv": ms_conv * 1e3, "tree_ssd": ms_ssd * 1e3, "commit_state": ms_commit * 1e3},
+        # the dominant kernel of the timed step
+        "roofline": roof_fused if fused_wins else roof_scan,
+        "roofline_tree_ssd_alone": roof_scan,
+        "steps_us": {"separate": ms_step * 1e3, "fused": ms_fstep * 1e3},
+        "kernels_us": {"tree_conv": ms_conv * 1e3, "tree_ssd": ms_ssd * 1e3, "commit_state": ms_commit * 1e3,
+                       "commit_state_conv_tail": ms_tail * 1e3, "tree_ssd_replay": ms_fused * 1e3},
     }
 
     if not args.no_cpu_baseline:

@@ -400,8 +400,10 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     auto path_R = [&](floatx16 &tw, int b, int h) {
         const int ln = opaque(lane);
         const int pn = R.pn;
-        const int rk = R.accepted[b];      // uniform: scalar loads, this wave is not in a hot window
-        const float rRA = A[h];
+        // uniform values by scalar loads (a vector load here would be the newest one in flight, and
+        // waiting for it would wait for the whole h0 prefetch)
+        const int rk = R.accepted[__builtin_amdgcn_readfirstlane(b)];
+        const float rRA = A[__builtin_amdgcn_readfirstlane(h)];
         const bool kbad = rk < -1 || rk >= pn;
         int pos = -1, len = 0;
         float cf = 0.f, dc = 1.f;
@@ -453,6 +455,22 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 tw[6 + 4 * i] = __uint_as_float(gb[i].z); tw[7 + 4 * i] = __uint_as_float(gb[i].w);
             }
             tw[12] = __int_as_float(pos); tw[13] = cf; tw[14] = __int_as_float(len); tw[15] = dc;
+        }
+    };
+    // a use of the registers the row loads of path_R land in: the loads are complete after it
+    auto park_R = [&](floatx16 &tw) {
+        if constexpr (WPE >= 4) {
+#pragma unroll
+            for (int i = 0; i < 4 + 4 * NBG; ++i) {
+                float t = tw[i];
+                asm volatile("" : "+v"(t));
+                tw[i] = t;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NXG; ++i) asm volatile("" : "+v"(gxw[i].x), "+v"(gxw[i].y), "+v"(gxw[i].z), "+v"(gxw[i].w));
+#pragma unroll
+            for (int i = 0; i < NBG; ++i) asm volatile("" : "+v"(gbw[i].x), "+v"(gbw[i].y), "+v"(gbw[i].z), "+v"(gbw[i].w));
         }
     };
     auto write_R = [&](const floatx16 &tw, char *rbuf) {
@@ -745,6 +763,24 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             STREE_PHASE_CLOCK(5);
             if (late_tiles) __syncthreads();                  // barrier (a): scratch use of the B tile is over
         } else if (more) {
+            if constexpr (RP) {
+                if (wave == kTreeWave) {
+                    if (!live) {                           // unit 0: path and rows within this pass
+                        path_R(acc[0], b1, h1);
+                        if (more2) load_R(b2, h2);
+                    }
+                    write_R(acc[0], rbuf);
+                }
+                __syncthreads();                           // barrier (c)
+                // path of unit k+2, its rows into registers; the loads fly during the tree index
+                // and the X^T staging and are waited for (park_R) before the loop goes round: a
+                // load left pending into registers that other waves use as accumulators would make
+                // the compiler wait for every outstanding load in front of their MFMAs.
+                if (wave == kTreeWave && more2) {
+                    path_R(acc[0], b2, h2);
+                    if (more3) load_R(b3, h3);
+                }
+            }
             if (wave == kTreeWave) {
                 stage_T(h1);
                 if (!live) STREE_PHASE_PRO(20, 384);
@@ -755,14 +791,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             stage_X((k + 1) & 1);                          // the other X^T tile: unit k still reads its own
             if (!live) STREE_PHASE_PRO(21, 256);
             if constexpr (RP) {
-                if (wave == kTreeWave) {
-                    if (!live) {                           // unit 0: path and rows within this pass
-                        path_R(acc[0], b1, h1);
-                        if (more2) load_R(b2, h2);
-                    }
-                    write_R(acc[0], rbuf);
-                }
-                __syncthreads();                           // barrier (c)
+                if (wave == kTreeWave && more2) park_R(acc[0]);
             }
             if (h0 && !y_stages) {
                 stage_H(rbuf, b1, h1);
@@ -771,12 +800,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             if (more2) {
                 load_X(b2, h2);
                 if (!live && h0) load_H(b2, h2);           // unit 1: the first odd unit
-            }
-            if constexpr (RP) {
-                if (wave == kTreeWave && more2) {          // path of unit k+2, rows into registers
-                    path_R(acc[0], b2, h2);
-                    if (more3) load_R(b3, h3);
-                }
             }
             if (!live) STREE_PHASE_PRO(22, 256);
             if (late_tiles) {

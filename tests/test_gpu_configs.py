@@ -73,6 +73,43 @@ def test_config2_tree64_batch16_with_commit(st, oracle):
     _pipeline(st, oracle, wl, to_dev(wl.h0), wl.h0.astype(np.float64))
 
 
+def test_config2_fused_sequence(st, oracle):
+    """The benchmark's fused call sequence at full size: the previous iteration's tree (the same
+    workload rolled by one along the batch, as the benchmark's buffer rotation does) is committed
+    inside the scan of the current one; conv tail updated alone in front of the conv."""
+    wl = synth.config(2)
+    H, P, S, G = wl.nheads, wl.headdim, wl.dstate, wl.ngroups
+    io = wl.io_dtype
+    roll = lambda a: np.roll(a, 1, axis=0)
+    pparent, pacc, pxbc_pre, pdt = roll(wl.parent), roll(wl.accepted), roll(wl.xbc_pre), roll(wl.dt)
+    # the previous tree's activations: its own conv output (oracle side rounded to bf16 as stored)
+    pconv = oracle.tree_conv(pparent, pxbc_pre, roll(wl.conv_state), wl.conv_w, wl.conv_b, True)
+    pxbc = synth.round_to_bf16(pconv.astype(np.float32))
+    px, pB, _ = split_xbc(pxbc, H, P, G, S)
+    # oracle: commit the previous tree (state and conv tail), conv and scan of the current one from there
+    h0 = wl.h0.astype(np.float64)
+    want_h, want_cs = oracle.commit(pparent, pacc, px, pdt, wl.A, pB, h0, pxbc_pre, wl.conv_state)
+    want_cs = want_cs.astype(np.float32)
+    want_conv = oracle.tree_conv(wl.parent, wl.xbc_pre, want_cs, wl.conv_w, wl.conv_b, True)
+    xbc = synth.round_to_bf16(want_conv.astype(np.float32))
+    x, Bm, Cm = split_xbc(xbc, H, P, G, S)
+    want_y = oracle.ssd_paths(wl.parent, x, wl.dt, wl.A, Bm, Cm, wl.D, want_h)
+    # GPU, stage-isolated inputs (the oracle's rounded activations), the three calls of the sequence
+    _, cs_d = st.stree_commit_state(to_dev(pparent), to_dev(pacc), None, None, None, None,
+                                    xbc_pre=to_dev(pxbc_pre, io), conv_state=to_dev(wl.conv_state, io),
+                                    dims=(H, P, S, G))
+    assert np.array_equal(to_host(cs_d), want_cs)
+    xbc_d = st.stree_tree_conv(to_dev(wl.parent), to_dev(wl.xbc_pre, io), cs_d, to_dev(wl.conv_w, io),
+                               to_dev(wl.conv_b, io), H, P, S, G, silu=True)
+    assert_parity(to_host(xbc_d), want_conv, 4e-3, "cfg2 fused: conv after the tail update")
+    dx, dB, dC = split_xbc_dev(to_dev(xbc, io), H, P, G, S)
+    qx, qB, _ = split_xbc_dev(to_dev(pxbc, io), H, P, G, S)
+    y, h = st.stree_tree_ssd_replay(to_dev(pparent), to_dev(pacc), qx, to_dev(pdt), qB, to_dev(wl.parent), dx,
+                                    to_dev(wl.dt), to_dev(wl.A), dB, dC, to_dev(wl.D), to_dev(wl.h0))
+    assert_parity(to_host(h), want_h, 1e-4, "cfg2 fused: replayed state")
+    assert_parity(to_host(y), want_y, TOL[io], "cfg2 fused: y")
+
+
 def test_config2_direct_inputs_scan_only(st, oracle):
     """The variant the benchmark's roofline is quoted on: x,B,C ~ N(0,1) directly."""
     wl = synth.direct_xbc(synth.config(2))
