@@ -7,11 +7,11 @@ configuration at batch 16 (Mamba2-2.7B layer shape, bf16 io, fp32 state).  Two
 call sequences do that work and both are timed:
   separate: stree_tree_conv -> stree_tree_ssd -> stree_commit_state
             (the tree is committed right after it is scanned)
-  fused:    stree_commit_state (conv tail only) -> stree_tree_conv ->
-            stree_tree_ssd_replay
-            (the previous iteration's tree is committed while the state is
-            loaded for this iteration's scan, as in Alg. 1: one pass over the
-            state per iteration instead of two)
+  fused:    stree_tree_conv_replay -> stree_tree_ssd_replay
+            (the previous iteration's tree is committed inside this iteration's
+            two kernels, as in Alg. 1: its conv tail while the conv rows are
+            staged, its state while the state is loaded for the scan -- one pass
+            over the state per iteration instead of two)
 `value` is the faster of the two; both are in the JSON line.  Inputs are resident in HBM before the timed region; the
 step rotates over several buffer sets so that the working set exceeds the
 256 MB Infinity Cache and the scan really streams from HBM.
@@ -139,14 +139,11 @@ def main():
     for r, s in enumerate(sets):
         s["prev"] = sets[r - 1]
 
-    def conv_tail(s):
+    def conv_replay(s):
         q = s["prev"]
-        st.stree_commit_state(q["parent"], q["accepted"], None, None, None, None, xbc_pre=q["xbc_pre"],
-                              conv_state=s["conv_state"], conv_state_out=s["cs_out"], dims=(H, P, S, G))
-
-    def conv_after_tail(s):
-        st.stree_tree_conv(s["parent"], s["xbc_pre"], s["cs_out"], conv_w, conv_b, H, P, S, G, silu=True,
-                           out=s["xbc"])
+        st.stree_tree_conv_replay(q["parent"], q["accepted"], q["xbc_pre"], s["parent"], s["xbc_pre"],
+                                  s["conv_state"], conv_w, conv_b, H, P, S, G, silu=True, out=s["xbc"],
+                                  conv_state_out=s["cs_out"])
 
     def fused(s):
         q = s["prev"]
@@ -154,8 +151,7 @@ def main():
                                  A, s["Bm"], s["Cm"], D, s["h0"], h_out=s["h_out"], out=s["y"])
 
     def step_fused(s):
-        conv_tail(s)
-        conv_after_tail(s)
+        conv_replay(s)
         fused(s)
 
     for s in sets:           # first launches (also sets the kernel's LDS attribute) outside any capture
@@ -191,7 +187,7 @@ def main():
             run_commit = make_graphs(commit)
             run_step_fused = make_graphs(step_fused)
             run_fused = make_graphs(fused)
-            run_tail = make_graphs(conv_tail)
+            run_tail = make_graphs(conv_replay)
         except Exception as exc:  # pragma: no cover
             log(f"[bench] HIP graph capture failed ({exc}); falling back to direct launches")
             use_graph = False
@@ -202,7 +198,7 @@ def main():
                     fn(s)
             return run
         run_step, run_ssd, run_conv, run_commit = all_sets(step), all_sets(ssd), all_sets(conv), all_sets(commit)
-        run_step_fused, run_fused, run_tail = all_sets(step_fused), all_sets(fused), all_sets(conv_tail)
+        run_step_fused, run_fused, run_tail = all_sets(step_fused), all_sets(fused), all_sets(conv_replay)
 
     def timed(run, k, warm, per_run=N_SETS):
         """Wall-clock and HIP-event time per launch of k launches on the current stream
@@ -259,7 +255,7 @@ def main():
         f"({achieved/HBM_PEAK_GBS*100:.1f}% of 8 TB/s); {alg_flops/ (ms_ssd*1e-3)/1e12:.1f} TFLOP/s bf16 MFMA "
         f"(dense-masked count); scan-only {nodes/(ms_ssd*1e-3)/1e6:.1f} M nodes/s")
     log(f"[bench] fused:    step {ms_fstep*1e3:.1f} us wall ({ms_fstep_ev*1e3:.1f} us events)")
-    log(f"[bench]   conv tail {ms_tail*1e3:.2f} us | tree_conv {ms_conv*1e3:.2f} us | replay+scan {ms_fused*1e3:.2f} us")
+    log(f"[bench]   conv (tail folded in) {ms_tail*1e3:.2f} us | replay+scan {ms_fused*1e3:.2f} us")
     log(f"[bench]   replay+scan: {alg_bytes_f/1e6:.2f} MB algorithmic -> {achieved_f:.0f} GB/s "
         f"({achieved_f/HBM_PEAK_GBS*100:.1f}% of 8 TB/s)")
 
@@ -284,8 +280,9 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "cfg2: batch 16 x 64-node random trees (depth 4-8), 80 heads x headdim 64, "
                                "dstate 128, ngroups 1, conv width 4; step = "
-                               + ("commit_state (conv tail) + tree_conv + tree_ssd_replay (previous tree committed "
-                                  "while the state is loaded for the scan)" if fused_wins
+                               + ("tree_conv_replay + tree_ssd_replay (the previous tree is committed inside both: "
+                                  "conv tail while the conv rows are staged, state while it is loaded for the scan)"
+                                  if fused_wins
                                   else "tree_conv + tree_ssd + commit_state"),
                    "sequence": "fused" if fused_wins else "separate",
                    "batch": B, "nnodes": N, "hip_graph": use_graph, "buffer_sets": N_SETS},
@@ -294,7 +291,7 @@ def main():
         "roofline_tree_ssd_alone": roof_scan,
         "steps_us": {"separate": ms_step * 1e3, "fused": ms_fstep * 1e3},
         "kernels_us": {"tree_conv": ms_conv * 1e3, "tree_ssd": ms_ssd * 1e3, "commit_state": ms_commit * 1e3,
-                       "commit_state_conv_tail": ms_tail * 1e3, "tree_ssd_replay": ms_fused * 1e3},
+                       "tree_conv_replay": ms_tail * 1e3, "tree_ssd_replay": ms_fused * 1e3},
     }
 
     if not args.no_cpu_baseline:

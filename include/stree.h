@@ -187,6 +187,24 @@ int stree_tree_ssd_replay(const stree_dims *dims, const stree_replay *prev, cons
                           const void *Cm, const float *D, const float *h0, float *h_out, void *y,
                           int32_t *tree_status, int32_t *replay_status, void *hip_stream);
 
+/*
+ * Tree conv with the conv-state part of the previous tree's commit folded in (the
+ * replay of Alg. 1 applied to the conv in front of the SSM): the rows above the
+ * root are taken from
+ *   conv_state* = last W-1 rows of [conv_state ; prev_xbc_pre[path(accepted)]]
+ * instead of conv_state, and conv_state* is written to conv_state_out.  Equal to
+ * stree_commit_state (conv part) on the previous tree followed by stree_tree_conv.
+ *   prev           only nnodes, parent and accepted are read
+ *   prev_xbc_pre   io [B, prev->nnodes, Cc]  pre-conv rows of the previous tree
+ *   conv_state_out io [B,W-1,Cc], must NOT alias conv_state
+ *   replay_status  as in stree_tree_ssd_replay (the state passes through on error)
+ *   every other argument as in stree_tree_conv.
+ */
+int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, const void *prev_xbc_pre,
+                           const int32_t *parent, const void *xbc_pre, const void *conv_state,
+                           const void *conv_w, const void *conv_b, void *xbc_out, void *conv_state_out,
+                           int32_t *tree_status, int32_t *replay_status, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

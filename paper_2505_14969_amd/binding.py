@@ -63,8 +63,9 @@ def load() -> C.CDLL:
         lib.stree_tree_ssd.argtypes = [dp] + [_VP] * 11
         lib.stree_commit_state.argtypes = [dp] + [_VP] * 13
         lib.stree_tree_ssd_replay.argtypes = [dp, C.POINTER(StreeReplay)] + [_VP] * 13
+        lib.stree_tree_conv_replay.argtypes = [dp, C.POINTER(StreeReplay)] + [_VP] * 11
         for f in (lib.stree_tree_index, lib.stree_tree_conv, lib.stree_tree_ssd, lib.stree_commit_state,
-                  lib.stree_tree_ssd_replay):
+                  lib.stree_tree_ssd_replay, lib.stree_tree_conv_replay):
             f.restype = C.c_int
         _lib = lib
     return _lib
@@ -210,3 +211,29 @@ def stree_tree_ssd_replay(prev_parent, prev_accepted, prev_x, prev_dt, prev_Bm, 
                                         _ptr(Cm), _ptr(D), _ptr(h0), _ptr(h_out), _ptr(out), _ptr(status),
                                         _ptr(replay_status), _stream()), "stree_tree_ssd_replay")
     return out, h_out
+
+
+def stree_tree_conv_replay(prev_parent, prev_accepted, prev_xbc_pre, parent, xbc_pre, conv_state, conv_w, conv_b,
+                           nheads, headdim, dstate, ngroups, silu: bool = True, out: Optional[torch.Tensor] = None,
+                           conv_state_out: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None,
+                           replay_status: Optional[torch.Tensor] = None):
+    """Tree conv seeded by the conv state after the previous tree's accepted path.
+    -> (xbc_out [B,N,Cc], conv_state_out [B,W-1,Cc]); conv_state_out must not be conv_state."""
+    B, N, Cc = xbc_pre.shape
+    W = conv_w.shape[1]
+    Np = prev_xbc_pre.shape[1]
+    assert Cc == nheads * headdim + 2 * ngroups * dstate and prev_xbc_pre.shape == (B, Np, Cc)
+    assert xbc_pre.is_contiguous() and conv_state.is_contiguous() and conv_w.is_contiguous()
+    assert prev_xbc_pre.is_contiguous()
+    if out is None:
+        out = torch.empty_like(xbc_pre)
+    if conv_state_out is None:
+        conv_state_out = torch.empty_like(conv_state)
+    assert conv_state_out.data_ptr() != conv_state.data_ptr()
+    d = make_dims(B, N, nheads, headdim, dstate, ngroups, W, _io_code(xbc_pre), FLAG_CONV_SILU if silu else 0)
+    r = StreeReplay(Np, 0, prev_parent.data_ptr(), prev_accepted.data_ptr(), None, None, None, 0, 0)
+    _check(load().stree_tree_conv_replay(C.byref(d), C.byref(r), _ptr(prev_xbc_pre), _ptr(parent), _ptr(xbc_pre),
+                                         _ptr(conv_state), _ptr(conv_w), _ptr(conv_b), _ptr(out),
+                                         _ptr(conv_state_out), _ptr(status), _ptr(replay_status), _stream()),
+           "stree_tree_conv_replay")
+    return out, conv_state_out

@@ -152,4 +152,20 @@ int stree_tree_ssd_replay(const stree_dims *dims, const stree_replay *prev, cons
     return hip_status(stree::launch_tree_ssd_fma(d, parent, x, dt, A, Bm, Cm, D, h_out, y, tree_status, st));
 }
 
+int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, const void *prev_xbc_pre,
+                           const int32_t *parent, const void *xbc_pre, const void *conv_state, const void *conv_w,
+                           const void *conv_b, void *xbc_out, void *conv_state_out, int32_t *tree_status,
+                           int32_t *replay_status, void *hip_stream) {
+    int rc = check_dims(dims, kConvChannels);
+    if (rc) return rc;
+    if (!prev || !prev->parent || !prev->accepted || !prev_xbc_pre) return STREE_ERR_NULL_ARG;
+    if (!parent || !xbc_pre || !conv_state || !conv_w || !xbc_out || !conv_state_out) return STREE_ERR_NULL_ARG;
+    if (prev->nnodes < 1 || prev->nnodes > STREE_MAX_NODES) return STREE_ERR_BAD_SHAPE;
+    if (dims->batch == 0) return STREE_OK;
+    return hip_status(stree::launch_tree_conv_replay(*dims, prev->nnodes, prev->parent, prev->accepted, prev_xbc_pre,
+                                                     parent, xbc_pre, conv_state, conv_w, conv_b, xbc_out,
+                                                     conv_state_out, tree_status, replay_status,
+                                                     (hipStream_t)hip_stream));
+}
+
 }  // extern "C"

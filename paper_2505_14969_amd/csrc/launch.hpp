@@ -14,6 +14,13 @@ hipError_t launch_tree_conv(const stree_dims &d, const int32_t *parent, const vo
                             const void *conv_state, const void *conv_w, const void *conv_b, void *xbc_out,
                             int32_t *status, hipStream_t st);
 
+// conv with the conv-tail update of the previous tree's commit folded in
+hipError_t launch_tree_conv_replay(const stree_dims &d, int prev_nnodes, const int32_t *prev_parent,
+                                   const int32_t *prev_accepted, const void *prev_xbc_pre, const int32_t *parent,
+                                   const void *xbc_pre, const void *conv_state, const void *conv_w,
+                                   const void *conv_b, void *xbc_out, void *conv_state_out, int32_t *status,
+                                   int32_t *replay_status, hipStream_t st);
+
 hipError_t launch_tree_ssd_fma(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                const float *A, const void *Bm, const void *Cm, const float *D,
                                const float *h0, void *y, int32_t *status, hipStream_t st);

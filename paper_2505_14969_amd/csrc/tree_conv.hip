@@ -1,6 +1,15 @@
 // stree_tree_conv: depthwise causal conv1d along each node's ancestor chain.
-// Pure streaming: one 16-byte channel vector per thread, W gathered rows
-// (ancestors hit L2, the tree's rows are a few hundred KB per sequence).
+//
+// A workgroup owns 16 channel vectors (16 bytes each) of one sequence and brings every row of
+// that channel block into LDS once: the N pre-conv rows of the tree and, behind them, the W-1
+// rows "above the root".  Each thread then walks the ancestor chains of its nodes in LDS, so a
+// pre-conv element is fetched from memory exactly once however many descendants read it.
+//
+// The rows above the root are the conv state.  In the replay variant they are the conv state
+// AFTER the previous iteration's accepted path,
+//   last W-1 rows of [conv_state ; prev_xbc_pre[path(k)]],
+// taken on the fly from the previous tree's rows (and written out as the new conv state), so
+// that the conv-tail update of the state commit needs no launch of its own.
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -11,131 +20,220 @@ struct Vec16;
 template <>
 struct Vec16<float> {
     static constexpr int N = 4;
-    static __device__ __forceinline__ void load(const float *p, float (&o)[4]) {
-        const float4 v = *reinterpret_cast<const float4 *>(p);
-        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    static __device__ __forceinline__ void unpack(const uint4 &v, float (&o)[4]) {
+        o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y); o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
     }
-    static __device__ __forceinline__ void store(float *p, const float (&o)[4]) {
-        *reinterpret_cast<float4 *>(p) = make_float4(o[0], o[1], o[2], o[3]);
+    static __device__ __forceinline__ uint4 pack(const float (&o)[4]) {
+        return make_uint4(__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3]));
     }
 };
 template <>
 struct Vec16<bf16_t> {
     static constexpr int N = 8;
-    static __device__ __forceinline__ void load(const bf16_t *p, float (&o)[8]) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(p);
+    static __device__ __forceinline__ void unpack(const uint4 &v, float (&o)[8]) {
         o[0] = bf16_lo(v.x); o[1] = bf16_hi(v.x); o[2] = bf16_lo(v.y); o[3] = bf16_hi(v.y);
         o[4] = bf16_lo(v.z); o[5] = bf16_hi(v.z); o[6] = bf16_lo(v.w); o[7] = bf16_hi(v.w);
     }
-    static __device__ __forceinline__ void store(bf16_t *p, const float (&o)[8]) {
+    static __device__ __forceinline__ uint4 pack(const float (&o)[8]) {
         bf16x8 v;
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = (bf16_t)o[e];
-        *reinterpret_cast<bf16x8 *>(p) = v;
+        return __builtin_bit_cast(uint4, v);
     }
 };
 
-constexpr int kConvNodes = 4;   // nodes per workgroup: weights and the tree check are shared
+constexpr int kConvVecs = 8;                        // channel vectors per workgroup
+constexpr int kConvLanes = kThreads / kConvVecs;    // node lanes: thread (g, v) does nodes g, g+16, ...
 
-// 1-D grid of ceil8(B * cblocks * nblocks) workgroups.  Workgroup ids are dealt to the 8 XCDs
-// round-robin by the hardware; the id is remapped so that each XCD gets a contiguous range of
-// (sequence, channel block, node block) with the node block fastest: the ancestors' rows that the
-// node blocks of one (sequence, channel block) share are then fetched into one L2 only.
-template <typename T, int W>
+struct ConvReplay {          // previous tree (replay variant); parent == nullptr: plain conv
+    const int32_t *parent, *accepted;
+    const void *xbc_pre;     // [B, pn, Cc]
+    void *conv_state_out;    // [B, W-1, Cc]
+    int32_t *status;         // [B] or null
+    int pn;
+};
+
+// grid: B * ceil(Cc / (16 vectors)); dynamic LDS: (N + W - 1) rows of 256 bytes
+template <typename T, int W, bool RP>
 __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
-    const int32_t *__restrict__ parent, int nbatch, int n, int Cc, int silu, const T *__restrict__ xbc_pre,
-    const T *__restrict__ conv_state, const T *__restrict__ w, const T *__restrict__ bias,
-    T *__restrict__ out, int32_t *__restrict__ status) {
+    const int32_t *__restrict__ parent, int n, int Cc, int silu, const T *__restrict__ xbc_pre,
+    const T *__restrict__ conv_state, const T *__restrict__ w, const T *__restrict__ bias, T *__restrict__ out,
+    int32_t *__restrict__ status, ConvReplay R) {
     constexpr int VEC = Vec16<T>::N;
+    extern __shared__ __align__(16) uint4 rows[];      // [n + W - 1][kConvVecs]; row n + m - 1 = m rows above the root
     __shared__ int par[kMaxNodes];
-    __shared__ int bad_s;
-    const int tid = threadIdx.x;
-    const int cblocks = (Cc / VEC + kThreads - 1) / kThreads, nblocks = (n + kConvNodes - 1) / kConvNodes;
-    const int logical = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    if (logical >= nbatch * cblocks * nblocks) return;
-    const int nb = logical % nblocks, cblk = (logical / nblocks) % cblocks, b = logical / (nblocks * cblocks);
-    const int i0 = nb * kConvNodes;
-    if (tid == 0) bad_s = 0x7fffffff;
+    __shared__ int bad_s, pbad_s;
+    const int tid = threadIdx.x, v = tid % kConvVecs, g = tid / kConvVecs;
+    const int cblocks = (Cc / VEC + kConvVecs - 1) / kConvVecs;
+    const int cblk = blockIdx.x % cblocks, b = blockIdx.x / cblocks;
+    const int c0 = (cblk * kConvVecs + v) * VEC;
+    const bool has_c = c0 < Cc;
+
+    if (tid == 0) {
+        bad_s = 0x7fffffff;
+        pbad_s = 0x7fffffff;
+    }
+    // Every global load of the kernel is issued up front, before anything is waited for: the
+    // tree's rows, weights and bias, the old conv state rows and (replay) the path rows.
+    const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
+    // (no ?: between a loaded and a constant uint4: that selects between addresses and parks the
+    // constant, and with it every array it is assigned to, in scratch memory)
+    auto ld16 = [&](const T *ptr, bool on) {
+        uint4 r = make_uint4(0u, 0u, 0u, 0u);
+        if (on) r = *reinterpret_cast<const uint4 *>(ptr);
+        return r;
+    };
+    auto ld_row = [&](int i) { return ld16(xbc_pre + ((size_t)b * n + min(i, n - 1)) * Cc + c0, has_c && i < n); };
+    // the first four rows of this thread (all of them for trees of up to 4 * kConvLanes nodes)
+    const uint4 t0 = ld_row(g), t1 = ld_row(g + kConvLanes), t2 = ld_row(g + 2 * kConvLanes),
+                t3 = ld_row(g + 3 * kConvLanes);
+    uint4 wq[W], bq = zero4;
+#pragma unroll
+    for (int q = 0; q < W; ++q) wq[q] = ld16(w + (size_t)c0 * W + q * VEC, has_c);
+    if (bias) bq = ld16(bias + c0, has_c);
+    // rows above the root, m = 1 (newest) .. W-1, one per node lane g = m - 1
+    const int m = g + 1;
+    const bool is_state_lane = g < W - 1 && has_c;
+    uint4 old[W - 1], prow = zero4;            // old[r]: conv_state row r (oldest first)
+#pragma unroll
+    for (int r = 0; r < W - 1; ++r)
+        old[r] = ld16(conv_state + ((size_t)b * (W - 1) + r) * Cc + c0, is_state_lane);
+    // Replay: walk up from the accepted node of the previous tree (uniform, scalar loads; each
+    // step checked on its own so that a corrupt parent array cannot send the walk out of bounds).
+    // anc_ok = nodes found on the walk, at most W-1; lane m needs the (m-1)-th of them.
+    int k_prev = -1, anc_ok = 0;
+    bool k_bad = false;
+    if constexpr (RP) {
+        k_prev = R.accepted[b];
+        k_bad = k_prev < -1 || k_prev >= R.pn;
+        int cur = k_bad ? -1 : k_prev, mine = -1;
+#pragma unroll
+        for (int sstep = 0; sstep < W - 1; ++sstep) {
+            if (cur >= 0) {
+                ++anc_ok;
+                if (sstep == m - 1) mine = cur;
+                const int pz = R.parent[(size_t)b * R.pn + cur];
+                cur = (cur > 0 && pz >= 0 && pz < cur) ? pz : -1;
+            }
+        }
+        prow = ld16(reinterpret_cast<const T *>(R.xbc_pre) + ((size_t)b * R.pn + max(mine, 0)) * Cc + c0,
+                    is_state_lane && mine >= 0);
+    }
     __syncthreads();
-    if (tid < n) {
-        const int p = parent[(size_t)b * n + tid];
-        const bool ok = (tid == 0) ? (p == -1) : (p >= 0 && p < tid);
-        if (!ok) atomicMin(&bad_s, tid + 1);
-        par[tid] = ok ? p : -1;
+    for (int i = tid; i < n; i += kThreads) {
+        const int pz = parent[(size_t)b * n + i];
+        const bool ok = (i == 0) ? (pz == -1) : (pz >= 0 && pz < i);
+        if (!ok) atomicMin(&bad_s, i + 1);
+        par[i] = ok ? pz : -1;
+    }
+    if constexpr (RP) {
+        for (int i = tid; i < R.pn; i += kThreads) {
+            const int pz = R.parent[(size_t)b * R.pn + i];
+            const bool ok = (i == 0) ? (pz == -1) : (pz >= 0 && pz < i);
+            if (!ok) atomicMin(&pbad_s, i + 1);
+        }
+    }
+    if (g < n) rows[g * kConvVecs + v] = t0;
+    if (g + kConvLanes < n) rows[(g + kConvLanes) * kConvVecs + v] = t1;
+    if (g + 2 * kConvLanes < n) rows[(g + 2 * kConvLanes) * kConvVecs + v] = t2;
+    if (g + 3 * kConvLanes < n) rows[(g + 3 * kConvLanes) * kConvVecs + v] = t3;
+    for (int i0 = g + 4 * kConvLanes; i0 < n; i0 += 4 * kConvLanes) {   // larger trees: four rows at a time
+        const uint4 u0 = ld_row(i0), u1 = ld_row(i0 + kConvLanes), u2 = ld_row(i0 + 2 * kConvLanes),
+                    u3 = ld_row(i0 + 3 * kConvLanes);
+        rows[i0 * kConvVecs + v] = u0;
+        if (i0 + kConvLanes < n) rows[(i0 + kConvLanes) * kConvVecs + v] = u1;
+        if (i0 + 2 * kConvLanes < n) rows[(i0 + 2 * kConvLanes) * kConvVecs + v] = u2;
+        if (i0 + 3 * kConvLanes < n) rows[(i0 + 3 * kConvLanes) * kConvVecs + v] = u3;
     }
     __syncthreads();
     const int bad = bad_s == 0x7fffffff ? 0 : bad_s;
-    if (status && cblk == 0 && nb == 0 && tid == 0) status[b] = bad;
-    const int c0 = (cblk * kThreads + tid) * VEC;
-    if (c0 >= Cc) return;
-    if (bad) {
-        float z[VEC];
+    if (status && cblk == 0 && tid == 0) status[b] = bad;
+    if (g < W - 1) {
+        // the m-th newest row of [conv_state ; path rows]: a path row if the path has at least m
+        // nodes, else the (m - L)-th newest old row, L = nodes on the path (0: nothing accepted,
+        // or the previous tree / the accepted index is invalid)
+        int L = 0;
+        if constexpr (RP) {
+            const int pbad = pbad_s == 0x7fffffff ? 0 : pbad_s;
+            if (R.status && cblk == 0 && tid == 0) R.status[b] = pbad ? pbad : (k_bad ? -1 : 0);
+            L = pbad ? 0 : anc_ok;
+        }
+        uint4 r = prow;
+        if (m > L) {
+            const int idx = (W - 1) - (m - L);
+            r = old[0];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) z[e] = 0.f;
-        for (int i = i0; i < min(i0 + kConvNodes, n); ++i) Vec16<T>::store(out + ((size_t)b * n + i) * Cc + c0, z);
+            for (int q = 1; q < W - 1; ++q)
+                if (idx == q) r = old[q];
+        }
+        rows[(n + m - 1) * kConvVecs + v] = r;
+        if constexpr (RP) {   // the new conv state, oldest first: row W-1-m
+            if (has_c)
+                *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(R.conv_state_out) +
+                                           ((size_t)b * (W - 1) + (W - 1 - m)) * Cc + c0) = r;
+        }
+    }
+    __syncthreads();
+    if (!has_c) return;
+    if (bad) {
+        for (int i = g; i < n; i += kConvLanes)
+            *reinterpret_cast<uint4 *>(out + ((size_t)b * n + i) * Cc + c0) = make_uint4(0u, 0u, 0u, 0u);
         return;
     }
     float wv[W][VEC];  // flat [e*W + j] = w[c0+e][j]
 #pragma unroll
-    for (int q = 0; q < W; ++q) Vec16<T>::load(w + (size_t)c0 * W + q * VEC, wv[q]);
+    for (int q = 0; q < W; ++q) Vec16<T>::unpack(wq[q], wv[q]);
     float bv[VEC];
-    if (bias) Vec16<T>::load(bias + c0, bv);
-    else {
+    Vec16<T>::unpack(bq, bv);
+    for (int i = g; i < n; i += kConvLanes) {
+        float acc[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) bv[e] = 0.f;
-    }
-    // all gathered rows of the workgroup's nodes are requested before any is used
-    float r[kConvNodes][W][VEC];
+        for (int e = 0; e < VEC; ++e) acc[e] = bv[e];
+        int node = i, above = 0;
 #pragma unroll
-    for (int m = 0; m < kConvNodes; ++m) {
-        const int i = min(i0 + m, n - 1);
-        int v = i, above = 0;
-#pragma unroll
-        for (int k = 0; k < W; ++k) {   // k-th ancestor, or conv_state once above the root
-            const T *src;
-            if (v >= 0) {
-                src = xbc_pre + ((size_t)b * n + v) * Cc + c0;
-                v = par[v];
+        for (int k = 0; k < W; ++k) {   // k-th ancestor, or `above` rows over the root
+            int row;
+            if (node >= 0) {
+                row = node;
+                node = par[node];
             } else {
-                ++above;  // `above` rows over the root: state row (W-1) - above
-                src = conv_state + ((size_t)b * (W - 1) + (W - 1 - above)) * Cc + c0;
+                ++above;
+                row = n + above - 1;
             }
-            Vec16<T>::load(src, r[m][k]);
+            float r[VEC];
+            Vec16<T>::unpack(rows[row * kConvVecs + v], r);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = fmaf((&wv[0][0])[e * W + (W - 1 - k)], r[e], acc[e]);
         }
-    }
+        if (silu) {
 #pragma unroll
-    for (int m = 0; m < kConvNodes; ++m) {
-        if (i0 + m < n) {
-            float acc[VEC];
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] = bv[e];
-#pragma unroll
-            for (int k = 0; k < W; ++k)
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[e] = fmaf((&wv[0][0])[e * W + (W - 1 - k)], r[m][k][e], acc[e]);
-            if (silu) {
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[e] = acc[e] / (1.f + __expf(-acc[e]));
-            }
-            Vec16<T>::store(out + ((size_t)b * n + i0 + m) * Cc + c0, acc);
+            for (int e = 0; e < VEC; ++e)   // z * sigmoid(z); hardware reciprocal (1 ulp) instead of a division
+                acc[e] = acc[e] * __builtin_amdgcn_rcpf(1.f + __expf(-acc[e]));
         }
+        *reinterpret_cast<uint4 *>(out + ((size_t)b * n + i) * Cc + c0) = Vec16<T>::pack(acc);
     }
 }
 
-template <typename T>
+template <typename T, bool RP>
 static hipError_t launch_conv_t(const stree_dims &d, const int32_t *parent, const void *xbc_pre,
                                 const void *conv_state, const void *conv_w, const void *conv_b,
-                                void *xbc_out, int32_t *status, hipStream_t st) {
+                                void *xbc_out, int32_t *status, const ConvReplay &R, hipStream_t st) {
     constexpr int VEC = Vec16<T>::N;
     const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
-    const int total = ((Cc / VEC + kThreads - 1) / kThreads) * ((d.nnodes + kConvNodes - 1) / kConvNodes) * d.batch;
-    const dim3 grid((total + 7) / 8 * 8);
+    const int cblocks = (Cc / VEC + kConvVecs - 1) / kConvVecs;
+    const dim3 grid(cblocks * d.batch);
+    const size_t lds = (size_t)(d.nnodes + d.conv_width - 1) * kConvVecs * sizeof(uint4);
     const int silu = (d.flags & STREE_FLAG_CONV_SILU) ? 1 : 0;
-#define STREE_CONV_CASE(WW)                                                                             \
-    case WW:                                                                                            \
-        hipLaunchKernelGGL((tree_conv_kernel<T, WW>), grid, dim3(kThreads), 0, st, parent, d.batch, d.nnodes, Cc, \
-                           silu, (const T *)xbc_pre, (const T *)conv_state, (const T *)conv_w,          \
-                           (const T *)conv_b, (T *)xbc_out, status);                                    \
+#define STREE_CONV_CASE(WW)                                                                                   \
+    case WW:                                                                                                  \
+        if (lds > 48 * 1024) { /* beyond the default cap on dynamic LDS: raise it for this kernel */          \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_conv_kernel<T, WW, RP>),   \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);         \
+            if (e != hipSuccess) return e;                                                                    \
+        }                                                                                                     \
+        hipLaunchKernelGGL((tree_conv_kernel<T, WW, RP>), grid, dim3(kThreads), lds, st, parent, d.nnodes, Cc, \
+                           silu, (const T *)xbc_pre, (const T *)conv_state, (const T *)conv_w,                \
+                           (const T *)conv_b, (T *)xbc_out, status, R);                                       \
         break;
     switch (d.conv_width) {
         STREE_CONV_CASE(2)
@@ -150,9 +248,21 @@ static hipError_t launch_conv_t(const stree_dims &d, const int32_t *parent, cons
 hipError_t launch_tree_conv(const stree_dims &d, const int32_t *parent, const void *xbc_pre,
                             const void *conv_state, const void *conv_w, const void *conv_b, void *xbc_out,
                             int32_t *status, hipStream_t st) {
+    const ConvReplay none = {};
     if (d.io_dtype == STREE_BF16)
-        return launch_conv_t<bf16_t>(d, parent, xbc_pre, conv_state, conv_w, conv_b, xbc_out, status, st);
-    return launch_conv_t<float>(d, parent, xbc_pre, conv_state, conv_w, conv_b, xbc_out, status, st);
+        return launch_conv_t<bf16_t, false>(d, parent, xbc_pre, conv_state, conv_w, conv_b, xbc_out, status, none, st);
+    return launch_conv_t<float, false>(d, parent, xbc_pre, conv_state, conv_w, conv_b, xbc_out, status, none, st);
+}
+
+hipError_t launch_tree_conv_replay(const stree_dims &d, int prev_nnodes, const int32_t *prev_parent,
+                                   const int32_t *prev_accepted, const void *prev_xbc_pre, const int32_t *parent,
+                                   const void *xbc_pre, const void *conv_state, const void *conv_w,
+                                   const void *conv_b, void *xbc_out, void *conv_state_out, int32_t *status,
+                                   int32_t *replay_status, hipStream_t st) {
+    const ConvReplay R = {prev_parent, prev_accepted, prev_xbc_pre, conv_state_out, replay_status, prev_nnodes};
+    if (d.io_dtype == STREE_BF16)
+        return launch_conv_t<bf16_t, true>(d, parent, xbc_pre, conv_state, conv_w, conv_b, xbc_out, status, R, st);
+    return launch_conv_t<float, true>(d, parent, xbc_pre, conv_state, conv_w, conv_b, xbc_out, status, R, st);
 }
 
 }  // namespace stree

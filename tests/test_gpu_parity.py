@@ -177,7 +177,7 @@ def test_relabelling_permutes_gpu_outputs(st):
 @pytest.mark.parametrize("io,W,silu,bias", [("bf16", 4, True, True), ("bf16", 2, False, False),
                                             ("f32", 4, True, True), ("f32", 3, False, True)])
 def test_tree_conv(st, oracle, io, W, silu, bias):
-    B, N, H, P, S, G = 3, 70, 4, 64, 32, 2
+    B, N, H, P, S, G = 3, (256 if W == 3 else 70), 4, 64, 32, 2
     Cc = H * P + 2 * G * S
     rng = np.random.default_rng(20 + W)
     rnd = synth.round_to_bf16 if io == "bf16" else (lambda a: a.astype(np.float32))

@@ -139,3 +139,51 @@ def test_replay_chain_of_iterations(st, oracle):
     cur, p = steps[3]
     want_y = oracle.ssd_paths(p, cur[0], cur[1], A, cur[3], cur[4], D, want_h)
     assert_parity(to_host(y), want_y, TOL[io], "scan of the fourth tree")
+
+
+@pytest.mark.parametrize("io,W,N,Np", [("bf16", 4, 70, 33), ("bf16", 2, 64, 64), ("f32", 3, 31, 100), ("bf16", 4, 256, 256)])
+def test_conv_replay_matches_commit_then_conv(st, oracle, io, W, N, Np):
+    """Tree conv seeded by the conv state after the previous tree's accepted path, and that state."""
+    import torch
+    B, H, P, S, G = 6, 3, 32, 16, 1
+    Cc = H * P + 2 * G * S
+    rng = np.random.default_rng(40 + W)
+    rnd = synth.round_to_bf16 if io == "bf16" else (lambda a: a.astype(np.float32))
+    pp, p = _trees(41, B, Np), _trees(42, B, N)
+    depth = np.stack([synth.tree_depths(pp[b]) for b in range(B)])
+    # accepted: none, the root (one row), a child of the root (two rows), the deepest node, out of range, deep
+    acc = np.array([-1, 0, int(np.argmax(depth[2] == 1)), int(depth[3].argmax()), Np + 2, int(depth[5].argmax())],
+                   dtype=np.int32)
+    pxbc = rnd(rng.standard_normal((B, Np, Cc)).astype(np.float32))
+    xbc = rnd(rng.standard_normal((B, N, Cc)).astype(np.float32))
+    cs = rnd(rng.standard_normal((B, W - 1, Cc)).astype(np.float32))
+    w = rnd(rng.uniform(-0.5, 0.5, (Cc, W)).astype(np.float32))
+    bias = rnd(rng.uniform(-0.5, 0.5, Cc).astype(np.float32))
+    # oracle: conv part of the commit (state part on dummies), then the conv
+    ok = acc < Np
+    z = np.zeros((B, Np, 1, 1))
+    want_cs = cs.astype(np.float64).copy()
+    _, c = oracle.commit(pp[ok], acc[ok], z[ok], np.zeros((ok.sum(), Np, 1)), np.array([-1.0]), z[ok], None,
+                         pxbc[ok], cs[ok])
+    want_cs[ok] = c
+    want = oracle.tree_conv(p, xbc, want_cs, w, bias, True)
+    status = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    rstatus = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    got, cso = st.stree_tree_conv_replay(to_dev(pp), to_dev(acc), to_dev(pxbc, io), to_dev(p), to_dev(xbc, io),
+                                         to_dev(cs, io), to_dev(w, io), to_dev(bias, io), H, P, S, G, silu=True,
+                                         status=status, replay_status=rstatus)
+    assert not to_host(status).any()
+    assert list(to_host(rstatus)) == [0, 0, 0, 0, -1, 0]
+    assert np.array_equal(to_host(cso), want_cs.astype(np.float32))          # row copies: exact
+    ulp = 2.0 ** -8 if io == "bf16" else 2.0 ** -22
+    assert np.all(np.abs(to_host(got) - want) <= ulp * np.abs(want) + 1e-5)
+    # a bad previous tree: the old state is used and passed through
+    pp[1, 5] = 7
+    got2, cso2 = st.stree_tree_conv_replay(to_dev(pp), to_dev(acc), to_dev(pxbc, io), to_dev(p), to_dev(xbc, io),
+                                           to_dev(cs, io), to_dev(w, io), to_dev(bias, io), H, P, S, G, silu=True,
+                                           replay_status=rstatus)
+    assert int(to_host(rstatus)[1]) == 6
+    assert np.array_equal(to_host(cso2)[1], cs[1])
+    plain = st.stree_tree_conv(to_dev(p[1:2]), to_dev(xbc[1:2], io), to_dev(cs[1:2], io), to_dev(w, io),
+                               to_dev(bias, io), H, P, S, G, silu=True)
+    assert np.array_equal(to_host(got2)[1], to_host(plain)[0])
