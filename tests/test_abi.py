@@ -109,3 +109,38 @@ def test_tree_index_rejects_bad_arguments(lib):
     assert lib.stree_tree_index(C.byref(d), FAKE, None, None, FAKE, None, None) == 2
     d = binding.make_dims(1, 30, 1, 1, 1, 1, 4, binding.F32)
     assert lib.stree_tree_index(C.byref(d), None, FAKE, None, None, None, None) == 1
+
+
+def test_replay_entry_points_reject_bad_arguments(lib):
+    ok = dict(batch=1, nnodes=64, nheads=8, headdim=64, dstate=128, ngroups=1, conv_width=4)
+    d = binding.make_dims(**ok)
+    prev = binding.StreeReplay(64, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0, 0)
+
+    def ssd(d=d, prev=prev, h0=FAKE, h_out=FAKE, y=FAKE):
+        pr = C.byref(prev) if prev is not None else None
+        return lib.stree_tree_ssd_replay(C.byref(d), pr, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, h0, h_out, y,
+                                         None, None, None)
+
+    assert ssd(prev=None) == 1
+    assert ssd(h0=None) == 1 and ssd(h_out=None) == 1 and ssd(y=None) == 1
+    assert ssd(prev=binding.StreeReplay(64, 0, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0, 0)) == 1
+    assert ssd(prev=binding.StreeReplay(0, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0, 0)) == 2
+    assert ssd(prev=binding.StreeReplay(257, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0, 0)) == 2
+    assert ssd(prev=binding.StreeReplay(64, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 8, 0)) == 4
+    assert ssd(d=binding.make_dims(**{**ok, "dstate": 30})) == 2
+    assert ssd(d=binding.make_dims(**{**ok, "batch": 0})) == 0
+
+    def conv(d=d, prev=prev, pxbc=FAKE, cso=FAKE):
+        pr = C.byref(prev) if prev is not None else None
+        return lib.stree_tree_conv_replay(C.byref(d), pr, pxbc, FAKE, FAKE, FAKE, FAKE, None, FAKE, cso, None, None,
+                                          None)
+
+    assert conv(prev=None) == 1 and conv(pxbc=None) == 1 and conv(cso=None) == 1
+    assert conv(prev=binding.StreeReplay(300, 0, 0x1000, 0x1000, 0, 0, 0, 0, 0)) == 2
+    assert conv(d=binding.make_dims(**{**ok, "conv_width": 5})) == 2
+    assert conv(d=binding.make_dims(**{**ok, "batch": 0})) == 0
+    # conv tail alone through stree_commit_state: state pointers all NULL
+    assert lib.stree_commit_state(C.byref(d), FAKE, FAKE, None, None, None, None, None, None, FAKE, FAKE, None,
+                                  None, None) == 1          # conv_state_out missing
+    assert lib.stree_commit_state(C.byref(d), FAKE, FAKE, None, None, None, None, None, None, None, None, None,
+                                  None, None) == 1          # nothing to do
