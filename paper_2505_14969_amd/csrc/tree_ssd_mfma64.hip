@@ -44,6 +44,9 @@
 #define STREE_EXIT_INIT
 #define STREE_EXIT_POINT(n)
 #endif
+#ifndef STREE_MARK_POINT
+#define STREE_MARK_POINT(n, t)
+#endif
 
 
 namespace stree {
@@ -715,6 +718,9 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
             STREE_PHASE_CLOCK(3);
             if (live) STREE_EXIT_POINT(13 + 10 * k);
+            // first pass: the Y threads have nothing to scan and stage the first C / B tiles (later
+            // tiles come from the G threads, after barrier (a))
+            if (!live && fresh_next) restage_CB(b1, h1);
             if (RP && more) __syncthreads();                  // barrier (c): path rows of unit k+1 are in LDS
             // next unit's state tile (its loads have been in flight for a whole unit period)
             if (more) {
@@ -759,7 +765,12 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                     }
                 }
             }
-            if (h0 && more3 && y_stages) load_H(b3, h3);
+            // h0 of unit k+3 after staging unit k+1.  Unit 2 is the exception: asked for in the
+            // first pass it would sit in the memory queues in front of the small x / parent / dt
+            // loads of units 1 and 2 and make the last scan wait for them; asked for one pass
+            // later, the state of the last unit of a short run is the last thing to arrive.
+            if (h0 && more3 && y_stages && live) load_H(b3, h3);
+            if (h0 && more2 && k == 0) load_H(b2, h2);
             STREE_PHASE_CLOCK(5);
             if (late_tiles) __syncthreads();                  // barrier (a): scratch use of the B tile is over
         } else if (more) {
@@ -784,24 +795,33 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             if (wave == kTreeWave) {
                 stage_T(h1);
                 if (!live) STREE_PHASE_PRO(20, 384);
-                if (more2) load_T(b2, h2);
+                if (!live) STREE_MARK_POINT(41, 384);
+                if (live) STREE_MARK_POINT(51 + 10 * k, 384);
             }
-            if (fresh_next && !live) restage_CB(b1, h1);
-            if (!live) STREE_PHASE_PRO(19, 256);
             stage_X((k + 1) & 1);                          // the other X^T tile: unit k still reads its own
             if (!live) STREE_PHASE_PRO(21, 256);
+            if (!live) STREE_MARK_POINT(42, 256);
+            if (live) STREE_MARK_POINT(52 + 10 * k, 256);
+            if (live) STREE_MARK_POINT(55 + 10 * k, 384);
             if constexpr (RP) {
                 if (wave == kTreeWave && more2) park_R(acc[0]);
+            }
+            // the registers just staged are free: x and parent / dt of unit k+2 go out at once (a
+            // pass is short when HBM is idle, and they are needed at this point of the next one)
+            if (more2) {
+                load_X(b2, h2);
+                if (wave == kTreeWave) load_T(b2, h2);
             }
             if (h0 && !y_stages) {
                 stage_H(rbuf, b1, h1);
                 if (more3) load_H(b3, h3);
             }
-            if (more2) {
-                load_X(b2, h2);
-                if (!live && h0) load_H(b2, h2);           // unit 1: the first odd unit
-            }
+            if (more2 && !live && h0) load_H(b2, h2);      // unit 1: the first odd unit
             if (!live) STREE_PHASE_PRO(22, 256);
+            if (!live) STREE_MARK_POINT(43, 256);
+            if (!live) STREE_MARK_POINT(44, 384);
+            if (live) STREE_MARK_POINT(53 + 10 * k, 256);
+            if (live) STREE_MARK_POINT(54 + 10 * k, 384);
             if (late_tiles) {
                 __syncthreads();                           // barrier (a)
                 restage_CB(b1, h1);
