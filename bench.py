@@ -79,6 +79,9 @@ def main():
                     help="profiling aid: run K tree-scan launches and exit")
     ap.add_argument("--only-fused", type=int, default=0, metavar="K",
                     help="profiling aid: run K fused replay + scan launches and exit")
+    ap.add_argument("--sweep", action="store_true",
+                    help="second workload: the paper's tree shapes, packed tree scan against the same scan on the "
+                         "tree unrolled into one chain per leaf (prints its own JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU; run with --gpus 1 (no collectives or sharding are built)")
@@ -91,6 +94,8 @@ def main():
     st.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.sweep:
+        return sweep(st, synth, torch, dev)
 
     wl = synth.config(2)
     B, N, H, P, S, G, W = wl.batch, wl.nnodes, wl.nheads, wl.headdim, wl.dstate, wl.ngroups, wl.conv_width
@@ -297,6 +302,108 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)
+
+
+def unroll_paths(parent):
+    """Root-to-leaf node lists of one tree (integer bookkeeping on the input, no arithmetic)."""
+    n = len(parent)
+    has_child = np.zeros(n, dtype=bool)
+    has_child[parent[parent >= 0]] = True
+    paths = []
+    for leaf in np.nonzero(~has_child)[0]:
+        p, v = [], int(leaf)
+        while v >= 0:
+            p.append(v)
+            v = int(parent[v])
+        paths.append(p[::-1])
+    return paths
+
+
+def sweep(st, synth, torch, dev):
+    """Tree scan on the shapes the paper measures (Sec. 5 "Efficiency of STree against unrolled
+    baseline": full binary trees of 15/31/63 tokens; beam trees M x N; static trees of 13-29 tokens),
+    layer shape of the 2.7B model, batch 16: the packed tree in one call against the same kernel
+    on the tree unrolled into one chain per leaf (one state per chain), plus a fit t = k N + C."""
+    B, H, P, S, G = 16, 80, 64, 128, 1
+    rng = np.random.default_rng(2025051499)
+    A = torch.from_numpy((-np.exp(rng.uniform(0, 2, H))).astype(np.float32)).to(dev)
+    D = torch.from_numpy(rng.standard_normal(H).astype(np.float32)).to(dev)
+    NSETS = 4
+
+    def bf16(a):
+        return torch.from_numpy(synth.f32_to_bf16_bits(a).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    def time_graph(calls):
+        for c in calls:
+            c()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for c in calls:
+                c()
+        for _ in range(5):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 60
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (reps * len(calls)) * 1e3
+
+    shapes = [("binary-%d" % (2 ** l - 1), [synth.full_binary_tree(l)] * B) for l in (4, 5, 6)]
+    shapes += [("static-%d" % (1 + w * d), [synth.static_tree(w, d)] * B) for w, d in ((3, 4), (3, 5), (4, 7))]
+    shapes += [("beam-%dx%d" % (m, n), [synth.beam_tree(m, n, rng) for _ in range(B)])
+               for m in (2, 3, 4, 5) for n in (4, 8, 16)]
+    rows = []
+    for name, trees in shapes:
+        parent = np.stack(trees).astype(np.int32)
+        N = parent.shape[1]
+        x = rng.standard_normal((B, N, H, P)).astype(np.float32)
+        Bm = rng.standard_normal((B, N, G, S)).astype(np.float32)
+        Cm = rng.standard_normal((B, N, G, S)).astype(np.float32)
+        dt = np.logaddexp(0, rng.standard_normal((B, N, H)) - 2).astype(np.float32)
+        h0 = (0.1 * rng.standard_normal((B, H, P, S))).astype(np.float32)
+        # unrolled: one chain per leaf, padded to the longest path with dt = 0 tokens (identity steps)
+        paths = [unroll_paths(parent[b]) for b in range(B)]
+        L = max(len(p) for ps in paths for p in ps)
+        idx_b = np.array([b for b in range(B) for _ in paths[b]])
+        idx_n = np.array([p + [p[-1]] * (L - len(p)) for ps in paths for p in ps])
+        pad = np.array([[0] * len(p) + [1] * (L - len(p)) for ps in paths for p in ps], dtype=bool)
+        ux, uB, uC = x[idx_b[:, None], idx_n], Bm[idx_b[:, None], idx_n], Cm[idx_b[:, None], idx_n]
+        udt = dt[idx_b[:, None], idx_n].copy()
+        udt[pad] = 0.0
+        uh0 = h0[idx_b]
+        chains = np.stack([synth.chain_tree(L)] * len(idx_b)).astype(np.int32)
+        packed_calls, unrolled_calls = [], []
+        for r in range(NSETS):
+            t = dict(parent=torch.from_numpy(parent).to(dev), x=bf16(x), B=bf16(Bm), C=bf16(Cm),
+                     dt=torch.from_numpy(dt).to(dev), h0=torch.from_numpy(h0).to(dev))
+            t["y"] = torch.empty((B, N, H, P), dtype=torch.bfloat16, device=dev)
+            u = dict(parent=torch.from_numpy(chains).to(dev), x=bf16(ux), B=bf16(uB), C=bf16(uC),
+                     dt=torch.from_numpy(udt).to(dev), h0=torch.from_numpy(uh0).to(dev))
+            u["y"] = torch.empty((len(idx_b), L, H, P), dtype=torch.bfloat16, device=dev)
+            packed_calls.append(lambda t=t: st.stree_tree_ssd(t["parent"], t["x"], t["dt"], A, t["B"], t["C"], D,
+                                                              t["h0"], out=t["y"]))
+            unrolled_calls.append(lambda u=u: st.stree_tree_ssd(u["parent"], u["x"], u["dt"], A, u["B"], u["C"], D,
+                                                                u["h0"], out=u["y"]))
+        tp, tu = time_graph(packed_calls), time_graph(unrolled_calls)
+        rows.append({"tree": name, "nodes": int(N), "states_unrolled": int(len(idx_b) // B),
+                     "tokens_unrolled": int(sum(len(p) for p in paths[0])), "packed_us": tp, "unrolled_us": tu})
+        log(f"[sweep] {name:12s} N={N:3d}  unrolled: {len(idx_b)//B:3d} states/seq, {rows[-1]['tokens_unrolled']:4d} tokens"
+            f"   packed {tp:7.2f} us   unrolled {tu:7.2f} us   ratio {tu/tp:5.2f}")
+        del packed_calls, unrolled_calls
+        torch.cuda.empty_cache()
+    n = np.array([r["nodes"] for r in rows if r["nodes"] <= 64], dtype=np.float64)
+    t = np.array([r["packed_us"] for r in rows if r["nodes"] <= 64])
+    k, c = np.polyfit(n, t, 1)
+    log(f"[sweep] packed scan, trees of at most 64 nodes: t = {k:.3f} us * N + {c:.2f} us")
+    print(json.dumps({"metric": "tree scan on the paper's tree shapes, packed vs unrolled (us per call, batch 16)",
+                      "unit": "us", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "full binary 15/31/63, static 13/16/29, beam MxN; 80 heads x 64, dstate 128"},
+                      "fit_packed_us": {"per_node": k, "constant": c}, "rows": rows}), flush=True)
 
 
 def cpu_baseline(wl):
