@@ -79,6 +79,9 @@ def main():
                     help="profiling aid: run K tree-scan launches and exit")
     ap.add_argument("--only-fused", type=int, default=0, metavar="K",
                     help="profiling aid: run K fused replay + scan launches and exit")
+    ap.add_argument("--prefix", action="store_true",
+                    help="the 4096-token prefix pass of the prefix-then-tree configuration: the chunked linear "
+                         "scan kernel against 16 chain-tree calls (prints its own JSON line)")
     ap.add_argument("--sweep", action="store_true",
                     help="second workload: the paper's tree shapes, packed tree scan against the same scan on the "
                          "tree unrolled into one chain per leaf (prints its own JSON line)")
@@ -96,6 +99,8 @@ def main():
     torch.cuda.set_device(dev)
     if args.sweep:
         return sweep(st, synth, torch, dev)
+    if args.prefix:
+        return prefix(st, synth, torch, dev)
 
     wl = synth.config(2)
     B, N, H, P, S, G, W = wl.batch, wl.nnodes, wl.nheads, wl.headdim, wl.dstate, wl.ngroups, wl.conv_width
@@ -302,6 +307,62 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)
+
+
+def prefix(st, synth, torch, dev):
+    """cfg4's prefix: B 8 x T 4096 tokens, 80 heads x 64, dstate 128.  Times stree_linear_ssd (y and
+    state; state only) and the route it replaces: per 256 tokens a chain-tree scan plus a commit."""
+    wl = synth.config(4)
+    e = wl.extras
+    B, H, P, S, G = wl.batch, wl.nheads, wl.headdim, wl.dstate, wl.ngroups
+    T = e["prefix_x"].shape[1]
+
+    def bf16(a):
+        return torch.from_numpy(synth.f32_to_bf16_bits(a).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    x, Bm, Cm = bf16(e["prefix_x"]), bf16(e["prefix_B"]), bf16(e["prefix_C"])
+    dt, A = torch.from_numpy(e["prefix_dt"]).to(dev), torch.from_numpy(wl.A).to(dev)
+    y = torch.empty((B, T, H, P), dtype=torch.bfloat16, device=dev)
+    h = torch.empty((B, H, P, S), dtype=torch.float32, device=dev)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    t_full = timed(lambda: st.stree_linear_ssd(x, dt, A, Bm, Cm, None, None, out=y, h_out=h), 20)
+    t_state = timed(lambda: st.stree_linear_ssd(x, dt, A, Bm, None, None, None, want_y=False, h_out=h), 20)
+    chunk = 256
+    chain = torch.from_numpy(np.stack([synth.chain_tree(chunk)] * B)).to(dev)
+    last = torch.full((B,), chunk - 1, dtype=torch.int32, device=dev)
+    parts = [(x[:, c:c + chunk].contiguous(), dt[:, c:c + chunk].contiguous(), Bm[:, c:c + chunk].contiguous(),
+              Cm[:, c:c + chunk].contiguous()) for c in range(0, T, chunk)]
+    hh = torch.zeros_like(h)
+    yc = torch.empty((B, chunk, H, P), dtype=torch.bfloat16, device=dev)
+
+    def chains():
+        hh.zero_()
+        for i, (xc, dc, bc, cc) in enumerate(parts):
+            st.stree_tree_ssd(chain, xc, dc, A, bc, cc, None, hh, out=yc)
+            st.stree_commit_state(chain, last, xc, dc, A, bc, hh, h_out=hh)
+
+    t_chain = timed(chains, 5)
+    alg = B * T * (2 * H * P * 2 + 2 * G * S * 2 + H * 4) + 2 * B * H * P * S * 4
+    flops = B * T * (G * 2 * 64 * S + H * (2 * 64 * P + 2 * S * P + 3 * 2 * S * P))   # per token, 64-token chunks
+    log(f"[prefix] B {B} x T {T}: linear scan {t_full:.0f} us ({B*T/t_full:.1f} M tokens/s, {alg/t_full/1e3:.0f} GB/s "
+        f"algorithmic, {flops/t_full/1e6:.1f} TFLOP/s bf16 MFMA), state only {t_state:.0f} us, "
+        f"16 x (chain-tree scan + commit) {t_chain:.0f} us")
+    print(json.dumps({"metric": "prefix tokens/s per SSD layer (linear scan kernel, y and state)", "unit": "tokens/s",
+                      "value": B * T / (t_full * 1e-6), "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"cfg4 prefix: batch {B} x {T} tokens, 80 heads x 64, dstate 128"},
+                      "us": {"linear_ssd": t_full, "linear_ssd_state_only": t_state, "chain_tree_route": t_chain},
+                      "algorithmic_bytes": alg, "achieved_GBps": alg / t_full / 1e3}), flush=True)
 
 
 def unroll_paths(parent):

@@ -205,6 +205,26 @@ int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, con
                            const void *conv_w, const void *conv_b, void *xbc_out, void *conv_state_out,
                            int32_t *tree_status, int32_t *replay_status, void *hip_stream);
 
+/*
+ * Linear prefix scan: the ordinary causal Mamba2 scan of T tokens per sequence (the
+ * chain case of the tree mask, Sec. 3: a lower-triangular L is Mamba2 with an
+ * initial state), chunked, with the state carried from chunk to chunk on chip.  It
+ * is the prefix pass in front of tree decoding: the state it returns seeds
+ * stree_tree_ssd.
+ *   dims->nnodes = T, any T >= 1 (not limited to STREE_MAX_NODES); conv_width ignored
+ *   x, dt, A, Bm, Cm, D, h0 as in stree_tree_ssd with T in place of N
+ *   y      io [B,T,H,P] or NULL: state only (then Cm and D may be NULL too)
+ *   h_out  f32 [B,H,P,S] state after token T-1, required, MAY alias h0
+ * Shapes: bf16 io, (headdim, dstate) in {(64,64), (64,128), (128,128)}, 16-byte
+ * aligned pointers and strides; anything else returns STREE_ERR_BAD_SHAPE
+ * (a chain tree through stree_tree_ssd / stree_commit_state covers it, 256
+ * tokens at a time).  The state is updated in fp32 accuracy (the weighted inputs
+ * enter the matrix units as three bf16 terms); only its use in y is rounded.
+ */
+int stree_linear_ssd(const stree_dims *dims, const void *x, const float *dt, const float *A,
+                     const void *Bm, const void *Cm, const float *D, const float *h0, void *y,
+                     float *h_out, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

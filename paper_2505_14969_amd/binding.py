@@ -64,6 +64,8 @@ def load() -> C.CDLL:
         lib.stree_commit_state.argtypes = [dp] + [_VP] * 13
         lib.stree_tree_ssd_replay.argtypes = [dp, C.POINTER(StreeReplay)] + [_VP] * 13
         lib.stree_tree_conv_replay.argtypes = [dp, C.POINTER(StreeReplay)] + [_VP] * 11
+        lib.stree_linear_ssd.argtypes = [dp] + [_VP] * 10
+        lib.stree_linear_ssd.restype = C.c_int
         for f in (lib.stree_tree_index, lib.stree_tree_conv, lib.stree_tree_ssd, lib.stree_commit_state,
                   lib.stree_tree_ssd_replay, lib.stree_tree_conv_replay):
             f.restype = C.c_int
@@ -237,3 +239,21 @@ def stree_tree_conv_replay(prev_parent, prev_accepted, prev_xbc_pre, parent, xbc
                                          _ptr(conv_state_out), _ptr(status), _ptr(replay_status), _stream()),
            "stree_tree_conv_replay")
     return out, conv_state_out
+
+
+def stree_linear_ssd(x, dt, A, Bm, Cm=None, D=None, h0=None, want_y: bool = True,
+                     out: Optional[torch.Tensor] = None, h_out: Optional[torch.Tensor] = None):
+    """Causal scan of T tokens per sequence: x [B,T,H,P], dt [B,T,H] f32, Bm/Cm [B,T,G,S].
+    -> (y [B,T,H,P] or None, h_out [B,H,P,S] f32).  h_out may be h0 itself."""
+    B, T, H, P = x.shape
+    G, S = Bm.shape[2], Bm.shape[3]
+    assert dt.is_contiguous() and dt.dtype == torch.float32 and dt.shape == (B, T, H)
+    if want_y and out is None:
+        out = torch.empty((B, T, H, P), dtype=x.dtype, device=x.device)
+    if h_out is None:
+        h_out = torch.empty((B, H, P, S), dtype=torch.float32, device=x.device)
+    d = make_dims(B, T, H, P, S, G, 0, _io_code(x), 0, _token_stride(x, T), _token_stride(Bm, T),
+                  _token_stride(Cm, T) if Cm is not None else 0)
+    _check(load().stree_linear_ssd(C.byref(d), _ptr(x), _ptr(dt), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(D), _ptr(h0),
+                                   _ptr(out) if want_y else None, _ptr(h_out), _stream()), "stree_linear_ssd")
+    return (out if want_y else None), h_out

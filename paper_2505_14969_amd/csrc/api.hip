@@ -168,4 +168,23 @@ int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, con
                                                      (hipStream_t)hip_stream));
 }
 
+int stree_linear_ssd(const stree_dims *dims, const void *x, const float *dt, const float *A, const void *Bm,
+                     const void *Cm, const float *D, const float *h0, void *y, float *h_out, void *hip_stream) {
+    if (!dims) return STREE_ERR_NULL_ARG;
+    stree_dims d = *dims;
+    const int T = d.nnodes;
+    d.nnodes = 1;                        // the envelope check of the tree entry points, bar the node limit
+    int rc = check_dims(&d, kNoConv);
+    if (rc) return rc;
+    if (T < 1 || T > (1 << 24)) return STREE_ERR_BAD_SHAPE;
+    d.nnodes = T;
+    if (!x || !dt || !A || !Bm || !h_out || (y && !Cm)) return STREE_ERR_NULL_ARG;
+    rc = resolve_strides(d);
+    if (rc) return rc;
+    if (!stree::linear_ssd_supported(d, x, Bm, Cm, y)) return STREE_ERR_BAD_SHAPE;
+    if (d.batch == 0) return STREE_OK;
+    return hip_status(stree::launch_linear_ssd(d, x, dt, A, Bm, Cm ? Cm : Bm, D, h0, y, h_out,
+                                               (hipStream_t)hip_stream));
+}
+
 }  // extern "C"

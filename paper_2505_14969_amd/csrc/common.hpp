@@ -137,6 +137,25 @@ __device__ __forceinline__ unsigned long long wave_read(unsigned long long v, in
     return ((unsigned long long)hi << 32) | lo;
 }
 
+// Transposing store of one 16-byte row piece (8 bf16 of row r, columns c8 .. c8+7) into an LDS
+// tile laid out [column][row] with `ld` elements per column.  Two-byte scatter writes would put
+// two lanes into every LDS word and serialise; instead the lanes holding rows r and r^1 of the
+// same columns (lane ^ VPR, VPR = 16-byte pieces per row) swap half of their data, and each
+// writes four full words (row pair, one column each).  Every lane of the wave must call it.
+template <int VPR>
+__device__ __forceinline__ void store_transposed_pair(unsigned short *tile, int ld, int r, int c8, uint4 v, int lane) {
+    const bool odd = r & 1;
+    const uint32_t r0 = wave_read(odd ? v.x : v.z, lane ^ VPR), r1 = wave_read(odd ? v.y : v.w, lane ^ VPR);
+    // even row: columns c8..c8+3, own values low; odd row: columns c8+4..c8+7, own values high
+    const uint32_t lo0 = odd ? r0 : v.x, lo1 = odd ? r1 : v.y, hi0 = odd ? v.z : r0, hi1 = odd ? v.w : r1;
+    uint32_t *dst = reinterpret_cast<uint32_t *>(tile + (c8 + (odd ? 4 : 0)) * ld + (r & ~1));
+    const int ldw = ld / 2;
+    dst[0] = (lo0 & 0xffffu) | (hi0 << 16);
+    dst[ldw] = (lo0 >> 16) | (hi0 & 0xffff0000u);
+    dst[2 * ldw] = (lo1 & 0xffffu) | (hi1 << 16);
+    dst[3 * ldw] = (lo1 >> 16) | (hi1 & 0xffff0000u);
+}
+
 // Path of the accepted node k for trees of at most 64 nodes, by one wave with no LDS and no
 // barrier: lane j owns node j; pointer doubling over the parent array with cross-lane reads
 // gives every lane s_j (the paper's A_tree) and its ancestor bit row; lane k's values are then

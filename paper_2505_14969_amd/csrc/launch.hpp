@@ -47,6 +47,11 @@ hipError_t launch_tree_ssd_replay_fused(const stree_dims &d, const stree_dims &d
                                         const void *Bm, const void *Cm, const float *D, const float *h0,
                                         float *h_out, void *y, int32_t *status, int32_t *rstatus, hipStream_t st);
 
+// chunked causal scan of a long sequence (d.nnodes = T tokens)
+bool linear_ssd_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm, const void *y);
+hipError_t launch_linear_ssd(const stree_dims &d, const void *x, const float *dt, const float *A, const void *Bm,
+                             const void *Cm, const float *D, const float *h0, void *y, float *h_out, hipStream_t st);
+
 // h_out == NULL: conv tail only
 hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const int32_t *accepted,
                                const void *x, const float *dt, const float *A, const void *Bm,

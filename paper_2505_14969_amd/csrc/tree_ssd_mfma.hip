@@ -170,13 +170,8 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
                 const int r = idx / (P / 8), c = idx % (P / 8), j = j0 + r;
                 uint4 v = make_uint4(0, 0, 0, 0);
                 if (j < n) v = *reinterpret_cast<const uint4 *>(xb + (size_t)j * x_sn + c * 8);
-                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
-                unsigned short *dst = reinterpret_cast<unsigned short *>(sXT) + (c * 8) * kNP + r;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    dst[(2 * e) * kNP] = (unsigned short)(wv[e] & 0xffffu);
-                    dst[(2 * e + 1) * kNP] = (unsigned short)(wv[e] >> 16);
-                }
+                // (every lane of the wave is here: kBlk * P/8 is a multiple of the workgroup size)
+                store_transposed_pair<P / 8>(reinterpret_cast<unsigned short *>(sXT), kNP, r, c * 8, v, lane);
             }
             __syncthreads();
             STREE_PHASE_CLOCK(5);

@@ -368,13 +368,8 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             const int rr = rx0 + q * kRowsX;
             const uint32_t keep = rr < n ? 0xffffffffu : 0u;
             const uint4 xq = pre[NH + q];
-            const uint32_t wv[4] = {xq.x & keep, xq.y & keep, xq.z & keep, xq.w & keep};
-            unsigned short *dst = sXT + (cx0 * 8) * kNP64 + rr;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                dst[(2 * e) * kNP64] = (unsigned short)(wv[e] & 0xffffu);
-                dst[(2 * e + 1) * kNP64] = (unsigned short)(wv[e] >> 16);
-            }
+            store_transposed_pair<P / 8>(sXT, kNP64, rr, cx0 * 8,
+                                         make_uint4(xq.x & keep, xq.y & keep, xq.z & keep, xq.w & keep), opaque(lane));
         }
     };
     auto stage_T = [&](int h) {

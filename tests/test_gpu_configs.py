@@ -141,7 +141,14 @@ def test_config4_prefix_then_tree(st, oracle):
     T = e["prefix_x"].shape[1]
     B, H, P, S = wl.batch, wl.nheads, wl.headdim, wl.dstate
     # oracle: one linear scan over the 4096-token prefix
-    _, h_ref = oracle.linear_scan(e["prefix_x"], e["prefix_dt"], wl.A, e["prefix_B"], e["prefix_C"], None, None)
+    y_ref, h_ref = oracle.linear_scan(e["prefix_x"], e["prefix_dt"], wl.A, e["prefix_B"], e["prefix_C"], None, None)
+    # GPU, first-class prefix kernel: y of every prefix token and the state after the last one
+    y_lin, h_lin = st.stree_linear_ssd(to_dev(e["prefix_x"], "bf16"), to_dev(e["prefix_dt"]), to_dev(wl.A),
+                                       to_dev(e["prefix_B"], "bf16"), to_dev(e["prefix_C"], "bf16"))
+    assert_parity(to_host(h_lin), h_ref, 1e-4, "cfg4 prefix state (linear scan kernel)")
+    y_lin = to_host(y_lin)
+    for b in range(B):
+        assert_parity(y_lin[b], y_ref[b], TOL["bf16"], f"cfg4 prefix y b={b}")
     # GPU: 16 x (256-node chain, commit at its last node), state updated in place
     chunk = 256
     chain = to_dev(np.stack([synth.chain_tree(chunk)] * B))

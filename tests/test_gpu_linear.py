@@ -1,0 +1,57 @@
+"""GPU parity of the chunked linear prefix scan against the oracle's plain causal scan
+(no tree code on the oracle side), and its consistency with the tree path: the state it
+returns seeds the tree scan, and a chain tree through the tree kernels gives the same y."""
+import numpy as np
+import pytest
+
+from paper_2505_14969_amd import synth
+from helpers import TOL, assert_parity, to_dev, to_host
+from test_gpu_parity import _rand, st  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("B,T,H,P,S,G,with_h0", [(2, 1, 2, 64, 128, 1, True), (2, 63, 4, 64, 128, 2, False),
+                                                  (1, 64, 2, 64, 128, 1, True), (3, 65, 4, 64, 64, 1, True),
+                                                  (2, 200, 2, 128, 128, 2, True), (2, 1000, 3, 64, 128, 1, True)])
+def test_linear_scan_against_oracle(st, oracle, B, T, H, P, S, G, with_h0):
+    io = "bf16"
+    x, dt, A, Bm, Cm, D, h0 = _rand(300 + T, io, B, T, H, P, S, G, h0=with_h0)
+    want_y, want_h = oracle.linear_scan(x, dt, A, Bm, Cm, D, h0)
+    y, h = st.stree_linear_ssd(to_dev(x, io), to_dev(dt), to_dev(A), to_dev(Bm, io), to_dev(Cm, io), to_dev(D),
+                               to_dev(h0))
+    assert_parity(to_host(h), want_h, 1e-4, f"state after {T} tokens")
+    assert_parity(to_host(y), want_y, TOL[io], f"y of {T} tokens")
+    # state only, in place
+    h_io = to_dev(h0) if with_h0 else None
+    if h_io is not None:
+        _, h2 = st.stree_linear_ssd(to_dev(x, io), to_dev(dt), to_dev(A), to_dev(Bm, io), h0=h_io, want_y=False,
+                                    h_out=h_io)
+        assert np.array_equal(to_host(h2), to_host(h))
+
+
+def test_linear_scan_equals_chain_tree_on_gpu(st, oracle):
+    """Same tokens through the tree kernel as a 200-node chain: same y within the bf16 bound, and
+    the committed state of the chain's last node equals the linear scan's final state."""
+    io, B, T, H, P, S, G = "bf16", 2, 200, 4, 64, 128, 1
+    x, dt, A, Bm, Cm, D, h0 = _rand(77, io, B, T, H, P, S, G)
+    y, h = st.stree_linear_ssd(to_dev(x, io), to_dev(dt), to_dev(A), to_dev(Bm, io), to_dev(Cm, io), to_dev(D),
+                               to_dev(h0))
+    chain = to_dev(np.stack([synth.chain_tree(T)] * B))
+    yt = st.stree_tree_ssd(chain, to_dev(x, io), to_dev(dt), to_dev(A), to_dev(Bm, io), to_dev(Cm, io), to_dev(D),
+                           to_dev(h0))
+    ht, _ = st.stree_commit_state(chain, to_dev(np.full(B, T - 1, dtype=np.int32)), to_dev(x, io), to_dev(dt),
+                                  to_dev(A), to_dev(Bm, io), to_dev(h0))
+    assert_parity(to_host(y), to_host(yt).astype(np.float64), TOL[io], "linear scan vs chain tree y")
+    assert_parity(to_host(h), to_host(ht).astype(np.float64), 1e-4, "linear scan vs chain commit state")
+
+
+def test_linear_scan_rejects_unsupported_shapes(st):
+    import torch
+    x = torch.zeros((1, 8, 2, 32), dtype=torch.bfloat16, device="cuda")
+    Bm = torch.zeros((1, 8, 1, 48), dtype=torch.bfloat16, device="cuda")
+    dt = torch.zeros((1, 8, 2), dtype=torch.float32, device="cuda")
+    A = torch.zeros((2,), dtype=torch.float32, device="cuda")
+    with pytest.raises(st.StreeError) as e:
+        st.stree_linear_ssd(x, dt, A, Bm, Bm)
+    assert e.value.code == 2
