@@ -195,8 +195,11 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     // into contiguous runs, so a workgroup mostly sees consecutive heads of one sequence and
     // group: their C, B tiles, the tree mask and Gt = B C^T are then reused, not redone.
     const int cnt = max(0, min(per_xcd, n_units - xcd * per_xcd));
-    const int u0 = xcd * per_xcd + (int)((long)wg * cnt / nwg);
-    const int nU = xcd * per_xcd + (int)((long)(wg + 1) * cnt / nwg) - u0;
+    // the first cnt % nwg workgroups take one unit more.  (Workgroups are placed one per CU first and
+    // the second one per CU later: a CU then holds workgroup w and w + nwg/2, a long and a short run.)
+    const int ubase = cnt / nwg, urem = cnt % nwg;
+    const int u0 = xcd * per_xcd + wg * ubase + min(wg, urem);
+    const int nU = ubase + (wg < urem ? 1 : 0);
     // (b, h) of unit k by stepping from unit 0 (k is 0, 1 or 2 units ahead of a known one):
     // scalar adds and compares only, no division inside the unit loop
     const int ub0 = __builtin_amdgcn_readfirstlane(u0 / H), uh0 = __builtin_amdgcn_readfirstlane(u0 % H);
