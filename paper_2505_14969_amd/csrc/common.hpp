@@ -44,12 +44,12 @@ struct __align__(16) TreeLds {
 // The ancestor bit rows live in a separate LDS array `mask` of npad*words words
 // (row i at mask[i*words ..)), so that kernels size it to the tree at hand.
 
-// Loads and validates parent[], returns the (uniform) status: 0 or bad node + 1.
-// On return (after the internal barriers) s/cnt/mask are final for i < n; rows
-// n..npad-1 of s, dt, mask are zero.  `dtA` is this thread's dt_i * A_h (any
-// value for i >= n).
-__device__ __forceinline__ int build_tree_index(TreeLds &T, uint32_t *mask, const int32_t *__restrict__ parent,
-                                                int n, int npad, int words, float dt_i, float A_h) {
+// Validates the parents (thread i passes parent[i]; any value for i >= n) and
+// returns the (uniform) status: 0 or bad node + 1.  On return (after the
+// internal barriers) s/cnt/mask are final for i < n; rows n..npad-1 of s, dt,
+// mask are zero.  dt_i is this thread's step size (any value for i >= n).
+__device__ __forceinline__ int build_tree_index(TreeLds &T, uint32_t *mask, int parent_i, int n, int npad,
+                                                int words, float dt_i, float A_h) {
     const int i = threadIdx.x;
     if (i == 0) T.bad = 0x7fffffff;
     __syncthreads();
@@ -60,7 +60,7 @@ __device__ __forceinline__ int build_tree_index(TreeLds &T, uint32_t *mask, cons
     float s = 0.f;
     int cnt = 1;
     if (i < n) {
-        p = parent[i];
+        p = parent_i;
         const bool ok = (i == 0) ? (p == -1) : (p >= 0 && p < i);
         if (!ok) {
             atomicMin(&T.bad, i + 1);
@@ -117,6 +117,13 @@ __device__ __forceinline__ int build_tree_index(TreeLds &T, uint32_t *mask, cons
     }
     __syncthreads();
     return 0;
+}
+
+// The same, with thread i loading parent[i] itself.
+__device__ __forceinline__ int build_tree_index(TreeLds &T, uint32_t *mask, const int32_t *__restrict__ parent,
+                                                int n, int npad, int words, float dt_i, float A_h) {
+    const int i = threadIdx.x;
+    return build_tree_index(T, mask, i < n ? parent[i] : -1, n, npad, words, dt_i, A_h);
 }
 
 __device__ __forceinline__ bool mask_bit(const uint32_t *mask, int words, int i, int j) {

@@ -21,6 +21,7 @@
 #include "common.hpp"
 #include "launch.hpp"
 
+// Probe builds define this to record per-workgroup timestamps; product builds compile it away.
 #ifndef STREE_PHASE_CLOCK
 #define STREE_PHASE_CLOCK(k)
 #endif
@@ -51,21 +52,32 @@ __host__ __device__ inline MfmaLdsPlan mfma_lds_plan(int P, int S, int npad, int
     return pl;
 }
 
+// Tile loads travel through registers: the loads of the next (row block, column block) pair are
+// issued before the current pair is computed and written to LDS after it, so that their latency
+// is hidden by the MFMA phases; the first tiles and the initial state are requested before the
+// tree index is built.
+constexpr int kMaxS32 = 8;       // dstate <= 256: at most 8 16-byte pieces of a C or B tile per thread
+constexpr int kH0Batch = 8;      // float4 pieces of h0 per thread requested ahead of the tree index
+
+// (for headdim <= 64 two workgroups fit the LDS of a CU: the register budget is held to that)
 template <int P>
-__global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
+__global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kernel(
     const int32_t *__restrict__ parent, int n, int H, int S, int G, const bf16_t *__restrict__ x, long x_sn,
     const float *__restrict__ dt, const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn,
     const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
     bf16_t *__restrict__ y, int32_t *__restrict__ status) {
     constexpr int YT = (P / 32) * 2;          // 32x32 tiles of Yt[p][i] per node block
     constexpr int YQ = (YT + 3) / 4;          // tiles per wave
+    constexpr int XQ = P / 32;                // 16-byte pieces of an x tile per thread
     extern __shared__ __align__(16) unsigned char lds[];
     __shared__ TreeLds tree;
+    __shared__ uint32_t nz_bits;              // bit 4*ib+jb: row block ib has an ancestor in column block jb < ib
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
     const int h = blockIdx.x, b = blockIdx.y;
     const int g = h / (H / G);
     const int npad = (n + kBlk - 1) / kBlk * kBlk;
+    const int nblk = npad / kBlk;
     const int words = (n + 31) / 32;
     const MfmaLdsPlan pl = mfma_lds_plan(P, S, npad, words);
     const int SP = pl.sp;
@@ -77,23 +89,92 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
     bf16_t *sM = reinterpret_cast<bf16_t *>(lds + pl.off_m);
     uint32_t *mask = reinterpret_cast<uint32_t *>(lds + pl.off_mask);
 
-    STREE_PHASE_CLOCK(0);
-    // ---- initial state -> bf16 MFMA operand rows sH[p][s] -------------------------------
-    if (h0) {
-        const float *hb = h0 + ((size_t)b * H + h) * P * S;
-        for (int idx = tid; idx < P * S / 4; idx += kThreads) {
-            const int e = idx * 4, p = e / S, s = e % S;
-            const float4 v = *reinterpret_cast<const float4 *>(hb + e);
-            bf16x4 o;
-            o[0] = (bf16_t)v.x; o[1] = (bf16_t)v.y; o[2] = (bf16_t)v.z; o[3] = (bf16_t)v.w;
-            *reinterpret_cast<bf16x4 *>(&sH[p * SP + s]) = o;
-        }
+    const bf16_t *xb = x + (size_t)b * n * x_sn + (size_t)h * P;
+    const bf16_t *Bb = Bm + (size_t)b * n * b_sn + (size_t)g * S;
+    const bf16_t *Cb = Cm + (size_t)b * n * c_sn + (size_t)g * S;
+    const float *hb = h0 ? h0 + ((size_t)b * H + h) * P * S : nullptr;
+    const int s8 = S / 8;
+    const int cb_items = kBlk * s8;           // 16-byte pieces of a C or B tile
+    const int h_items = P * S / 4;            // float4 pieces of h0
+
+    // ---- tile movers: global -> registers, registers -> LDS ---------------------------------
+    // Loads are unconditional (rows past the tree and pieces past the tile are clamped to valid
+    // addresses), so that they are issued back to back with no wait between them; what must be
+    // zero is zeroed when the registers are written to LDS.
+    uint4 creg[kMaxS32], breg[kMaxS32], xreg[XQ];
+    float4 hreg[kH0Batch];
+    int rc[kMaxS32];                          // piece q of a C or B tile: (row << 8) | 16-byte column
+#pragma unroll
+    for (int q = 0; q < kMaxS32; ++q) {
+        const int idx = min(q * kThreads + tid, cb_items - 1);
+        rc[q] = ((idx / s8) << 8) | (idx % s8);
     }
-    STREE_PHASE_CLOCK(1);
-    // ---- tree index: depth, mask rows L_i, s_i = (A_tree)_i ---------------------------
+    auto load_rows = [&](uint4 (&r)[kMaxS32], const bf16_t *base, long sn, int row0) {
+#pragma unroll
+        for (int q = 0; q < kMaxS32; ++q) {
+            const int i = min(row0 + (rc[q] >> 8), n - 1);
+            r[q] = *reinterpret_cast<const uint4 *>(base + (size_t)i * sn + (rc[q] & 0xff) * 8);
+        }
+    };
+    auto store_rows = [&](const uint4 (&r)[kMaxS32], bf16_t *tile, int row0) {
+#pragma unroll
+        for (int q = 0; q < kMaxS32; ++q) {
+            if (q * kThreads + tid < cb_items) {
+                uint4 v = r[q];
+                if (row0 + (rc[q] >> 8) >= n) v = make_uint4(0, 0, 0, 0);
+                *reinterpret_cast<uint4 *>(&tile[(rc[q] >> 8) * SP + (rc[q] & 0xff) * 8]) = v;
+            }
+        }
+    };
+    auto load_x = [&](int row0) {
+#pragma unroll
+        for (int q = 0; q < XQ; ++q) {
+            const int idx = q * kThreads + tid;
+            const int j = min(row0 + idx / (P / 8), n - 1);
+            xreg[q] = *reinterpret_cast<const uint4 *>(xb + (size_t)j * x_sn + (idx % (P / 8)) * 8);
+        }
+    };
+    auto store_x = [&](int row0) {
+#pragma unroll
+        for (int q = 0; q < XQ; ++q) {
+            const int idx = q * kThreads + tid;
+            uint4 v = xreg[q];
+            if (row0 + idx / (P / 8) >= n) v = make_uint4(0, 0, 0, 0);
+            // (every lane of the wave is here: kBlk * P/8 is a multiple of the workgroup size)
+            store_transposed_pair<P / 8>(reinterpret_cast<unsigned short *>(sXT), kNP, idx / (P / 8),
+                                         (idx % (P / 8)) * 8, v, lane);
+        }
+    };
+    // `one` is 1.0f that the compiler cannot see through, defined after the tree index: the
+    // conversion of the prefetched h0 pieces (and the wait for them) cannot move above that point.
+    auto store_h = [&](int idx, const float4 &v, float one) {
+        const int e = idx * 4, p = e / S, s = e % S;
+        bf16x4 o;
+        o[0] = (bf16_t)(v.x * one); o[1] = (bf16_t)(v.y * one); o[2] = (bf16_t)(v.z * one); o[3] = (bf16_t)(v.w * one);
+        *reinterpret_cast<bf16x4 *>(&sH[p * SP + s]) = o;
+    };
+
+    STREE_PHASE_CLOCK(0);
+    // ---- requests that do not depend on the tree: the small per-node values first (loads return
+    //      in order, and the tree index needs only these), then h0 and the tiles of pair (0, 0) ----
     const float A_h = A[h];
     const float dt_i = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
-    const int bad = build_tree_index(tree, mask, parent + (size_t)b * n, n, npad, words, dt_i, A_h);
+    const int parent_i = tid < n ? parent[(size_t)b * n + tid] : -1;
+    if (h0) {
+#pragma unroll
+        for (int q = 0; q < kH0Batch; ++q) {
+            const int idx = min(q * kThreads + tid, h_items - 1);
+            hreg[q] = *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4);
+        }
+    }
+    load_rows(creg, Cb, c_sn, 0);
+    load_rows(breg, Bb, b_sn, 0);
+    load_x(0);
+
+    STREE_PHASE_CLOCK(1);
+    // ---- tree index: depth, mask rows L_i, s_i = (A_tree)_i ---------------------------------
+    if (tid == 0) nz_bits = 0u;
+    const int bad = build_tree_index(tree, mask, parent_i, n, npad, words, dt_i, A_h);
     if (status && h == 0 && tid == 0) status[b] = bad;
     STREE_PHASE_CLOCK(2);
     bf16_t *yb = y + (size_t)b * n * H * P + (size_t)h * P;
@@ -104,170 +185,197 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_mfma_kernel(
         }
         return;
     }
-    const bf16_t *xb = x + (size_t)b * n * x_sn + (size_t)h * P;
-    const bf16_t *Bb = Bm + (size_t)b * n * b_sn + (size_t)g * S;
-    const bf16_t *Cb = Cm + (size_t)b * n * c_sn + (size_t)g * S;
+    // column blocks that hold an ancestor of some node of a row block (the others are skipped)
+    if (tid < n) {
+        const int ib = tid >> 6;
+        uint32_t bits = 0u;
+        for (int jb = 0; jb < ib; ++jb)
+            if ((mask[tid * words + 2 * jb] | mask[tid * words + 2 * jb + 1]) != 0u) bits |= 1u << (4 * ib + jb);
+        if (bits) atomicOr(&nz_bits, bits);
+    }
+    // ---- initial state -> bf16 MFMA operand rows sH[p][s] ----------------------------------
+    if (h0) {
+        float one = 1.0f;
+        asm volatile("" : "+v"(one));
+#pragma unroll
+        for (int q = 0; q < kH0Batch; ++q) {
+            const int idx = q * kThreads + tid;
+            if (idx < h_items) store_h(idx, hreg[q], one);
+        }
+        for (int idx = kH0Batch * kThreads + tid; idx < h_items; idx += kThreads)
+            store_h(idx, *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4), one);
+    }
+    __syncthreads();
+    STREE_PHASE_CLOCK(3);
+    const uint32_t nz = __builtin_amdgcn_readfirstlane(nz_bits);
     const float D_h = D ? D[h] : 0.f;
-    const int s8 = S / 8;
 
-    for (int i0 = 0; i0 < npad; i0 += kBlk) {
-        // ---- C rows of this block -------------------------------------------------------
-        for (int idx = tid; idx < kBlk * s8; idx += kThreads) {
-            const int r = idx / s8, c = idx % s8, i = i0 + r;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (i < n) v = *reinterpret_cast<const uint4 *>(Cb + (size_t)i * c_sn + c * 8);
-            *reinterpret_cast<uint4 *>(&sC[r * SP + c * 8]) = v;
+    // first column block of row block ib, and the one after jb (the diagonal block is always taken)
+    auto next_col = [&](int ib, int after) {
+        const uint32_t row = ((nz >> (4 * ib)) & 0xfu) | (1u << ib);
+        const uint32_t rest = row & ~((1u << (after + 1)) - 1u);
+        return __builtin_ctz(rest);
+    };
+
+    // acc += sum over the S state indices of a-row * b-row, four 16-wide steps per round so that
+    // the LDS reads of a round are in flight together (S is a multiple of 16, not always of 64)
+    auto contract_s = [&](floatx16 &c, const bf16_t *ap, const bf16_t *bp) {
+        for (int k0 = 0; k0 < S; k0 += 64) {
+            bf16x8 a[4], bb[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int kk = min(k0 + 16 * u, S - 16);
+                a[u] = *reinterpret_cast<const bf16x8 *>(ap + kk);
+                bb[u] = *reinterpret_cast<const bf16x8 *>(bp + kk);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (k0 + 16 * u < S) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], bb[u], c, 0, 0, 0);
+        }
+    };
+
+    floatx16 acc[YQ];
+    int ib = 0, jb = 0;
+    bool new_rows = true;
+    while (true) {
+        const int i0 = ib * kBlk, j0 = jb * kBlk;
+        // ---- this pair's tiles: registers -> LDS; the next pair's: global -> registers ------
+        if (new_rows) store_rows(creg, sC, i0);
+        store_rows(breg, sB, j0);
+        store_x(j0);
+        int nib = ib, njb;
+        if (jb == ib) {
+            nib = ib + 1;
+            njb = nib < nblk ? next_col(nib, -1) : 0;
+        } else {
+            njb = next_col(ib, jb);
+        }
+        const bool more = nib < nblk;
+        if (more) {
+            if (nib != ib) load_rows(creg, Cb, c_sn, nib * kBlk);
+            load_rows(breg, Bb, b_sn, njb * kBlk);
+            load_x(njb * kBlk);
         }
         __syncthreads();
-        STREE_PHASE_CLOCK(3);
-
-        floatx16 acc[YQ];
-#pragma unroll
-        for (int q = 0; q < YQ; ++q)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[q][r] = 0.f;
-
-        // ---- phase 1: Yt = h0b * C^T, scaled by exp(s_i) -------------------------------
-        if (h0) {
-#pragma unroll
-            for (int q = 0; q < YQ; ++q) {
-                const int t = wave + 4 * q;
-                if (t < YT) {
-                    const int it = t & 1, pt = t >> 1;
-                    const bf16_t *ap = &sH[(pt * 32 + l32) * SP + 8 * lh];
-                    const bf16_t *bp = &sC[(it * 32 + l32) * SP + 8 * lh];
-                    for (int k0 = 0; k0 < S; k0 += 16) {
-                        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ap + k0);
-                        const bf16x8 bb = *reinterpret_cast<const bf16x8 *>(bp + k0);
-                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[q], 0, 0, 0);
-                    }
-                    const float e = __expf(tree.s[i0 + it * 32 + l32]);
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[q][r] *= e;
-                }
-            }
-        }
-
         STREE_PHASE_CLOCK(4);
-        for (int j0 = 0; j0 <= i0; j0 += kBlk) {
-            // ---- skip column blocks that hold no ancestor of this row block ------------
-            if (j0 < i0) {
-                int any = 0;
-                if (tid < kBlk && i0 + tid < n) {
-                    const int wj = j0 >> 5;
-                    any = (mask[(i0 + tid) * words + wj] | mask[(i0 + tid) * words + wj + 1]) != 0u;
-                }
-                if (!__syncthreads_or(any)) continue;
-            }
-            // ---- B rows and X^T of the column block ---------------------------------------
-            for (int idx = tid; idx < kBlk * s8; idx += kThreads) {
-                const int r = idx / s8, c = idx % s8, j = j0 + r;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (j < n) v = *reinterpret_cast<const uint4 *>(Bb + (size_t)j * b_sn + c * 8);
-                *reinterpret_cast<uint4 *>(&sB[r * SP + c * 8]) = v;
-            }
-            for (int idx = tid; idx < kBlk * (P / 8); idx += kThreads) {
-                const int r = idx / (P / 8), c = idx % (P / 8), j = j0 + r;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (j < n) v = *reinterpret_cast<const uint4 *>(xb + (size_t)j * x_sn + c * 8);
-                // (every lane of the wave is here: kBlk * P/8 is a multiple of the workgroup size)
-                store_transposed_pair<P / 8>(reinterpret_cast<unsigned short *>(sXT), kNP, r, c * 8, v, lane);
-            }
-            __syncthreads();
-            STREE_PHASE_CLOCK(5);
 
-            // ---- phase 2: Gt = B * C^T; mask and decay -> M[i][j] as bf16 ----------------
-            {
-                const int it = wave & 1, jt = wave >> 1;
-                floatx16 gt;
+        // ---- phase 1 (once per row block): Yt = h0b * C^T, scaled by exp(s_i) ---------------
+        if (new_rows) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) gt[r] = 0.f;
-                const bf16_t *ap = &sB[(jt * 32 + l32) * SP + 8 * lh];
-                const bf16_t *bp = &sC[(it * 32 + l32) * SP + 8 * lh];
-                for (int k0 = 0; k0 < S; k0 += 16) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ap + k0);
-                    const bf16x8 bb = *reinterpret_cast<const bf16x8 *>(bp + k0);
-                    gt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, gt, 0, 0, 0);
-                }
-                const int il = it * 32 + l32, i = i0 + il;
-                const int wj = (j0 >> 5) + jt;
-                const uint32_t mrow = (i < n && wj < words) ? mask[i * words + wj] : 0u;
-                const float s_i = tree.s[i];
+            for (int q = 0; q < YQ; ++q)
 #pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    const int jl = jt * 32 + 8 * rg + 4 * lh;      // first of 4 consecutive j
-                    const float4 sj = *reinterpret_cast<const float4 *>(&tree.s[j0 + jl]);
-                    const float4 dj = *reinterpret_cast<const float4 *>(&tree.dt[j0 + jl]);
-                    const float sjv[4] = {sj.x, sj.y, sj.z, sj.w};
-                    const float djv[4] = {dj.x, dj.y, dj.z, dj.w};
-                    bf16x4 o;
+                for (int r = 0; r < 16; ++r) acc[q][r] = 0.f;
+            if (h0) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const bool on = (mrow >> (8 * rg + 4 * lh + e)) & 1u;
-                        const float v = on ? gt[4 * rg + e] * __expf(s_i - sjv[e]) * djv[e] : 0.f;
-                        o[e] = (bf16_t)v;
-                    }
-                    *reinterpret_cast<bf16x4 *>(&sM[il * kNP + jl]) = o;
-                }
-            }
-            __syncthreads();
-            STREE_PHASE_CLOCK(6);
-
-            // ---- phase 3: Yt += Xt * M^T ---------------------------------------------------
+                for (int q = 0; q < YQ; ++q) {
+                    const int t = wave + 4 * q;
+                    if (t < YT) {
+                        const int it = t & 1, pt = t >> 1;
+                        const bf16_t *ap = &sH[(pt * 32 + l32) * SP + 8 * lh];
+                        const bf16_t *bp = &sC[(it * 32 + l32) * SP + 8 * lh];
+                        contract_s(acc[q], ap, bp);
+                        const float e = __expf(tree.s[i0 + it * 32 + l32]);
 #pragma unroll
-            for (int q = 0; q < YQ; ++q) {
-                const int t = wave + 4 * q;
-                if (t < YT) {
-                    const int it = t & 1, pt = t >> 1;
-                    const bf16_t *ap = &sXT[(pt * 32 + l32) * kNP + 8 * lh];
-                    const bf16_t *bp = &sM[(it * 32 + l32) * kNP + 8 * lh];
-#pragma unroll
-                    for (int k0 = 0; k0 < kBlk; k0 += 16) {
-                        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ap + k0);
-                        const bf16x8 bb = *reinterpret_cast<const bf16x8 *>(bp + k0);
-                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[q], 0, 0, 0);
+                        for (int r = 0; r < 16; ++r) acc[q][r] *= e;
                     }
                 }
             }
-            __syncthreads();
         }
-        STREE_PHASE_CLOCK(7);
 
-        // ---- epilogue: stage fp32 Y rows (over the dead B tile), add D*x, store bf16 -----
+        // ---- phase 2: Gt = B * C^T; mask and decay -> M[i][j] as bf16 ------------------------
+        {
+            const int it = wave & 1, jt = wave >> 1;
+            floatx16 gt;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) gt[r] = 0.f;
+            const bf16_t *ap = &sB[(jt * 32 + l32) * SP + 8 * lh];
+            const bf16_t *bp = &sC[(it * 32 + l32) * SP + 8 * lh];
+            contract_s(gt, ap, bp);
+            const int il = it * 32 + l32, i = i0 + il;
+            const int wj = (j0 >> 5) + jt;
+            const uint32_t mrow = (i < n && wj < words) ? mask[i * words + wj] : 0u;
+            const float s_i = tree.s[i];
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int jl = jt * 32 + 8 * rg + 4 * lh;      // first of 4 consecutive j
+                const float4 sj = *reinterpret_cast<const float4 *>(&tree.s[j0 + jl]);
+                const float4 dj = *reinterpret_cast<const float4 *>(&tree.dt[j0 + jl]);
+                const float sjv[4] = {sj.x, sj.y, sj.z, sj.w};
+                const float djv[4] = {dj.x, dj.y, dj.z, dj.w};
+                bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool on = (mrow >> (8 * rg + 4 * lh + e)) & 1u;
+                    const float v = on ? gt[4 * rg + e] * __expf(s_i - sjv[e]) * djv[e] : 0.f;
+                    o[e] = (bf16_t)v;
+                }
+                *reinterpret_cast<bf16x4 *>(&sM[il * kNP + jl]) = o;
+            }
+        }
+        __syncthreads();
+        STREE_PHASE_CLOCK(5);
+
+        // ---- phase 3: Yt += Xt * M^T ------------------------------------------------------------
 #pragma unroll
         for (int q = 0; q < YQ; ++q) {
             const int t = wave + 4 * q;
             if (t < YT) {
                 const int it = t & 1, pt = t >> 1;
+                const bf16_t *ap = &sXT[(pt * 32 + l32) * kNP + 8 * lh];
+                const bf16_t *bp = &sM[(it * 32 + l32) * kNP + 8 * lh];
 #pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    const float4 v = make_float4(acc[q][4 * rg], acc[q][4 * rg + 1], acc[q][4 * rg + 2], acc[q][4 * rg + 3]);
-                    *reinterpret_cast<float4 *>(&sY[(it * 32 + l32) * (P + 4) + pt * 32 + 8 * rg + 4 * lh]) = v;
+                for (int k0 = 0; k0 < kBlk; k0 += 16) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ap + k0);
+                    const bf16x8 bb = *reinterpret_cast<const bf16x8 *>(bp + k0);
+                    acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[q], 0, 0, 0);
                 }
             }
         }
-        __syncthreads();
-        for (int idx = tid; idx < kBlk * (P / 8); idx += kThreads) {
-            const int r = idx / (P / 8), c = idx % (P / 8), i = i0 + r;
-            if (i < n) {
-                const float4 a0 = *reinterpret_cast<const float4 *>(&sY[r * (P + 4) + c * 8]);
-                const float4 a1 = *reinterpret_cast<const float4 *>(&sY[r * (P + 4) + c * 8 + 4]);
-                const uint4 xv = *reinterpret_cast<const uint4 *>(xb + (size_t)i * x_sn + c * 8);
-                bf16x8 o;
-                o[0] = (bf16_t)fmaf(D_h, bf16_lo(xv.x), a0.x);
-                o[1] = (bf16_t)fmaf(D_h, bf16_hi(xv.x), a0.y);
-                o[2] = (bf16_t)fmaf(D_h, bf16_lo(xv.y), a0.z);
-                o[3] = (bf16_t)fmaf(D_h, bf16_hi(xv.y), a0.w);
-                o[4] = (bf16_t)fmaf(D_h, bf16_lo(xv.z), a1.x);
-                o[5] = (bf16_t)fmaf(D_h, bf16_hi(xv.z), a1.y);
-                o[6] = (bf16_t)fmaf(D_h, bf16_lo(xv.w), a1.z);
-                o[7] = (bf16_t)fmaf(D_h, bf16_hi(xv.w), a1.w);
-                *reinterpret_cast<bf16x8 *>(yb + (size_t)i * H * P + c * 8) = o;
+
+        // ---- after the diagonal block: fp32 Y rows staged over the B tile (its last reader was
+        //      phase 2), D * x added from the X^T tile of this same block, bf16 rows stored -----
+        STREE_PHASE_CLOCK(6);
+        if (jb == ib) {
+#pragma unroll
+            for (int q = 0; q < YQ; ++q) {
+                const int t = wave + 4 * q;
+                if (t < YT) {
+                    const int it = t & 1, pt = t >> 1;
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const float4 v =
+                            make_float4(acc[q][4 * rg], acc[q][4 * rg + 1], acc[q][4 * rg + 2], acc[q][4 * rg + 3]);
+                        *reinterpret_cast<float4 *>(&sY[(it * 32 + l32) * (P + 4) + pt * 32 + 8 * rg + 4 * lh]) = v;
+                    }
+                }
+            }
+            __syncthreads();
+            const unsigned short *xt = reinterpret_cast<const unsigned short *>(sXT);
+#pragma unroll
+            for (int q = 0; q < XQ; ++q) {
+                const int idx = q * kThreads + tid;
+                const int r = idx / (P / 8), c = idx % (P / 8), i = i0 + r;
+                if (i < n) {
+                    const float4 a0 = *reinterpret_cast<const float4 *>(&sY[r * (P + 4) + c * 8]);
+                    const float4 a1 = *reinterpret_cast<const float4 *>(&sY[r * (P + 4) + c * 8 + 4]);
+                    const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                    bf16x8 o;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float xv = __uint_as_float((uint32_t)xt[(c * 8 + e) * kNP + r] << 16);
+                        o[e] = (bf16_t)fmaf(D_h, xv, av[e]);
+                    }
+                    *reinterpret_cast<bf16x8 *>(yb + (size_t)i * H * P + c * 8) = o;
+                }
             }
         }
-        // the next block's C load and its barrier separate these sY reads from the next B load
+        STREE_PHASE_CLOCK(7);
+        if (!more) break;
+        __syncthreads();   // every reader of the tiles is done before the next pair overwrites them
+        new_rows = nib != ib;
+        ib = nib;
+        jb = njb;
     }
-    STREE_PHASE_CLOCK(8);
 }
 
 bool tree_ssd_mfma_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm,

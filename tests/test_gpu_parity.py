@@ -134,6 +134,24 @@ def test_bf16_mfma_kernel_shapes(st, oracle, N, H, P, S, G):
     assert_parity(got2, want, 6e-3, f"fma-bf16 N={N}")
 
 
+def test_bf16_mfma_kernel_skips_column_blocks_without_ancestors(st, oracle):
+    # trees of several 64-node blocks in which whole (row block, column block) pairs hold no
+    # ancestor: a star, two far-apart families (parent i - 128), and a chain hanging off node 0
+    # that starts in the last block
+    N, H, P, S, G = 250, 2, 64, 128, 1
+    far = np.arange(N, dtype=np.int32) - 128
+    far[:128] = np.arange(128, dtype=np.int32) - 1
+    late = np.zeros(N, dtype=np.int32)
+    late[0] = -1
+    late[200:] = np.arange(199, N - 1, dtype=np.int32)
+    late[200] = 0
+    parent = np.stack([synth.star_tree(N), far, late]).astype(np.int32)
+    x, dt, A, Bm, Cm, D, h0 = _rand(77, "bf16", 3, N, H, P, S, G)
+    want = oracle.ssd_paths(parent, x, dt, A, Bm, Cm, D, h0)
+    got = _run_ssd(st, "bf16", parent, x, dt, A, Bm, Cm, D, h0)
+    assert_parity(got, want, TOL["bf16"], "mfma block skipping")
+
+
 def test_bf16_optional_arguments(st, oracle):
     N, H, P, S, G = 48, 2, 64, 64, 1
     parent = _trees(9, 2, N)
