@@ -92,8 +92,11 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
 #pragma unroll
     for (int q = 0; q < kQ; ++q) {
         const int p = p0 + q;
-        acc[q] = (h0 && owner && p < P) ? *reinterpret_cast<const float4 *>(h0 + sbase + (size_t)p * S)
-                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+        acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (h0 && owner && p < P) {   // read once: streaming hint (as for the store of the result below)
+            const uint4 v = load_stream16(h0 + sbase + (size_t)p * S);
+            acc[q] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+        }
     }
 
     const int k = accepted[b];
@@ -199,7 +202,10 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
             const int p = p0 + q;
-            if (p < P) *reinterpret_cast<float4 *>(h_out + sbase + (size_t)p * S) = acc[q];
+            if (p < P)
+                store_stream16(h_out + sbase + (size_t)p * S,
+                               make_uint4(__float_as_uint(acc[q].x), __float_as_uint(acc[q].y),
+                                          __float_as_uint(acc[q].z), __float_as_uint(acc[q].w)));
         }
     }
 }

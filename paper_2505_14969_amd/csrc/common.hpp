@@ -130,6 +130,21 @@ __device__ __forceinline__ bool mask_bit(const uint32_t *mask, int words, int i,
     return (mask[i * words + (j >> 5)] >> (j & 31)) & 1u;
 }
 
+// 16-byte load of data that is read once (the state tiles): the streaming hint keeps it from
+// displacing the B / C rows that the heads of a group share in L2.
+__device__ __forceinline__ uint4 load_stream16(const void *p) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// 16-byte store of data that this kernel does not read again.
+__device__ __forceinline__ void store_stream16(void *p, uint4 v) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 vv = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(vv, reinterpret_cast<u32x4 *>(p));
+}
+
 // Cross-lane read within a wave of 64: value `v` of lane `src` (0..63).  Unlike __shfl this
 // needs no lane id of the caller, so nothing lane-derived stays live around it.
 __device__ __forceinline__ int wave_read(int v, int src) { return __builtin_amdgcn_ds_bpermute(src << 2, v); }

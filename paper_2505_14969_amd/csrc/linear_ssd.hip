@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
 #pragma unroll
         for (int q = 0; q < NX; ++q) {
             const int tok = min(c0 + rx0 + q * kRowsX, T - 1);
-            rx[q] = *reinterpret_cast<const uint4 *>(xb + ((size_t)tok * x_sn + cx0 * 8) * 2);
+            rx[q] = load_stream16(xb + ((size_t)tok * x_sn + cx0 * 8) * 2);   // x and y: touched once
         }
         if constexpr (WY) {
 #pragma unroll
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
                     const uint4 v = *reinterpret_cast<const uint4 *>(ys + row * 64 + ((rcc ^ ((row >> 2) & 3)) * 16));
                     const int tok = it * 32 + row;
                     if (c0 + tok < T)
-                        *reinterpret_cast<uint4 *>(yb + ((size_t)tok * H * P + pt * 32 + rcc * 8) * 2) = v;
+                        store_stream16(yb + ((size_t)tok * H * P + pt * 32 + rcc * 8) * 2, v);
                 }
             }
             __syncthreads();   // B^T is complete

@@ -164,7 +164,8 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
 #pragma unroll
         for (int q = 0; q < kH0Batch; ++q) {
             const int idx = min(q * kThreads + tid, h_items - 1);
-            hreg[q] = *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4);
+            const uint4 v = load_stream16(hb + (size_t)idx * 4);   // read once: streaming hint
+            hreg[q] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
         }
     }
     load_rows(creg, Cb, c_sn, 0);
@@ -365,7 +366,9 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
                         const float xv = __uint_as_float((uint32_t)xt[(c * 8 + e) * kNP + r] << 16);
                         o[e] = (bf16_t)fmaf(D_h, xv, av[e]);
                     }
-                    *reinterpret_cast<bf16x8 *>(yb + (size_t)i * H * P + c * 8) = o;
+                    uint4 ov;
+                    __builtin_memcpy(&ov, &o, 16);
+                    store_stream16(yb + (size_t)i * H * P + c * 8, ov);
                 }
             }
         }
