@@ -54,6 +54,17 @@ def algorithmic_bytes_replay(B, N, Np, H, P, S, G, path_nodes):
     return algorithmic_bytes_tree_ssd(B, N, H, P, S, G) + extra
 
 
+def algorithmic_bytes_step(B, N, Np, H, P, S, G, W, path_nodes):
+    """The whole step in one kernel: the conv's operands (pre-conv rows read, conv output written,
+    conv state read and written, weights and bias, the previous tree's pre-conv rows on the last
+    W-1 path nodes) and the replay + scan's, whose x / B / C are the conv output and are not read
+    from memory a second time."""
+    Cc = H * P + 2 * G * S
+    conv = B * (2 * N * Cc * 2 + 2 * (W - 1) * Cc * 2) + Cc * (W + 1) * 2 + min(path_nodes, B * (W - 1)) * Cc * 2
+    xbc_reads = B * (N * H * P * 2 + 2 * N * G * S * 2)
+    return algorithmic_bytes_replay(B, N, Np, H, P, S, G, path_nodes) - xbc_reads + conv
+
+
 def algorithmic_flops_tree_ssd(B, N, H, P, S, G):
     """C B^T once per group, (L o CB^T) X and C h0^T per head, dense-masked."""
     return B * (G * 2 * N * N * S + H * (2 * N * N * P + 2 * N * S * P))
@@ -77,6 +88,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-ssd", type=int, default=0, metavar="K",
                     help="profiling aid: run K tree-scan launches and exit")
+    ap.add_argument("--only-step", type=int, default=0, metavar="K",
+                    help="profiling aid: K launches of the one-launch step kernel only, no timing, then exit")
     ap.add_argument("--only-fused", type=int, default=0, metavar="K",
                     help="profiling aid: run K fused replay + scan launches and exit")
     ap.add_argument("--prefix", action="store_true",
@@ -164,17 +177,27 @@ def main():
         conv_replay(s)
         fused(s)
 
+    def step_one(s):         # the same step as one launch
+        q = s["prev"]
+        st.stree_tree_step(q["parent"], q["accepted"], q["xbc_pre"], q["xbc"], q["dt"], s["parent"], s["xbc_pre"],
+                           s["conv_state"], conv_w, conv_b, s["dt"], A, D, s["h0"], H, P, S, G, silu=True,
+                           xbc_out=s["xbc"], conv_state_out=s["cs_out"], h_out=s["h_out"], out=s["y"], one_launch=True)
+
     for s in sets:           # first launches (also sets the kernel's LDS attribute) outside any capture
         step(s)
     for s in sets:
         step_fused(s)
+    for s in sets:
+        step_one(s)
     torch.cuda.synchronize()
 
-    if args.only_ssd or args.only_fused:
+    if args.only_ssd or args.only_fused or args.only_step:
         for k in range(args.only_ssd):
             ssd(sets[k % N_SETS])
         for k in range(args.only_fused):
             fused(sets[k % N_SETS])
+        for k in range(args.only_step):
+            step_one(sets[k % N_SETS])
         torch.cuda.synchronize()
         return
 
@@ -198,6 +221,7 @@ def main():
             run_step_fused = make_graphs(step_fused)
             run_fused = make_graphs(fused)
             run_tail = make_graphs(conv_replay)
+            run_step_one = make_graphs(step_one)
         except Exception as exc:  # pragma: no cover
             log(f"[bench] HIP graph capture failed ({exc}); falling back to direct launches")
             use_graph = False
@@ -209,6 +233,7 @@ def main():
             return run
         run_step, run_ssd, run_conv, run_commit = all_sets(step), all_sets(ssd), all_sets(conv), all_sets(commit)
         run_step_fused, run_fused, run_tail = all_sets(step_fused), all_sets(fused), all_sets(conv_replay)
+        run_step_one = all_sets(step_one)
 
     def timed(run, k, warm, per_run=N_SETS):
         """Wall-clock and HIP-event time per launch of k launches on the current stream
@@ -237,6 +262,7 @@ def main():
     ms_fstep, ms_fstep_ev = timed(run_step_fused, K, Wm)
     _, ms_fused = timed(run_fused, K, Wm)
     _, ms_tail = timed(run_tail, K, Wm)
+    ms_ostep, ms_ostep_ev = timed(run_step_one, K, Wm)
     # one buffer set only: inputs stay in the 256 MB Infinity Cache
     warm_fn = (lambda: ssd(sets[0]))
     if use_graph:
@@ -269,8 +295,14 @@ def main():
     log(f"[bench]   replay+scan: {alg_bytes_f/1e6:.2f} MB algorithmic -> {achieved_f:.0f} GB/s "
         f"({achieved_f/HBM_PEAK_GBS*100:.1f}% of 8 TB/s)")
 
-    fused_wins = ms_fstep < ms_step
-    ms_best = ms_fstep if fused_wins else ms_step
+    alg_bytes_o = algorithmic_bytes_step(B, N, N, H, P, S, G, W, path_nodes)
+    achieved_o = alg_bytes_o / (ms_ostep_ev * 1e-3) / 1e9
+    log(f"[bench] one launch: step {ms_ostep*1e3:.1f} us wall ({ms_ostep_ev*1e3:.1f} us events): "
+        f"{alg_bytes_o/1e6:.2f} MB algorithmic -> {achieved_o:.0f} GB/s ({achieved_o/HBM_PEAK_GBS*100:.1f}% of 8 TB/s)")
+
+    steps = {"separate": ms_step, "fused": ms_fstep, "one_launch": ms_ostep}
+    best = min(steps, key=steps.get)
+    ms_best = steps[best]
     roof_scan = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,false>", "achieved": achieved,
                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                  "traffic": read_traffic("tree_ssd_mfma_cfg2"),
@@ -281,6 +313,15 @@ def main():
                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_f / HBM_PEAK_GBS,
                   "traffic": read_traffic("tree_ssd_replay_cfg2"),
                   "algorithmic_bytes": alg_bytes_f, "avg_launch_us": ms_fused * 1e3}
+    roof_one = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,true,true>", "achieved": achieved_o,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_o / HBM_PEAK_GBS,
+                "traffic": read_traffic("tree_step_cfg2"),
+                "algorithmic_bytes": alg_bytes_o, "avg_launch_us": ms_ostep_ev * 1e3}
+    what = {"separate": "tree_conv + tree_ssd + commit_state",
+            "fused": "tree_conv_replay + tree_ssd_replay (the previous tree is committed inside both: conv tail "
+                     "while the conv rows are staged, state while it is loaded for the scan)",
+            "one_launch": "tree_step: one launch that convolves (the previous tree's conv tail folded in), replays "
+                          "the previous tree's accepted path on the state as it is loaded, and scans"}
     out = {
         "metric": "tree-nodes/sec per SSD layer at 1 MI355X; % of MFMA/HBM roofline",
         "value": nodes / (ms_best * 1e-3),
@@ -289,17 +330,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "cfg2: batch 16 x 64-node random trees (depth 4-8), 80 heads x headdim 64, "
-                               "dstate 128, ngroups 1, conv width 4; step = "
-                               + ("tree_conv_replay + tree_ssd_replay (the previous tree is committed inside both: "
-                                  "conv tail while the conv rows are staged, state while it is loaded for the scan)"
-                                  if fused_wins
-                                  else "tree_conv + tree_ssd + commit_state"),
-                   "sequence": "fused" if fused_wins else "separate",
+                               "dstate 128, ngroups 1, conv width 4; step = " + what[best],
+                   "sequence": best,
                    "batch": B, "nnodes": N, "hip_graph": use_graph, "buffer_sets": N_SETS},
         # the dominant kernel of the timed step
-        "roofline": roof_fused if fused_wins else roof_scan,
+        "roofline": {"separate": roof_scan, "fused": roof_fused, "one_launch": roof_one}[best],
         "roofline_tree_ssd_alone": roof_scan,
-        "steps_us": {"separate": ms_step * 1e3, "fused": ms_fstep * 1e3},
+        "steps_us": {k: v * 1e3 for k, v in steps.items()},
         "kernels_us": {"tree_conv": ms_conv * 1e3, "tree_ssd": ms_ssd * 1e3, "commit_state": ms_commit * 1e3,
                        "tree_conv_replay": ms_tail * 1e3, "tree_ssd_replay": ms_fused * 1e3},
     }

@@ -52,7 +52,8 @@ enum stree_dtype { STREE_F32 = 0, STREE_BF16 = 1 };
 
 enum stree_flags {
     STREE_FLAG_CONV_SILU = 1,    /* tree_conv applies z * sigmoid(z) */
-    STREE_FLAG_FORCE_FMA = 256   /* tree_ssd: use the plain fp32-FMA kernel even where MFMA applies */
+    STREE_FLAG_FORCE_FMA = 256,  /* tree_ssd: use the plain fp32-FMA kernel even where MFMA applies */
+    STREE_FLAG_ONE_LAUNCH = 512  /* tree_step: conv, replay and scan in a single kernel where the shape allows */
 };
 
 /* Problem sizes.  POD, host memory. */
@@ -204,6 +205,32 @@ int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, con
                            const int32_t *parent, const void *xbc_pre, const void *conv_state,
                            const void *conv_w, const void *conv_b, void *xbc_out, void *conv_state_out,
                            int32_t *tree_status, int32_t *replay_status, void *hip_stream);
+
+/*
+ * One decoding step of the layer in one launch: stree_tree_conv_replay followed by
+ * stree_tree_ssd_replay on the column ranges of its output (Sec. 3: tree conv, tree
+ * scan; Alg. 1: replay at the start of the next iteration), with the same results:
+ *   xbc_out        io [B,N,Cc]: conv output; x = columns [0, H*P), B = the next G*S,
+ *                  C = the last G*S, each with token stride Cc (the strides in dims
+ *                  are ignored)
+ *   conv_state_out io [B,W-1,Cc], must NOT alias conv_state
+ *   h_out          f32 [B,H,P,S], MAY alias h0;  y io [B,N,H,P] dense
+ *   prev           the previous tree; prev->x and prev->Bm are the x and B columns of
+ *                  the previous step's xbc_out (strides in prev), prev_xbc_pre its
+ *                  pre-conv rows [B, prev->nnodes, Cc]
+ *   tree_status, replay_status  as in stree_tree_ssd_replay
+ * By default the two entry points above run back to back on the stream (the faster
+ * route on MI355X).  With STREE_FLAG_ONE_LAUNCH the whole step is a single kernel
+ * for the shapes of a decoding step (both trees of at most 64 nodes, bf16, conv width
+ * 4, the MFMA head shapes, 16-byte aligned pointers): every workgroup then convolves
+ * the columns its own units need in front of its scan.  Same results bit for bit;
+ * other shapes ignore the flag.
+ */
+int stree_tree_step(const stree_dims *dims, const stree_replay *prev, const void *prev_xbc_pre,
+                    const int32_t *parent, const void *xbc_pre, const void *conv_state,
+                    const void *conv_w, const void *conv_b, void *xbc_out, void *conv_state_out,
+                    const float *dt, const float *A, const float *D, const float *h0, float *h_out,
+                    void *y, int32_t *tree_status, int32_t *replay_status, void *hip_stream);
 
 /*
  * Linear prefix scan: the ordinary causal Mamba2 scan of T tokens per sequence (the

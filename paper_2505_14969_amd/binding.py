@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libstree.so")
 F32, BF16 = 0, 1
 FLAG_CONV_SILU = 1
 FLAG_FORCE_FMA = 256
+FLAG_ONE_LAUNCH = 512
 MAX_NODES = 256
 
 
@@ -64,10 +65,11 @@ def load() -> C.CDLL:
         lib.stree_commit_state.argtypes = [dp] + [_VP] * 13
         lib.stree_tree_ssd_replay.argtypes = [dp, C.POINTER(StreeReplay)] + [_VP] * 13
         lib.stree_tree_conv_replay.argtypes = [dp, C.POINTER(StreeReplay)] + [_VP] * 11
+        lib.stree_tree_step.argtypes = [dp, C.POINTER(StreeReplay)] + [_VP] * 17
         lib.stree_linear_ssd.argtypes = [dp] + [_VP] * 10
         lib.stree_linear_ssd.restype = C.c_int
         for f in (lib.stree_tree_index, lib.stree_tree_conv, lib.stree_tree_ssd, lib.stree_commit_state,
-                  lib.stree_tree_ssd_replay, lib.stree_tree_conv_replay):
+                  lib.stree_tree_ssd_replay, lib.stree_tree_conv_replay, lib.stree_tree_step):
             f.restype = C.c_int
         _lib = lib
     return _lib
@@ -94,6 +96,8 @@ def _token_stride(t: torch.Tensor, nnodes: int) -> int:
     dense and whose batch stride is N * token stride."""
     assert t.dim() == 4 and t.stride(3) == 1 and t.stride(2) == t.shape[3], "inner dims must be dense"
     sn = t.stride(1)
+    if nnodes == 1 and t.shape[0] > 1:
+        sn = t.stride(0)     # (the stride torch keeps for a dimension of size 1 means nothing)
     assert t.shape[0] == 1 or t.stride(0) == nnodes * sn, "batch stride must be N * token stride"
     return sn
 
@@ -239,6 +243,48 @@ def stree_tree_conv_replay(prev_parent, prev_accepted, prev_xbc_pre, parent, xbc
                                          _ptr(conv_state_out), _ptr(status), _ptr(replay_status), _stream()),
            "stree_tree_conv_replay")
     return out, conv_state_out
+
+
+def stree_tree_step(prev_parent, prev_accepted, prev_xbc_pre, prev_xbc_out, prev_dt, parent, xbc_pre, conv_state,
+                    conv_w, conv_b, dt, A, D, h0, nheads, headdim, dstate, ngroups, silu: bool = True,
+                    xbc_out: Optional[torch.Tensor] = None, conv_state_out: Optional[torch.Tensor] = None,
+                    h_out: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                    status: Optional[torch.Tensor] = None, replay_status: Optional[torch.Tensor] = None,
+                    force_fma: bool = False, one_launch: bool = False):
+    """One decoding step in one call: tree conv (seeded by the conv state after the previous tree's
+    accepted path), state replay along that path and tree scan.  prev_xbc_out is the previous step's
+    conv output [B,Np,Cc] (its x and B columns are replayed).  one_launch: a single kernel where
+    the shape allows (same results; slower than the default two kernels on MI355X).
+    -> (y [B,N,H,P], h_out [B,H,P,S] f32, xbc_out [B,N,Cc], conv_state_out [B,W-1,Cc])."""
+    B, N, Cc = xbc_pre.shape
+    W = conv_w.shape[1]
+    Np = prev_xbc_pre.shape[1]
+    H, P, S, G = nheads, headdim, dstate, ngroups
+    assert Cc == H * P + 2 * G * S and prev_xbc_pre.shape == (B, Np, Cc) and prev_xbc_out.shape == (B, Np, Cc)
+    for t_ in (xbc_pre, conv_state, conv_w, prev_xbc_pre, prev_xbc_out, prev_dt, dt, h0):
+        assert t_.is_contiguous()
+    assert dt.dtype == torch.float32 and prev_dt.dtype == torch.float32 and prev_dt.shape == (B, Np, H)
+    if xbc_out is None:
+        xbc_out = torch.empty_like(xbc_pre)
+    if conv_state_out is None:
+        conv_state_out = torch.empty_like(conv_state)
+    if h_out is None:
+        h_out = torch.empty_like(h0)
+    if out is None:
+        out = torch.empty((B, N, H, P), dtype=xbc_pre.dtype, device=xbc_pre.device)
+    assert xbc_out.is_contiguous() and out.is_contiguous() and h_out.is_contiguous()
+    assert conv_state_out.data_ptr() != conv_state.data_ptr()
+    flags = ((FLAG_CONV_SILU if silu else 0) | (FLAG_FORCE_FMA if force_fma else 0) |
+             (FLAG_ONE_LAUNCH if one_launch else 0))
+    d = make_dims(B, N, H, P, S, G, W, _io_code(xbc_pre), flags)
+    prev_B = prev_xbc_out[:, :, H * P:H * P + G * S]
+    r = StreeReplay(Np, 0, prev_parent.data_ptr(), prev_accepted.data_ptr(), prev_xbc_out.data_ptr(),
+                    prev_dt.data_ptr(), prev_B.data_ptr(), Cc, Cc)
+    _check(load().stree_tree_step(C.byref(d), C.byref(r), _ptr(prev_xbc_pre), _ptr(parent), _ptr(xbc_pre),
+                                  _ptr(conv_state), _ptr(conv_w), _ptr(conv_b), _ptr(xbc_out), _ptr(conv_state_out),
+                                  _ptr(dt), _ptr(A), _ptr(D), _ptr(h0), _ptr(h_out), _ptr(out), _ptr(status),
+                                  _ptr(replay_status), _stream()), "stree_tree_step")
+    return out, h_out, xbc_out, conv_state_out
 
 
 def stree_linear_ssd(x, dt, A, Bm, Cm=None, D=None, h0=None, want_y: bool = True,

@@ -168,6 +168,48 @@ int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, con
                                                      (hipStream_t)hip_stream));
 }
 
+int stree_tree_step(const stree_dims *dims, const stree_replay *prev, const void *prev_xbc_pre,
+                    const int32_t *parent, const void *xbc_pre, const void *conv_state, const void *conv_w,
+                    const void *conv_b, void *xbc_out, void *conv_state_out, const float *dt, const float *A,
+                    const float *D, const float *h0, float *h_out, void *y, int32_t *tree_status,
+                    int32_t *replay_status, void *hip_stream) {
+    int rc = check_dims(dims, kConvChannels);
+    if (rc) return rc;
+    if (!prev || !prev->parent || !prev->accepted || !prev->x || !prev->dt || !prev->Bm || !prev_xbc_pre)
+        return STREE_ERR_NULL_ARG;
+    if (!parent || !xbc_pre || !conv_state || !conv_w || !xbc_out || !conv_state_out) return STREE_ERR_NULL_ARG;
+    if (!dt || !A || !h0 || !h_out || !y) return STREE_ERR_NULL_ARG;
+    if (prev->nnodes < 1 || prev->nnodes > STREE_MAX_NODES || dims->dstate % 4 != 0) return STREE_ERR_BAD_SHAPE;
+    // x, B, C of the scan: column ranges of the conv output
+    stree_dims d = *dims;
+    const int64_t Cc = (int64_t)d.nheads * d.headdim + 2 * (int64_t)d.ngroups * d.dstate;
+    d.x_stride_n = d.b_stride_n = d.c_stride_n = Cc;
+    stree_dims dp = *dims;
+    dp.nnodes = prev->nnodes;
+    dp.x_stride_n = prev->x_stride_n;
+    dp.b_stride_n = prev->b_stride_n;
+    dp.c_stride_n = 0;
+    rc = resolve_strides(dp);
+    if (rc) return rc;
+    if (d.batch == 0) return STREE_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if ((d.flags & STREE_FLAG_ONE_LAUNCH) && !(d.flags & STREE_FLAG_FORCE_FMA) &&
+        stree::tree_step_fused_supported(d, dp, prev->x, prev->Bm, xbc_pre, prev_xbc_pre, conv_state, conv_w, conv_b,
+                                         xbc_out, conv_state_out, y))
+        return hip_status(stree::launch_tree_step_fused(d, dp, prev->parent, prev->accepted, prev->x, prev->dt,
+                                                        prev->Bm, prev_xbc_pre, parent, xbc_pre, conv_state, conv_w,
+                                                        conv_b, xbc_out, conv_state_out, dt, A, D, h0, h_out, y,
+                                                        tree_status, replay_status, st));
+    rc = stree_tree_conv_replay(dims, prev, prev_xbc_pre, parent, xbc_pre, conv_state, conv_w, conv_b, xbc_out,
+                                conv_state_out, tree_status, replay_status, hip_stream);
+    if (rc) return rc;
+    const size_t e = d.io_dtype == STREE_BF16 ? 2 : 4;
+    const char *xo = static_cast<const char *>(xbc_out);
+    return stree_tree_ssd_replay(&d, prev, parent, xo, dt, A, xo + (size_t)d.nheads * d.headdim * e,
+                                 xo + ((size_t)d.nheads * d.headdim + (size_t)d.ngroups * d.dstate) * e, D, h0, h_out,
+                                 y, tree_status, replay_status, hip_stream);
+}
+
 int stree_linear_ssd(const stree_dims *dims, const void *x, const float *dt, const float *A, const void *Bm,
                      const void *Cm, const float *D, const float *h0, void *y, float *h_out, void *hip_stream) {
     if (!dims) return STREE_ERR_NULL_ARG;

@@ -1,0 +1,181 @@
+"""GPU parity of the decoding step entry point (tree conv seeded by the conv state after the
+previous tree's accepted path, state replay along that path, tree scan), in both of its routes:
+the default (two kernels) and the single kernel (one_launch).
+
+Two kinds of check: against the two entry points it stands for, called back to back on the same
+inputs (every output bit for bit: the arithmetic is the same, only the launches differ), and
+against the oracle, composed as commit -> tree conv -> path-unrolled scan."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_14969_amd import synth
+from helpers import TOL, assert_parity, split_xbc, to_dev, to_host
+from test_gpu_parity import _trees, st  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(seed, B, Np, N, H, P, S, G, W=4):
+    rng = np.random.default_rng(seed)
+    Cc = H * P + 2 * G * S
+    r = synth.round_to_bf16
+    d = dict(
+        pxbc_pre=r(rng.standard_normal((B, Np, Cc)).astype(np.float32)),
+        xbc_pre=r(rng.standard_normal((B, N, Cc)).astype(np.float32)),
+        conv_state=r(rng.standard_normal((B, W - 1, Cc)).astype(np.float32)),
+        conv_w=r((rng.standard_normal((Cc, W)) * 0.5).astype(np.float32)),
+        conv_b=r((rng.standard_normal(Cc) * 0.1).astype(np.float32)),
+        pdt=np.logaddexp(0, rng.standard_normal((B, Np, H)) - 2).astype(np.float32),
+        dt=np.logaddexp(0, rng.standard_normal((B, N, H)) - 2).astype(np.float32),
+        A=(-np.exp(rng.uniform(0, 2, H))).astype(np.float32),
+        D=rng.standard_normal(H).astype(np.float32),
+        h0=(0.1 * rng.standard_normal((B, H, P, S))).astype(np.float32),
+        pparent=_trees(seed + 1, B, Np), parent=_trees(seed + 2, B, N),
+    )
+    depth = np.stack([synth.tree_depths(d["pparent"][b]) for b in range(B)])
+    d["acc"] = np.array([int(rng.integers(-1, Np)) for _ in range(B)], dtype=np.int32)
+    d["depth"] = depth
+    return d
+
+
+def _prev_conv_out(st, d, H, P, S, G, silu=True):
+    """The previous step's conv output (whatever conv state it started from: here zeros)."""
+    zero = torch.zeros_like(to_dev(d["conv_state"], "bf16"))
+    return st.stree_tree_conv(to_dev(d["pparent"]), to_dev(d["pxbc_pre"], "bf16"), zero, to_dev(d["conv_w"], "bf16"),
+                              to_dev(d["conv_b"], "bf16"), H, P, S, G, silu=silu)
+
+
+def _two_calls(st, d, pout, H, P, S, G, silu=True, bias=True):
+    B = d["parent"].shape[0]
+    stt = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    rst = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    cb = to_dev(d["conv_b"], "bf16") if bias else None
+    xbc, cs = st.stree_tree_conv_replay(to_dev(d["pparent"]), to_dev(d["acc"]), to_dev(d["pxbc_pre"], "bf16"),
+                                        to_dev(d["parent"]), to_dev(d["xbc_pre"], "bf16"),
+                                        to_dev(d["conv_state"], "bf16"), to_dev(d["conv_w"], "bf16"), cb, H, P, S, G,
+                                        silu=silu)
+    x = xbc[:, :, :H * P].unflatten(2, (H, P))
+    Bm = xbc[:, :, H * P:H * P + G * S].unflatten(2, (G, S))
+    Cm = xbc[:, :, H * P + G * S:].unflatten(2, (G, S))
+    px = pout[:, :, :H * P].unflatten(2, (H, P))
+    pB = pout[:, :, H * P:H * P + G * S].unflatten(2, (G, S))
+    y, h = st.stree_tree_ssd_replay(to_dev(d["pparent"]), to_dev(d["acc"]), px, to_dev(d["pdt"]), pB,
+                                    to_dev(d["parent"]), x, to_dev(d["dt"]), to_dev(d["A"]), Bm, Cm, to_dev(d["D"]),
+                                    to_dev(d["h0"]), status=stt, replay_status=rst)
+    return y, h, xbc, cs, stt, rst
+
+
+def _one_call(st, d, pout, H, P, S, G, silu=True, bias=True, one_launch=True, **kw):
+    B = d["parent"].shape[0]
+    stt = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    rst = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    cb = to_dev(d["conv_b"], "bf16") if bias else None
+    y, h, xbc, cs = st.stree_tree_step(to_dev(d["pparent"]), to_dev(d["acc"]), to_dev(d["pxbc_pre"], "bf16"), pout,
+                                       to_dev(d["pdt"]), to_dev(d["parent"]), to_dev(d["xbc_pre"], "bf16"),
+                                       to_dev(d["conv_state"], "bf16"), to_dev(d["conv_w"], "bf16"), cb,
+                                       to_dev(d["dt"]), to_dev(d["A"]), to_dev(d["D"]), to_dev(d["h0"]), H, P, S, G,
+                                       silu=silu, status=stt, replay_status=rst, one_launch=one_launch, **kw)
+    return y, h, xbc, cs, stt, rst
+
+
+def _same(a, b, what):
+    names = ("y", "h_out", "xbc_out", "conv_state_out", "tree_status", "replay_status")
+    for nm, u, v in zip(names, a, b):
+        uh, vh = u.cpu(), v.cpu()
+        if uh.dtype == torch.bfloat16:
+            uh, vh = uh.view(torch.int16), vh.view(torch.int16)
+        assert torch.equal(uh, vh), f"{what}: {nm} differs from the two-call sequence"
+
+
+# shapes of the single-launch kernel: several units per workgroup run, runs that cross a sequence
+# or a group boundary, ragged node counts, previous tree of another size
+STEP_SHAPES = [(3, 64, 64, 5, 64, 128, 1), (2, 37, 50, 4, 64, 128, 2), (4, 1, 13, 3, 64, 64, 1),
+               (2, 64, 1, 2, 128, 128, 1), (20, 20, 64, 80, 64, 128, 1), (3, 64, 64, 6, 64, 128, 3)]
+
+
+@pytest.mark.parametrize("B,Np,N,H,P,S,G", STEP_SHAPES)
+def test_step_equals_the_two_entry_points(st, B, Np, N, H, P, S, G):
+    d = _inputs(500 + N + H, B, Np, N, H, P, S, G)
+    pout = _prev_conv_out(st, d, H, P, S, G)
+    ref = _two_calls(st, d, pout, H, P, S, G)
+    _same(_one_call(st, d, pout, H, P, S, G), ref, f"step, one launch, B={B} N={N} H={H}")
+    _same(_one_call(st, d, pout, H, P, S, G, one_launch=False), ref, f"step, default route, B={B} N={N} H={H}")
+
+
+def test_step_options_and_degenerate_paths(st):
+    B, Np, N, H, P, S, G = 4, 40, 64, 4, 64, 128, 1
+    d = _inputs(77, B, Np, N, H, P, S, G)
+    d["acc"][:] = [-1, 0, int(d["depth"][2].argmax()), Np - 1]       # nothing, root only, deepest, last node
+    pout = _prev_conv_out(st, d, H, P, S, G)
+    for silu, bias in ((True, True), (False, True), (True, False)):
+        _same(_one_call(st, d, pout, H, P, S, G, silu, bias), _two_calls(st, d, pout, H, P, S, G, silu, bias),
+              f"step silu={silu} bias={bias}")
+
+
+def test_step_bad_trees_and_bad_accepted(st):
+    B, Np, N, H, P, S, G = 4, 30, 48, 3, 64, 128, 1
+    d = _inputs(91, B, Np, N, H, P, S, G)
+    d["parent"][1, 20] = 33          # this tree invalid in sequence 1: zero rows, status 21
+    d["pparent"][2, 7] = 9           # previous tree invalid in sequence 2: nothing replayed
+    d["acc"][3] = Np + 5             # accepted index out of range: nothing replayed
+    pout = _prev_conv_out(st, d, H, P, S, G)
+    one, two = _one_call(st, d, pout, H, P, S, G), _two_calls(st, d, pout, H, P, S, G)
+    _same(one, two, "step with invalid inputs")
+    assert list(to_host(one[4])) == [0, 21, 0, 0]
+    assert list(to_host(one[5])) == [0, 0, 8, -1]
+    assert not to_host(one[0])[1].any()
+
+
+def test_step_other_shapes_take_the_two_kernel_route(st):
+    # conv width 3 and a head shape outside the single-launch kernel: same entry point, same results
+    for (B, Np, N, H, P, S, G, W) in ((2, 20, 30, 3, 64, 128, 1, 3), (2, 20, 70, 2, 32, 16, 1, 4)):
+        d = _inputs(33 + W, B, Np, N, H, P, S, G, W)
+        pout = _prev_conv_out(st, d, H, P, S, G)
+        _same(_one_call(st, d, pout, H, P, S, G), _two_calls(st, d, pout, H, P, S, G), f"step fallback W={W} P={P}")
+
+
+def test_step_in_place_state(st):
+    B, Np, N, H, P, S, G = 2, 64, 64, 4, 64, 128, 1
+    d = _inputs(5, B, Np, N, H, P, S, G)
+    pout = _prev_conv_out(st, d, H, P, S, G)
+    ref = _two_calls(st, d, pout, H, P, S, G)
+    h_io = to_dev(d["h0"])
+    stt = torch.zeros(B, dtype=torch.int32, device="cuda")
+    y, h, _, _ = st.stree_tree_step(to_dev(d["pparent"]), to_dev(d["acc"]), to_dev(d["pxbc_pre"], "bf16"), pout,
+                                    to_dev(d["pdt"]), to_dev(d["parent"]), to_dev(d["xbc_pre"], "bf16"),
+                                    to_dev(d["conv_state"], "bf16"), to_dev(d["conv_w"], "bf16"),
+                                    to_dev(d["conv_b"], "bf16"), to_dev(d["dt"]), to_dev(d["A"]), to_dev(d["D"]), h_io,
+                                    H, P, S, G, h_out=h_io, status=stt, one_launch=True)
+    assert h.data_ptr() == h_io.data_ptr()
+    assert torch.equal(h.cpu(), ref[1].cpu()) and torch.equal(y.cpu().view(torch.int16), ref[0].cpu().view(torch.int16))
+
+
+def test_step_against_the_oracle_full_size(st, oracle):
+    """cfg2 at full size, the launch configuration the benchmark times: the previous iteration is
+    the same workload rolled by one along the batch."""
+    wl = synth.config(2)
+    H, P, S, G = wl.nheads, wl.headdim, wl.dstate, wl.ngroups
+    io = wl.io_dtype
+    roll = lambda a: np.roll(a, 1, axis=0)
+    pparent, pacc, pxbc_pre, pdt = roll(wl.parent), roll(wl.accepted), roll(wl.xbc_pre), roll(wl.dt)
+    pconv = oracle.tree_conv(pparent, pxbc_pre, roll(wl.conv_state), wl.conv_w, wl.conv_b, True)
+    pxbc = synth.round_to_bf16(pconv.astype(np.float32))
+    px, pB, _ = split_xbc(pxbc, H, P, G, S)
+    h0 = wl.h0.astype(np.float64)
+    want_h, want_cs = oracle.commit(pparent, pacc, px, pdt, wl.A, pB, h0, pxbc_pre, wl.conv_state)
+    want_cs = want_cs.astype(np.float32)
+    want_conv = oracle.tree_conv(wl.parent, wl.xbc_pre, want_cs, wl.conv_w, wl.conv_b, True)
+    y, h, xbc, cs = st.stree_tree_step(to_dev(pparent), to_dev(pacc), to_dev(pxbc_pre, io), to_dev(pxbc, io),
+                                       to_dev(pdt), to_dev(wl.parent), to_dev(wl.xbc_pre, io),
+                                       to_dev(wl.conv_state, io), to_dev(wl.conv_w, io), to_dev(wl.conv_b, io),
+                                       to_dev(wl.dt), to_dev(wl.A), to_dev(wl.D), to_dev(wl.h0), H, P, S, G,
+                                       one_launch=True)
+    assert np.array_equal(to_host(cs), want_cs)
+    got_conv = to_host(xbc)
+    assert_parity(got_conv, want_conv, 4e-3, "step: conv output")
+    assert_parity(to_host(h), want_h, 1e-4, "step: replayed state")
+    # the scan is checked on the inputs it actually saw (the GPU's own rounded conv output)
+    x, Bm, Cm = split_xbc(got_conv.astype(np.float32), H, P, G, S)
+    want_y = oracle.ssd_paths(wl.parent, x, wl.dt, wl.A, Bm, Cm, wl.D, want_h)
+    assert_parity(to_host(y), want_y, TOL[io], "step: y")
