@@ -30,16 +30,6 @@
 #include "common.hpp"
 #include "launch.hpp"
 
-#ifndef STREE_PHASE_CLOCK
-#define STREE_PHASE_CLOCK(k)
-#endif
-#ifndef STREE_PHASE_CLOCK_G
-#define STREE_PHASE_CLOCK_G(k)
-#endif
-#ifndef STREE_PHASE_ENTRY
-#define STREE_PHASE_ENTRY(u)
-#define STREE_PHASE_PRO(slot, t)
-#endif
 #ifndef STREE_EXIT_POINT
 #define STREE_EXIT_INIT
 #define STREE_EXIT_POINT(n)
@@ -831,8 +821,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     if (nU <= 0) return;
     STREE_EXIT_INIT;
     STREE_EXIT_POINT(1);
-    STREE_PHASE_PRO(23, 0);
-    STREE_PHASE_ENTRY(u0);
     // (b, h) of the current unit and of the next three.  The loop starts one unit early (k = -1):
     // that pass has no unit to compute and only runs the staging half, which brings unit 0 into
     // LDS and issues the loads of units 1 and 2 -- the same code as in the steady state, so the
@@ -847,14 +835,12 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         if constexpr (!CV) {
             if (h0) load_H(b1, h1);
         }
-        STREE_PHASE_PRO(16, 0);
     } else {
         if constexpr (!CV) load_X(b1, h1);
         if (wave == kTreeWave) {
             load_T(b1, h1);
             if constexpr (RP) load_R(b1, h1);
         }
-        STREE_PHASE_PRO(18, 256);
     }
     STREE_EXIT_POINT(2);
     if constexpr (CV) {
@@ -871,13 +857,11 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
 
     for (int k = -1; k < nU; ++k) {
-        [[maybe_unused]] const int prof_unit = cb * H + ch;  // only read by probe builds
         const bool live = k >= 0;                             // false in the staging-only first pass
         int bad = 0;
         float D_h = 0.f;
         if (live) {
             __syncthreads();                                  // barrier 1: unit k is staged
-            STREE_PHASE_CLOCK(0);
             bad = *sBad;
             D_h = *sDh;
             if (status && ch == 0 && tid == 0) status[cb] = bad;
@@ -919,12 +903,10 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
 #pragma unroll
                     for (int rg = 0; rg < 16; ++rg) acc[q][rg] *= e;
             }
-            STREE_PHASE_CLOCK(1);
         } else if (wave != kTreeWave && !bad) {
             // ---- phase 2: Gt = B C^T (only when the C/B tiles are new), mask and decay -> M ----------
             const int jt = (wave - 4) >> 1;
             const int lnp = opaque(lane), l32 = lnp & 31, lh = lnp >> 5, il = it * 32 + l32;   // re-derived per phase
-            STREE_PHASE_CLOCK_G(9);
             floatx16 &gt = acc[0];
             if (fresh_at(k, ch)) {
 #pragma unroll
@@ -944,7 +926,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                         gt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], cf[j], gt, 0, 0, 0);
                 }
             }
-            STREE_PHASE_CLOCK_G(10);
             const float s2_i = sS2[il];
             const uint32_t mrow = sMask[il * 2 + jt] >> (4 * lh);   // bit 8*rg + e <-> j = jl + e
             float4 uj[4];
@@ -964,12 +945,10 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 }
                 *reinterpret_cast<bf16x4 *>(&sM[il * kNP64 + jl]) = o;
             }
-            STREE_PHASE_CLOCK_G(11);
         }
         if (live) STREE_EXIT_POINT(11 + 10 * k);
         if (live) __syncthreads();                            // barrier 2: M is ready; h0b, C and the tree arrays are dead
         if (live) STREE_EXIT_POINT(12 + 10 * k);
-        STREE_PHASE_CLOCK(2);
 
         const bool more = k + 1 < nU, more2 = k + 2 < nU, more3 = k + 3 < nU;
         const bool y_stages = (k & 1) != 0;    // unit k+1 is even: its h0 sits in the Y threads
@@ -1032,7 +1011,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                     yreg[q][rg] = o;
                 }
             }
-            STREE_PHASE_CLOCK(3);
             if (live) STREE_EXIT_POINT(13 + 10 * k);
             // first pass: the Y threads have nothing to scan and stage the first C / B tiles (later
             // tiles come from the G threads, after barrier (a))
@@ -1042,12 +1020,10 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             if (more) {
                 if (h0) {
                     if (y_stages) stage_H(rbuf, b1, h1);
-                    if (!live) STREE_PHASE_PRO(17, 0);
                 } else if (rt == 0) {
                     *sDh = D ? D[h1] : 0.f;
                 }
             }
-            STREE_PHASE_CLOCK(4);
             // y leaves as 64-byte row pieces: the accumulators give a lane 4 consecutive p of one
             // node, which as direct stores would be 16-byte pieces of 32 different lines per
             // instruction.  Each wave therefore turns its 32x32 tile around in a private 2 KB of LDS
@@ -1087,7 +1063,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             // later, the state of the last unit of a short run is the last thing to arrive.
             if (h0 && more3 && y_stages && live) load_H(b3, h3);
             if (h0 && more2 && k == 0) load_H(b2, h2);
-            STREE_PHASE_CLOCK(5);
             if (late_tiles) __syncthreads();                  // barrier (a): scratch use of the B tile is over
         } else if (more) {
             if constexpr (RP) {
@@ -1110,12 +1085,10 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
             if (wave == kTreeWave) {
                 stage_T(h1);
-                if (!live) STREE_PHASE_PRO(20, 384);
                 if (!live) STREE_MARK_POINT(41, 384);
                 if (live) STREE_MARK_POINT(51 + 10 * k, 384);
             }
             stage_X((k + 1) & 1);                          // the other X^T tile: unit k still reads its own
-            if (!live) STREE_PHASE_PRO(21, 256);
             if (!live) STREE_MARK_POINT(42, 256);
             if (live) STREE_MARK_POINT(52 + 10 * k, 256);
             if (live) STREE_MARK_POINT(55 + 10 * k, 384);
@@ -1133,7 +1106,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 if (more3) load_H(b3, h3);
             }
             if (more2 && !live && h0) load_H(b2, h2);      // unit 1: the first odd unit
-            if (!live) STREE_PHASE_PRO(22, 256);
             if (!live) STREE_MARK_POINT(43, 256);
             if (!live) STREE_MARK_POINT(44, 384);
             if (live) STREE_MARK_POINT(53 + 10 * k, 256);
@@ -1143,8 +1115,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 restage_CB(b1, h1);
             }
         }
-        STREE_PHASE_CLOCK(6);
-        STREE_PHASE_CLOCK(7);
         STREE_EXIT_POINT(4 + k);
         cb = b1; ch = h1;
         b1 = b2; h1 = h2;
