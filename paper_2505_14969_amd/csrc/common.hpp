@@ -145,6 +145,34 @@ __device__ __forceinline__ void store_stream16(void *p, uint4 v) {
     __builtin_nontemporal_store(vv, reinterpret_cast<u32x4 *>(p));
 }
 
+// Four-tap conv of 8 bf16 channels on the packed dot unit (v_dot2c_f32_bf16: d += a.lo b.lo + a.hi b.hi):
+//   a[e] += w[e][3] r0[e] + w[e][2] r1[e] + w[e][1] r2[e] + w[e][0] r3[e]
+// r0 = the node's own row, r1..r3 its first three ancestors (8 bf16 each); ww = the 32 weights as 16
+// dwords, bf16 number e * 4 + j = w[e][j].  Per channel two byte permutes pair the rows' values with
+// the weight pairs as they lie in memory, instead of eight conversions and four FMAs.
+__device__ __forceinline__ void conv4_bf16_dot(float (&a)[8], const uint4 &r0, const uint4 &r1, const uint4 &r2,
+                                               const uint4 &r3, const uint32_t (&ww)[16]) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const uint32_t q0[4] = {r0.x, r0.y, r0.z, r0.w}, q1[4] = {r1.x, r1.y, r1.z, r1.w};
+    const uint32_t q2[4] = {r2.x, r2.y, r2.z, r2.w}, q3[4] = {r3.x, r3.y, r3.z, r3.w};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+#pragma unroll
+        for (int hi = 0; hi < 2; ++hi) {
+            const int e = 2 * d + hi;
+            const uint32_t sel = hi ? 0x07060302u : 0x05040100u;     // (lo, hi) = (second row, first row)[channel e]
+            const uint32_t x10 = __builtin_amdgcn_perm(q0[d], q1[d], sel);   // pairs with (w[e][2], w[e][3])
+            const uint32_t x32 = __builtin_amdgcn_perm(q2[d], q3[d], sel);   // pairs with (w[e][0], w[e][1])
+            float acc = a[e];
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, ww[2 * e + 1]),
+                                                  __builtin_bit_cast(bf16x2_t, x10), acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, ww[2 * e]),
+                                                  __builtin_bit_cast(bf16x2_t, x32), acc, false);
+            a[e] = acc;
+        }
+    }
+}
+
 // Cross-lane read within a wave of 64: value `v` of lane `src` (0..63).  Unlike __shfl this
 // needs no lane id of the caller, so nothing lane-derived stays live around it.
 __device__ __forceinline__ int wave_read(int v, int src) { return __builtin_amdgcn_ds_bpermute(src << 2, v); }

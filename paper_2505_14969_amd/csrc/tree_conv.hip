@@ -190,8 +190,9 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = bv[e];
         int node = i, above = 0;
+        uint4 rk[W];                    // row of the k-th ancestor, or of the rows over the root
 #pragma unroll
-        for (int k = 0; k < W; ++k) {   // k-th ancestor, or `above` rows over the root
+        for (int k = 0; k < W; ++k) {
             int row;
             if (node >= 0) {
                 row = node;
@@ -200,10 +201,20 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
                 ++above;
                 row = n + above - 1;
             }
-            float r[VEC];
-            Vec16<T>::unpack(rows[row * kConvVecs + v], r);
+            rk[k] = rows[row * kConvVecs + v];
+        }
+        if constexpr (W == 4 && VEC == 8) {
+            const uint32_t ww[16] = {wq[0].x, wq[0].y, wq[0].z, wq[0].w, wq[1].x, wq[1].y, wq[1].z, wq[1].w,
+                                     wq[2].x, wq[2].y, wq[2].z, wq[2].w, wq[3].x, wq[3].y, wq[3].z, wq[3].w};
+            conv4_bf16_dot(acc, rk[0], rk[1], rk[2], rk[3], ww);
+        } else {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] = fmaf((&wv[0][0])[e * W + (W - 1 - k)], r[e], acc[e]);
+            for (int k = 0; k < W; ++k) {
+                float r[VEC];
+                Vec16<T>::unpack(rk[k], r);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] = fmaf((&wv[0][0])[e * W + (W - 1 - k)], r[e], acc[e]);
+            }
         }
         if (silu) {
 #pragma unroll

@@ -334,9 +334,10 @@ __device__ __noinline__ void conv_prologue_worker(
 #pragma unroll
             for (int e = 0; e < 8; ++e) a[e] = bv[e];
             int node = row_i < n ? row_i : -1, above = 0;
+            uint4 rk[kCW];                                          // row of the kk-th ancestor, or of the rows over the root
 #pragma unroll
-            for (int kk = 0; kk < kCW; ++kk) {                  // kk-th ancestor, or `above` rows over the root
-                const int up = wave_read(bt.pv, max(node, 0));   // (every lane takes part in the cross-lane read)
+            for (int kk = 0; kk < kCW; ++kk) {
+                const int up = wave_read(bt.pv, max(node, 0));       // (every lane takes part in the cross-lane read)
                 int row;
                 if (node >= 0) {
                     row = node;
@@ -345,16 +346,9 @@ __device__ __noinline__ void conv_prologue_worker(
                     row = kB64 + above;
                     ++above;
                 }
-                const uint4 q = lds_ld(&buf[row * 8 + v]);
-                const float xr[8] = {bf16_lo(q.x), bf16_hi(q.x), bf16_lo(q.y), bf16_hi(q.y),
-                                     bf16_lo(q.z), bf16_hi(q.z), bf16_lo(q.w), bf16_hi(q.w)};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int f = e * kCW + (kCW - 1 - kk);
-                    const float wgt = (f & 1) ? bf16_hi(ww[f >> 1]) : bf16_lo(ww[f >> 1]);
-                    a[e] = fmaf(wgt, xr[e], a[e]);
-                }
+                rk[kk] = lds_ld(&buf[row * 8 + v]);
             }
+            conv4_bf16_dot(a, rk[0], rk[1], rk[2], rk[3], ww);      // (the same arithmetic as the conv kernel's)
             if (V.silu) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a[e] = a[e] * __builtin_amdgcn_rcpf(1.f + __expf(-a[e]));
