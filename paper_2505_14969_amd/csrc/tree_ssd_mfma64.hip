@@ -21,12 +21,18 @@
 //     Y: phase 1  Yt = h0b C^T, *= exp(s_i)
 //     G: phase 2  (Gt = B C^T if the tiles are new) M = L ? Gt exp(s_i - s_j) dt_j : 0 -> LDS
 //   barrier 2   (h0b tile and the tree arrays are dead from here on)
-//     Y: phase 3  Yt += Xt M^T; y = Yt + D x -> bf16, stored straight from the accumulators
+//     Y: phase 3  Yt += Xt M^T; y = Yt + D x -> bf16, turned around per wave in LDS, stored as row pieces
 //     Y or G (whoever carries unit k+1): h0(k+1) regs -> LDS as bf16; issue h0(k+3) loads
 //     G: new C tile if unit k+1 starts another sequence or group
 //     T: tree index of unit k+1, issue parent/dt (k+2) loads
 //     G: x(k+1) regs -> the other X^T tile in LDS, issue x(k+2) loads
 // so the big global loads (h0, x) are in flight for a whole unit period.
+//
+// Template flags: RP folds the commit of the previous tree into the state as it is loaded
+// (Alg. 1: replay at the start of the next iteration); CV also puts the tree conv of the
+// workgroup's own columns in front of the unit loop (the whole step in one launch).
+// Probe builds (timing harnesses outside the library) define the STREE_EXIT_* / STREE_MARK_*
+// hooks; in the library they compile to nothing.
 #include "common.hpp"
 #include "launch.hpp"
 
