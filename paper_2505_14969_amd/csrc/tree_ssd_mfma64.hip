@@ -401,10 +401,11 @@ __device__ __noinline__ void conv_prologue_worker(
 // accepted path of the previous tree,
 //   h* = exp(s_k) h0 + sum_{j on path(k)} dt_j exp(s_k - s_j) x_j (outer) B_j,
 // in the fp32 registers it arrives in, written back once to h_out, and only then rounded to the
-// bf16 MFMA operand.  The tree wave works the path out one unit ahead (same pointer doubling as
-// the tree index, on the previous tree), fetches the x / B rows of its first kRC nodes and puts
-// them into LDS at the start of the staging half; one more barrier per unit (c) separates that
-// from the FMAs of the threads that carry the unit.  Longer paths read the remaining rows from
+// bf16 MFMA operand.  The tree wave works the path of the next unit out in the scan half, in which
+// it has nothing else to do (same pointer doubling as the tree index, on the previous tree), and
+// asks for the x / B rows of its first kRC nodes; they are in flight until the staging half,
+// where it puts them into LDS; one more barrier per unit (c) separates that from the FMAs of the
+// threads that carry the unit.  Longer paths read the remaining rows from
 // global memory.  Each thread owns one 4-wide piece of the state index and NH consecutive rows.
 //
 // CV (with RP) = the whole step in one launch: before the unit loop every workgroup convolves,
@@ -729,22 +730,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             tw[12] = __int_as_float(pos); tw[13] = cf; tw[14] = __int_as_float(len); tw[15] = dc;
         }
     };
-    // a use of the registers the row loads of path_R land in: the loads are complete after it
-    auto park_R = [&](floatx16 &tw) {
-        if constexpr (WPE >= 4) {
-#pragma unroll
-            for (int i = 0; i < 4 + 4 * NBG; ++i) {
-                float t = tw[i];
-                asm volatile("" : "+v"(t));
-                tw[i] = t;
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < NXG; ++i) asm volatile("" : "+v"(gxw[i].x), "+v"(gxw[i].y), "+v"(gxw[i].z), "+v"(gxw[i].w));
-#pragma unroll
-            for (int i = 0; i < NBG; ++i) asm volatile("" : "+v"(gbw[i].x), "+v"(gbw[i].y), "+v"(gbw[i].z), "+v"(gbw[i].w));
-        }
-    };
     auto write_R = [&](const floatx16 &tw, char *rbuf) {
         const int ln = opaque(lane);
         uint4 gx[NXG], gb[NBG];
@@ -945,6 +930,14 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 }
                 *reinterpret_cast<bf16x4 *>(&sM[il * kNP64 + jl]) = o;
             }
+        } else if (RP && wave == kTreeWave) {
+            // ---- replay: path of unit k+1 on the previous tree and the loads of its x / B rows, in the
+            //      half in which this wave has nothing else to do; they are written to LDS at the start
+            //      of the staging half.  Then the parent / dt loads for the path of unit k+2.
+            if (k + 1 < nU) {
+                path_R(acc[0], b1, h1);
+                if (k + 2 < nU) load_R(b2, h2);
+            }
         }
         if (live) STREE_EXIT_POINT(11 + 10 * k);
         if (live) __syncthreads();                            // barrier 2: M is ready; h0b, C and the tree arrays are dead
@@ -1071,17 +1064,9 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                         path_R(acc[0], b1, h1);
                         if (more2) load_R(b2, h2);
                     }
-                    write_R(acc[0], rbuf);
+                    write_R(acc[0], rbuf);                 // (waits for the row loads issued in the scan half)
                 }
                 __syncthreads();                           // barrier (c)
-                // path of unit k+2, its rows into registers; the loads fly during the tree index
-                // and the X^T staging and are waited for (park_R) before the loop goes round: a
-                // load left pending into registers that other waves use as accumulators would make
-                // the compiler wait for every outstanding load in front of their MFMAs.
-                if (wave == kTreeWave && more2) {
-                    path_R(acc[0], b2, h2);
-                    if (more3) load_R(b3, h3);
-                }
             }
             if (wave == kTreeWave) {
                 stage_T(h1);
@@ -1092,9 +1077,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             if (!live) STREE_MARK_POINT(42, 256);
             if (live) STREE_MARK_POINT(52 + 10 * k, 256);
             if (live) STREE_MARK_POINT(55 + 10 * k, 384);
-            if constexpr (RP) {
-                if (wave == kTreeWave && more2) park_R(acc[0]);
-            }
             // the registers just staged are free: x and parent / dt of unit k+2 go out at once (a
             // pass is short when HBM is idle, and they are needed at this point of the next one)
             if (more2) {
