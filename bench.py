@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--prefix", action="store_true",
                     help="the 4096-token prefix pass of the prefix-then-tree configuration: the chunked linear "
                          "scan kernel against 16 chain-tree calls (prints its own JSON line)")
+    ap.add_argument("--batches", action="store_true",
+                    help="the scan and the replay + scan kernels at batch 8 .. 128 of the headline shape: how far "
+                         "the fill and drain of a 2-3 unit run are from the steady state (prints its own JSON line)")
     ap.add_argument("--sweep", action="store_true",
                     help="second workload: the paper's tree shapes, packed tree scan against the same scan on the "
                          "tree unrolled into one chain per leaf (prints its own JSON line)")
@@ -114,6 +117,8 @@ def main():
         return sweep(st, synth, torch, dev)
     if args.prefix:
         return prefix(st, synth, torch, dev)
+    if args.batches:
+        return batches(st, synth, torch, dev)
 
     wl = synth.config(2)
     B, N, H, P, S, G, W = wl.batch, wl.nnodes, wl.nheads, wl.headdim, wl.dstate, wl.ngroups, wl.conv_width
@@ -415,6 +420,78 @@ def unroll_paths(parent):
             v = int(parent[v])
         paths.append(p[::-1])
     return paths
+
+
+def batches(st, synth, torch, dev):
+    """The 64-node / 80-head layer shape at batch 8 .. 128 (cfg2's tree and path-length recipe, random
+    activations): scan alone and replay + scan, HBM-cold (4 rotating buffer sets), in HIP graphs."""
+    N, H, P, S, G = 64, 80, 64, 128, 1
+    Cc = H * P + 2 * G * S
+    n_sets = 4
+    rows = []
+    for B in (8, 16, 32, 64, 128):
+        rng = np.random.default_rng(B)
+        parent = np.stack([synth.gen_tree(N, int(rng.integers(4, 9)), 4, rng) for _ in range(B)]).astype(np.int32)
+        depth = np.stack([synth.tree_depths(parent[b]) for b in range(B)])
+        acc = np.array([int(rng.choice(np.nonzero(depth[b] == min(int(rng.integers(0, 8)), depth[b].max()))[0]))
+                        for b in range(B)], dtype=np.int32)
+        sets = []
+        for r in range(n_sets):
+            s = dict(parent=torch.from_numpy(np.roll(parent, r, 0).copy()).to(dev),
+                     acc=torch.from_numpy(np.roll(acc, r, 0).copy()).to(dev),
+                     dt=torch.rand((B, N, H), device=dev) * 0.1 + 0.01, h0=torch.randn((B, H, P, S), device=dev) * 0.1,
+                     xbc=torch.randn((B, N, Cc), device=dev).to(torch.bfloat16))
+            s["y"] = torch.empty((B, N, H, P), dtype=torch.bfloat16, device=dev)
+            s["h_out"] = torch.empty((B, H, P, S), dtype=torch.float32, device=dev)
+            s["x"] = s["xbc"][:, :, : H * P].unflatten(2, (H, P))
+            s["Bm"] = s["xbc"][:, :, H * P: H * P + G * S].unflatten(2, (G, S))
+            s["Cm"] = s["xbc"][:, :, H * P + G * S:].unflatten(2, (G, S))
+            sets.append(s)
+        for r, s in enumerate(sets):
+            s["prev"] = sets[r - 1]
+        A, D = -torch.rand(H, device=dev) - 0.5, torch.randn(H, device=dev)
+
+        def timeit(fn, reps=50):
+            for s in sets:
+                fn(s)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for s in sets:
+                    fn(s)
+            for _ in range(5):
+                g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / (reps * n_sets) * 1e3
+
+        def scan(s):
+            st.stree_tree_ssd(s["parent"], s["x"], s["dt"], A, s["Bm"], s["Cm"], D, s["h0"], out=s["y"])
+
+        def fused(s):
+            q = s["prev"]
+            st.stree_tree_ssd_replay(q["parent"], q["acc"], q["x"], q["dt"], q["Bm"], s["parent"], s["x"], s["dt"], A,
+                                     s["Bm"], s["Cm"], D, s["h0"], h_out=s["h_out"], out=s["y"])
+
+        t_scan, t_fused = timeit(scan), timeit(fused)
+        pn = int(sum(depth[b, acc[b]] + 1 for b in range(B)))
+        ab = algorithmic_bytes_tree_ssd(B, N, H, P, S, G)
+        af = algorithmic_bytes_replay(B, N, N, H, P, S, G, pn)
+        log(f"[batches] B {B:3d}: scan {t_scan:7.2f} us {ab / t_scan / 1e3:5.0f} GB/s ({ab / t_scan / 8e4:4.1f}% of 8 TB/s)   "
+            f"replay+scan {t_fused:7.2f} us {af / t_fused / 1e3:5.0f} GB/s ({af / t_fused / 8e4:4.1f}%)")
+        rows.append({"batch": B, "scan_us": t_scan, "scan_GBps": ab / t_scan / 1e3, "replay_scan_us": t_fused,
+                     "replay_scan_GBps": af / t_fused / 1e3})
+        del sets
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "achieved algorithmic GB/s of the tree-scan kernels against batch", "unit": "GB/s",
+                      "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "64-node trees, 80 heads x 64, dstate 128, batch 8..128"},
+                      "rows": rows}), flush=True)
 
 
 def sweep(st, synth, torch, dev):
