@@ -162,6 +162,10 @@ def main():
         ssd(s)
         commit(s)
 
+    def conv_ssd(s):         # the verification pass without the commit
+        conv(s)
+        ssd(s)
+
     # fused sequence: the "previous tree" of a set is the tree of the set before it in the
     # rotation, with the activations that set's conv left in its buffer
     for r, s in enumerate(sets):
@@ -227,6 +231,7 @@ def main():
             run_fused = make_graphs(fused)
             run_tail = make_graphs(conv_replay)
             run_step_one = make_graphs(step_one)
+            run_conv_ssd = make_graphs(conv_ssd)
         except Exception as exc:  # pragma: no cover
             log(f"[bench] HIP graph capture failed ({exc}); falling back to direct launches")
             use_graph = False
@@ -239,6 +244,7 @@ def main():
         run_step, run_ssd, run_conv, run_commit = all_sets(step), all_sets(ssd), all_sets(conv), all_sets(commit)
         run_step_fused, run_fused, run_tail = all_sets(step_fused), all_sets(fused), all_sets(conv_replay)
         run_step_one = all_sets(step_one)
+        run_conv_ssd = all_sets(conv_ssd)
 
     def timed(run, k, warm, per_run=N_SETS):
         """Wall-clock and HIP-event time per launch of k launches on the current stream
@@ -268,6 +274,7 @@ def main():
     _, ms_fused = timed(run_fused, K, Wm)
     _, ms_tail = timed(run_tail, K, Wm)
     ms_ostep, ms_ostep_ev = timed(run_step_one, K, Wm)
+    ms_cs, _ = timed(run_conv_ssd, K, Wm)
     # one buffer set only: inputs stay in the 256 MB Infinity Cache
     warm_fn = (lambda: ssd(sets[0]))
     if use_graph:
@@ -342,6 +349,9 @@ def main():
         "roofline": {"separate": roof_scan, "fused": roof_fused, "one_launch": roof_one}[best],
         "roofline_tree_ssd_alone": roof_scan,
         "steps_us": {k: v * 1e3 for k, v in steps.items()},
+        # tree-nodes/s of the scan alone, of conv + scan, and of the whole step (conv + scan + commit, best sequence)
+        "nodes_per_s": {"tree_ssd": nodes / (ms_ssd * 1e-3), "conv+ssd": nodes / (ms_cs * 1e-3),
+                        "conv+ssd+commit": nodes / (ms_best * 1e-3)},
         "kernels_us": {"tree_conv": ms_conv * 1e3, "tree_ssd": ms_ssd * 1e3, "commit_state": ms_commit * 1e3,
                        "tree_conv_replay": ms_tail * 1e3, "tree_ssd_replay": ms_fused * 1e3},
     }
