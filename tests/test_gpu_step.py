@@ -39,21 +39,21 @@ def _inputs(seed, B, Np, N, H, P, S, G, W=4):
     return d
 
 
-def _prev_conv_out(st, d, H, P, S, G, silu=True):
+def _prev_conv_out(st, d, H, P, S, G, silu=True, io="bf16"):
     """The previous step's conv output (whatever conv state it started from: here zeros)."""
-    zero = torch.zeros_like(to_dev(d["conv_state"], "bf16"))
-    return st.stree_tree_conv(to_dev(d["pparent"]), to_dev(d["pxbc_pre"], "bf16"), zero, to_dev(d["conv_w"], "bf16"),
-                              to_dev(d["conv_b"], "bf16"), H, P, S, G, silu=silu)
+    zero = torch.zeros_like(to_dev(d["conv_state"], io))
+    return st.stree_tree_conv(to_dev(d["pparent"]), to_dev(d["pxbc_pre"], io), zero, to_dev(d["conv_w"], io),
+                              to_dev(d["conv_b"], io), H, P, S, G, silu=silu)
 
 
-def _two_calls(st, d, pout, H, P, S, G, silu=True, bias=True):
+def _two_calls(st, d, pout, H, P, S, G, silu=True, bias=True, io="bf16"):
     B = d["parent"].shape[0]
     stt = torch.full((B,), -7, dtype=torch.int32, device="cuda")
     rst = torch.full((B,), -7, dtype=torch.int32, device="cuda")
-    cb = to_dev(d["conv_b"], "bf16") if bias else None
-    xbc, cs = st.stree_tree_conv_replay(to_dev(d["pparent"]), to_dev(d["acc"]), to_dev(d["pxbc_pre"], "bf16"),
-                                        to_dev(d["parent"]), to_dev(d["xbc_pre"], "bf16"),
-                                        to_dev(d["conv_state"], "bf16"), to_dev(d["conv_w"], "bf16"), cb, H, P, S, G,
+    cb = to_dev(d["conv_b"], io) if bias else None
+    xbc, cs = st.stree_tree_conv_replay(to_dev(d["pparent"]), to_dev(d["acc"]), to_dev(d["pxbc_pre"], io),
+                                        to_dev(d["parent"]), to_dev(d["xbc_pre"], io),
+                                        to_dev(d["conv_state"], io), to_dev(d["conv_w"], io), cb, H, P, S, G,
                                         silu=silu)
     x = xbc[:, :, :H * P].unflatten(2, (H, P))
     Bm = xbc[:, :, H * P:H * P + G * S].unflatten(2, (G, S))
@@ -66,14 +66,14 @@ def _two_calls(st, d, pout, H, P, S, G, silu=True, bias=True):
     return y, h, xbc, cs, stt, rst
 
 
-def _one_call(st, d, pout, H, P, S, G, silu=True, bias=True, one_launch=True, **kw):
+def _one_call(st, d, pout, H, P, S, G, silu=True, bias=True, one_launch=True, io="bf16", **kw):
     B = d["parent"].shape[0]
     stt = torch.full((B,), -7, dtype=torch.int32, device="cuda")
     rst = torch.full((B,), -7, dtype=torch.int32, device="cuda")
-    cb = to_dev(d["conv_b"], "bf16") if bias else None
-    y, h, xbc, cs = st.stree_tree_step(to_dev(d["pparent"]), to_dev(d["acc"]), to_dev(d["pxbc_pre"], "bf16"), pout,
-                                       to_dev(d["pdt"]), to_dev(d["parent"]), to_dev(d["xbc_pre"], "bf16"),
-                                       to_dev(d["conv_state"], "bf16"), to_dev(d["conv_w"], "bf16"), cb,
+    cb = to_dev(d["conv_b"], io) if bias else None
+    y, h, xbc, cs = st.stree_tree_step(to_dev(d["pparent"]), to_dev(d["acc"]), to_dev(d["pxbc_pre"], io), pout,
+                                       to_dev(d["pdt"]), to_dev(d["parent"]), to_dev(d["xbc_pre"], io),
+                                       to_dev(d["conv_state"], io), to_dev(d["conv_w"], io), cb,
                                        to_dev(d["dt"]), to_dev(d["A"]), to_dev(d["D"]), to_dev(d["h0"]), H, P, S, G,
                                        silu=silu, status=stt, replay_status=rst, one_launch=one_launch, **kw)
     return y, h, xbc, cs, stt, rst
@@ -133,6 +133,27 @@ def test_step_other_shapes_take_the_two_kernel_route(st):
         d = _inputs(33 + W, B, Np, N, H, P, S, G, W)
         pout = _prev_conv_out(st, d, H, P, S, G)
         _same(_one_call(st, d, pout, H, P, S, G), _two_calls(st, d, pout, H, P, S, G), f"step fallback W={W} P={P}")
+
+
+def test_step_fp32_and_large_trees(st, oracle):
+    """fp32 storage and a 200-node tree: outside the single kernel (the flag is ignored), same entry
+    point; checked against the two calls bit for bit and against the oracle."""
+    B, Np, N, H, P, S, G = 2, 50, 200, 2, 16, 32, 1
+    d = _inputs(4242, B, Np, N, H, P, S, G)
+    pout = _prev_conv_out(st, d, H, P, S, G, io="f32")
+    one = _one_call(st, d, pout, H, P, S, G, io="f32")
+    _same(one, _two_calls(st, d, pout, H, P, S, G, io="f32"), "step fp32 N=200")
+    pxbc = to_host(pout)
+    px, pB, _ = split_xbc(pxbc, H, P, G, S)
+    want_h, want_cs = oracle.commit(d["pparent"], d["acc"], px, d["pdt"], d["A"], pB, d["h0"].astype(np.float64),
+                                    d["pxbc_pre"], d["conv_state"])
+    assert np.array_equal(to_host(one[3]), want_cs.astype(np.float32))
+    assert_parity(to_host(one[1]), want_h, 1e-4, "step fp32: replayed state")
+    want_conv = oracle.tree_conv(d["parent"], d["xbc_pre"], want_cs.astype(np.float32), d["conv_w"], d["conv_b"], True)
+    assert_parity(to_host(one[2]), want_conv, 1e-4, "step fp32: conv output")
+    x, Bm, Cm = split_xbc(to_host(one[2]), H, P, G, S)
+    want_y = oracle.ssd_paths(d["parent"], x, d["dt"], d["A"], Bm, Cm, d["D"], want_h)
+    assert_parity(to_host(one[0]), want_y, TOL["f32"], "step fp32: y")
 
 
 def test_step_in_place_state(st):
