@@ -36,15 +36,24 @@ struct MfmaLdsPlan {
     size_t off_c, off_b, off_h, off_xt, off_m, off_mask, total;
 };
 
+// share_h: the bf16 state tile (needed in phase 1 only) lives in the B tile's LDS instead of its
+// own: taken for trees of more than 128 nodes, where it is the difference between one and two
+// workgroups per CU
+__host__ __device__ inline bool mfma_share_h(int npad) { return npad > 128; }
 __host__ __device__ inline MfmaLdsPlan mfma_lds_plan(int P, int S, int npad, int words) {
     MfmaLdsPlan pl;
     pl.sp = S + 8;
     const size_t c_bytes = (size_t)kBlk * pl.sp * 2;
     const size_t y_bytes = (size_t)kBlk * (P + 4) * 4;  // fp32 output staging shares the B tile
+    const size_t h_bytes = (size_t)P * pl.sp * 2;       // and so does the bf16 state tile (phase 1 only)
+    const bool share = mfma_share_h(npad);
+    size_t b_bytes = c_bytes > y_bytes ? c_bytes : y_bytes;
+    if (share && h_bytes > b_bytes) b_bytes = h_bytes;
     size_t o = 0;
     pl.off_c = o; o += c_bytes;
-    pl.off_b = o; o += (c_bytes > y_bytes ? c_bytes : y_bytes);
-    pl.off_h = o; o += (size_t)P * pl.sp * 2;
+    pl.off_b = o; o += b_bytes;
+    pl.off_h = pl.off_b;
+    if (!share) { pl.off_h = o; o += h_bytes; }
     pl.off_xt = o; o += (size_t)P * kNP * 2;
     pl.off_m = o; o += (size_t)kBlk * kNP * 2;
     pl.off_mask = o; o += (size_t)npad * words * 4;
@@ -60,7 +69,7 @@ constexpr int kMaxS32 = 8;       // dstate <= 256: at most 8 16-byte pieces of a
 constexpr int kH0Batch = 8;      // float4 pieces of h0 per thread requested ahead of the tree index
 
 // (for headdim <= 64 two workgroups fit the LDS of a CU: the register budget is held to that)
-template <int P>
+template <int P, bool SH>
 __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kernel(
     const int32_t *__restrict__ parent, int n, int H, int S, int G, const bf16_t *__restrict__ x, long x_sn,
     const float *__restrict__ dt, const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn,
@@ -84,7 +93,7 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
     bf16_t *sC = reinterpret_cast<bf16_t *>(lds + pl.off_c);
     bf16_t *sB = reinterpret_cast<bf16_t *>(lds + pl.off_b);
     float *sY = reinterpret_cast<float *>(lds + pl.off_b);
-    bf16_t *sH = reinterpret_cast<bf16_t *>(lds + pl.off_h);
+    bf16_t *sH = reinterpret_cast<bf16_t *>(lds + pl.off_h);   // SH: the B tile's LDS, between a row block's start and its first B tile
     bf16_t *sXT = reinterpret_cast<bf16_t *>(lds + pl.off_xt);
     bf16_t *sM = reinterpret_cast<bf16_t *>(lds + pl.off_m);
     uint32_t *mask = reinterpret_cast<uint32_t *>(lds + pl.off_mask);
@@ -164,8 +173,7 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
 #pragma unroll
         for (int q = 0; q < kH0Batch; ++q) {
             const int idx = min(q * kThreads + tid, h_items - 1);
-            const uint4 v = load_stream16(hb + (size_t)idx * 4);   // read once: streaming hint
-            hreg[q] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+            hreg[q] = *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4);
         }
     }
     load_rows(creg, Cb, c_sn, 0);
@@ -194,18 +202,8 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
             if ((mask[tid * words + 2 * jb] | mask[tid * words + 2 * jb + 1]) != 0u) bits |= 1u << (4 * ib + jb);
         if (bits) atomicOr(&nz_bits, bits);
     }
-    // ---- initial state -> bf16 MFMA operand rows sH[p][s] ----------------------------------
-    if (h0) {
-        float one = 1.0f;
-        asm volatile("" : "+v"(one));
-#pragma unroll
-        for (int q = 0; q < kH0Batch; ++q) {
-            const int idx = q * kThreads + tid;
-            if (idx < h_items) store_h(idx, hreg[q], one);
-        }
-        for (int idx = kH0Batch * kThreads + tid; idx < h_items; idx += kThreads)
-            store_h(idx, *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4), one);
-    }
+    float one = 1.0f;                        // (see store_h)
+    asm volatile("" : "+v"(one));
     __syncthreads();
     STREE_PHASE_CLOCK(3);
     const uint32_t nz = __builtin_amdgcn_readfirstlane(nz_bits);
@@ -241,31 +239,31 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
     while (true) {
         const int i0 = ib * kBlk, j0 = jb * kBlk;
         // ---- this pair's tiles: registers -> LDS; the next pair's: global -> registers ------
-        if (new_rows) store_rows(creg, sC, i0);
-        store_rows(breg, sB, j0);
-        store_x(j0);
-        int nib = ib, njb;
-        if (jb == ib) {
-            nib = ib + 1;
-            njb = nib < nblk ? next_col(nib, -1) : 0;
-        } else {
-            njb = next_col(ib, jb);
-        }
-        const bool more = nib < nblk;
-        if (more) {
-            if (nib != ib) load_rows(creg, Cb, c_sn, nib * kBlk);
-            load_rows(breg, Bb, b_sn, njb * kBlk);
-            load_x(njb * kBlk);
-        }
-        __syncthreads();
-        STREE_PHASE_CLOCK(4);
-
-        // ---- phase 1 (once per row block): Yt = h0b * C^T, scaled by exp(s_i) ---------------
         if (new_rows) {
+            // ---- a row block starts: C rows, and the state tile in the B tile's LDS for phase 1 -----
+            store_rows(creg, sC, i0);
+            if (h0 && (SH || ib == 0)) {
+                if (SH && ib > 0) {    // the state tile again (from L2)
+#pragma unroll
+                    for (int q = 0; q < kH0Batch; ++q) {
+                        const int idx = min(q * kThreads + tid, h_items - 1);
+                        hreg[q] = *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4);
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < kH0Batch; ++q) {
+                    const int idx = q * kThreads + tid;
+                    if (idx < h_items) store_h(idx, hreg[q], one);
+                }
+                for (int idx = kH0Batch * kThreads + tid; idx < h_items; idx += kThreads)
+                    store_h(idx, *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4), one);
+            }
+            __syncthreads();
 #pragma unroll
             for (int q = 0; q < YQ; ++q)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[q][r] = 0.f;
+            // ---- phase 1 (once per row block): Yt = h0b * C^T, scaled by exp(s_i) -------------------
             if (h0) {
 #pragma unroll
                 for (int q = 0; q < YQ; ++q) {
@@ -280,8 +278,28 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
                         for (int r = 0; r < 16; ++r) acc[q][r] *= e;
                     }
                 }
+                if constexpr (SH) __syncthreads();   // the state tile's readers are done before the B tile takes its place
             }
         }
+        store_rows(breg, sB, j0);
+        store_x(j0);
+        int nib = ib, njb;
+        if (jb == ib) {
+            nib = ib + 1;
+            njb = nib < nblk ? next_col(nib, -1) : 0;
+        } else {
+            njb = next_col(ib, jb);
+        }
+        const bool more = nib < nblk;
+        if (more) {
+            if (nib != ib) {
+                load_rows(creg, Cb, c_sn, nib * kBlk);
+            }
+            load_rows(breg, Bb, b_sn, njb * kBlk);
+            load_x(njb * kBlk);
+        }
+        __syncthreads();
+        STREE_PHASE_CLOCK(4);
 
         // ---- phase 2: Gt = B * C^T; mask and decay -> M[i][j] as bf16 ------------------------
         {
@@ -393,7 +411,7 @@ bool tree_ssd_mfma_supported(const stree_dims &d, const void *x, const void *Bm,
     return mfma_lds_plan(d.headdim, d.dstate, npad, (d.nnodes + 31) / 32).total + sizeof(TreeLds) <= 160 * 1024;
 }
 
-template <int P>
+template <int P, bool SH>
 static hipError_t launch_p(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                            const float *A, const void *Bm, const void *Cm, const float *D, const float *h0,
                            void *y, int32_t *status, hipStream_t st) {
@@ -401,12 +419,12 @@ static hipError_t launch_p(const stree_dims &d, const int32_t *parent, const voi
     const size_t lds = mfma_lds_plan(P, d.dstate, npad, (d.nnodes + 31) / 32).total;
     static size_t lds_set = 0;  // raise the dynamic-LDS limit once per size (64 KB is the default cap)
     if (lds > lds_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_mfma_kernel<P>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_mfma_kernel<P, SH>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         lds_set = lds;
     }
-    hipLaunchKernelGGL(tree_ssd_mfma_kernel<P>, dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
+    hipLaunchKernelGGL((tree_ssd_mfma_kernel<P, SH>), dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
                        d.nheads, d.dstate, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A,
                        (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,
                        (bf16_t *)y, status);
@@ -418,10 +436,17 @@ hipError_t launch_tree_ssd_mfma(const stree_dims &d, const int32_t *parent, cons
                                 const float *h0, void *y, int32_t *status, hipStream_t st) {
     if (tree_ssd_mfma64_supported(d))
         return launch_tree_ssd_mfma64(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+    const bool sh = mfma_share_h((d.nnodes + kBlk - 1) / kBlk * kBlk);
     switch (d.headdim) {
-        case 32: return launch_p<32>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
-        case 64: return launch_p<64>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
-        case 128: return launch_p<128>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+        case 32:
+            return sh ? launch_p<32, true>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st)
+                      : launch_p<32, false>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+        case 64:
+            return sh ? launch_p<64, true>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st)
+                      : launch_p<64, false>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+        case 128:
+            return sh ? launch_p<128, true>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st)
+                      : launch_p<128, false>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
     }
     return hipErrorInvalidValue;
 }
