@@ -52,24 +52,42 @@ __device__ __forceinline__ void conv_tail(int b, int cblk, const int32_t *__rest
 struct ConvTailArgs {      // conv part folded into the state kernel's grid (cblocks = 0: none)
     const void *xbc_pre, *conv_state;
     void *conv_state_out;
-    int Cc, W, cblocks;
+    int Cc, W, cblocks, batch;
+    int state_z;           // z slices of the grid that belong to the state (batch, or 0 with no state)
 };
 
-// grid (slabs [+ 1], H, B); dynamic LDS = kPathChunk * (P + S) floats.
+// grid (slabs, H, B [+ conv-tail slices]); dynamic LDS = kPathChunk * (P + S) floats.
 // A thread owns one 4-wide piece s4 of the state index and kQ consecutive rows p, so that per
 // path node it needs one B piece and kQ x values: three 16-byte LDS reads for 4*kQ FMAs.  A
 // workgroup covers rows_wg = kQ * (256 / (S/4)) rows; slabs = ceil(P / rows_wg).
-// The extra x index, when present, carries the conv tail: its workgroups with h < cblocks each copy
-// one channel block, so that the whole commit is one launch.
-template <typename T, bool WAVE>
+// The z slices behind the batch, when present, carry the conv tail: their first cblocks * B
+// workgroups each copy one channel block of one sequence, so that the whole commit is one launch.
+// (They follow the state's workgroups rather than alternate with them: workgroups go to the eight
+// XCDs in turn, and a grid that alternates would put all of the state on every other XCD.)
+//
+// FAST (every thread owns kQ rows inside the state, 16-byte aligned x / B rows; see
+// commit_fast_shape): nothing on the way from the state loads to the state stores is predicated.
+// The small parent / dt loads go out ahead of the state loads, so that the wave that works out
+// the path waits for those alone; the path rows are fetched as 16-byte pieces, all requested
+// before any is waited for; the stores follow each other with no wait between them.  (With
+// per-row bounds branches the compiler had put a full wait in front of every load of the path rows
+// and of every store: a dozen serial round trips per workgroup.)
+// NS = 16-byte pieces of a chunk of path rows per thread (0: the general, predicated kernel).  With
+// two pieces the kernel needs under 102 registers, i.e. five workgroups per CU: at 80 heads x
+// batch 16 every workgroup of the launch is resident at once.  (Forcing that budget on the compiler
+// where it does not come by itself is worse than four per CU: the spills wait on the state loads.)
+template <typename T, bool WAVE, int NS>
 __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     const int32_t *__restrict__ parent, const int32_t *__restrict__ accepted, int n, int H, int P, int S,
     int G, const T *__restrict__ x, long x_sn, const float *__restrict__ dt, const float *__restrict__ A,
     const T *__restrict__ Bm, long b_sn, const float *h0, float *h_out, int32_t *__restrict__ status,
     int slabs, ConvTailArgs ct) {
-    if ((int)blockIdx.x >= slabs) {                    // the conv-tail slot of the grid
-        if ((int)blockIdx.y < ct.cblocks)
-            conv_tail<T, 16 / (int)sizeof(T)>(blockIdx.z, blockIdx.y, parent, accepted, n, ct.Cc, ct.W,
+    constexpr bool FAST = NS > 0;
+    constexpr int kStageMax = NS ? NS : 1;
+    if ((int)blockIdx.z >= ct.state_z) {               // the conv-tail slices at the end of the grid
+        const int idx = (((int)blockIdx.z - ct.state_z) * (int)gridDim.y + (int)blockIdx.y) * (int)gridDim.x + (int)blockIdx.x;
+        if (idx < ct.cblocks * ct.batch)
+            conv_tail<T, 16 / (int)sizeof(T)>(idx / ct.cblocks, idx % ct.cblocks, parent, accepted, n, ct.Cc, ct.W,
                                               (const T *)ct.xbc_pre, (const T *)ct.conv_state,
                                               (T *)ct.conv_state_out);
         return;
@@ -77,56 +95,63 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     extern __shared__ __align__(16) float rows[];     // xs[kPathChunk][P] then bs[kPathChunk][S]
     __shared__ int path[kMaxNodes];
     __shared__ float coef[kMaxNodes];
-    __shared__ float scal[2];                          // decay, then path length (as int bits)
-    __shared__ int bad_s;
     float *xs = rows, *bs = rows + kPathChunk * P;
     const int tid = threadIdx.x, lane = tid & 63, h = blockIdx.y, b = blockIdx.z;
     const int g = h / (H / G);
 
-    // the state rows first: these loads fly while the path is worked out
     const int S4 = S >> 2, RP = kThreads / S4;
     const int s4 = tid % S4, p0 = (blockIdx.x * RP + tid / S4) * kQ;   // rows p0 .. p0 + kQ - 1
-    const bool owner = tid < RP * S4;                  // S/4 need not divide the thread count
+    const bool owner = FAST || tid < RP * S4;          // S/4 need not divide the thread count
     const size_t sbase = ((size_t)b * H + h) * P * S + (size_t)s4 * 4;
+    const size_t ubase = ((size_t)b * H + h) * P * S;              // FAST: the head's state, uniform
+    const uint32_t loff = (uint32_t)(p0 * S + s4 * 4) * 4u;       //       and this thread's place in it, bytes
+    // n <= 64: every wave asks for the parents and step sizes (wave 0 uses them), ahead of the state
+    int par_j = -1;
+    float dt_j = 0.f;
+    if constexpr (WAVE) {
+        const int node = min(lane, n - 1);
+        par_j = parent[(size_t)b * n + node];
+        dt_j = dt[((size_t)b * n + node) * H + h];
+    }
+    // the state rows: these loads fly while the path is worked out (read once: streaming hint,
+    // as for the store of the result below)
     float4 acc[kQ];
+    if constexpr (FAST) {
+        const float *src = h0 ? h0 : h_out;           // no initial state: any readable rows, zeroed below
 #pragma unroll
-    for (int q = 0; q < kQ; ++q) {
-        const int p = p0 + q;
-        acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (h0 && owner && p < P) {   // read once: streaming hint (as for the store of the result below)
-            const uint4 v = load_stream16(h0 + sbase + (size_t)p * S);
+        for (int q = 0; q < kQ; ++q) {
+            // (uniform row pointer + one 32-bit lane offset: one address register for all kQ rows)
+            const uint4 v = load_stream16(reinterpret_cast<const char *>(src + ubase + (size_t)q * S) + loff);
             acc[q] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < kQ; ++q) {
+            const int p = p0 + q;
+            acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (h0 && owner && p < P) {
+                const uint4 v = load_stream16(h0 + sbase + (size_t)p * S);
+                acc[q] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+            }
         }
     }
 
     const int k = accepted[b];
     const bool k_bad = (k < -1) || (k >= n);
     const float A_h = A[h];
-    int bad, len;
-    float decay;
+    int bad, len = 0;
+    float decay = 1.f;
     if constexpr (WAVE) {
-        // n <= 64: wave 0 finds the path in registers and publishes it
-        if (tid < 64) {
-            const int node = min(lane, n - 1);
-            const int par_j = parent[(size_t)b * n + node];
-            const float dt_j = dt[((size_t)b * n + node) * H + h];
-            int pos, ln;
-            float cf, dc;
-            const int st = wave_path(lane, n, (k >= 0 && !k_bad) ? k : 0, par_j, dt_j, A_h, pos, cf, ln, dc);
-            if (st == 0 && pos >= 0) {
-                path[pos] = lane;
-                coef[pos] = cf;
-            }
-            if (lane == 0) {
-                bad_s = st;
-                scal[0] = dc;
-                scal[1] = __int_as_float(ln);
-            }
+        // n <= 64: every wave finds the path in registers (all of them use the parent / dt values, so
+        // their loads stay where they were issued, ahead of the state); wave 0 publishes it
+        int pos;
+        float cf;
+        bad = wave_path(lane, n, (k >= 0 && !k_bad) ? k : 0, par_j, dt_j, A_h, pos, cf, len, decay);
+        if (tid < 64 && bad == 0 && pos >= 0) {
+            path[pos] = lane;
+            coef[pos] = cf;
         }
         __syncthreads();
-        bad = bad_s;
-        decay = scal[0];
-        len = __float_as_int(scal[1]);
     } else {
         __shared__ TreeLds tree;
         __shared__ uint32_t mask[kMaxNodes * kMaxWords];
@@ -154,16 +179,59 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
 
     const bool pass = bad || k < 0 || k_bad;          // the state goes through unchanged
     if (pass && h_out == h0 && h0) return;
+    if constexpr (FAST) {
+        if (!h0) {                                     // (here, not at the loads: this is their first use)
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
     const T *xb = x + (size_t)b * n * x_sn + (size_t)h * P;
     const T *Bb = Bm + (size_t)b * n * b_sn + (size_t)g * S;
     bool scaled = false;
     for (int c0 = 0; !pass && c0 < len; c0 += kPathChunk) {
         const int cn = min(kPathChunk, len - c0);
-        for (int idx = tid; idx < cn * (P + S); idx += kThreads) {
-            const int t = idx / (P + S), col = idx % (P + S);
-            const int node = path[c0 + t];
-            if (col < P) xs[t * P + col] = to_f32(xb[(size_t)node * x_sn + col]);
-            else bs[t * S + col - P] = coef[c0 + t] * to_f32(Bb[(size_t)node * b_sn + (col - P)]);
+        if constexpr (FAST) {
+            constexpr int EPV = 16 / (int)sizeof(T);   // elements of a 16-byte piece
+            const int px = P / EPV, ppn = (P + S) / EPV, total = cn * ppn;
+            uint4 piece[kStageMax];
+#pragma unroll
+            for (int q = 0; q < kStageMax; ++q) {      // (clamped: the last piece again past the end)
+                const int idx = min(q * kThreads + tid, total - 1);
+                const int t = idx / ppn, c = idx % ppn;
+                const int node = path[c0 + t];
+                const T *src = c < px ? xb + (size_t)node * x_sn + c * EPV : Bb + (size_t)node * b_sn + (c - px) * EPV;
+                piece[q] = *reinterpret_cast<const uint4 *>(src);
+            }
+            // (the decay is made opaque here so that the scaling of the state below, which waits for
+            // the state loads, is not scheduled in front of these requests)
+            asm volatile("" : "+v"(decay) : : "memory");
+#pragma unroll
+            for (int q = 0; q < kStageMax; ++q) {
+                const int idx = q * kThreads + tid;
+                if (idx < total) {
+                    const int t = idx / ppn, c = idx % ppn;
+                    const float w = c < px ? 1.f : coef[c0 + t];
+                    float *dst = c < px ? xs + t * P + c * EPV : bs + t * S + (c - px) * EPV;
+                    float f[8];
+                    if constexpr (sizeof(T) == 2) {
+                        f[0] = bf16_lo(piece[q].x); f[1] = bf16_hi(piece[q].x); f[2] = bf16_lo(piece[q].y); f[3] = bf16_hi(piece[q].y);
+                        f[4] = bf16_lo(piece[q].z); f[5] = bf16_hi(piece[q].z); f[6] = bf16_lo(piece[q].w); f[7] = bf16_hi(piece[q].w);
+                    } else {
+                        f[0] = __uint_as_float(piece[q].x); f[1] = __uint_as_float(piece[q].y);
+                        f[2] = __uint_as_float(piece[q].z); f[3] = __uint_as_float(piece[q].w);
+                    }
+#pragma unroll
+                    for (int e = 0; e < EPV; e += 4)
+                        *reinterpret_cast<float4 *>(dst + e) = make_float4(w * f[e], w * f[e + 1], w * f[e + 2], w * f[e + 3]);
+                }
+            }
+        } else {
+            for (int idx = tid; idx < cn * (P + S); idx += kThreads) {
+                const int t = idx / (P + S), col = idx % (P + S);
+                const int node = path[c0 + t];
+                if (col < P) xs[t * P + col] = to_f32(xb[(size_t)node * x_sn + col]);
+                else bs[t * S + col - P] = coef[c0 + t] * to_f32(Bb[(size_t)node * b_sn + (col - P)]);
+            }
         }
         if (!scaled) {   // the state loads are first needed here
 #pragma unroll
@@ -198,7 +266,13 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
         }
         __syncthreads();
     }
-    if (owner) {
+    if constexpr (FAST) {
+#pragma unroll
+        for (int q = 0; q < kQ; ++q)
+            store_stream16(reinterpret_cast<char *>(h_out + ubase + (size_t)q * S) + loff,
+                           make_uint4(__float_as_uint(acc[q].x), __float_as_uint(acc[q].y),
+                                      __float_as_uint(acc[q].z), __float_as_uint(acc[q].w)));
+    } else if (owner) {
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
             const int p = p0 + q;
@@ -208,6 +282,23 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
                                           __float_as_uint(acc[q].z), __float_as_uint(acc[q].w)));
         }
     }
+}
+
+// Shapes of the unpredicated kernel: the threads tile the state exactly (S/4 divides the workgroup,
+// its kQ-row slabs divide P), x and B rows are whole 16-byte pieces at 16-byte addresses, and a
+// chunk of path rows is at most four pieces per thread.  Returns that number of pieces (2 or 4), or 0.
+static int commit_fast_shape(const stree_dims &d, const void *x, const void *Bm, const float *h0,
+                              const float *h_out) {
+    const int S4 = d.dstate / 4;
+    if (d.dstate % 4 != 0 || S4 > kThreads || kThreads % S4 != 0) return 0;
+    const int rows_wg = kQ * (kThreads / S4);
+    if (d.headdim % rows_wg != 0) return 0;
+    const int epv = d.io_dtype == STREE_BF16 ? 8 : 4;
+    if (d.headdim % epv != 0 || d.dstate % epv != 0 || d.x_stride_n % epv != 0 || d.b_stride_n % epv != 0)
+        return 0;
+    if (((uintptr_t)x | (uintptr_t)Bm | (uintptr_t)h0 | (uintptr_t)h_out) % 16 != 0) return 0;
+    const int pieces = kPathChunk * ((d.headdim + d.dstate) / epv);
+    return pieces <= 2 * kThreads ? 2 : pieces <= 4 * kThreads ? 4 : 0;
 }
 
 hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const int32_t *accepted,
@@ -221,23 +312,33 @@ hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const
     // channel blocks of the conv tail; never more than heads: Cc = H*P + 2*G*S <= H*(P + 2*S) and
     // P, S <= 256 give Cc / (vec*256) <= 0.75 * H
     const int cblocks = conv_state_out ? (Cc / vec + kThreads - 1) / kThreads : 0;
-    if (cblocks > d.nheads) return hipErrorInvalidValue;
-    ConvTailArgs ct = {xbc_pre, conv_state, conv_state_out, Cc, d.conv_width, cblocks};
     if (slabs + cblocks == 0) return hipSuccess;
-    const dim3 grid(slabs + (cblocks ? 1 : 0), slabs ? d.nheads : cblocks, d.batch);
+    const int gx = slabs ? slabs : cblocks, gy = slabs ? d.nheads : 1, state_z = slabs ? d.batch : 0;
+    const int tail_z = (cblocks * d.batch + gx * gy - 1) / (gx * gy);
+    if (state_z + tail_z > 65535) return hipErrorInvalidValue;
+    ConvTailArgs ct = {xbc_pre, conv_state, conv_state_out, Cc, d.conv_width, cblocks, d.batch, state_z};
+    const dim3 grid(gx, gy, state_z + tail_z);
     const size_t lds = (size_t)kPathChunk * (d.headdim + d.dstate) * sizeof(float);
-#define STREE_COMMIT_LAUNCH(TT, WV)                                                                           \
-    hipLaunchKernelGGL((commit_h_kernel<TT, WV>), grid, dim3(kThreads), lds, st, parent, accepted, d.nnodes,     \
+#define STREE_COMMIT_LAUNCH(TT, WV, NS)                                                                      \
+    hipLaunchKernelGGL((commit_h_kernel<TT, WV, NS>), grid, dim3(kThreads), lds, st, parent, accepted, d.nnodes, \
                        d.nheads, d.headdim, d.dstate, d.ngroups, (const TT *)x, (long)d.x_stride_n, dt, A,      \
                        (const TT *)Bm, (long)d.b_stride_n, h0, h_out, status, slabs, ct)
     const bool wave = d.nnodes <= 64;
+    const int ns = slabs > 0 ? commit_fast_shape(d, x, Bm, h0, h_out) : 0;
+#define STREE_COMMIT_NS(TT, WV)                                 \
+    do {                                                        \
+        if (ns == 2) STREE_COMMIT_LAUNCH(TT, WV, 2);            \
+        else if (ns == 4) STREE_COMMIT_LAUNCH(TT, WV, 4);       \
+        else STREE_COMMIT_LAUNCH(TT, WV, 0);                    \
+    } while (0)
     if (d.io_dtype == STREE_BF16) {
-        if (wave) STREE_COMMIT_LAUNCH(bf16_t, true);
-        else STREE_COMMIT_LAUNCH(bf16_t, false);
+        if (wave) STREE_COMMIT_NS(bf16_t, true);
+        else STREE_COMMIT_NS(bf16_t, false);
     } else {
-        if (wave) STREE_COMMIT_LAUNCH(float, true);
-        else STREE_COMMIT_LAUNCH(float, false);
+        if (wave) STREE_COMMIT_NS(float, true);
+        else STREE_COMMIT_NS(float, false);
     }
+#undef STREE_COMMIT_NS
 #undef STREE_COMMIT_LAUNCH
     return hipGetLastError();
 }
