@@ -273,6 +273,50 @@ def test_commit_edge_cases(st, oracle):
     assert_parity(to_host(h3), want3, 1e-4, "commit without h0")
 
 
+@pytest.mark.parametrize("io", ["bf16", "f32"])
+@pytest.mark.parametrize("N", [40, 100])
+def test_commit_unpredicated_kernel_cases(st, oracle, io, N):
+    """Shapes whose state the threads tile exactly (the kernel variant without bounds checks), on both
+    tree-size branches: missing initial state, a bad tree, accepted = -1 and out of range, a long and a
+    one-node path, several heads per group."""
+    import torch
+    B, H, P, S, G = 6, 6, 64, 128, 2
+    parent = _trees(71, B, N)
+    parent[0] = synth.chain_tree(N)
+    parent[3, N // 2] = N - 1                                     # bad tree
+    x, dt, A, Bm, Cm, D, h0 = _rand(72, io, B, N, H, P, S, G)
+    acc = np.array([N - 1, 0, -1, 5, N + 2, N // 3], dtype=np.int32)
+    good = [0, 1, 5]
+    want, _ = oracle.commit(parent[good], acc[good], x[good], dt[good], A, Bm[good], h0[good])
+    status = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    h, _ = st.stree_commit_state(to_dev(parent), to_dev(acc), to_dev(x, io), to_dev(dt), to_dev(A),
+                                 to_dev(Bm, io), to_dev(h0), status=status)
+    assert list(to_host(status)) == [0, 0, 0, N // 2 + 1, -1, 0]
+    h = to_host(h)
+    for i, b in enumerate(good):
+        assert_parity(h[b], want[i], 1e-4, f"commit b={b}")
+    for b in (2, 3, 4):                                           # kept bit-exactly
+        assert np.array_equal(h[b], h0[b])
+    # no initial state: zeros for the sequences that keep it, the update alone for the others
+    want0, _ = oracle.commit(parent[good], acc[good], x[good], dt[good], A, Bm[good], None)
+    hz, _ = st.stree_commit_state(to_dev(parent), to_dev(acc), to_dev(x, io), to_dev(dt), to_dev(A),
+                                  to_dev(Bm, io), None,
+                                  h_out=torch.full((B, H, P, S), float("nan"), dtype=torch.float32, device="cuda"))
+    hz = to_host(hz)
+    for i, b in enumerate(good):
+        assert_parity(hz[b], want0[i], 1e-4, f"commit without h0 b={b}")
+    for b in (2, 3, 4):
+        assert not hz[b].any()
+    # x / B as strided views of one buffer whose rows are not a whole number of 16-byte pieces: the
+    # predicated kernel takes over, same result
+    pad = 4 if io == "bf16" else 2
+    xw = torch.zeros((B, N, H * P + pad), dtype=to_dev(x, io).dtype, device="cuda")
+    xw[..., :H * P] = to_dev(x, io).reshape(B, N, H * P)
+    hv, _ = st.stree_commit_state(to_dev(parent), to_dev(acc), xw[..., :H * P].view(B, N, H, P), to_dev(dt),
+                                  to_dev(A), to_dev(Bm, io), to_dev(h0))
+    assert_parity(to_host(hv)[good], h[good], 1e-6, "commit from a misaligned view")
+
+
 @pytest.mark.parametrize("N,H,P,S,G", [(13, 3, 24, 20, 1), (30, 2, 12, 48, 2), (64, 2, 256, 256, 1), (7, 4, 1, 4, 4)])
 def test_commit_ragged_shapes(st, oracle, N, H, P, S, G):
     """State tiles that do not divide evenly over the threads of a workgroup."""
