@@ -457,7 +457,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     constexpr int kTreeWave = 6;
     const bool isY = wave < 4;
     const int rt = tid & (kHalf - 1);    // thread index within its role group
-    const int it = wave & 1;             // node half of the tiles this wave owns
     const int n_units = nbatch * H;
     const int per_xcd = (n_units + 7) >> 3;
     const int xcd = blockIdx.x & 7;
@@ -502,6 +501,11 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         asm volatile("" : "+v"(v));
         return v;
     };
+    // the node half of the tiles a wave owns.  With the replay the register budget has no room for
+    // it (nor for anything else the compiler would hoist out of the unit loop): kept live it is
+    // spilled, and a reload waits for every load in flight, so there it is re-derived where used
+    // from a copy of the wave index that the compiler cannot see through.
+    const int it0 = wave & 1;
 
     float rD = 0.f;                  // D[h] of the unit whose h0 is in pre[]
     // chunk q of a thread: without replay element (t + q*kHalf)*4 of the P x S tile; with replay
@@ -862,7 +866,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
             // ---- phase 1: Yt = h0b C^T, then *= exp(s_i) -------------------------------------------
             if (h0 && !bad) {
-                const int lnp = opaque(lane), l32 = lnp & 31, lh = lnp >> 5, il = it * 32 + l32;   // re-derived per phase
+                const int lnp = opaque(lane), l32 = lnp & 31, lh = lnp >> 5, it = RP ? (opaque(wave) & 1) : it0, il = it * 32 + l32;   // re-derived per phase
                 const bf16_t *cp = &sC[il * SP + 8 * lh];
 #pragma unroll
                 for (int kb = 0; kb < S; kb += S / 2) {   // fragments of half the state index per batch
@@ -890,8 +894,8 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
         } else if (wave != kTreeWave && !bad) {
             // ---- phase 2: Gt = B C^T (only when the C/B tiles are new), mask and decay -> M ----------
-            const int jt = (wave - 4) >> 1;
-            const int lnp = opaque(lane), l32 = lnp & 31, lh = lnp >> 5, il = it * 32 + l32;   // re-derived per phase
+            const int jt = ((RP ? opaque(wave) : wave) - 4) >> 1;   // (see it0)
+            const int lnp = opaque(lane), l32 = lnp & 31, lh = lnp >> 5, it = RP ? (opaque(wave) & 1) : it0, il = it * 32 + l32;   // re-derived per phase
             floatx16 &gt = acc[0];
             if (fresh_at(k, ch)) {
 #pragma unroll
@@ -957,7 +961,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             // ---- phase 3: Yt += Xt M^T over j <= i only (nodes i < 32 have no ancestor j >= 32:
             //      that quadrant of M is never written or read); y = Yt + D x ---------------------------
             bf16x4 yreg[YQ][4];
-            const int lnp = opaque(lane), l32 = lnp & 31, lh = lnp >> 5, il = it * 32 + l32;   // re-derived per phase
+            const int lnp = opaque(lane), l32 = lnp & 31, lh = lnp >> 5, it = RP ? (opaque(wave) & 1) : it0, il = it * 32 + l32;   // re-derived per phase
 #pragma unroll
             for (int q = 0; q < YQ; ++q) {
                 if (!live) break;
@@ -1044,7 +1048,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                         const int row = half * 16 + rr;
                         const uint4 v =
                             *reinterpret_cast<const uint4 *>(ys + row * 64 + ((rc ^ ((row >> 2) & 3)) * 16));
-                        const int node = it * 32 + row;
+                        const int node = (RP ? (opaque(wave) & 1) : it0) * 32 + row;
                         if (node < n)
                             store_through16(yb + (uint32_t)(node * H * P + pt * 32 + rc * 8) * 2u, v);
                     }
