@@ -118,6 +118,15 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
         const int idx = min(q * kThreads + tid, cb_items - 1);
         rc[q] = ((idx / s8) << 8) | (idx % s8);
     }
+    // Per-thread tile coordinates are loop invariants: left alone, the compiler hoists every LDS and
+    // global address derived from them out of the pair loop, runs out of registers and spills them,
+    // and each reload is followed by a wait for everything in flight (some thirty serial round trips
+    // per row block in the 256-node configuration).  The movers below therefore derive their
+    // addresses from a copy of the coordinates that the compiler cannot see through.
+    auto opaque = [](int v) {
+        asm volatile("" : "+v"(v));
+        return v;
+    };
     auto load_rows = [&](uint4 (&r)[kMaxS32], const bf16_t *base, long sn, int row0) {
 #pragma unroll
         for (int q = 0; q < kMaxS32; ++q) {
@@ -129,9 +138,10 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
 #pragma unroll
         for (int q = 0; q < kMaxS32; ++q) {
             if (q * kThreads + tid < cb_items) {
+                const int rcq = opaque(rc[q]);
                 uint4 v = r[q];
-                if (row0 + (rc[q] >> 8) >= n) v = make_uint4(0, 0, 0, 0);
-                *reinterpret_cast<uint4 *>(&tile[(rc[q] >> 8) * SP + (rc[q] & 0xff) * 8]) = v;
+                if (row0 + (rcq >> 8) >= n) v = make_uint4(0, 0, 0, 0);
+                *reinterpret_cast<uint4 *>(&tile[(rcq >> 8) * SP + (rcq & 0xff) * 8]) = v;
             }
         }
     };
@@ -146,7 +156,7 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
     auto store_x = [&](int row0) {
 #pragma unroll
         for (int q = 0; q < XQ; ++q) {
-            const int idx = q * kThreads + tid;
+            const int idx = q * kThreads + opaque(tid);
             uint4 v = xreg[q];
             if (row0 + idx / (P / 8) >= n) v = make_uint4(0, 0, 0, 0);
             // (every lane of the wave is here: kBlk * P/8 is a multiple of the workgroup size)
@@ -246,13 +256,13 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
                 if (SH && ib > 0) {    // the state tile again (from L2)
 #pragma unroll
                     for (int q = 0; q < kH0Batch; ++q) {
-                        const int idx = min(q * kThreads + tid, h_items - 1);
+                        const int idx = min(q * kThreads + opaque(tid), h_items - 1);
                         hreg[q] = *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4);
                     }
                 }
 #pragma unroll
                 for (int q = 0; q < kH0Batch; ++q) {
-                    const int idx = q * kThreads + tid;
+                    const int idx = q * kThreads + opaque(tid);
                     if (idx < h_items) store_h(idx, hreg[q], one);
                 }
                 for (int idx = kH0Batch * kThreads + tid; idx < h_items; idx += kThreads)
