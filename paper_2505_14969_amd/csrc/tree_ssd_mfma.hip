@@ -177,6 +177,7 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
     // ---- requests that do not depend on the tree: the small per-node values first (loads return
     //      in order, and the tree index needs only these), then h0 and the tiles of pair (0, 0) ----
     const float A_h = A[h];
+    const float D_h = D ? D[h] : 0.f;          // (asked for here: after the tree index its latency is exposed)
     const float dt_i = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
     const int parent_i = tid < n ? parent[(size_t)b * n + tid] : -1;
     if (h0) {
@@ -217,7 +218,6 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
     __syncthreads();
     STREE_PHASE_CLOCK(3);
     const uint32_t nz = __builtin_amdgcn_readfirstlane(nz_bits);
-    const float D_h = D ? D[h] : 0.f;
 
     // first column block of row block ib, and the one after jb (the diagonal block is always taken)
     auto next_col = [&](int ib, int after) {
