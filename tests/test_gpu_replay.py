@@ -187,3 +187,38 @@ def test_conv_replay_matches_commit_then_conv(st, oracle, io, W, N, Np):
     plain = st.stree_tree_conv(to_dev(p[1:2]), to_dev(xbc[1:2], io), to_dev(cs[1:2], io), to_dev(w, io),
                                to_dev(bias, io), H, P, S, G, silu=True)
     assert np.array_equal(to_host(got2)[1], to_host(plain)[0])
+
+
+@pytest.mark.parametrize("B", [33, 96])
+def test_fused_kernel_equals_commit_then_scan_at_large_batches(st, B):
+    """Runs of 6 to 15 units per workgroup, and a unit count that does not divide over the eight
+    XCDs: the fused kernel against stree_commit_state followed by stree_tree_ssd on the same
+    device inputs (the replay arithmetic is the same chain of fp32 FMAs in path order in both)."""
+    import torch
+    N, H, P, S, G = 64, 80, 64, 128, 1
+    rng = np.random.default_rng(900 + B)
+    parent = np.stack([synth.gen_tree(N, int(rng.integers(4, 9)), 4, rng) for _ in range(B)]).astype(np.int32)
+    pparent = np.roll(parent, 1, 0).copy()
+    acc = rng.integers(-1, N, size=B).astype(np.int32)
+    dev = torch.device("cuda")
+    gen = torch.Generator(device=dev).manual_seed(901 + B)
+
+    def randn(*shape):
+        return torch.randn(shape, device=dev, generator=gen)
+
+    x, px = randn(B, N, H, P).bfloat16(), randn(B, N, H, P).bfloat16()
+    Bm, pB, Cm = randn(B, N, G, S).bfloat16(), randn(B, N, G, S).bfloat16(), randn(B, N, G, S).bfloat16()
+    dt = torch.rand((B, N, H), device=dev, generator=gen) * 0.1 + 0.01
+    pdt = torch.rand((B, N, H), device=dev, generator=gen) * 0.1 + 0.01
+    A = -torch.rand(H, device=dev, generator=gen) - 0.5
+    D = randn(H)
+    h0 = randn(B, H, P, S) * 0.1
+    tp, tpp, tacc = to_dev(parent), to_dev(pparent), to_dev(acc)
+    y1, h1 = st.stree_tree_ssd_replay(tpp, tacc, px, pdt, pB, tp, x, dt, A, Bm, Cm, D, h0)
+    h2, _ = st.stree_commit_state(tpp, tacc, px, pdt, A, pB, h0)
+    y2 = st.stree_tree_ssd(tp, x, dt, A, Bm, Cm, D, h2)
+    torch.cuda.synchronize()
+    eh = ((h1 - h2).abs().max() / h2.abs().max()).item()
+    ey = ((y1.float() - y2.float()).abs().max() / y2.float().abs().max()).item()
+    assert eh <= 1e-6, f"state: {eh}"
+    assert ey <= TOL["bf16"], f"y: {ey}"
