@@ -145,6 +145,33 @@ __device__ __forceinline__ void store_stream16(void *p, uint4 v) {
     __builtin_nontemporal_store(vv, reinterpret_cast<u32x4 *>(p));
 }
 
+// Output stores that write through L2 (system scope) with the streaming hint: y and the replayed
+// state are never read again by this kernel, and lines left dirty in the eight L2s would all be
+// written back at once when the kernel ends.  (Measured on the 64-node / 80-head / batch-16 shape:
+// the hint on these stores and on the h0 loads takes the scan from 18.4 to 15.8 us and the fused
+// replay + scan from 33.2 to 27.6 us; on the x loads, whose lines the replay of the next step's
+// kernel reads again, it costs time.)  The store is inline assembly, so the compiler does not know that it reads
+// four data registers after issue: the trailing s_nop keeps the next instruction from overwriting
+// them in that window (the wait states a store of more than 8 bytes needs).
+__device__ __forceinline__ void store_through16(void *p, uint4 v) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 vv = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(vv) : "memory");
+}
+
+// 16-byte store that writes through L2 to memory (system scope) and keeps the default temporal
+// policy: for an output that the next kernel reads.  The line stays in L2 for that reader, but not
+// dirty: lines left dirty are all written back when the kernel ends, and the kernel is not over
+// until they are.  (Measured on the 64-node / 80-head / batch-16 conv: 8.7 -> 7.5 us, and the scan
+// behind it is none the slower; with the streaming hint added the scan loses what the conv wins.)
+// Inline assembly: the compiler has no builtin for these cache bits; the trailing s_nop keeps the
+// next instruction from overwriting the four data registers while the store still reads them.
+__device__ __forceinline__ void store_written_through16(void *p, uint4 v) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 vv = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(vv) : "memory");
+}
+
 // Four-tap conv of 8 bf16 channels on the packed dot unit (v_dot2c_f32_bf16: d += a.lo b.lo + a.hi b.hi):
 //   a[e] += w[e][3] r0[e] + w[e][2] r1[e] + w[e][1] r2[e] + w[e][0] r3[e]
 // r0 = the node's own row, r1..r3 its first three ancestors (8 bf16 each); ww = the 32 weights as 16

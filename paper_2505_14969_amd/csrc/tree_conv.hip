@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
             for (int e = 0; e < VEC; ++e)   // z * sigmoid(z); hardware reciprocal (1 ulp) instead of a division
                 acc[e] = acc[e] * __builtin_amdgcn_rcpf(1.f + __expf(-acc[e]));
         }
-        *reinterpret_cast<uint4 *>(out + ((size_t)b * n + i) * Cc + c0) = Vec16<T>::pack(acc);
+        store_written_through16(out + ((size_t)b * n + i) * Cc + c0, Vec16<T>::pack(acc));
     }
 }
 

@@ -92,20 +92,6 @@ struct ConvArgs {
 };
 constexpr int kCW = 4;            // conv width of the one-launch step (other widths take the two-kernel route)
 
-// Output stores that write through L2 (system scope) with the streaming hint: y and the replayed
-// state are never read again by this kernel, and lines left dirty in the eight L2s would all be
-// written back at once when the kernel ends.  (Measured on the 64-node / 80-head / batch-16 shape:
-// the hint on these stores and on the h0 loads takes the scan from 18.4 to 15.8 us and the fused
-// replay + scan from 33.2 to 27.6 us; on the x loads, whose lines the replay of the next step's
-// kernel reads again, it costs time.)  The store is inline assembly, so the compiler does not know that it reads
-// four data registers after issue: the trailing s_nop keeps the next instruction from overwriting
-// them in that window (the wait states a store of more than 8 bytes needs).
-__device__ __forceinline__ void store_through16(void *p, uint4 v) {
-    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 vv = {v.x, v.y, v.z, v.w};
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(vv) : "memory");
-}
-
 // 16-byte store with the default cache policy, as inline assembly (see store_through16 for the
 // trailing s_nop): for rows that this kernel reads back through L2.
 __device__ __forceinline__ void store_plain16(void *p, uint4 v) {
