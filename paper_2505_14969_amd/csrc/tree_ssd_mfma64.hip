@@ -805,31 +805,57 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     step(b2, h2);
     int b3 = b2, h3 = h2;
     step(b3, h3);
-    // the first loads of every role, before anything is waited for
-    if (isY) {
-        if constexpr (!CV) {
-            if (h0) load_H(b1, h1);
-        }
-    } else {
-        if constexpr (!CV) load_X(b1, h1);
-        if (wave == kTreeWave) {
-            load_T(b1, h1);
-            if constexpr (RP) load_R(b1, h1);
-        }
-    }
-    STREE_EXIT_POINT(2);
-    if constexpr (CV) {
-        conv_prologue();
-        if (!isY) load_X(b1, h1);
-    }
-
     // One accumulator set serves both roles: the Y waves' Yt tiles of the current unit, or
     // (acc[0]) the G waves' Gt tile of the current (sequence, group), kept across its heads.
     floatx16 acc[YQ];
+
+    // the first loads of every role, before anything is waited for.  With the replay the first
+    // state tile is the exception (kLateH0): it is asked for once the tree wave has requested the
+    // path rows of unit 0.  The replay of unit 0 is two dependent round trips (the previous tree's
+    // parents and step sizes, then the rows of the path), and behind 16 KB of state per thread
+    // group and workgroup each of them takes several times as long, while the first scan waits for
+    // them all the same.
+    constexpr bool kLateH0 = RP && !CV;
+    if constexpr (kLateH0) {
 #pragma unroll
-    for (int q = 0; q < YQ; ++q)
+        for (int q = 0; q < YQ; ++q)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+            for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+        if (!isY) {
+            load_X(b1, h1);
+            if (wave == kTreeWave) {
+                load_T(b1, h1);
+                load_R(b1, h1);
+            }
+        }
+        if (wave == kTreeWave) path_R(acc[0], b1, h1);
+        __syncthreads();                                      // the path rows of unit 0 are requested
+        if (isY) {
+            if (h0) load_H(b1, h1);
+        }
+        STREE_EXIT_POINT(2);
+    } else {
+        if (isY) {
+            if constexpr (!CV) {
+                if (h0) load_H(b1, h1);
+            }
+        } else {
+            if constexpr (!CV) load_X(b1, h1);
+            if (wave == kTreeWave) {
+                load_T(b1, h1);
+                if constexpr (RP) load_R(b1, h1);
+            }
+        }
+        STREE_EXIT_POINT(2);
+        if constexpr (CV) {
+            conv_prologue();
+            if (!isY) load_X(b1, h1);
+        }
+#pragma unroll
+        for (int q = 0; q < YQ; ++q)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+    }
 
     for (int k = -1; k < nU; ++k) {
         const bool live = k >= 0;                             // false in the staging-only first pass
@@ -1051,7 +1077,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             if constexpr (RP) {
                 if (wave == kTreeWave) {
                     if (!live) {                           // unit 0: path and rows within this pass
-                        path_R(acc[0], b1, h1);
+                        if constexpr (!kLateH0) path_R(acc[0], b1, h1);   // (else: done before the loop)
                         if (more2) load_R(b2, h2);
                     }
                     write_R(acc[0], rbuf);                 // (waits for the row loads issued in the scan half)
