@@ -829,6 +829,9 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
         }
         if (wave == kTreeWave) path_R(acc[0], b1, h1);
+        // the state of unit 1 (carried by the G threads) goes out now, while nothing else uses the
+        // memory system; the tree wave asks for its share after its path rows
+        if (!isY && h0 && nU > 1) load_H(b2, h2);
         __syncthreads();                                      // the path rows of unit 0 are requested
         if (isY) {
             if (h0) load_H(b1, h1);
@@ -1103,7 +1106,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 stage_H(rbuf, b1, h1);
                 if (more3) load_H(b3, h3);
             }
-            if (more2 && !live && h0) load_H(b2, h2);      // unit 1: the first odd unit
+            if (!kLateH0 && more2 && !live && h0) load_H(b2, h2);      // unit 1: the first odd unit (kLateH0: before the loop)
             if (!live) STREE_MARK_POINT(43, 256);
             if (!live) STREE_MARK_POINT(44, 384);
             if (live) STREE_MARK_POINT(53 + 10 * k, 256);
