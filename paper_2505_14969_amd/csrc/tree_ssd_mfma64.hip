@@ -980,7 +980,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
 #pragma unroll
             for (int q = 0; q < YQ; ++q) {
                 if (!live) break;
-                const int pt = (wave + 4 * q) >> 1;
+                const int pt = ((RP ? opaque(wave) : wave) + 4 * q) >> 1;   // (see it0)
                 float xv[16];   // x[i][p] of this lane's node for the 16 p of its accumulator
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg)
