@@ -169,8 +169,8 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
         rows[(n + m - 1) * kConvVecs + v] = r;
         if constexpr (RP) {   // the new conv state, oldest first: row W-1-m
             if (has_c)
-                *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(R.conv_state_out) +
-                                           ((size_t)b * (W - 1) + (W - 1 - m)) * Cc + c0) = r;
+                store_written_through16(reinterpret_cast<T *>(R.conv_state_out) +
+                                            ((size_t)b * (W - 1) + (W - 1 - m)) * Cc + c0, r);
         }
     }
     __syncthreads();
