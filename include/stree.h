@@ -45,15 +45,15 @@ enum stree_status {
     STREE_ERR_BAD_SHAPE = 2,  /* a dimension is outside the envelope */
     STREE_ERR_BAD_DTYPE = 3,  /* unknown io_dtype / unsupported state_dtype */
     STREE_ERR_BAD_STRIDE = 4, /* a token stride is smaller than its row */
-    STREE_ERR_HIP = 5         /* a HIP launch failed */
+    STREE_ERR_HIP = 5,        /* a HIP launch failed */
+    STREE_ERR_BAD_ALIAS = 6   /* an output overlaps an input that the same call still reads */
 };
 
 enum stree_dtype { STREE_F32 = 0, STREE_BF16 = 1 };
 
 enum stree_flags {
     STREE_FLAG_CONV_SILU = 1,    /* tree_conv applies z * sigmoid(z) */
-    STREE_FLAG_FORCE_FMA = 256,  /* tree_ssd: use the plain fp32-FMA kernel even where MFMA applies */
-    STREE_FLAG_ONE_LAUNCH = 512  /* tree_step: conv, replay and scan in a single kernel where the shape allows */
+    STREE_FLAG_FORCE_FMA = 256   /* tree_ssd: use the plain fp32-FMA kernel even where MFMA applies */
 };
 
 /* Problem sizes.  POD, host memory. */
@@ -76,6 +76,17 @@ typedef struct stree_dims {
 
 int stree_version(void);
 const char *stree_status_string(int status);
+
+/*
+ * Device scratch that the entry points below would need for a problem of these sizes
+ * (the problem statement of Sec. 3 "Formalization" fixes the operands; this call sizes
+ * what the library needs beyond them).  Every intermediate of every kernel -- the tree
+ * index, the decay-weighted mask, the state tile -- lives in LDS or registers, so the
+ * answer is 0 for every valid `dims`, and no entry point takes a workspace argument.
+ * Invalid `dims` (NULL, unknown dtype, a dimension outside the envelope) return
+ * (size_t)-1.  conv_width and flags are not looked at.  Launches nothing.
+ */
+size_t stree_workspace_bytes(const stree_dims *dims);
 
 /*
  * Tree structure (the tree mask L of Sec. 3 "Formalization", in index form).
@@ -207,7 +218,7 @@ int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, con
                            int32_t *tree_status, int32_t *replay_status, void *hip_stream);
 
 /*
- * One decoding step of the layer in one launch: stree_tree_conv_replay followed by
+ * One decoding step of the layer behind one call: stree_tree_conv_replay followed by
  * stree_tree_ssd_replay on the column ranges of its output (Sec. 3: tree conv, tree
  * scan; Alg. 1: replay at the start of the next iteration), with the same results:
  *   xbc_out        io [B,N,Cc]: conv output; x = columns [0, H*P), B = the next G*S,
@@ -219,12 +230,15 @@ int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, con
  *                  the previous step's xbc_out (strides in prev), prev_xbc_pre its
  *                  pre-conv rows [B, prev->nnodes, Cc]
  *   tree_status, replay_status  as in stree_tree_ssd_replay
- * By default the two entry points above run back to back on the stream (the faster
- * route on MI355X).  With STREE_FLAG_ONE_LAUNCH the whole step is a single kernel
- * for the shapes of a decoding step (both trees of at most 64 nodes, bf16, conv width
- * 4, the MFMA head shapes, 16-byte aligned pointers): every workgroup then convolves
- * the columns its own units need in front of its scan.  Same results bit for bit;
- * other shapes ignore the flag.
+ * xbc_out must NOT overlap prev->x or prev->Bm: the conv overwrites xbc_out before the
+ * replay reads the previous step's rows, so a caller that ping-pongs conv outputs needs
+ * two buffers.  The overlap is detected on the host and returns STREE_ERR_BAD_ALIAS
+ * with nothing launched.  (The same holds for a caller that makes the two calls itself;
+ * there the library cannot see it.)
+ * The two kernels run back to back on the stream.  A single kernel that also convolves
+ * was built and measured on MI355X at 1.5 x the time of the two (every workgroup has to
+ * redo the B / C columns of its group, or wait for another workgroup of the same launch):
+ * it is not part of the library.
  */
 int stree_tree_step(const stree_dims *dims, const stree_replay *prev, const void *prev_xbc_pre,
                     const int32_t *parent, const void *xbc_pre, const void *conv_state,

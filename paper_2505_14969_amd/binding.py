@@ -20,7 +20,6 @@ LIB_PATH = os.path.join(_HERE, "libstree.so")
 F32, BF16 = 0, 1
 FLAG_CONV_SILU = 1
 FLAG_FORCE_FMA = 256
-FLAG_ONE_LAUNCH = 512
 MAX_NODES = 256
 
 
@@ -58,6 +57,8 @@ def load() -> C.CDLL:
         lib.stree_version.restype = C.c_int
         lib.stree_status_string.restype = C.c_char_p
         lib.stree_status_string.argtypes = [C.c_int]
+        lib.stree_workspace_bytes.restype = C.c_size_t
+        lib.stree_workspace_bytes.argtypes = [C.POINTER(StreeDims)]
         dp = C.POINTER(StreeDims)
         lib.stree_tree_index.argtypes = [dp] + [_VP] * 6
         lib.stree_tree_conv.argtypes = [dp] + [_VP] * 8
@@ -106,6 +107,11 @@ def make_dims(batch, nnodes, nheads, headdim, dstate, ngroups, conv_width=0, io_
               x_stride_n=0, b_stride_n=0, c_stride_n=0) -> StreeDims:
     return StreeDims(batch, nnodes, nheads, headdim, dstate, ngroups, conv_width, io_dtype, F32, flags,
                      x_stride_n, b_stride_n, c_stride_n)
+
+
+def stree_workspace_bytes(d: StreeDims) -> int:
+    """Device scratch the entry points need for these sizes: 0 for every valid shape."""
+    return int(load().stree_workspace_bytes(C.byref(d)))
 
 
 def _check(rc: int, where: str):
@@ -250,11 +256,10 @@ def stree_tree_step(prev_parent, prev_accepted, prev_xbc_pre, prev_xbc_out, prev
                     xbc_out: Optional[torch.Tensor] = None, conv_state_out: Optional[torch.Tensor] = None,
                     h_out: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
                     status: Optional[torch.Tensor] = None, replay_status: Optional[torch.Tensor] = None,
-                    force_fma: bool = False, one_launch: bool = False):
+                    force_fma: bool = False):
     """One decoding step in one call: tree conv (seeded by the conv state after the previous tree's
     accepted path), state replay along that path and tree scan.  prev_xbc_out is the previous step's
-    conv output [B,Np,Cc] (its x and B columns are replayed).  one_launch: a single kernel where
-    the shape allows (same results; slower than the default two kernels on MI355X).
+    conv output [B,Np,Cc] (its x and B columns are replayed; it must not be xbc_out).
     -> (y [B,N,H,P], h_out [B,H,P,S] f32, xbc_out [B,N,Cc], conv_state_out [B,W-1,Cc])."""
     B, N, Cc = xbc_pre.shape
     W = conv_w.shape[1]
@@ -274,8 +279,7 @@ def stree_tree_step(prev_parent, prev_accepted, prev_xbc_pre, prev_xbc_out, prev
         out = torch.empty((B, N, H, P), dtype=xbc_pre.dtype, device=xbc_pre.device)
     assert xbc_out.is_contiguous() and out.is_contiguous() and h_out.is_contiguous()
     assert conv_state_out.data_ptr() != conv_state.data_ptr()
-    flags = ((FLAG_CONV_SILU if silu else 0) | (FLAG_FORCE_FMA if force_fma else 0) |
-             (FLAG_ONE_LAUNCH if one_launch else 0))
+    flags = (FLAG_CONV_SILU if silu else 0) | (FLAG_FORCE_FMA if force_fma else 0)
     d = make_dims(B, N, H, P, S, G, W, _io_code(xbc_pre), flags)
     prev_B = prev_xbc_out[:, :, H * P:H * P + G * S]
     r = StreeReplay(Np, 0, prev_parent.data_ptr(), prev_accepted.data_ptr(), prev_xbc_out.data_ptr(),

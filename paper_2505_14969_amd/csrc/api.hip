@@ -41,11 +41,27 @@ int resolve_strides(stree_dims &d) {
 
 int hip_status(hipError_t e) { return e == hipSuccess ? STREE_OK : STREE_ERR_HIP; }
 
+// true when the byte ranges [a, a + na) and [b, b + nb) share a byte
+bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+// bytes spanned by `rows` rows of `row` elements that lie `stride` elements apart
+size_t span_bytes(int64_t rows, int64_t stride, int64_t row, size_t elem) {
+    return rows > 0 ? (size_t)((rows - 1) * stride + row) * elem : 0;
+}
+
 }  // namespace
 
 extern "C" {
 
-int stree_version(void) { return 1; }
+int stree_version(void) { return 2; }
+
+size_t stree_workspace_bytes(const stree_dims *dims) {
+    // every intermediate of every kernel lives in LDS or registers: no entry point needs device scratch
+    return check_dims(dims, kNoConv) == STREE_OK ? 0 : (size_t)-1;
+}
 
 const char *stree_status_string(int status) {
     switch (status) {
@@ -55,6 +71,7 @@ const char *stree_status_string(int status) {
         case STREE_ERR_BAD_DTYPE: return "unknown io_dtype or unsupported state_dtype";
         case STREE_ERR_BAD_STRIDE: return "a token stride is smaller than its row";
         case STREE_ERR_HIP: return "a HIP call failed";
+        case STREE_ERR_BAD_ALIAS: return "an output overlaps an input that the same call still reads";
     }
     return "unknown status";
 }
@@ -140,7 +157,7 @@ int stree_tree_ssd_replay(const stree_dims *dims, const stree_replay *prev, cons
     if (rc) return rc;
     if (d.batch == 0) return STREE_OK;
     hipStream_t st = (hipStream_t)hip_stream;
-    if (!(d.flags & STREE_FLAG_FORCE_FMA) && stree::tree_ssd_replay_fused_supported(d, dp, prev->x, prev->Bm, x, Bm, Cm, y))
+    if (!(d.flags & STREE_FLAG_FORCE_FMA) && stree::tree_ssd_replay_fused_supported(d, dp, prev->x, prev->Bm, x, Bm, Cm, y, h0, h_out))
         return hip_status(stree::launch_tree_ssd_replay_fused(d, dp, prev->parent, prev->accepted, prev->x, prev->dt,
                                                               prev->Bm, parent, x, dt, A, Bm, Cm, D, h0, h_out, y,
                                                               tree_status, replay_status, st));
@@ -192,14 +209,14 @@ int stree_tree_step(const stree_dims *dims, const stree_replay *prev, const void
     rc = resolve_strides(dp);
     if (rc) return rc;
     if (d.batch == 0) return STREE_OK;
-    hipStream_t st = (hipStream_t)hip_stream;
-    if ((d.flags & STREE_FLAG_ONE_LAUNCH) && !(d.flags & STREE_FLAG_FORCE_FMA) &&
-        stree::tree_step_fused_supported(d, dp, prev->x, prev->Bm, xbc_pre, prev_xbc_pre, conv_state, conv_w, conv_b,
-                                         xbc_out, conv_state_out, y))
-        return hip_status(stree::launch_tree_step_fused(d, dp, prev->parent, prev->accepted, prev->x, prev->dt,
-                                                        prev->Bm, prev_xbc_pre, parent, xbc_pre, conv_state, conv_w,
-                                                        conv_b, xbc_out, conv_state_out, dt, A, D, h0, h_out, y,
-                                                        tree_status, replay_status, st));
+    {   // the conv overwrites xbc_out before the replay reads the previous step's x / B rows
+        const size_t e = d.io_dtype == STREE_BF16 ? 2 : 4;
+        const size_t out_bytes = (size_t)d.batch * d.nnodes * (size_t)Cc * e;
+        const int64_t prows = (int64_t)d.batch * dp.nnodes;
+        if (ranges_overlap(xbc_out, out_bytes, prev->x, span_bytes(prows, dp.x_stride_n, (int64_t)d.nheads * d.headdim, e)) ||
+            ranges_overlap(xbc_out, out_bytes, prev->Bm, span_bytes(prows, dp.b_stride_n, (int64_t)d.ngroups * d.dstate, e)))
+            return STREE_ERR_BAD_ALIAS;
+    }
     rc = stree_tree_conv_replay(dims, prev, prev_xbc_pre, parent, xbc_pre, conv_state, conv_w, conv_b, xbc_out,
                                 conv_state_out, tree_status, replay_status, hip_stream);
     if (rc) return rc;
@@ -223,7 +240,7 @@ int stree_linear_ssd(const stree_dims *dims, const void *x, const float *dt, con
     if (!x || !dt || !A || !Bm || !h_out || (y && !Cm)) return STREE_ERR_NULL_ARG;
     rc = resolve_strides(d);
     if (rc) return rc;
-    if (!stree::linear_ssd_supported(d, x, Bm, Cm, y)) return STREE_ERR_BAD_SHAPE;
+    if (!stree::linear_ssd_supported(d, x, Bm, Cm, y, h0, h_out)) return STREE_ERR_BAD_SHAPE;
     if (d.batch == 0) return STREE_OK;
     return hip_status(stree::launch_linear_ssd(d, x, dt, A, Bm, Cm ? Cm : Bm, D, h0, y, h_out,
                                                (hipStream_t)hip_stream));

@@ -15,20 +15,29 @@ constexpr int kPathChunk = 16;     // path nodes staged in LDS at a time
 
 // conv tail: out row r (oldest first) = pre-conv row of the (W-2-r)-th ancestor of k, or the old
 // state row once above the root.  One workgroup covers VEC*256 channels of one sequence.
+// `status` (null unless the call has no state part, whose workgroups report otherwise): the first
+// channel block of a sequence writes 0, the first bad node + 1, or -1 for an accepted index
+// outside [-1, n).
 template <typename T, int VEC>
 __device__ __forceinline__ void conv_tail(int b, int cblk, const int32_t *__restrict__ parent,
                                           const int32_t *__restrict__ accepted, int n, int Cc, int W,
-                                          const T *__restrict__ xbc_pre, const T *conv_state, T *conv_state_out) {
+                                          const T *__restrict__ xbc_pre, const T *conv_state, T *conv_state_out,
+                                          int32_t *__restrict__ status) {
     __shared__ int par[kMaxNodes];
+    __shared__ int first_bad;
     const int tid = threadIdx.x;
+    if (tid == 0) first_bad = 0x7fffffff;
+    __syncthreads();
     int ok = 1;
     if (tid < n) {
         const int p = parent[(size_t)b * n + tid];
         ok = (tid == 0) ? (p == -1) : (p >= 0 && p < tid);
         par[tid] = ok ? p : -1;
+        if (!ok) atomicMin(&first_bad, tid + 1);
     }
     const int any_bad = __syncthreads_or(!ok);
     const int k = accepted[b];
+    if (status && cblk == 0 && tid == 0) status[b] = any_bad ? first_bad : ((k < -1 || k >= n) ? -1 : 0);
     const int c0 = (cblk * kThreads + tid) * VEC;
     if (c0 >= Cc) return;
     const bool pass = any_bad || k < 0 || k >= n;
@@ -89,7 +98,7 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
         if (idx < ct.cblocks * ct.batch)
             conv_tail<T, 16 / (int)sizeof(T)>(idx / ct.cblocks, idx % ct.cblocks, parent, accepted, n, ct.Cc, ct.W,
                                               (const T *)ct.xbc_pre, (const T *)ct.conv_state,
-                                              (T *)ct.conv_state_out);
+                                              (T *)ct.conv_state_out, ct.state_z == 0 ? status : nullptr);
         return;
     }
     extern __shared__ __align__(16) float rows[];     // xs[kPathChunk][P] then bs[kPathChunk][S]

@@ -7,7 +7,7 @@
 
 namespace stree {
 
-constexpr int kThreads = 256;  // every kernel here runs 256-thread workgroups (4 waves)
+constexpr int kThreads = 256;  // workgroup size of the kernels that do not set their own (the persistent scan runs 512)
 constexpr int kMaxNodes = STREE_MAX_NODES;
 constexpr int kMaxWords = kMaxNodes / 32;
 

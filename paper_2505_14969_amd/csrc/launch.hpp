@@ -40,28 +40,17 @@ hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, co
 
 // fused replay + scan: `dp` describes the previous tree (its node count and strides)
 bool tree_ssd_replay_fused_supported(const stree_dims &d, const stree_dims &dp, const void *px, const void *pB,
-                                     const void *x, const void *Bm, const void *Cm, const void *y);
+                                     const void *x, const void *Bm, const void *Cm, const void *y, const float *h0,
+                                     const float *h_out);
 hipError_t launch_tree_ssd_replay_fused(const stree_dims &d, const stree_dims &dp, const int32_t *pparent,
                                         const int32_t *paccepted, const void *px, const float *pdt, const void *pB,
                                         const int32_t *parent, const void *x, const float *dt, const float *A,
                                         const void *Bm, const void *Cm, const float *D, const float *h0,
                                         float *h_out, void *y, int32_t *status, int32_t *rstatus, hipStream_t st);
 
-// conv + replay + scan in one launch (x / B / C are column ranges of xbc_out; d's strides = Cc)
-bool tree_step_fused_supported(const stree_dims &d, const stree_dims &dp, const void *px, const void *pB,
-                               const void *xbc_pre, const void *prev_xbc_pre, const void *conv_state,
-                               const void *conv_w, const void *conv_b, const void *xbc_out,
-                               const void *conv_state_out, const void *y);
-hipError_t launch_tree_step_fused(const stree_dims &d, const stree_dims &dp, const int32_t *pparent,
-                                  const int32_t *paccepted, const void *px, const float *pdt, const void *pB,
-                                  const void *prev_xbc_pre, const int32_t *parent, const void *xbc_pre,
-                                  const void *conv_state, const void *conv_w, const void *conv_b, void *xbc_out,
-                                  void *conv_state_out, const float *dt, const float *A, const float *D,
-                                  const float *h0, float *h_out, void *y, int32_t *status, int32_t *rstatus,
-                                  hipStream_t st);
-
 // chunked causal scan of a long sequence (d.nnodes = T tokens)
-bool linear_ssd_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm, const void *y);
+bool linear_ssd_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm, const void *y,
+                          const float *h0, const float *h_out);
 hipError_t launch_linear_ssd(const stree_dims &d, const void *x, const float *dt, const float *A, const void *Bm,
                              const void *Cm, const float *D, const float *h0, void *y, float *h_out, hipStream_t st);
 

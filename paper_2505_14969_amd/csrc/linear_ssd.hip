@@ -335,12 +335,14 @@ hipError_t launch_ps(const stree_dims &d, const void *x, const float *dt, const 
 
 }  // namespace
 
-bool linear_ssd_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm, const void *y) {
+bool linear_ssd_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm, const void *y,
+                          const float *h0, const float *h_out) {
     if (d.io_dtype != STREE_BF16) return false;
     const int P = d.headdim, S = d.dstate;
     if (!((P == 64 && (S == 128 || S == 64)) || (P == 128 && S == 128))) return false;
     if ((d.x_stride_n | d.b_stride_n | d.c_stride_n) % 8 != 0) return false;
-    return (((uintptr_t)x | (uintptr_t)Bm | (uintptr_t)Cm | (uintptr_t)y) % 16) == 0;
+    // (the state is read and written 16 bytes at a time, like the rows)
+    return (((uintptr_t)x | (uintptr_t)Bm | (uintptr_t)Cm | (uintptr_t)y | (uintptr_t)h0 | (uintptr_t)h_out) % 16) == 0;
 }
 
 hipError_t launch_linear_ssd(const stree_dims &d, const void *x, const float *dt, const float *A, const void *Bm,

@@ -1,6 +1,6 @@
 // stree_tree_conv: depthwise causal conv1d along each node's ancestor chain.
 //
-// A workgroup owns 16 channel vectors (16 bytes each) of one sequence and brings every row of
+// A workgroup owns 8 channel vectors (16 bytes each) of one sequence and brings every row of
 // that channel block into LDS once: the N pre-conv rows of the tree and, behind them, the W-1
 // rows "above the root".  Each thread then walks the ancestor chains of its nodes in LDS, so a
 // pre-conv element is fetched from memory exactly once however many descendants read it.
@@ -53,7 +53,7 @@ struct ConvReplay {          // previous tree (replay variant); parent == nullpt
     int pn;
 };
 
-// grid: B * ceil(Cc / (16 vectors)); dynamic LDS: (N + W - 1) rows of 256 bytes
+// grid: B * ceil(Cc / (8 vectors)); dynamic LDS: (N + W - 1) rows of 128 bytes
 template <typename T, int W, bool RP>
 __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
     const int32_t *__restrict__ parent, int n, int Cc, int silu, const T *__restrict__ xbc_pre,
@@ -237,10 +237,13 @@ static hipError_t launch_conv_t(const stree_dims &d, const int32_t *parent, cons
     const int silu = (d.flags & STREE_FLAG_CONV_SILU) ? 1 : 0;
 #define STREE_CONV_CASE(WW)                                                                                   \
     case WW:                                                                                                  \
-        if (lds > 48 * 1024) { /* beyond the default cap on dynamic LDS: raise it for this kernel */          \
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_conv_kernel<T, WW, RP>),   \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);         \
-            if (e != hipSuccess) return e;                                                                    \
+        if (lds > 48 * 1024) { /* beyond the default cap on dynamic LDS: raise it for this kernel, once,   */ \
+            /* to the most any tree in the envelope needs (thread-safe: a function-local static)          */ \
+            static const hipError_t raised = hipFuncSetAttribute(                                             \
+                reinterpret_cast<const void *>(&tree_conv_kernel<T, WW, RP>),                                 \
+                hipFuncAttributeMaxDynamicSharedMemorySize,                                                   \
+                (int)((kMaxNodes + WW - 1) * kConvVecs * sizeof(uint4)));                                     \
+            if (raised != hipSuccess) return raised;                                                          \
         }                                                                                                     \
         hipLaunchKernelGGL((tree_conv_kernel<T, WW, RP>), grid, dim3(kThreads), lds, st, parent, d.nnodes, Cc, \
                            silu, (const T *)xbc_pre, (const T *)conv_state, (const T *)conv_w,                \

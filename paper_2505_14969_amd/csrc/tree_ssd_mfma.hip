@@ -18,13 +18,10 @@
 // MFMA operand layout (32x32x16): lane l holds row (l % 32) of its operand and
 // the 8 contraction indices 8*(l/32)..+7; accumulator register r of lane l is
 // element [8*(r/4) + 4*(l/32) + r%4][l % 32].
+#include <mutex>
+
 #include "common.hpp"
 #include "launch.hpp"
-
-// Probe builds define this to record per-workgroup timestamps; product builds compile it away.
-#ifndef STREE_PHASE_CLOCK
-#define STREE_PHASE_CLOCK(k)
-#endif
 
 namespace stree {
 
@@ -173,7 +170,6 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
         *reinterpret_cast<bf16x4 *>(&sH[p * SP + s]) = o;
     };
 
-    STREE_PHASE_CLOCK(0);
     // ---- requests that do not depend on the tree: the small per-node values first (loads return
     //      in order, and the tree index needs only these), then h0 and the tiles of pair (0, 0) ----
     const float A_h = A[h];
@@ -191,12 +187,10 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
     load_rows(breg, Bb, b_sn, 0);
     load_x(0);
 
-    STREE_PHASE_CLOCK(1);
     // ---- tree index: depth, mask rows L_i, s_i = (A_tree)_i ---------------------------------
     if (tid == 0) nz_bits = 0u;
     const int bad = build_tree_index(tree, mask, parent_i, n, npad, words, dt_i, A_h);
     if (status && h == 0 && tid == 0) status[b] = bad;
-    STREE_PHASE_CLOCK(2);
     bf16_t *yb = y + (size_t)b * n * H * P + (size_t)h * P;
     if (bad) {
         for (int idx = tid; idx < n * (P / 8); idx += kThreads) {
@@ -216,7 +210,6 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
     float one = 1.0f;                        // (see store_h)
     asm volatile("" : "+v"(one));
     __syncthreads();
-    STREE_PHASE_CLOCK(3);
     const uint32_t nz = __builtin_amdgcn_readfirstlane(nz_bits);
 
     // first column block of row block ib, and the one after jb (the diagonal block is always taken)
@@ -309,7 +302,6 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
             load_x(njb * kBlk);
         }
         __syncthreads();
-        STREE_PHASE_CLOCK(4);
 
         // ---- phase 2: Gt = B * C^T; mask and decay -> M[i][j] as bf16 ------------------------
         {
@@ -342,7 +334,6 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
             }
         }
         __syncthreads();
-        STREE_PHASE_CLOCK(5);
 
         // ---- phase 3: Yt += Xt * M^T ------------------------------------------------------------
 #pragma unroll
@@ -363,7 +354,6 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
 
         // ---- after the diagonal block: fp32 Y rows staged over the B tile (its last reader was
         //      phase 2), D * x added from the X^T tile of this same block, bf16 rows stored -----
-        STREE_PHASE_CLOCK(6);
         if (jb == ib) {
 #pragma unroll
             for (int q = 0; q < YQ; ++q) {
@@ -400,7 +390,6 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
                 }
             }
         }
-        STREE_PHASE_CLOCK(7);
         if (!more) break;
         __syncthreads();   // every reader of the tiles is done before the next pair overwrites them
         new_rows = nib != ib;
@@ -427,12 +416,17 @@ static hipError_t launch_p(const stree_dims &d, const int32_t *parent, const voi
                            void *y, int32_t *status, hipStream_t st) {
     const int npad = (d.nnodes + kBlk - 1) / kBlk * kBlk;
     const size_t lds = mfma_lds_plan(P, d.dstate, npad, (d.nnodes + 31) / 32).total;
-    static size_t lds_set = 0;  // raise the dynamic-LDS limit once per size (64 KB is the default cap)
-    if (lds > lds_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_mfma_kernel<P, SH>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        lds_set = lds;
+    {   // raise the dynamic-LDS limit of this instantiation (64 KB is the default cap).  The limit only
+        // ever grows, under a lock, so a launch from another host thread never finds it lowered.
+        static std::mutex mu;
+        static size_t lds_set = 0;
+        std::lock_guard<std::mutex> hold(mu);
+        if (lds > lds_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_mfma_kernel<P, SH>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            lds_set = lds;
+        }
     }
     hipLaunchKernelGGL((tree_ssd_mfma_kernel<P, SH>), dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
                        d.nheads, d.dstate, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A,

@@ -28,22 +28,10 @@
 //     G: x(k+1) regs -> the other X^T tile in LDS, issue x(k+2) loads
 // so the big global loads (h0, x) are in flight for a whole unit period.
 //
-// Template flags: RP folds the commit of the previous tree into the state as it is loaded
-// (Alg. 1: replay at the start of the next iteration); CV also puts the tree conv of the
-// workgroup's own columns in front of the unit loop (the whole step in one launch).
-// Probe builds (timing harnesses outside the library) define the STREE_EXIT_* / STREE_MARK_*
-// hooks; in the library they compile to nothing.
+// Template flag RP folds the commit of the previous tree into the state as it is loaded
+// (Alg. 1: replay at the start of the next iteration).
 #include "common.hpp"
 #include "launch.hpp"
-
-#ifndef STREE_EXIT_POINT
-#define STREE_EXIT_INIT
-#define STREE_EXIT_POINT(n)
-#endif
-#ifndef STREE_MARK_POINT
-#define STREE_MARK_POINT(n, t)
-#endif
-
 
 namespace stree {
 
@@ -78,27 +66,6 @@ struct ReplayArgs {
     float *h_out;                       // [B, H, P, S]: the replayed state
     int32_t *status;                    // [B] or null
 };
-
-// The tree convolution in front of the scan (one-launch step variant only): x, B and C of the
-// kernel's arguments are then column ranges of xbc_out, which the kernel itself fills first.
-struct ConvArgs {
-    const bf16_t *xbc_pre;        // [B, n, Cc] pre-conv rows of this tree
-    const bf16_t *conv_state;     // [B, 3, Cc] conv state before the previous tree's accepted path
-    const bf16_t *w, *bias;       // [Cc, 4], [Cc] or null
-    const bf16_t *prev_xbc_pre;   // [B, pn, Cc] pre-conv rows of the previous tree
-    bf16_t *xbc_out;              // [B, n, Cc]
-    bf16_t *conv_state_out;       // [B, 3, Cc]
-    int Cc, silu;
-};
-constexpr int kCW = 4;            // conv width of the one-launch step (other widths take the two-kernel route)
-
-// 16-byte store with the default cache policy, as inline assembly (see store_through16 for the
-// trailing s_nop): for rows that this kernel reads back through L2.
-__device__ __forceinline__ void store_plain16(void *p, uint4 v) {
-    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 vv = {v.x, v.y, v.z, v.w};
-    asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 1" ::"v"(p), "v"(vv) : "memory");
-}
 
 // Wave-level tree index for n <= 64: lane i owns node i; pointer doubling with
 // cross-lane reads (ds_bpermute), no barriers.  Returns the status (uniform).
@@ -140,247 +107,6 @@ __device__ __forceinline__ int wave_tree_index(int lane, int n, int parent_i, fl
     return 0;
 }
 
-// ---- one-launch step: tree conv of a workgroup's columns, in front of the unit loop ----------------
-// Sub-tiles of 64 rows x 64 channels (8 vectors of 16 bytes), two items (row, vector) per G / T
-// thread.  A sub-tile's raw rows and, behind them, the kCW-1 rows above the root, the weights and
-// the bias go through an LDS buffer of 72 rows, where the ancestor chains are walked; the parent
-// of node i sits in lane i of every wave and is read across lanes.  Sub-tiles are taken in rounds
-// of up to six (same sequence; one LDS buffer each: the tiles the unit loop uses later), all loads
-// of a round in flight together, so that a workgroup with two or three units pays one or two
-// memory round trips.
-// The stores are inline assembly like the y stores: a store the compiler knows of would make it
-// wait, at the next barrier, for every load in flight -- in the Y threads, which only keep the
-// barrier count here, that is the first state tile.
-//
-// The G / T threads' part is a function of its own, not inlined: its registers are then allotted
-// apart from the unit loop's, which has none to spare (inlined, the pressure here pushed values
-// that live across the loop into scratch memory, and their reloads in the loop wait for the state
-// prefetch).
-struct ConvRounds {                  // iterator over the sub-tiles of a workgroup's units
-    int nU, H, G, P, S, hpg, ik, ib, ih, ipos, remaining;
-    __device__ __forceinline__ bool fresh(int k, int h) const { return k == 0 || h % hpg == 0; }
-    __device__ __forceinline__ void init(int nU_, int H_, int G_, int P_, int S_, int b0, int h0_) {
-        nU = nU_; H = H_; G = G_; P = P_; S = S_; hpg = H_ / G_; ik = 0; ib = b0; ih = h0_; ipos = 0;
-        remaining = 0;
-        int hh = h0_;
-        for (int k = 0; k < nU; ++k) {
-            remaining += P / 64 + (fresh(k, hh) ? 2 * (S / 64) : 0);
-            if (++hh == H) hh = 0;
-        }
-    }
-    // column of the iterator's sub-tile: for every unit, the B and C columns of its group when they
-    // are new to this workgroup, then the unit's x columns; advances
-    __device__ __forceinline__ void sub_col(int &col) {
-        const int nbc = fresh(ik, ih) ? 2 * (S / 64) : 0;
-        const int g = ih / hpg, HP = H * P, GS = G * S;
-        if (ipos < nbc) col = (ipos < S / 64) ? HP + g * S + ipos * 64 : HP + GS + g * S + (ipos - S / 64) * 64;
-        else col = ih * P + (ipos - nbc) * 64;
-        if (++ipos == nbc + P / 64) {
-            ipos = 0;
-            ++ik;
-            if (++ih == H) {
-                ih = 0;
-                ++ib;
-            }
-        }
-        --remaining;
-    }
-    static constexpr int kRS = 4;    // sub-tiles per round (at most six: one staging buffer each)
-    struct Round {
-        int b, cnt, c[kRS];          // sequence, live sub-tiles, their columns
-    };
-    __device__ __forceinline__ Round next_round() {   // up to kRS sub-tiles of one sequence
-        Round r;
-        r.b = ib;
-        r.cnt = 0;
-#pragma unroll
-        for (int i = 0; i < kRS; ++i) {
-            if (i == 0 || (r.cnt == i && remaining > 0 && ib == r.b)) {
-                sub_col(r.c[i]);
-                r.cnt = i + 1;
-            } else {
-                r.c[i] = r.c[0];     // (slots past cnt repeat a live one: loaded, not used)
-            }
-        }
-        return r;
-    }
-};
-
-// LDS pointers keep their address space across the call (plain pointers would turn every access
-// into a flat one); a plain vector type, since the HIP vector classes cannot be copied out of a
-// qualified address space in the host pass
-typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) u32x4_t lds_uint4;
-__device__ __forceinline__ uint4 lds_ld(const lds_uint4 *p) {
-    const u32x4_t v = *p;
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void lds_st(lds_uint4 *p, uint4 v) {
-    const u32x4_t q = {v.x, v.y, v.z, v.w};
-    *p = q;
-}
-
-template <int WPE>
-__device__ __noinline__ void conv_prologue_worker(
-    ConvRounds it, lds_uint4 *bufA0, lds_uint4 *bufA1, lds_uint4 *bufA2, lds_uint4 *bufB0, lds_uint4 *bufB1,
-    lds_uint4 *bufB2, const int32_t *__restrict__ parent, int n, ReplayArgs R, ConvArgs V, int rt_in) {
-    // bufA*, bufB*: two sets of three staging buffers (72 rows of 8 vectors each)
-    constexpr int kRowW = kB64 + kCW - 1, kRowBias = kRowW + kCW;
-    static_assert(kCW == 4, "three path nodes kept as scalars");
-    typedef ConvRounds::Round Round;
-    const int Cc = V.Cc;
-    int &remaining = it.remaining;
-    auto next_round = [&]() { return it.next_round(); };
-    auto opaque = [](int v) {
-        asm volatile("" : "+v"(v));
-        return v;
-    };
-    const int rt = rt_in, lane = rt_in & 63;
-    const int t = opaque(rt), v = t & 7, r0 = t >> 3;           // items: rows r0 and r0 + 32, vector v
-    const int ln = opaque(lane);
-    // per sequence: this tree's parents (lane i: node i; -1 for the root and for an invalid entry)
-    // and validity, the previous tree's validity, and its accepted path, at most kCW-1 nodes up
-    // from the accepted one (walked across lanes in the loaded parent vector -- dependent loads
-    // would each cost a memory round trip -- every step bounds-checked)
-    struct Batch {
-        int pv, bad, L, a0, a1, a2;
-    };
-    auto load_batch = [&](int b) __attribute__((always_inline)) {
-        Batch q;
-        const int sb = __builtin_amdgcn_readfirstlane(b);
-        const int pz = parent[(uint32_t)(sb * n + min(ln, n - 1))];
-        const int ppz = R.parent[(uint32_t)(sb * R.pn + min(ln, R.pn - 1))];
-        const int kp = R.accepted[sb];
-        int cur = (kp < -1 || kp >= R.pn) ? -1 : kp, cnt = 0;
-        q.a0 = q.a1 = q.a2 = 0;
-        auto up = [&](int &slot) {
-            const int nx = __builtin_amdgcn_readfirstlane(wave_read(ppz, max(cur, 0)));   // (all lanes take part)
-            if (cur >= 0) {
-                slot = cur;
-                ++cnt;
-                cur = (cur > 0 && nx >= 0 && nx < cur) ? nx : -1;
-            }
-        };
-        up(q.a0);
-        up(q.a1);
-        up(q.a2);
-        const bool ok = ln >= n || ((ln == 0) ? (pz == -1) : (pz >= 0 && pz < ln));
-        const bool pok = ln >= R.pn || ((ln == 0) ? (ppz == -1) : (ppz >= 0 && ppz < ln));
-        q.pv = (ok && ln < n) ? pz : -1;
-        q.bad = __ballot(!ok) ? 1 : 0;
-        q.L = __ballot(!pok) ? 0 : cnt;        // an invalid previous tree: nothing was accepted
-        return q;
-    };
-    // per thread and sub-tile: its two raw row vectors and one more vector that depends on its
-    // row slot r0: a row above the root (r0 < kCW-1), a weight vector (the next kCW slots) or
-    // the bias
-    struct SubRegs {
-        uint4 raw0, raw1, aux;
-    };
-    auto load_sub = [&](int b, int col, const Batch &bt) __attribute__((always_inline)) {
-        SubRegs q;
-        const int c0 = col + v * 8;
-        q.raw0 = *reinterpret_cast<const uint4 *>(V.xbc_pre + ((size_t)b * n + min(r0, n - 1)) * Cc + c0);
-        q.raw1 = *reinterpret_cast<const uint4 *>(V.xbc_pre + ((size_t)b * n + min(r0 + 32, n - 1)) * Cc + c0);
-        // weights of the 8 channels: kCW vectors from V.w + c0 * kCW.  (bias == null: a weight
-        // vector is loaded in its place and ignored; row slots past the bias load it as well)
-        const bf16_t *wp = V.w + (size_t)c0 * kCW;
-        // row m above the root (m = 1 newest): a path row if the path has at least m nodes, else
-        // the (m - L)-th newest row of the old conv state
-        const int m = min(r0 + 1, kCW - 1);
-        const int node = m == 1 ? bt.a0 : (m == 2 ? bt.a1 : bt.a2);
-        const bf16_t *src = (m <= bt.L) ? V.prev_xbc_pre + ((size_t)b * R.pn + node) * Cc + c0
-                                        : V.conv_state + ((size_t)b * (kCW - 1) + ((kCW - 1) - (m - bt.L))) * Cc + c0;
-        if (r0 >= kCW - 1) src = wp + min(r0 - (kCW - 1), kCW - 1) * 8;
-        if (r0 == 2 * kCW - 1 && V.bias) src = V.bias + c0;
-        q.aux = *reinterpret_cast<const uint4 *>(src);
-        return q;
-    };
-    // registers -> LDS buffer; the rows above the root are also the new conv state
-    auto stage_sub = [&](const SubRegs &q, lds_uint4 *buf, int b, int col) __attribute__((always_inline)) {
-        const uint32_t keep0 = r0 < n ? 0xffffffffu : 0u, keep1 = r0 + 32 < n ? 0xffffffffu : 0u;
-        lds_st(&buf[r0 * 8 + v], make_uint4(q.raw0.x & keep0, q.raw0.y & keep0, q.raw0.z & keep0, q.raw0.w & keep0));
-        lds_st(&buf[(r0 + 32) * 8 + v], make_uint4(q.raw1.x & keep1, q.raw1.y & keep1, q.raw1.z & keep1, q.raw1.w & keep1));
-        if (r0 < 2 * kCW) lds_st(&buf[(kB64 + r0) * 8 + v], q.aux);     // rows above the root (m = r0 + 1), weights, bias
-        if (r0 < kCW - 1)                                        // the new conv state, oldest first: row kCW-1-m
-            store_plain16(V.conv_state_out + ((size_t)b * (kCW - 1) + (kCW - 2 - r0)) * Cc + col + v * 8, q.aux);
-    };
-    // the two items of this thread in one staged sub-tile
-    auto conv_sub = [&](const lds_uint4 *buf, int b, int col, const Batch &bt) __attribute__((always_inline)) {
-        float bv[8];
-        {
-            const uint4 q = lds_ld(&buf[kRowBias * 8 + v]);
-            const float on = V.bias ? 1.f : 0.f;
-            bv[0] = on * bf16_lo(q.x); bv[1] = on * bf16_hi(q.x); bv[2] = on * bf16_lo(q.y); bv[3] = on * bf16_hi(q.y);
-            bv[4] = on * bf16_lo(q.z); bv[5] = on * bf16_hi(q.z); bv[6] = on * bf16_lo(q.w); bv[7] = on * bf16_hi(q.w);
-        }
-        // weight of channel e, tap j: bf16 number e * kCW + j of the kCW loaded vectors
-        const uint4 w0 = lds_ld(&buf[kRowW * 8 + v]), w1 = lds_ld(&buf[(kRowW + 1) * 8 + v]),
-                    w2 = lds_ld(&buf[(kRowW + 2) * 8 + v]), w3 = lds_ld(&buf[(kRowW + 3) * 8 + v]);
-        const uint32_t ww[4 * kCW] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w,
-                                      w2.x, w2.y, w2.z, w2.w, w3.x, w3.y, w3.z, w3.w};
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int row_i = r0 + 32 * i;
-            float a[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) a[e] = bv[e];
-            int node = row_i < n ? row_i : -1, above = 0;
-            uint4 rk[kCW];                                          // row of the kk-th ancestor, or of the rows over the root
-#pragma unroll
-            for (int kk = 0; kk < kCW; ++kk) {
-                const int up = wave_read(bt.pv, max(node, 0));       // (every lane takes part in the cross-lane read)
-                int row;
-                if (node >= 0) {
-                    row = node;
-                    node = up;
-                } else {
-                    row = kB64 + above;
-                    ++above;
-                }
-                rk[kk] = lds_ld(&buf[row * 8 + v]);
-            }
-            conv4_bf16_dot(a, rk[0], rk[1], rk[2], rk[3], ww);      // (the same arithmetic as the conv kernel's)
-            if (V.silu) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) a[e] = a[e] * __builtin_amdgcn_rcpf(1.f + __expf(-a[e]));
-            }
-            bf16x8 o;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = bt.bad ? (bf16_t)0.f : (bf16_t)a[e];
-            if (row_i < n)
-                store_plain16(V.xbc_out + ((size_t)b * n + row_i) * Cc + col + v * 8, __builtin_bit_cast(uint4, o));
-        }
-    };
-    // a round: all its loads at once, staged, one barrier, computed; the next round's loads go out
-    // only after that (with them in flight the arithmetic would not fit the register budget)
-    lds_uint4 *const bufs[6] = {bufA0, bufA1, bufA2, bufB0, bufB1, bufB2};
-    Batch bc = load_batch(it.ib);
-    int bc_b = it.ib;
-    while (true) {
-        const Round rc = next_round();
-        if (rc.b != bc_b) {
-            bc = load_batch(rc.b);
-            bc_b = rc.b;
-        }
-        SubRegs g[ConvRounds::kRS];
-#pragma unroll
-        for (int i = 0; i < ConvRounds::kRS; ++i) g[i] = load_sub(rc.b, rc.c[i], bc);
-#pragma unroll
-        for (int i = 0; i < ConvRounds::kRS; ++i)
-            if (i < rc.cnt) stage_sub(g[i], bufs[i], rc.b, rc.c[i]);
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < ConvRounds::kRS; ++i)
-            if (i < rc.cnt) conv_sub(bufs[i], rc.b, rc.c[i], bc);
-        if (remaining <= 0) break;
-        __syncthreads();             // the buffers are free for the next round
-    }
-    // the rows are in L2 (their stores acknowledged) before anyone reads them back
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-}
-
 // WPE = waves per SIMD the register budget is sized for: 4 when two workgroups fit a CU's LDS.
 //
 // RP = fused activation replay (Alg. 1): the state loaded for a unit is first advanced along the
@@ -393,22 +119,12 @@ __device__ __noinline__ void conv_prologue_worker(
 // where it puts them into LDS; one more barrier per unit (c) separates that from the FMAs of the
 // threads that carry the unit.  Longer paths read the remaining rows from
 // global memory.  Each thread owns one 4-wide piece of the state index and NH consecutive rows.
-//
-// CV (with RP) = the whole step in one launch: before the unit loop every workgroup convolves,
-// along the ancestor chains, the x columns of its own units and the B / C columns of the groups
-// they belong to (Sec. 3 "tree conv"; the rows above the root are the conv state after the
-// previous tree's accepted path, written out as the new conv state), stores them to xbc_out and
-// reads them back as the scan's inputs.  The B / C columns are redone by every workgroup that
-// needs them (identical values to the same addresses: 0.5 MB of the 22 MB), which is what lets
-// the step do without a grid-wide dependency.  Only the G / T threads do this work: the Y threads
-// have the first state tile in flight, and any wait behind it would be a wait for it.
-template <int P, int S, int WPE, bool RP, bool CV>
+template <int P, int S, int WPE, bool RP>
 __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void tree_ssd_mfma64_kernel(
     const int32_t *__restrict__ parent, int n, int nbatch, int H, int G, const bf16_t *__restrict__ x, long x_sn,
     const float *__restrict__ dt, const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn,
     const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
-    bf16_t *__restrict__ y, int32_t *__restrict__ status, ReplayArgs R, ConvArgs V) {
-    static_assert(!CV || RP, "the one-launch step includes the replay");
+    bf16_t *__restrict__ y, int32_t *__restrict__ status, ReplayArgs R) {
     using L = Lds64<P, S>;
     constexpr int SP = L::SP;
     constexpr int kHalf = kT64 / 2;                 // threads per role group
@@ -762,40 +478,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     // LDS rows of the replayed path: behind the y staging area of the idle B tile, or their own array
     char *const rrows = L::rows_in_b ? reinterpret_cast<char *>(sB) + kYStage : reinterpret_cast<char *>(sRrows);
 
-    // ---- one-launch step: the tree conv of this workgroup's columns (conv_prologue_worker) ------------
-    auto conv_prologue = [&]() {
-        constexpr int kSubBytes = (kB64 + 2 * kCW) * 8 * 16;
-        static_assert(kSubBytes <= P * kNP64 * 2 && kSubBytes <= kB64 * kNP64 * 2 && kSubBytes <= kB64 * SP * 2 &&
-                      kSubBytes <= P * SP * 2, "conv staging buffer exceeds a tile");
-        static_assert(P % 64 == 0 && S % 64 == 0, "sub-tiles are 64 channels wide");
-        ConvRounds it;
-        it.init(nU, H, G, P, S, ub0, uh0);
-        if (isY) {
-            // the Y threads ask for the first state tile and keep the barrier count.  (The request
-            // sits in this branch so that its 32 registers are not live in the other one.)
-            // The request goes out after the first round's barrier: until then the conv's own
-            // loads -- two dependent round trips: the path, then the rows above the root -- have the
-            // memory system to themselves; behind 16 KB per thread group of state they would each
-            // take several times as long, and the first scan waits for them all the same.
-            bool first = true;
-            while (true) {
-                it.next_round();
-                __syncthreads();
-                if (first && h0) load_H(ub0, uh0);
-                first = false;
-                if (it.remaining <= 0) break;
-                __syncthreads();
-            }
-            __syncthreads();
-            return;
-        }
-        conv_prologue_worker<WPE>(it, (lds_uint4 *)&sXT2[0][0], (lds_uint4 *)&sXT2[1][0], (lds_uint4 *)sM,
-                                  (lds_uint4 *)sC, (lds_uint4 *)sB, (lds_uint4 *)sH, parent, n, R, V, rt);
-    };
-
     if (nU <= 0) return;
-    STREE_EXIT_INIT;
-    STREE_EXIT_POINT(1);
     // (b, h) of the current unit and of the next three.  The loop starts one unit early (k = -1):
     // that pass has no unit to compute and only runs the staging half, which brings unit 0 into
     // LDS and issues the loads of units 1 and 2 -- the same code as in the steady state, so the
@@ -815,7 +498,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     // parents and step sizes, then the rows of the path), and behind 16 KB of state per thread
     // group and workgroup each of them takes several times as long, while the first scan waits for
     // them all the same.
-    constexpr bool kLateH0 = RP && !CV;
+    constexpr bool kLateH0 = RP;
     if constexpr (kLateH0) {
 #pragma unroll
         for (int q = 0; q < YQ; ++q)
@@ -836,23 +519,12 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         if (isY) {
             if (h0) load_H(b1, h1);
         }
-        STREE_EXIT_POINT(2);
     } else {
         if (isY) {
-            if constexpr (!CV) {
-                if (h0) load_H(b1, h1);
-            }
+            if (h0) load_H(b1, h1);
         } else {
-            if constexpr (!CV) load_X(b1, h1);
-            if (wave == kTreeWave) {
-                load_T(b1, h1);
-                if constexpr (RP) load_R(b1, h1);
-            }
-        }
-        STREE_EXIT_POINT(2);
-        if constexpr (CV) {
-            conv_prologue();
-            if (!isY) load_X(b1, h1);
+            load_X(b1, h1);
+            if (wave == kTreeWave) load_T(b1, h1);
         }
 #pragma unroll
         for (int q = 0; q < YQ; ++q)
@@ -869,7 +541,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             bad = *sBad;
             D_h = *sDh;
             if (status && ch == 0 && tid == 0) status[cb] = bad;
-            STREE_EXIT_POINT(10 + 10 * k);
         }
         const unsigned short *sXT = sXT2[k & 1];
 
@@ -958,9 +629,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 if (k + 2 < nU) load_R(b2, h2);
             }
         }
-        if (live) STREE_EXIT_POINT(11 + 10 * k);
         if (live) __syncthreads();                            // barrier 2: M is ready; h0b, C and the tree arrays are dead
-        if (live) STREE_EXIT_POINT(12 + 10 * k);
 
         const bool more = k + 1 < nU, more2 = k + 2 < nU, more3 = k + 3 < nU;
         const bool y_stages = (k & 1) != 0;    // unit k+1 is even: its h0 sits in the Y threads
@@ -1023,7 +692,6 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                     yreg[q][rg] = o;
                 }
             }
-            if (live) STREE_EXIT_POINT(13 + 10 * k);
             // first pass: the Y threads have nothing to scan and stage the first C / B tiles (later
             // tiles come from the G threads, after barrier (a))
             if (!live && fresh_next) restage_CB(b1, h1);
@@ -1089,13 +757,8 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             }
             if (wave == kTreeWave) {
                 stage_T(h1);
-                if (!live) STREE_MARK_POINT(41, 384);
-                if (live) STREE_MARK_POINT(51 + 10 * k, 384);
             }
             stage_X((k + 1) & 1);                          // the other X^T tile: unit k still reads its own
-            if (!live) STREE_MARK_POINT(42, 256);
-            if (live) STREE_MARK_POINT(52 + 10 * k, 256);
-            if (live) STREE_MARK_POINT(55 + 10 * k, 384);
             // the registers just staged are free: x and parent / dt of unit k+2 go out at once (a
             // pass is short when HBM is idle, and they are needed at this point of the next one)
             if (more2) {
@@ -1107,16 +770,11 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 if (more3) load_H(b3, h3);
             }
             if (!kLateH0 && more2 && !live && h0) load_H(b2, h2);      // unit 1: the first odd unit (kLateH0: before the loop)
-            if (!live) STREE_MARK_POINT(43, 256);
-            if (!live) STREE_MARK_POINT(44, 384);
-            if (live) STREE_MARK_POINT(53 + 10 * k, 256);
-            if (live) STREE_MARK_POINT(54 + 10 * k, 384);
             if (late_tiles) {
                 __syncthreads();                           // barrier (a)
                 restage_CB(b1, h1);
             }
         }
-        STREE_EXIT_POINT(4 + k);
         cb = b1; ch = h1;
         b1 = b2; h1 = h2;
         b2 = b3; h2 = h3;
@@ -1124,10 +782,10 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     }
 }
 
-template <int P, int S, bool RP, bool CV>
+template <int P, int S, bool RP>
 hipError_t launch64_ps(const stree_dims &d, const int32_t *parent, const void *x, const float *dt, const float *A,
                        const void *Bm, const void *Cm, const float *D, const float *h0, void *y,
-                       int32_t *status, const ReplayArgs &R, const ConvArgs &V, hipStream_t st) {
+                       int32_t *status, const ReplayArgs &R, hipStream_t st) {
     constexpr size_t lds = RP ? Lds64<P, S>::total_replay : Lds64<P, S>::total;   // static LDS (upper bound)
     constexpr int WPE = (2 * (lds + 64) <= 160 * 1024) ? 4 : 2;
     const int n_units = d.batch * d.nheads;
@@ -1135,21 +793,21 @@ hipError_t launch64_ps(const stree_dims &d, const int32_t *parent, const void *x
     int grid = (n_units + 7) / 8 * 8;
     const int cap = 256 * (per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu));
     if (grid > cap) grid = cap;
-    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE, RP, CV>), dim3(grid), dim3(kT64), 0, st, parent, d.nnodes,
+    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE, RP>), dim3(grid), dim3(kT64), 0, st, parent, d.nnodes,
                        d.batch, d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A,
                        (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,
-                       (bf16_t *)y, status, R, V);
+                       (bf16_t *)y, status, R);
     return hipGetLastError();
 }
 
-template <bool RP, bool CV>
+template <bool RP>
 hipError_t launch64(const stree_dims &d, const int32_t *parent, const void *x, const float *dt, const float *A,
                     const void *Bm, const void *Cm, const float *D, const float *h0, void *y, int32_t *status,
-                    const ReplayArgs &R, const ConvArgs &V, hipStream_t st) {
+                    const ReplayArgs &R, hipStream_t st) {
     const int P = d.headdim, S = d.dstate;
-    if (P == 64 && S == 128) return launch64_ps<64, 128, RP, CV>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, V, st);
-    if (P == 64 && S == 64) return launch64_ps<64, 64, RP, CV>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, V, st);
-    if (P == 128 && S == 128) return launch64_ps<128, 128, RP, CV>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, V, st);
+    if (P == 64 && S == 128) return launch64_ps<64, 128, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
+    if (P == 64 && S == 64) return launch64_ps<64, 64, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
+    if (P == 128 && S == 128) return launch64_ps<128, 128, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
     return hipErrorInvalidValue;
 }
 
@@ -1162,10 +820,12 @@ bool tree_ssd_mfma64_supported(const stree_dims &d) {
 }
 
 bool tree_ssd_replay_fused_supported(const stree_dims &d, const stree_dims &dp, const void *px, const void *pB,
-                                     const void *x, const void *Bm, const void *Cm, const void *y) {
+                                     const void *x, const void *Bm, const void *Cm, const void *y, const float *h0,
+                                     const float *h_out) {
     if (d.io_dtype != STREE_BF16 || !tree_ssd_mfma64_supported(d) || dp.nnodes > kB64) return false;
     if ((d.x_stride_n | d.b_stride_n | d.c_stride_n | dp.x_stride_n | dp.b_stride_n) % 8 != 0) return false;
-    const uintptr_t bits = (uintptr_t)x | (uintptr_t)Bm | (uintptr_t)Cm | (uintptr_t)y | (uintptr_t)px | (uintptr_t)pB;
+    const uintptr_t bits = (uintptr_t)x | (uintptr_t)Bm | (uintptr_t)Cm | (uintptr_t)y | (uintptr_t)px | (uintptr_t)pB |
+                           (uintptr_t)h0 | (uintptr_t)h_out;   // (the state is read and written 16 bytes at a time)
     return bits % 16 == 0;
 }
 
@@ -1176,47 +836,13 @@ hipError_t launch_tree_ssd_replay_fused(const stree_dims &d, const stree_dims &d
                                         float *h_out, void *y, int32_t *status, int32_t *rstatus, hipStream_t st) {
     const ReplayArgs R = {pparent, paccepted, (const bf16_t *)px, (const bf16_t *)pB, pdt,
                           (long)dp.x_stride_n, (long)dp.b_stride_n, dp.nnodes, h_out, rstatus};
-    return launch64<true, false>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, ConvArgs{}, st);
-}
-
-bool tree_step_fused_supported(const stree_dims &d, const stree_dims &dp, const void *px, const void *pB,
-                               const void *xbc_pre, const void *prev_xbc_pre, const void *conv_state,
-                               const void *conv_w, const void *conv_b, const void *xbc_out,
-                               const void *conv_state_out, const void *y) {
-    const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
-    if (d.conv_width != kCW || Cc % 8 != 0) return false;
-    const char *xo = static_cast<const char *>(xbc_out);
-    if (!tree_ssd_replay_fused_supported(d, dp, px, pB, xo, xo + (size_t)d.nheads * d.headdim * 2,
-                                         xo + ((size_t)d.nheads * d.headdim + (size_t)d.ngroups * d.dstate) * 2, y))
-        return false;
-    const uintptr_t bits = (uintptr_t)xbc_pre | (uintptr_t)prev_xbc_pre | (uintptr_t)conv_state | (uintptr_t)conv_w |
-                           (uintptr_t)conv_b | (uintptr_t)conv_state_out;
-    return bits % 16 == 0;
-}
-
-// d: strides of x / B / C already set to the conv channel count (column ranges of xbc_out)
-hipError_t launch_tree_step_fused(const stree_dims &d, const stree_dims &dp, const int32_t *pparent,
-                                  const int32_t *paccepted, const void *px, const float *pdt, const void *pB,
-                                  const void *prev_xbc_pre, const int32_t *parent, const void *xbc_pre,
-                                  const void *conv_state, const void *conv_w, const void *conv_b, void *xbc_out,
-                                  void *conv_state_out, const float *dt, const float *A, const float *D,
-                                  const float *h0, float *h_out, void *y, int32_t *status, int32_t *rstatus,
-                                  hipStream_t st) {
-    const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
-    const ReplayArgs R = {pparent, paccepted, (const bf16_t *)px, (const bf16_t *)pB, pdt,
-                          (long)dp.x_stride_n, (long)dp.b_stride_n, dp.nnodes, h_out, rstatus};
-    const ConvArgs V = {(const bf16_t *)xbc_pre, (const bf16_t *)conv_state, (const bf16_t *)conv_w,
-                        (const bf16_t *)conv_b, (const bf16_t *)prev_xbc_pre, (bf16_t *)xbc_out,
-                        (bf16_t *)conv_state_out, Cc, (d.flags & STREE_FLAG_CONV_SILU) ? 1 : 0};
-    const bf16_t *xo = (const bf16_t *)xbc_out;
-    return launch64<true, true>(d, parent, xo, dt, A, xo + (size_t)d.nheads * d.headdim,
-                                xo + (size_t)d.nheads * d.headdim + (size_t)d.ngroups * d.dstate, D, h0, y, status, R, V, st);
+    return launch64<true>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
 }
 
 hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                   const float *A, const void *Bm, const void *Cm, const float *D,
                                   const float *h0, void *y, int32_t *status, hipStream_t st) {
-    return launch64<false, false>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, ReplayArgs{}, ConvArgs{}, st);
+    return launch64<false>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, ReplayArgs{}, st);
 }
 
 }  // namespace stree

@@ -43,9 +43,28 @@ def parity(got: np.ndarray, want: np.ndarray):
     return float(np.max(np.abs(got - want))) / scale, float(np.linalg.norm((got - want).ravel())) / l2
 
 
+def elementwise(got: np.ndarray, want: np.ndarray) -> float:
+    """Worst |err| / (|ref| + rms(ref)), the rms taken over the last axis: the P outputs of one
+    (sequence, node, head) for y, one row of S state entries for the state, the channels of one node
+    for the conv.  Those entries are sums of the same number of terms of the same magnitude, so
+    their rms is the scale that rounding errors of the terms are proportional to.  Unlike the ratio
+    to the tensor's maximum this does not let an error hide in a strongly decayed node or in a
+    head with small steps."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    rms = np.sqrt(np.mean(want * want, axis=-1, keepdims=True))
+    den = np.abs(want) + rms
+    err = np.abs(got - want)
+    return float(np.max(np.where(err == 0.0, 0.0, err / np.maximum(den, 1e-300))))
+
+
 def assert_parity(got, want, tol: float, what: str = ""):
+    """Per tensor: max-abs and l2 error relative to the reference's, AND elementwise
+    |err| <= tol * (|ref| + rms(ref over the last axis))."""
     emax, el2 = parity(got, want)
     assert emax <= tol and el2 <= tol, f"{what}: max-rel {emax:.3e}, l2-rel {el2:.3e} > tol {tol:g}"
+    ew = elementwise(got, want)
+    assert ew <= tol, f"{what}: elementwise |err| / (|ref| + rms) {ew:.3e} > tol {tol:g}"
     return emax, el2
 
 

@@ -28,7 +28,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert {"stree_tree_conv", "stree_tree_ssd", "stree_commit_state", "stree_tree_index",
+    assert {"stree_workspace_bytes", "stree_tree_conv", "stree_tree_ssd", "stree_commit_state", "stree_tree_index",
             "stree_version", "stree_status_string"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/stree.h but not exported"
@@ -42,8 +42,24 @@ def test_dims_struct_matches_header_layout():
 
 def test_version_and_status_strings(lib):
     assert lib.stree_version() >= 1
-    seen = {lib.stree_status_string(c) for c in range(6)}
-    assert len(seen) == 6 and all(s for s in seen)
+    seen = {lib.stree_status_string(c) for c in range(7)}
+    assert len(seen) == 7 and all(s for s in seen)
+    assert lib.stree_status_string(99) not in seen
+
+
+def test_workspace_bytes(lib):
+    """No kernel uses device scratch: 0 for every valid shape, (size_t)-1 for invalid dims."""
+    bad = C.c_size_t(-1).value
+    for cfg in (dict(batch=1, nnodes=15, nheads=4, headdim=64, dstate=64, ngroups=1, io_dtype=binding.F32),
+                dict(batch=16, nnodes=64, nheads=80, headdim=64, dstate=128, ngroups=1, conv_width=4),
+                dict(batch=4, nnodes=256, nheads=128, headdim=64, dstate=128, ngroups=8),
+                dict(batch=0, nnodes=1, nheads=1, headdim=1, dstate=1, ngroups=1)):
+        assert binding.stree_workspace_bytes(binding.make_dims(**cfg)) == 0
+    ok = dict(batch=1, nnodes=64, nheads=8, headdim=64, dstate=128, ngroups=1)
+    assert lib.stree_workspace_bytes(None) == bad
+    for k, v in (("nnodes", 0), ("nnodes", 257), ("ngroups", 3), ("dstate", 512), ("batch", -1)):
+        assert binding.stree_workspace_bytes(binding.make_dims(**{**ok, k: v})) == bad
+    assert binding.stree_workspace_bytes(binding.make_dims(**ok, io_dtype=7)) == bad
 
 
 FAKE = C.c_void_p(0x1000)   # never dereferenced: every call below fails validation first
@@ -144,3 +160,23 @@ def test_replay_entry_points_reject_bad_arguments(lib):
                                   None, None) == 1          # conv_state_out missing
     assert lib.stree_commit_state(C.byref(d), FAKE, FAKE, None, None, None, None, None, None, None, None, None,
                                   None, None) == 1          # nothing to do
+
+
+def test_step_rejects_overlapping_conv_outputs(lib):
+    """xbc_out overlapping the previous step's x / B rows is caught on the host (status 6)."""
+    ok = dict(batch=2, nnodes=64, nheads=8, headdim=64, dstate=128, ngroups=1, conv_width=4)
+    d = binding.make_dims(**ok)
+    Cc = 8 * 64 + 2 * 128
+    nbytes = 2 * 64 * Cc * 2
+    base = 0x100000
+
+    def step(xbc_out, px, pB, d=d):
+        prev = binding.StreeReplay(64, 0, 0x1000, 0x1000, px, 0x1000, pB, Cc, Cc)
+        return lib.stree_tree_step(C.byref(d), C.byref(prev), FAKE, FAKE, FAKE, FAKE, FAKE, None,
+                                   C.c_void_p(xbc_out), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, None, None)
+
+    assert step(base, base, base + 8 * 64 * 2) == 6                      # the same buffer
+    assert step(base, base + nbytes - 16, base + 4 * nbytes) == 6        # x rows start inside xbc_out
+    assert step(base, base + 4 * nbytes, base - 256) == 6                # B rows run into xbc_out
+    assert step(base, None, base) == 1                                   # (NULL is reported first)
+    assert step(base, base, base, d=binding.make_dims(**{**ok, "batch": 0})) == 0

@@ -273,6 +273,34 @@ def test_commit_edge_cases(st, oracle):
     assert_parity(to_host(h3), want3, 1e-4, "commit without h0")
 
 
+@pytest.mark.parametrize("N", [30, 130])
+def test_commit_conv_tail_alone_reports_status(st, oracle, N):
+    """Conv tail only (all state pointers NULL): the per-sequence status is written by the conv-tail
+    workgroups -- 0, first bad node + 1, or -1 for an accepted index outside [-1, N) -- and in the
+    last two cases the conv state passes through."""
+    import torch
+    B, H, P, S, G, W = 5, 3, 64, 128, 1, 4
+    Cc = H * P + 2 * G * S
+    rng = np.random.default_rng(300 + N)
+    parent = _trees(301 + N, B, N)
+    parent[1, 7] = 12                                             # invalid: parent label above the node's
+    parent[3, 0] = 0                                              # invalid root
+    xbc = synth.round_to_bf16(rng.standard_normal((B, N, Cc)).astype(np.float32))
+    cs = synth.round_to_bf16(rng.standard_normal((B, W - 1, Cc)).astype(np.float32))
+    acc = np.array([N - 1, 3, N + 4, 2, -1], dtype=np.int32)
+    status = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    _, cso = st.stree_commit_state(to_dev(parent), to_dev(acc), None, None, None, None, xbc_pre=to_dev(xbc, "bf16"),
+                                   conv_state=to_dev(cs, "bf16"), status=status, dims=(H, P, S, G))
+    assert list(to_host(status)) == [0, 8, -1, 1, 0]
+    got = to_host(cso)
+    z = np.zeros((1, N, 1, 4), dtype=np.float32)                  # (the oracle's commit wants a state part: a dummy one)
+    _, want = oracle.commit(parent[:1], acc[:1], z, z[..., 0], np.array([-1.0], dtype=np.float32), z, None, xbc[:1],
+                            cs[:1])
+    assert np.array_equal(got[0], want[0].astype(np.float32))
+    for b in (1, 2, 3, 4):
+        assert np.array_equal(got[b], cs[b])
+
+
 @pytest.mark.parametrize("io", ["bf16", "f32"])
 @pytest.mark.parametrize("N", [40, 100])
 def test_commit_unpredicated_kernel_cases(st, oracle, io, N):

@@ -1,6 +1,5 @@
 """GPU parity of the decoding step entry point (tree conv seeded by the conv state after the
-previous tree's accepted path, state replay along that path, tree scan), in both of its routes:
-the default (two kernels) and the single kernel (one_launch).
+previous tree's accepted path, state replay along that path, tree scan).
 
 Two kinds of check: against the two entry points it stands for, called back to back on the same
 inputs (every output bit for bit: the arithmetic is the same, only the launches differ), and
@@ -66,7 +65,7 @@ def _two_calls(st, d, pout, H, P, S, G, silu=True, bias=True, io="bf16"):
     return y, h, xbc, cs, stt, rst
 
 
-def _one_call(st, d, pout, H, P, S, G, silu=True, bias=True, one_launch=True, io="bf16", **kw):
+def _one_call(st, d, pout, H, P, S, G, silu=True, bias=True, io="bf16", **kw):
     B = d["parent"].shape[0]
     stt = torch.full((B,), -7, dtype=torch.int32, device="cuda")
     rst = torch.full((B,), -7, dtype=torch.int32, device="cuda")
@@ -75,7 +74,7 @@ def _one_call(st, d, pout, H, P, S, G, silu=True, bias=True, one_launch=True, io
                                        to_dev(d["pdt"]), to_dev(d["parent"]), to_dev(d["xbc_pre"], io),
                                        to_dev(d["conv_state"], io), to_dev(d["conv_w"], io), cb,
                                        to_dev(d["dt"]), to_dev(d["A"]), to_dev(d["D"]), to_dev(d["h0"]), H, P, S, G,
-                                       silu=silu, status=stt, replay_status=rst, one_launch=one_launch, **kw)
+                                       silu=silu, status=stt, replay_status=rst, **kw)
     return y, h, xbc, cs, stt, rst
 
 
@@ -88,8 +87,8 @@ def _same(a, b, what):
         assert torch.equal(uh, vh), f"{what}: {nm} differs from the two-call sequence"
 
 
-# shapes of the single-launch kernel: several units per workgroup run, runs that cross a sequence
-# or a group boundary, ragged node counts, previous tree of another size
+# several units per workgroup run, runs that cross a sequence or a group boundary, ragged node
+# counts, previous tree of another size
 STEP_SHAPES = [(3, 64, 64, 5, 64, 128, 1), (2, 37, 50, 4, 64, 128, 2), (4, 1, 13, 3, 64, 64, 1),
                (2, 64, 1, 2, 128, 128, 1), (20, 20, 64, 80, 64, 128, 1), (3, 64, 64, 6, 64, 128, 3)]
 
@@ -99,8 +98,7 @@ def test_step_equals_the_two_entry_points(st, B, Np, N, H, P, S, G):
     d = _inputs(500 + N + H, B, Np, N, H, P, S, G)
     pout = _prev_conv_out(st, d, H, P, S, G)
     ref = _two_calls(st, d, pout, H, P, S, G)
-    _same(_one_call(st, d, pout, H, P, S, G), ref, f"step, one launch, B={B} N={N} H={H}")
-    _same(_one_call(st, d, pout, H, P, S, G, one_launch=False), ref, f"step, default route, B={B} N={N} H={H}")
+    _same(_one_call(st, d, pout, H, P, S, G), ref, f"step, B={B} N={N} H={H}")
 
 
 def test_step_options_and_degenerate_paths(st):
@@ -127,8 +125,8 @@ def test_step_bad_trees_and_bad_accepted(st):
     assert not to_host(one[0])[1].any()
 
 
-def test_step_other_shapes_take_the_two_kernel_route(st):
-    # conv width 3 and a head shape outside the single-launch kernel: same entry point, same results
+def test_step_other_shapes(st):
+    # conv width 3 and a head shape outside the fused replay + scan kernel: same entry point, same results
     for (B, Np, N, H, P, S, G, W) in ((2, 20, 30, 3, 64, 128, 1, 3), (2, 20, 70, 2, 32, 16, 1, 4)):
         d = _inputs(33 + W, B, Np, N, H, P, S, G, W)
         pout = _prev_conv_out(st, d, H, P, S, G)
@@ -136,8 +134,8 @@ def test_step_other_shapes_take_the_two_kernel_route(st):
 
 
 def test_step_fp32_and_large_trees(st, oracle):
-    """fp32 storage and a 200-node tree: outside the single kernel (the flag is ignored), same entry
-    point; checked against the two calls bit for bit and against the oracle."""
+    """fp32 storage and a 200-node tree: checked against the two calls bit for bit and against the
+    oracle."""
     B, Np, N, H, P, S, G = 2, 50, 200, 2, 16, 32, 1
     d = _inputs(4242, B, Np, N, H, P, S, G)
     pout = _prev_conv_out(st, d, H, P, S, G, io="f32")
@@ -167,7 +165,7 @@ def test_step_in_place_state(st):
                                     to_dev(d["pdt"]), to_dev(d["parent"]), to_dev(d["xbc_pre"], "bf16"),
                                     to_dev(d["conv_state"], "bf16"), to_dev(d["conv_w"], "bf16"),
                                     to_dev(d["conv_b"], "bf16"), to_dev(d["dt"]), to_dev(d["A"]), to_dev(d["D"]), h_io,
-                                    H, P, S, G, h_out=h_io, status=stt, one_launch=True)
+                                    H, P, S, G, h_out=h_io, status=stt)
     assert h.data_ptr() == h_io.data_ptr()
     assert torch.equal(h.cpu(), ref[1].cpu()) and torch.equal(y.cpu().view(torch.int16), ref[0].cpu().view(torch.int16))
 
@@ -190,8 +188,7 @@ def test_step_against_the_oracle_full_size(st, oracle):
     y, h, xbc, cs = st.stree_tree_step(to_dev(pparent), to_dev(pacc), to_dev(pxbc_pre, io), to_dev(pxbc, io),
                                        to_dev(pdt), to_dev(wl.parent), to_dev(wl.xbc_pre, io),
                                        to_dev(wl.conv_state, io), to_dev(wl.conv_w, io), to_dev(wl.conv_b, io),
-                                       to_dev(wl.dt), to_dev(wl.A), to_dev(wl.D), to_dev(wl.h0), H, P, S, G,
-                                       one_launch=True)
+                                       to_dev(wl.dt), to_dev(wl.A), to_dev(wl.D), to_dev(wl.h0), H, P, S, G)
     assert np.array_equal(to_host(cs), want_cs)
     got_conv = to_host(xbc)
     assert_parity(got_conv, want_conv, 4e-3, "step: conv output")
@@ -200,3 +197,18 @@ def test_step_against_the_oracle_full_size(st, oracle):
     x, Bm, Cm = split_xbc(got_conv.astype(np.float32), H, P, G, S)
     want_y = oracle.ssd_paths(wl.parent, x, wl.dt, wl.A, Bm, Cm, wl.D, want_h)
     assert_parity(to_host(y), want_y, TOL[io], "step: y")
+
+
+def test_step_rejects_a_conv_output_that_overlaps_the_previous_one(st):
+    """The conv overwrites xbc_out before the replay reads the previous step's x / B rows: a caller
+    that passes one buffer for both gets an error from the host check and nothing is launched."""
+    from paper_2505_14969_amd.binding import StreeError
+    B, Np, N, H, P, S, G = 2, 64, 64, 4, 64, 128, 1
+    d = _inputs(6, B, Np, N, H, P, S, G)
+    pout = _prev_conv_out(st, d, H, P, S, G)
+    before = pout.clone()
+    with pytest.raises(StreeError) as e:
+        _one_call(st, d, pout, H, P, S, G, xbc_out=pout)
+    assert e.value.code == 6
+    torch.cuda.synchronize()
+    assert torch.equal(pout.view(torch.int16), before.view(torch.int16))
