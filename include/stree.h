@@ -53,7 +53,9 @@ enum stree_dtype { STREE_F32 = 0, STREE_BF16 = 1 };
 
 enum stree_flags {
     STREE_FLAG_CONV_SILU = 1,    /* tree_conv applies z * sigmoid(z) */
-    STREE_FLAG_FORCE_FMA = 256   /* tree_ssd: use the plain fp32-FMA kernel even where MFMA applies */
+    STREE_FLAG_FORCE_FMA = 256,    /* tree_ssd: use the plain fp32-FMA kernel even where MFMA applies */
+    STREE_FLAG_GENERAL_MFMA = 1024 /* tree_ssd: trees of more than 64 nodes take the one-workgroup-per-(b,h) MFMA
+                                      kernel even where the persistent one applies (same results to rounding) */
 };
 
 /* Problem sizes.  POD, host memory. */

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libstree.so")
 F32, BF16 = 0, 1
 FLAG_CONV_SILU = 1
 FLAG_FORCE_FMA = 256
+FLAG_GENERAL_MFMA = 1024
 MAX_NODES = 256
 
 
@@ -151,14 +152,15 @@ def stree_tree_conv(parent, xbc_pre, conv_state, conv_w, conv_b, nheads, headdim
 
 
 def stree_tree_ssd(parent, x, dt, A, Bm, Cm, D=None, h0=None, out: Optional[torch.Tensor] = None,
-                   status: Optional[torch.Tensor] = None, force_fma: bool = False):
+                   status: Optional[torch.Tensor] = None, force_fma: bool = False, general_mfma: bool = False):
     """x [B,N,H,P], dt [B,N,H] f32, A [H] f32, Bm/Cm [B,N,G,S], D [H]|None, h0 [B,H,P,S] f32|None
     -> y [B,N,H,P].  x, Bm, Cm may be column views of one [B,N,Cc] buffer."""
     B, N, H, P = x.shape
     G, S = Bm.shape[2], Bm.shape[3]
     if out is None:
         out = torch.empty((B, N, H, P), dtype=x.dtype, device=x.device)
-    d = make_dims(B, N, H, P, S, G, 0, _io_code(x), FLAG_FORCE_FMA if force_fma else 0,
+    d = make_dims(B, N, H, P, S, G, 0, _io_code(x),
+                  (FLAG_FORCE_FMA if force_fma else 0) | (FLAG_GENERAL_MFMA if general_mfma else 0),
                   _token_stride(x, N), _token_stride(Bm, N), _token_stride(Cm, N))
     assert dt.is_contiguous() and dt.dtype == torch.float32 and out.is_contiguous()
     _check(load().stree_tree_ssd(C.byref(d), _ptr(parent), _ptr(x), _ptr(dt), _ptr(A), _ptr(Bm), _ptr(Cm),

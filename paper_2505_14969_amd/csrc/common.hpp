@@ -159,6 +159,20 @@ __device__ __forceinline__ void store_through16(void *p, uint4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(vv) : "memory");
 }
 
+// The same store as a raw buffer store, the cache bits riding on an instruction the compiler knows.
+// (The compiler's wait-count pass treats the operand registers of inline assembly as if a memory
+// operation of unknown age still read them: the next write to any of them -- they are ordinary
+// temporaries -- becomes a wait for EVERYTHING in flight, prefetches included.  A store it knows it
+// counts exactly.)  `rsrc` covers `bytes` bytes from `base` (uniform); stores past the end are dropped.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_store_rsrc(void *base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ void buffer_store_through16(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, uint4 v) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 vv = {v.x, v.y, v.z, v.w};
+    __builtin_amdgcn_raw_buffer_store_b128(vv, rsrc, (int)off, 0, 1 | 2 | 16);   // sc0 | nt | sc1
+}
+
 // 16-byte store that writes through L2 to memory (system scope) and keeps the default temporal
 // policy: for an output that the next kernel reads.  The line stays in L2 for that reader, but not
 // dirty: lines left dirty are all written back when the kernel ends, and the kernel is not over

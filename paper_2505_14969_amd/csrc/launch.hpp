@@ -38,6 +38,12 @@ hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, co
                                   const float *A, const void *Bm, const void *Cm, const float *D,
                                   const float *h0, void *y, int32_t *status, hipStream_t st);
 
+// 65 .. 256 nodes: the persistent kernel over (row block, column block) pairs
+bool tree_ssd_blocks_supported(const stree_dims &d);
+hipError_t launch_tree_ssd_blocks(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
+                                  const float *A, const void *Bm, const void *Cm, const float *D, const float *h0,
+                                  void *y, int32_t *status, hipStream_t st);
+
 // fused replay + scan: `dp` describes the previous tree (its node count and strides)
 bool tree_ssd_replay_fused_supported(const stree_dims &d, const stree_dims &dp, const void *px, const void *pB,
                                      const void *x, const void *Bm, const void *Cm, const void *y, const float *h0,

@@ -440,6 +440,8 @@ hipError_t launch_tree_ssd_mfma(const stree_dims &d, const int32_t *parent, cons
                                 const float *h0, void *y, int32_t *status, hipStream_t st) {
     if (tree_ssd_mfma64_supported(d))
         return launch_tree_ssd_mfma64(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+    if (tree_ssd_blocks_supported(d) && !(d.flags & STREE_FLAG_GENERAL_MFMA))
+        return launch_tree_ssd_blocks(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
     const bool sh = mfma_share_h((d.nnodes + kBlk - 1) / kBlk * kBlk);
     switch (d.headdim) {
         case 32:

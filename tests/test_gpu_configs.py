@@ -42,12 +42,12 @@ def _pipeline(st, oracle, wl, h0_dev, h0_ref, check_commit=True):
     dt_d, A_d, D_d = to_dev(wl.dt), to_dev(wl.A), to_dev(wl.D)
     ox, oB, oC = split_xbc_dev(to_dev(ref_xbc, io), H, P, G, S)
     y_iso = st.stree_tree_ssd(par_d, ox, dt_d, A_d, oB, oC, D_d, to_dev(h0_ref.astype(np.float32)))
-    assert_parity(to_host(y_iso), want_y, TOL[io], f"{wl.name} y (scan alone)")
+    assert_parity(to_host(y_iso), want_y, TOL[io], f"{wl.name} y (scan alone)", kind="y")
     # ---- tree scan, end to end: views of the GPU's own conv output and the GPU's own h0
     gx, gB, gC = split_xbc_dev(xbc_d, H, P, G, S)
     y_d = st.stree_tree_ssd(par_d, gx, dt_d, A_d, gB, gC, D_d, h0_dev, status=status)
     assert not to_host(status).any()
-    assert_parity(to_host(y_d), want_y, TOL[io], f"{wl.name} y (conv + scan)")
+    assert_parity(to_host(y_d), want_y, TOL[io], f"{wl.name} y (conv + scan)", kind="y")
     if not check_commit:
         return
     # ---- commit
@@ -56,10 +56,10 @@ def _pipeline(st, oracle, wl, h0_dev, h0_ref, check_commit=True):
     h_iso, cs_out = st.stree_commit_state(par_d, acc_d, ox, dt_d, A_d, oB, to_dev(h0_ref.astype(np.float32)),
                                           xbc_pre=xbc_pre_d, conv_state=cs_d, status=status)
     assert not to_host(status).any()
-    assert_parity(to_host(h_iso), want_h, 1e-4, f"{wl.name} committed state (commit alone)")
+    assert_parity(to_host(h_iso), want_h, 1e-4, f"{wl.name} committed state (commit alone)", kind="state")
     assert np.array_equal(to_host(cs_out), want_cs.astype(np.float32)), "conv state rows are copies: exact"
     h_e2e, _ = st.stree_commit_state(par_d, acc_d, gx, dt_d, A_d, gB, h0_dev)
-    assert_parity(to_host(h_e2e), want_h, TOL[io], f"{wl.name} committed state (end to end)")
+    assert_parity(to_host(h_e2e), want_h, TOL[io], f"{wl.name} committed state (end to end)", kind="state")
 
 
 def test_config1_tree64_batch1(st, oracle):
@@ -106,8 +106,8 @@ def test_config2_fused_sequence(st, oracle):
     qx, qB, _ = split_xbc_dev(to_dev(pxbc, io), H, P, G, S)
     y, h = st.stree_tree_ssd_replay(to_dev(pparent), to_dev(pacc), qx, to_dev(pdt), qB, to_dev(wl.parent), dx,
                                     to_dev(wl.dt), to_dev(wl.A), dB, dC, to_dev(wl.D), to_dev(wl.h0))
-    assert_parity(to_host(h), want_h, 1e-4, "cfg2 fused: replayed state")
-    assert_parity(to_host(y), want_y, TOL[io], "cfg2 fused: y")
+    assert_parity(to_host(h), want_h, 1e-4, "cfg2 fused: replayed state", kind="state")
+    assert_parity(to_host(y), want_y, TOL[io], "cfg2 fused: y", kind="y")
 
 
 def test_config2_direct_inputs_scan_only(st, oracle):
@@ -116,7 +116,7 @@ def test_config2_direct_inputs_scan_only(st, oracle):
     want = oracle.ssd_paths(wl.parent, wl.x, wl.dt, wl.A, wl.Bm, wl.Cm, wl.D, wl.h0)
     y = st.stree_tree_ssd(to_dev(wl.parent), to_dev(wl.x, "bf16"), to_dev(wl.dt), to_dev(wl.A),
                           to_dev(wl.Bm, "bf16"), to_dev(wl.Cm, "bf16"), to_dev(wl.D), to_dev(wl.h0))
-    assert_parity(to_host(y), want, TOL["bf16"], "cfg2 direct")
+    assert_parity(to_host(y), want, TOL["bf16"], "cfg2 direct", kind="y")
 
 
 def test_config3_wide_deep_256_groups8(st, oracle):
@@ -131,7 +131,7 @@ def test_config3_wide_deep_256_groups8(st, oracle):
                           to_dev(wl.Bm, "bf16"), to_dev(wl.Cm, "bf16"), to_dev(wl.D), to_dev(wl.h0))
     got = to_host(y)
     for b in range(wl.batch):
-        assert_parity(got[b], want[b], TOL["bf16"], f"cfg3 b={b}")
+        assert_parity(got[b], want[b], TOL["bf16"], f"cfg3 b={b}", kind="y")
 
 
 def test_config4_prefix_then_tree(st, oracle):
@@ -145,10 +145,10 @@ def test_config4_prefix_then_tree(st, oracle):
     # GPU, first-class prefix kernel: y of every prefix token and the state after the last one
     y_lin, h_lin = st.stree_linear_ssd(to_dev(e["prefix_x"], "bf16"), to_dev(e["prefix_dt"]), to_dev(wl.A),
                                        to_dev(e["prefix_B"], "bf16"), to_dev(e["prefix_C"], "bf16"))
-    assert_parity(to_host(h_lin), h_ref, 1e-4, "cfg4 prefix state (linear scan kernel)")
+    assert_parity(to_host(h_lin), h_ref, 1e-4, "cfg4 prefix state (linear scan kernel)", kind="state")
     y_lin = to_host(y_lin)
     for b in range(B):
-        assert_parity(y_lin[b], y_ref[b], TOL["bf16"], f"cfg4 prefix y b={b}")
+        assert_parity(y_lin[b], y_ref[b], TOL["bf16"], f"cfg4 prefix y b={b}", kind="y")
     # GPU: 16 x (256-node chain, commit at its last node), state updated in place
     chunk = 256
     chain = to_dev(np.stack([synth.chain_tree(chunk)] * B))
@@ -160,5 +160,5 @@ def test_config4_prefix_then_tree(st, oracle):
         sl = slice(c * chunk, (c + 1) * chunk)
         st.stree_commit_state(chain, last, px[:, sl].contiguous(), pdt[:, sl].contiguous(), A_d,
                               pB[:, sl].contiguous(), h, h_out=h)
-    assert_parity(to_host(h), h_ref, 1e-4, "cfg4 prefix state")
+    assert_parity(to_host(h), h_ref, 1e-4, "cfg4 prefix state", kind="state")
     _pipeline(st, oracle, wl, h, h_ref)

@@ -20,8 +20,8 @@ def test_linear_scan_against_oracle(st, oracle, B, T, H, P, S, G, with_h0):
     want_y, want_h = oracle.linear_scan(x, dt, A, Bm, Cm, D, h0)
     y, h = st.stree_linear_ssd(to_dev(x, io), to_dev(dt), to_dev(A), to_dev(Bm, io), to_dev(Cm, io), to_dev(D),
                                to_dev(h0))
-    assert_parity(to_host(h), want_h, 1e-4, f"state after {T} tokens")
-    assert_parity(to_host(y), want_y, TOL[io], f"y of {T} tokens")
+    assert_parity(to_host(h), want_h, 1e-4, f"state after {T} tokens", kind="state")
+    assert_parity(to_host(y), want_y, TOL[io], f"y of {T} tokens", kind="y")
     # state only, in place
     h_io = to_dev(h0) if with_h0 else None
     if h_io is not None:
@@ -42,8 +42,8 @@ def test_linear_scan_equals_chain_tree_on_gpu(st, oracle):
                            to_dev(h0))
     ht, _ = st.stree_commit_state(chain, to_dev(np.full(B, T - 1, dtype=np.int32)), to_dev(x, io), to_dev(dt),
                                   to_dev(A), to_dev(Bm, io), to_dev(h0))
-    assert_parity(to_host(y), to_host(yt).astype(np.float64), TOL[io], "linear scan vs chain tree y")
-    assert_parity(to_host(h), to_host(ht).astype(np.float64), 1e-4, "linear scan vs chain commit state")
+    assert_parity(to_host(y), to_host(yt).astype(np.float64), TOL[io], "linear scan vs chain tree y", kind="y")
+    assert_parity(to_host(h), to_host(ht).astype(np.float64), 1e-4, "linear scan vs chain commit state", kind="state")
 
 
 def test_linear_scan_rejects_unsupported_shapes(st):

@@ -91,7 +91,7 @@ def test_config0_fp32(st, oracle):
     wl = synth.config(0)
     want = oracle.ssd_paths(wl.parent, wl.x, wl.dt, wl.A, wl.Bm, wl.Cm, wl.D, wl.h0)
     got = _run_ssd(st, "f32", wl.parent, wl.x, wl.dt, wl.A, wl.Bm, wl.Cm, wl.D, wl.h0)
-    assert_parity(got, want, TOL["f32"], "cfg0 y")
+    assert_parity(got, want, TOL["f32"], "cfg0 y", kind="y")
 
 
 @pytest.mark.parametrize("N,H,P,S,G", [(1, 2, 8, 8, 1), (13, 3, 24, 20, 1), (64, 4, 64, 64, 2),
@@ -101,7 +101,7 @@ def test_fp32_fma_kernel_shapes(st, oracle, N, H, P, S, G):
     x, dt, A, Bm, Cm, D, h0 = _rand(N + 1, "f32", 2, N, H, P, S, G)
     want = oracle.ssd_paths(parent, x, dt, A, Bm, Cm, D, h0)
     got = _run_ssd(st, "f32", parent, x, dt, A, Bm, Cm, D, h0)
-    assert_parity(got, want, TOL["f32"], f"fp32 N={N}")
+    assert_parity(got, want, TOL["f32"], f"fp32 N={N}", kind="y")
 
 
 def test_fp32_chain_256_against_linear_scan(st, oracle):
@@ -110,7 +110,7 @@ def test_fp32_chain_256_against_linear_scan(st, oracle):
     x, dt, A, Bm, Cm, D, h0 = _rand(5, "f32", 2, N, 2, 32, 32, 1)
     want, _ = oracle.linear_scan(x, dt, A, Bm, Cm, D, h0)
     got = _run_ssd(st, "f32", parent, x, dt, A, Bm, Cm, D, h0)
-    assert_parity(got, want, TOL["f32"], "fp32 chain")
+    assert_parity(got, want, TOL["f32"], "fp32 chain", kind="y")
 
 
 # --------------------------------------------------------------------------- #
@@ -128,10 +128,10 @@ def test_bf16_mfma_kernel_shapes(st, oracle, N, H, P, S, G):
     x, dt, A, Bm, Cm, D, h0 = _rand(N + P, "bf16", 3, N, H, P, S, G)
     want = oracle.ssd_paths(parent, x, dt, A, Bm, Cm, D, h0)
     got = _run_ssd(st, "bf16", parent, x, dt, A, Bm, Cm, D, h0)
-    assert_parity(got, want, TOL["bf16"], f"mfma N={N} P={P} S={S}")
+    assert_parity(got, want, TOL["bf16"], f"mfma N={N} P={P} S={S}", kind="y")
     # the plain-FMA kernel on the same bf16 inputs only rounds the output
     got2 = _run_ssd(st, "bf16", parent, x, dt, A, Bm, Cm, D, h0, force_fma=True)
-    assert_parity(got2, want, 6e-3, f"fma-bf16 N={N}")
+    assert_parity(got2, want, 6e-3, f"fma-bf16 N={N}", kind="y")
 
 
 def test_bf16_mfma_kernel_skips_column_blocks_without_ancestors(st, oracle):
@@ -149,7 +149,7 @@ def test_bf16_mfma_kernel_skips_column_blocks_without_ancestors(st, oracle):
     x, dt, A, Bm, Cm, D, h0 = _rand(77, "bf16", 3, N, H, P, S, G)
     want = oracle.ssd_paths(parent, x, dt, A, Bm, Cm, D, h0)
     got = _run_ssd(st, "bf16", parent, x, dt, A, Bm, Cm, D, h0)
-    assert_parity(got, want, TOL["bf16"], "mfma block skipping")
+    assert_parity(got, want, TOL["bf16"], "mfma block skipping", kind="y")
 
 
 def test_bf16_optional_arguments(st, oracle):
@@ -159,7 +159,7 @@ def test_bf16_optional_arguments(st, oracle):
     for Dv, hv in ((None, h0), (D, None), (None, None)):
         want = oracle.ssd_paths(parent, x, dt, A, Bm, Cm, Dv, hv)
         got = _run_ssd(st, "bf16", parent, x, dt, A, Bm, Cm, Dv, hv)
-        assert_parity(got, want, TOL["bf16"], "optional args")
+        assert_parity(got, want, TOL["bf16"], "optional args", kind="y")
 
 
 def test_bad_tree_zero_fills_that_sequence_only(st, oracle):
@@ -175,7 +175,7 @@ def test_bad_tree_zero_fills_that_sequence_only(st, oracle):
         assert not got[1].any()
         keep = [0, 2]
         want = oracle.ssd_paths(parent[keep], x[keep], dt[keep], A, Bm[keep], Cm[keep], D, h0[keep])
-        assert_parity(got[keep], want, TOL["bf16"], "good sequences next to a bad one")
+        assert_parity(got[keep], want, TOL["bf16"], "good sequences next to a bad one", kind="y")
 
 
 def test_relabelling_permutes_gpu_outputs(st):
@@ -186,7 +186,7 @@ def test_relabelling_permutes_gpu_outputs(st):
     y1 = _run_ssd(st, "bf16", tree[None], x, dt, A, Bm, Cm, D, h0)
     y2 = _run_ssd(st, "bf16", synth.relabel_dfs(tree)[None], x[:, perm], dt[:, perm], A, Bm[:, perm], Cm[:, perm],
                   D, h0)
-    assert_parity(y2, y1[:, perm], 1e-2, "relabel")
+    assert_parity(y2, y1[:, perm], 1e-2, "relabel", kind="y")
 
 
 # --------------------------------------------------------------------------- #
@@ -236,7 +236,7 @@ def test_commit_state(st, oracle, io):
                                    status=status)
     assert not to_host(status).any()
     for b in range(B):
-        assert_parity(to_host(h)[b], want_h[b], 1e-4, f"commit h b={b}")
+        assert_parity(to_host(h)[b], want_h[b], 1e-4, f"commit h b={b}", kind="state")
     assert np.array_equal(to_host(h)[2], h0[2])                  # -1 keeps the state bit-exactly
     assert np.array_equal(to_host(cso), want_cs.astype(np.float32))   # row copies: exact
     # in place
@@ -261,7 +261,7 @@ def test_commit_edge_cases(st, oracle):
     h = to_host(h)
     assert np.array_equal(h[0], h0[0]) and np.array_equal(h[1], h0[1])
     want, _ = oracle.commit(parent[2:], acc[2:], x[2:], dt[2:], A, Bm[2:], h0[2:])
-    assert_parity(h[2], want[0], 1e-4, "commit next to bad sequences")
+    assert_parity(h[2], want[0], 1e-4, "commit next to bad sequences", kind="state")
     # zero dt: the state comes back bit-exactly
     h2, _ = st.stree_commit_state(to_dev(parent[2:]), to_dev(acc[2:]), to_dev(x[2:], "bf16"),
                                   to_dev(np.zeros_like(dt[2:])), to_dev(A), to_dev(Bm[2:], "bf16"), to_dev(h0[2:]))
@@ -270,7 +270,7 @@ def test_commit_edge_cases(st, oracle):
     h3, _ = st.stree_commit_state(to_dev(parent[2:]), to_dev(acc[2:]), to_dev(x[2:], "bf16"), to_dev(dt[2:]),
                                   to_dev(A), to_dev(Bm[2:], "bf16"), None)
     want3, _ = oracle.commit(parent[2:], acc[2:], x[2:], dt[2:], A, Bm[2:], None)
-    assert_parity(to_host(h3), want3, 1e-4, "commit without h0")
+    assert_parity(to_host(h3), want3, 1e-4, "commit without h0", kind="state")
 
 
 @pytest.mark.parametrize("N", [30, 130])
@@ -322,7 +322,7 @@ def test_commit_unpredicated_kernel_cases(st, oracle, io, N):
     assert list(to_host(status)) == [0, 0, 0, N // 2 + 1, -1, 0]
     h = to_host(h)
     for i, b in enumerate(good):
-        assert_parity(h[b], want[i], 1e-4, f"commit b={b}")
+        assert_parity(h[b], want[i], 1e-4, f"commit b={b}", kind="state")
     for b in (2, 3, 4):                                           # kept bit-exactly
         assert np.array_equal(h[b], h0[b])
     # no initial state: zeros for the sequences that keep it, the update alone for the others
@@ -332,7 +332,7 @@ def test_commit_unpredicated_kernel_cases(st, oracle, io, N):
                                   h_out=torch.full((B, H, P, S), float("nan"), dtype=torch.float32, device="cuda"))
     hz = to_host(hz)
     for i, b in enumerate(good):
-        assert_parity(hz[b], want0[i], 1e-4, f"commit without h0 b={b}")
+        assert_parity(hz[b], want0[i], 1e-4, f"commit without h0 b={b}", kind="state")
     for b in (2, 3, 4):
         assert not hz[b].any()
     # x / B as strided views of one buffer whose rows are not a whole number of 16-byte pieces: the
@@ -342,7 +342,7 @@ def test_commit_unpredicated_kernel_cases(st, oracle, io, N):
     xw[..., :H * P] = to_dev(x, io).reshape(B, N, H * P)
     hv, _ = st.stree_commit_state(to_dev(parent), to_dev(acc), xw[..., :H * P].view(B, N, H, P), to_dev(dt),
                                   to_dev(A), to_dev(Bm, io), to_dev(h0))
-    assert_parity(to_host(hv)[good], h[good], 1e-6, "commit from a misaligned view")
+    assert_parity(to_host(hv)[good], h[good], 1e-6, "commit from a misaligned view", kind="state")
 
 
 @pytest.mark.parametrize("N,H,P,S,G", [(13, 3, 24, 20, 1), (30, 2, 12, 48, 2), (64, 2, 256, 256, 1), (7, 4, 1, 4, 4)])
@@ -355,7 +355,7 @@ def test_commit_ragged_shapes(st, oracle, N, H, P, S, G):
     want, _ = oracle.commit(parent, acc, x, dt, A, Bm, h0)
     h, _ = st.stree_commit_state(to_dev(parent), to_dev(acc), to_dev(x, "f32"), to_dev(dt), to_dev(A),
                                  to_dev(Bm, "f32"), to_dev(h0))
-    assert_parity(to_host(h), want, 1e-4, f"commit P={P} S={S}")
+    assert_parity(to_host(h), want, 1e-4, f"commit P={P} S={S}", kind="state")
 
 
 def test_commit_then_continue_on_gpu(st, oracle):
@@ -372,5 +372,5 @@ def test_commit_then_continue_on_gpu(st, oracle):
                                   to_dev(Bm[:, :n1], "bf16"), to_dev(h0))
     y2 = st.stree_tree_ssd(to_dev(p2[None]), to_dev(x[:, n1:], "bf16"), to_dev(dt[:, n1:]), to_dev(A),
                            to_dev(Bm[:, n1:], "bf16"), to_dev(Cm[:, n1:], "bf16"), to_dev(D), hk)
-    assert_parity(to_host(y2), want, TOL["bf16"], "commit then continue")
+    assert_parity(to_host(y2), want, TOL["bf16"], "commit then continue", kind="y")
 

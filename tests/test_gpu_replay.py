@@ -62,8 +62,8 @@ def test_replay_matches_commit_then_scan(st, oracle, io, B, Np, N, H, P, S, G):
     y, h = _run(st, io, pp, acc, prev, p, cur, A, D, status=status, replay_status=rstatus)
     assert not to_host(status).any() and not to_host(rstatus).any()
     for b in range(B):
-        assert_parity(h[b], want_h[b], 1e-4, f"replayed state b={b}")
-        assert_parity(y[b], want_y[b], TOL[io], f"scan after replay b={b}")
+        assert_parity(h[b], want_h[b], 1e-4, f"replayed state b={b}", kind="state")
+        assert_parity(y[b], want_y[b], TOL[io], f"scan after replay b={b}", kind="y")
     if B > 2:
         assert np.array_equal(h[2], prev[6][2])       # bit-exact pass-through
     # in place: same bits
@@ -94,13 +94,13 @@ def test_replay_edge_cases(st, oracle):
     x, dt, _, Bm, Cm, _, _ = cur
     for b in (0, 1):
         want = oracle.ssd_paths(p[b:b + 1], x[b:b + 1], dt[b:b + 1], A, Bm[b:b + 1], Cm[b:b + 1], D, h0[b:b + 1])
-        assert_parity(y[b], want[0], TOL[io], f"scan from the untouched state b={b}")
+        assert_parity(y[b], want[0], TOL[io], f"scan from the untouched state b={b}", kind="y")
     px, pdt, _, pB, _, _, _ = prev
     for b in (2, 3):
         want_h, _ = oracle.commit(pp[b:b + 1], acc[b:b + 1], px[b:b + 1], pdt[b:b + 1], A, pB[b:b + 1], h0[b:b + 1])
-        assert_parity(h[b], want_h[0], 1e-4, f"replayed state b={b}")
+        assert_parity(h[b], want_h[0], 1e-4, f"replayed state b={b}", kind="state")
     want = oracle.ssd_paths(p[3:4], x[3:4], dt[3:4], A, Bm[3:4], Cm[3:4], D, want_h)
-    assert_parity(y[3], want[0], TOL[io], "scan after replay b=3")
+    assert_parity(y[3], want[0], TOL[io], "scan after replay b=3", kind="y")
 
 
 def test_replay_chain_of_iterations(st, oracle):
@@ -135,10 +135,10 @@ def test_replay_chain_of_iterations(st, oracle):
         xs, dts, Bs = np.concatenate(xs)[None], np.concatenate(dts)[None], np.concatenate(Bs)[None]
         _, hf = oracle.linear_scan(xs, dts, A, Bs, np.zeros_like(Bs), None, h0[b:b + 1])
         want_h[b] = hf[0]
-    assert_parity(to_host(h_dev), want_h, 1e-4, "state after three fused iterations")
+    assert_parity(to_host(h_dev), want_h, 1e-4, "state after three fused iterations", kind="state")
     cur, p = steps[3]
     want_y = oracle.ssd_paths(p, cur[0], cur[1], A, cur[3], cur[4], D, want_h)
-    assert_parity(to_host(y), want_y, TOL[io], "scan of the fourth tree")
+    assert_parity(to_host(y), want_y, TOL[io], "scan of the fourth tree", kind="y")
 
 
 @pytest.mark.parametrize("io,W,N,Np", [("bf16", 4, 70, 33), ("bf16", 2, 64, 64), ("f32", 3, 31, 100), ("bf16", 4, 256, 256)])

@@ -146,12 +146,12 @@ def test_step_fp32_and_large_trees(st, oracle):
     want_h, want_cs = oracle.commit(d["pparent"], d["acc"], px, d["pdt"], d["A"], pB, d["h0"].astype(np.float64),
                                     d["pxbc_pre"], d["conv_state"])
     assert np.array_equal(to_host(one[3]), want_cs.astype(np.float32))
-    assert_parity(to_host(one[1]), want_h, 1e-4, "step fp32: replayed state")
+    assert_parity(to_host(one[1]), want_h, 1e-4, "step fp32: replayed state", kind="state")
     want_conv = oracle.tree_conv(d["parent"], d["xbc_pre"], want_cs.astype(np.float32), d["conv_w"], d["conv_b"], True)
     assert_parity(to_host(one[2]), want_conv, 1e-4, "step fp32: conv output")
     x, Bm, Cm = split_xbc(to_host(one[2]), H, P, G, S)
     want_y = oracle.ssd_paths(d["parent"], x, d["dt"], d["A"], Bm, Cm, d["D"], want_h)
-    assert_parity(to_host(one[0]), want_y, TOL["f32"], "step fp32: y")
+    assert_parity(to_host(one[0]), want_y, TOL["f32"], "step fp32: y", kind="y")
 
 
 def test_step_in_place_state(st):
@@ -192,11 +192,11 @@ def test_step_against_the_oracle_full_size(st, oracle):
     assert np.array_equal(to_host(cs), want_cs)
     got_conv = to_host(xbc)
     assert_parity(got_conv, want_conv, 4e-3, "step: conv output")
-    assert_parity(to_host(h), want_h, 1e-4, "step: replayed state")
+    assert_parity(to_host(h), want_h, 1e-4, "step: replayed state", kind="state")
     # the scan is checked on the inputs it actually saw (the GPU's own rounded conv output)
     x, Bm, Cm = split_xbc(got_conv.astype(np.float32), H, P, G, S)
     want_y = oracle.ssd_paths(wl.parent, x, wl.dt, wl.A, Bm, Cm, wl.D, want_h)
-    assert_parity(to_host(y), want_y, TOL[io], "step: y")
+    assert_parity(to_host(y), want_y, TOL[io], "step: y", kind="y")
 
 
 def test_step_rejects_a_conv_output_that_overlaps_the_previous_one(st):

@@ -33,7 +33,7 @@ def test_paper_tree_shapes_packed_and_unrolled(st, oracle, kind, arg):
     want = oracle.ssd_paths(parent, x, dt, A, Bm, Cm, D, h0)
     got = to_host(st.stree_tree_ssd(to_dev(parent), to_dev(x, io), to_dev(dt), to_dev(A), to_dev(Bm, io),
                                     to_dev(Cm, io), to_dev(D), to_dev(h0)))
-    assert_parity(got, want, TOL[io], f"{kind}{arg} packed")
+    assert_parity(got, want, TOL[io], f"{kind}{arg} packed", kind="y")
     # unrolled: one chain per leaf of sequence 0, its own copy of the state
     ns, nt = oracle.unroll_counts(parent[0])
     has_child = np.zeros(N, dtype=bool)
@@ -47,5 +47,5 @@ def test_paper_tree_shapes_packed_and_unrolled(st, oracle, kind, arg):
         chain = synth.chain_tree(len(path))[None]
         yu = to_host(st.stree_tree_ssd(to_dev(chain), to_dev(x[:1, path], io), to_dev(dt[:1, path]), to_dev(A),
                                        to_dev(Bm[:1, path], io), to_dev(Cm[:1, path], io), to_dev(D), to_dev(h0[:1])))
-        assert_parity(yu[0], want[0, path], TOL[io], f"{kind}{arg} unrolled path to leaf {leaf}")
+        assert_parity(yu[0], want[0, path], TOL[io], f"{kind}{arg} unrolled path to leaf {leaf}", kind="y")
     assert ns == int((~has_child).sum())
