@@ -14,7 +14,9 @@ call sequences do that work and both are timed:
             over the state per iteration instead of two)
 `value` is the faster of the two; both are in the JSON line.  Inputs are resident in HBM before the timed region; the
 step rotates over several buffer sets so that the working set exceeds the
-256 MB Infinity Cache and the scan really streams from HBM.
+256 MB Infinity Cache and the scan really streams from HBM.  The other
+configurations (cfg0, cfg1, cfg3, cfg4) are measured kernel by kernel, HBM-cold
+and cache-warm, under the `configs` key.
 
 Prints ONE JSON line on stdout (metric = tree-nodes/s per SSD layer).  Details
 (per-kernel times, cache-warm numbers) go to stderr.
@@ -54,15 +56,18 @@ def algorithmic_bytes_replay(B, N, Np, H, P, S, G, path_nodes):
     return algorithmic_bytes_tree_ssd(B, N, H, P, S, G) + extra
 
 
-def algorithmic_bytes_step(B, N, Np, H, P, S, G, W, path_nodes):
-    """The whole step in one kernel: the conv's operands (pre-conv rows read, conv output written,
-    conv state read and written, weights and bias, the previous tree's pre-conv rows on the last
-    W-1 path nodes) and the replay + scan's, whose x / B / C are the conv output and are not read
-    from memory a second time."""
+def algorithmic_bytes_conv(B, N, H, P, S, G, W, e=2):
+    """Pre-conv rows read, conv output written, conv state read, weights and bias."""
     Cc = H * P + 2 * G * S
-    conv = B * (2 * N * Cc * 2 + 2 * (W - 1) * Cc * 2) + Cc * (W + 1) * 2 + min(path_nodes, B * (W - 1)) * Cc * 2
-    xbc_reads = B * (N * H * P * 2 + 2 * N * G * S * 2)
-    return algorithmic_bytes_replay(B, N, Np, H, P, S, G, path_nodes) - xbc_reads + conv
+    return B * (2 * N * Cc + (W - 1) * Cc) * e + Cc * (W + 1) * e
+
+
+def algorithmic_bytes_commit(B, N, H, P, S, G, W, path_nodes, e=2):
+    """State read and written once, parent / accepted / dt, the x and B rows of the accepted paths,
+    and (W > 0) the conv tail: W-1 rows read and written per sequence."""
+    Cc = H * P + 2 * G * S
+    tail = B * 2 * (W - 1) * Cc * e if W else 0
+    return 2 * B * H * P * S * 4 + B * (N * 4 + 4 + N * H * 4) + path_nodes * (H * P + G * S) * e + tail
 
 
 def algorithmic_flops_tree_ssd(B, N, H, P, S, G):
@@ -71,12 +76,14 @@ def algorithmic_flops_tree_ssd(B, N, H, P, S, G):
 
 
 def read_traffic(kernel_tag):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None."""
-    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_pmc.txt")
+    """(HBM bytes per launch, source) from the committed rocprofv3 --pmc summary of this kernel and
+    workload -- a figure measured in a profiler run of its own, not by this run -- or (None, None)."""
+    rel = os.path.join("profiles", f"{kernel_tag}_pmc.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, None
     m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
-    return float(m.group(1)) if m else None
+    return (float(m.group(1)), rel) if m else (None, None)
 
 
 def main():
@@ -88,8 +95,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-ssd", type=int, default=0, metavar="K",
                     help="profiling aid: run K tree-scan launches and exit")
-    ap.add_argument("--only-step", type=int, default=0, metavar="K",
-                    help="profiling aid: K launches of the one-launch step kernel only, no timing, then exit")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the kernel-by-kernel table of the other configurations")
+    ap.add_argument("--only-config", type=int, default=-1, metavar="C",
+                    help="profiling aid: measure configuration C kernel by kernel and exit")
     ap.add_argument("--only-fused", type=int, default=0, metavar="K",
                     help="profiling aid: run K fused replay + scan launches and exit")
     ap.add_argument("--prefix", action="store_true",
@@ -119,6 +128,10 @@ def main():
         return prefix(st, synth, torch, dev)
     if args.batches:
         return batches(st, synth, torch, dev)
+    if args.only_config >= 0:
+        print(json.dumps({f"cfg{args.only_config}": measure_config(args.only_config, st, synth, torch, dev,
+                                                                   not args.no_graph)}), flush=True)
+        return
 
     wl = synth.config(2)
     B, N, H, P, S, G, W = wl.batch, wl.nnodes, wl.nheads, wl.headdim, wl.dstate, wl.ngroups, wl.conv_width
@@ -186,106 +199,82 @@ def main():
         conv_replay(s)
         fused(s)
 
-    def step_one(s):         # the same step as one launch
-        q = s["prev"]
-        st.stree_tree_step(q["parent"], q["accepted"], q["xbc_pre"], q["xbc"], q["dt"], s["parent"], s["xbc_pre"],
-                           s["conv_state"], conv_w, conv_b, s["dt"], A, D, s["h0"], H, P, S, G, silu=True,
-                           xbc_out=s["xbc"], conv_state_out=s["cs_out"], h_out=s["h_out"], out=s["y"], one_launch=True)
-
     for s in sets:           # first launches (also sets the kernel's LDS attribute) outside any capture
         step(s)
     for s in sets:
         step_fused(s)
-    for s in sets:
-        step_one(s)
     torch.cuda.synchronize()
 
-    if args.only_ssd or args.only_fused or args.only_step:
+    if args.only_ssd or args.only_fused:
         for k in range(args.only_ssd):
             ssd(sets[k % N_SETS])
         for k in range(args.only_fused):
             fused(sets[k % N_SETS])
-        for k in range(args.only_step):
-            step_one(sets[k % N_SETS])
         torch.cuda.synchronize()
         return
 
-    def make_graphs(fn):
-        """One HIP graph holding fn on every buffer set in turn (N_SETS launches of fn per
-        replay): a replay's own launch cost is then shared by N_SETS kernels."""
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            for s in sets:
-                fn(s)
-        torch.cuda.synchronize()
-        return g.replay
-
     use_graph = not args.no_graph
-    if use_graph:
-        try:
-            run_step = make_graphs(step)
-            run_ssd = make_graphs(ssd)
-            run_conv = make_graphs(conv)
-            run_commit = make_graphs(commit)
-            run_step_fused = make_graphs(step_fused)
-            run_fused = make_graphs(fused)
-            run_tail = make_graphs(conv_replay)
-            run_step_one = make_graphs(step_one)
-            run_conv_ssd = make_graphs(conv_ssd)
-        except Exception as exc:  # pragma: no cover
-            log(f"[bench] HIP graph capture failed ({exc}); falling back to direct launches")
-            use_graph = False
-    if not use_graph:
-        def all_sets(fn):
-            def run():
-                for s in sets:
-                    fn(s)
-            return run
-        run_step, run_ssd, run_conv, run_commit = all_sets(step), all_sets(ssd), all_sets(conv), all_sets(commit)
-        run_step_fused, run_fused, run_tail = all_sets(step_fused), all_sets(fused), all_sets(conv_replay)
-        run_step_one = all_sets(step_one)
-        run_conv_ssd = all_sets(conv_ssd)
 
-    def timed(run, k, warm, per_run=N_SETS):
-        """Wall-clock and HIP-event time per launch of k launches on the current stream
-        (run() issues per_run of them)."""
-        for _ in range(max(1, warm // per_run)):
+    def make_runner(fn, count=N_SETS):
+        """fn on the first `count` buffer sets in turn, as one HIP graph (a replay's own launch cost
+        is then shared by `count` kernels) or, without graphs, as direct launches."""
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for s in sets[:count]:
+                    fn(s)
+            torch.cuda.synchronize()
+            return g.replay
+
+        def run():
+            for s in sets[:count]:
+                fn(s)
+        return run
+
+    def timed(fn, k, warm):
+        """Wall-clock and HIP-event time per launch of EXACTLY k launches of fn on the current stream:
+        whole rotations of the buffer sets, then the remaining k % N_SETS launches."""
+        run = make_runner(fn)
+        rem = k % N_SETS
+        run_rem = make_runner(fn, rem) if rem else None
+        for _ in range(max(1, warm // N_SETS)):
             run()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = k // per_run
+        reps = k // N_SETS
         t0 = time.perf_counter()
         e0.record()
         for _ in range(reps):
             run()
+        if run_rem:
+            run_rem()
         e1.record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        return (t1 - t0) * 1e3 / (reps * per_run), e0.elapsed_time(e1) / (reps * per_run)
+        return (t1 - t0) * 1e3 / k, e0.elapsed_time(e1) / k
 
-    K, Wm = args.steps, args.warmup
-    K -= K % N_SETS                      # whole rotations of the buffer sets
-    ms_step, ms_step_ev = timed(run_step, K, Wm)
+    K, Wm = max(1, args.steps), args.warmup
+    try:
+        ms_step, ms_step_ev = timed(step, K, Wm)
+    except Exception as exc:  # pragma: no cover
+        if not use_graph:
+            raise
+        log(f"[bench] HIP graph capture failed ({exc}); falling back to direct launches")
+        use_graph = False
+        ms_step, ms_step_ev = timed(step, K, Wm)
     # dominant kernel alone, same rotation (HBM-cold), HIP events on the launch stream
-    _, ms_ssd = timed(run_ssd, K, Wm)
-    _, ms_conv = timed(run_conv, K, Wm)
-    _, ms_commit = timed(run_commit, K, Wm)
-    ms_fstep, ms_fstep_ev = timed(run_step_fused, K, Wm)
-    _, ms_fused = timed(run_fused, K, Wm)
-    _, ms_tail = timed(run_tail, K, Wm)
-    ms_ostep, ms_ostep_ev = timed(run_step_one, K, Wm)
-    ms_cs, _ = timed(run_conv_ssd, K, Wm)
+    _, ms_ssd = timed(ssd, K, Wm)
+    _, ms_conv = timed(conv, K, Wm)
+    _, ms_commit = timed(commit, K, Wm)
+    ms_fstep, ms_fstep_ev = timed(step_fused, K, Wm)
+    _, ms_fused = timed(fused, K, Wm)
+    _, ms_tail = timed(conv_replay, K, Wm)
+    ms_cs, _ = timed(conv_ssd, K, Wm)
     # one buffer set only: inputs stay in the 256 MB Infinity Cache
-    warm_fn = (lambda: ssd(sets[0]))
-    if use_graph:
-        gw = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(gw):
-            for _ in range(N_SETS):
-                ssd(sets[0])
-        warm_fn = gw.replay
-        _, ms_ssd_warm = timed(warm_fn, K, Wm)
-    else:
-        _, ms_ssd_warm = timed(warm_fn, K, Wm, per_run=1)
+    keep = sets
+    sets = [keep[0]] * N_SETS
+    _, ms_ssd_warm = timed(ssd, K, Wm)
+    sets = keep
 
     nodes = B * N
     alg_bytes = algorithmic_bytes_tree_ssd(B, N, H, P, S, G)
@@ -307,33 +296,24 @@ def main():
     log(f"[bench]   replay+scan: {alg_bytes_f/1e6:.2f} MB algorithmic -> {achieved_f:.0f} GB/s "
         f"({achieved_f/HBM_PEAK_GBS*100:.1f}% of 8 TB/s)")
 
-    alg_bytes_o = algorithmic_bytes_step(B, N, N, H, P, S, G, W, path_nodes)
-    achieved_o = alg_bytes_o / (ms_ostep_ev * 1e-3) / 1e9
-    log(f"[bench] one launch: step {ms_ostep*1e3:.1f} us wall ({ms_ostep_ev*1e3:.1f} us events): "
-        f"{alg_bytes_o/1e6:.2f} MB algorithmic -> {achieved_o:.0f} GB/s ({achieved_o/HBM_PEAK_GBS*100:.1f}% of 8 TB/s)")
-
-    steps = {"separate": ms_step, "fused": ms_fstep, "one_launch": ms_ostep}
+    steps = {"separate": ms_step, "fused": ms_fstep}
     best = min(steps, key=steps.get)
     ms_best = steps[best]
-    roof_scan = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,false,false>", "achieved": achieved,
+    tr_scan, src_scan = read_traffic("tree_ssd_mfma_cfg2")
+    tr_fused, src_fused = read_traffic("tree_ssd_replay_cfg2")
+    roof_scan = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,false>", "achieved": achieved,
                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                 "traffic": read_traffic("tree_ssd_mfma_cfg2"),
+                 "traffic": tr_scan, "traffic_source": src_scan,
                  "algorithmic_bytes": alg_bytes, "avg_launch_us": ms_ssd * 1e3,
                  "cache_warm_us": ms_ssd_warm * 1e3,
                  "mfma_tflops": alg_flops / (ms_ssd * 1e-3) / 1e12}
-    roof_fused = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,true,false>", "achieved": achieved_f,
+    roof_fused = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,true>", "achieved": achieved_f,
                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_f / HBM_PEAK_GBS,
-                  "traffic": read_traffic("tree_ssd_replay_cfg2"),
+                  "traffic": tr_fused, "traffic_source": src_fused,
                   "algorithmic_bytes": alg_bytes_f, "avg_launch_us": ms_fused * 1e3}
-    roof_one = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,true,true>", "achieved": achieved_o,
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_o / HBM_PEAK_GBS,
-                "traffic": read_traffic("tree_step_cfg2"),
-                "algorithmic_bytes": alg_bytes_o, "avg_launch_us": ms_ostep_ev * 1e3}
     what = {"separate": "tree_conv + tree_ssd + commit_state",
             "fused": "tree_conv_replay + tree_ssd_replay (the previous tree is committed inside both: conv tail "
-                     "while the conv rows are staged, state while it is loaded for the scan)",
-            "one_launch": "tree_step: one launch that convolves (the previous tree's conv tail folded in), replays "
-                          "the previous tree's accepted path on the state as it is loaded, and scans"}
+                     "while the conv rows are staged, state while it is loaded for the scan)"}
     out = {
         "metric": "tree-nodes/sec per SSD layer at 1 MI355X; % of MFMA/HBM roofline",
         "value": nodes / (ms_best * 1e-3),
@@ -346,7 +326,7 @@ def main():
                    "sequence": best,
                    "batch": B, "nnodes": N, "hip_graph": use_graph, "buffer_sets": N_SETS},
         # the dominant kernel of the timed step
-        "roofline": {"separate": roof_scan, "fused": roof_fused, "one_launch": roof_one}[best],
+        "roofline": {"separate": roof_scan, "fused": roof_fused}[best],
         "roofline_tree_ssd_alone": roof_scan,
         "steps_us": {k: v * 1e3 for k, v in steps.items()},
         # tree-nodes/s of the scan alone, of conv + scan, and of the whole step (conv + scan + commit, best sequence)
@@ -355,10 +335,119 @@ def main():
         "kernels_us": {"tree_conv": ms_conv * 1e3, "tree_ssd": ms_ssd * 1e3, "commit_state": ms_commit * 1e3,
                        "tree_conv_replay": ms_tail * 1e3, "tree_ssd_replay": ms_fused * 1e3},
     }
+    del sets, keep
+    torch.cuda.empty_cache()
+    if not args.no_configs:
+        out["configs"] = {f"cfg{c}": measure_config(c, st, synth, torch, dev, use_graph) for c in (0, 1, 3, 4)}
+        out["configs"]["cfg2"] = {
+            "workload": "the headline workload above", "tree_ssd": {
+                "us_cold": ms_ssd * 1e3, "us_warm": ms_ssd_warm * 1e3, "algorithmic_bytes": alg_bytes,
+                "GBps": achieved, "frac": achieved / HBM_PEAK_GBS, "nodes_per_s": nodes / (ms_ssd * 1e-3)},
+            "tree_conv": {"us_cold": ms_conv * 1e3, "algorithmic_bytes": algorithmic_bytes_conv(B, N, H, P, S, G, W),
+                          "GBps": algorithmic_bytes_conv(B, N, H, P, S, G, W) / (ms_conv * 1e-3) / 1e9},
+            "commit_state": {"us_cold": ms_commit * 1e3,
+                             "algorithmic_bytes": algorithmic_bytes_commit(B, N, H, P, S, G, W, path_nodes),
+                             "GBps": algorithmic_bytes_commit(B, N, H, P, S, G, W, path_nodes) / (ms_commit * 1e-3) / 1e9}}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)
+
+
+def measure_config(cid, st, synth, torch, dev, use_graph):
+    """One configuration kernel by kernel: tree scan (and conv / commit where the configuration has
+    them), HBM-cold (rotating buffer sets of more than 256 MB in total) and cache-warm (one set),
+    HIP events around graph replays on the launch stream.  The trees are the configuration's seeded
+    ones; activations are random tensors drawn on the device (timing depends on shapes and trees)."""
+    wl = synth.config(cid, {"prefix": 64} if cid == 4 else None)
+    B, N, H, P, S, G, W = wl.batch, wl.nnodes, wl.nheads, wl.headdim, wl.dstate, wl.ngroups, wl.conv_width
+    Cc = H * P + 2 * G * S
+    io = torch.bfloat16 if wl.io_dtype == "bf16" else torch.float32
+    e = 2 if wl.io_dtype == "bf16" else 4
+    per_set = B * (2 * N * Cc * e + N * H * P * e + 2 * H * P * S * 4 + N * H * 4)
+    n_sets = int(min(96, max(3, -(-320 * 2 ** 20 // per_set))))
+    parent = torch.from_numpy(wl.parent).to(dev)
+    rng = np.random.default_rng(cid)
+    depth = np.stack([synth.tree_depths(wl.parent[b]) for b in range(B)])
+    acc_np = wl.accepted if wl.accepted is not None else np.array(
+        [int(rng.integers(0, N)) for _ in range(B)], dtype=np.int32)
+    path_nodes = int(sum(depth[b, acc_np[b]] + 1 for b in range(B) if acc_np[b] >= 0))
+    accepted = torch.from_numpy(np.asarray(acc_np, dtype=np.int32)).to(dev)
+    A = -torch.rand(H, device=dev) - 0.5
+    D = torch.randn(H, device=dev)
+    conv_w = (torch.rand((Cc, max(W, 1)), device=dev) - 0.5).to(io)
+    conv_b = (torch.rand(Cc, device=dev) - 0.5).to(io)
+    sets = []
+    for _ in range(n_sets):
+        s = dict(xbc_pre=torch.randn((B, N, Cc), device=dev).to(io), xbc=torch.randn((B, N, Cc), device=dev).to(io),
+                 dt=torch.rand((B, N, H), device=dev) * 0.1 + 0.01, h0=torch.randn((B, H, P, S), device=dev) * 0.1,
+                 y=torch.empty((B, N, H, P), dtype=io, device=dev),
+                 h_out=torch.empty((B, H, P, S), dtype=torch.float32, device=dev))
+        if W:
+            s["cs"] = torch.randn((B, W - 1, Cc), device=dev).to(io)
+            s["cs_out"] = torch.empty_like(s["cs"])
+        s["x"] = s["xbc"][:, :, : H * P].unflatten(2, (H, P))
+        s["Bm"] = s["xbc"][:, :, H * P: H * P + G * S].unflatten(2, (G, S))
+        s["Cm"] = s["xbc"][:, :, H * P + G * S:].unflatten(2, (G, S))
+        sets.append(s)
+
+    def ssd(s):
+        st.stree_tree_ssd(parent, s["x"], s["dt"], A, s["Bm"], s["Cm"], D, s["h0"], out=s["y"])
+
+    def conv(s):
+        st.stree_tree_conv(parent, s["xbc_pre"], s["cs"], conv_w, conv_b, H, P, S, G, silu=True, out=s["xbc"])
+
+    def commit(s):
+        st.stree_commit_state(parent, accepted, s["x"], s["dt"], A, s["Bm"], s["h0"], h_out=s["h_out"],
+                              xbc_pre=s["xbc_pre"] if W else None, conv_state=s["cs"] if W else None,
+                              conv_state_out=s["cs_out"] if W else None)
+
+    def time_us(fn, use_sets, reps):
+        for s in use_sets:
+            fn(s)
+        torch.cuda.synchronize()
+        run = None
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for s in use_sets:
+                    fn(s)
+            run = g.replay
+        else:
+            def run():
+                for s in use_sets:
+                    fn(s)
+        run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (reps * len(use_sets)) * 1e3
+
+    reps = max(2, 240 // n_sets)
+    row = {"workload": f"{wl.name}: batch {B} x {N}-node trees, {H} heads x {P}, dstate {S}, ngroups {G}, "
+                       f"conv width {W}, {wl.io_dtype} io", "buffer_sets": n_sets}
+    kernels = [("tree_ssd", ssd, algorithmic_bytes_tree_ssd(B, N, H, P, S, G) if e == 2 else
+                algorithmic_bytes_tree_ssd(B, N, H, P, S, G) + B * (2 * N * H * P + 2 * N * G * S) * 2)]
+    if W:
+        kernels.append(("tree_conv", conv, algorithmic_bytes_conv(B, N, H, P, S, G, W, e)))
+    if wl.accepted is not None:
+        kernels.append(("commit_state", commit, algorithmic_bytes_commit(B, N, H, P, S, G, W, path_nodes, e)))
+    for name, fn, nbytes in kernels:
+        cold = time_us(fn, sets, reps)
+        warm = time_us(fn, [sets[0]] * min(n_sets, 8), max(2, 240 // min(n_sets, 8)))
+        row[name] = {"us_cold": cold, "us_warm": warm, "algorithmic_bytes": nbytes, "GBps": nbytes / cold / 1e3,
+                     "frac": nbytes / cold / 1e3 / HBM_PEAK_GBS}
+        if name == "tree_ssd":
+            row[name]["nodes_per_s"] = B * N / (cold * 1e-6)
+        log(f"[bench] {wl.name}: {name:12s} {cold:7.2f} us cold ({nbytes/cold/1e3:5.0f} GB/s = "
+            f"{nbytes/cold/8e4:4.1f}% of 8 TB/s), {warm:7.2f} us warm; {nbytes/1e6:.2f} MB algorithmic")
+    del sets
+    torch.cuda.empty_cache()
+    return row
 
 
 def prefix(st, synth, torch, dev):
@@ -592,8 +681,9 @@ def sweep(st, synth, torch, dev):
 
 
 def cpu_baseline(wl):
-    """The oracle as it stands (fp64 C, OpenMP over batch x head), timed on the
-    host: full-size steps of the same workload, repeated to about 10-20 s."""
+    """The oracle as it stands (fp64 C, OpenMP over batch x head), timed on the host: full-size steps of
+    the same workload (conv + scan + commit), repeated to about 12 s with the path-unrolled scan (the
+    oracle's primary form) and to about 6 s more with its per-node-state scan (the faster formulation)."""
     from oracle import ref
     from paper_2505_14969_amd import synth
     H, P, S, G = wl.nheads, wl.headdim, wl.dstate, wl.ngroups
@@ -601,26 +691,34 @@ def cpu_baseline(wl):
     xbc_pre, cs, w, b, dt, A, D, h0 = map(f64, (wl.xbc_pre, wl.conv_state, wl.conv_w, wl.conv_b, wl.dt, wl.A, wl.D,
                                                 wl.h0))
 
-    def one():
+    def one(scan):
         conv = ref.tree_conv(wl.parent, xbc_pre, cs, w, b, True)
         xbc = synth.round_to_bf16(conv.astype(np.float32)).astype(np.float64)
         Bn, N, _ = xbc.shape
         x = np.ascontiguousarray(xbc[:, :, : H * P].reshape(Bn, N, H, P))
         Bm = np.ascontiguousarray(xbc[:, :, H * P: H * P + G * S].reshape(Bn, N, G, S))
         Cm = np.ascontiguousarray(xbc[:, :, H * P + G * S:].reshape(Bn, N, G, S))
-        ref.ssd_paths(wl.parent, x, dt, A, Bm, Cm, D, h0)
+        scan(wl.parent, x, dt, A, Bm, Cm, D, h0)
         ref.commit(wl.parent, wl.accepted, x, dt, A, Bm, h0, xbc_pre, cs)
 
-    one()
-    t0 = time.perf_counter()
-    reps = 0
-    while reps < 3 or (time.perf_counter() - t0 < 12.0 and reps < 200):
-        one()
-        reps += 1
-    dt_s = (time.perf_counter() - t0) / reps
-    return {"value": wl.batch * wl.nnodes / dt_s, "unit": "tree-nodes/s", "cores": ref.num_threads(),
+    def run(scan, budget_s):
+        one(scan)
+        t0 = time.perf_counter()
+        reps = 0
+        while reps < 3 or (time.perf_counter() - t0 < budget_s and reps < 200):
+            one(scan)
+            reps += 1
+        return reps, (time.perf_counter() - t0) / reps
+
+    reps, dt_s = run(ref.ssd_paths, 12.0)
+    reps2, dt2_s = run(ref.ssd_nodes, 6.0)
+    nodes = wl.batch * wl.nnodes
+    return {"value": nodes / dt_s, "unit": "tree-nodes/s", "cores": ref.num_threads(),
             "kind": "oracle", "sample": f"{reps} full-size steps of the same cfg2 batch (conv + path-unrolled "
-                                       f"fp64 scan + commit), {dt_s*1e3:.0f} ms each"}
+                                       f"fp64 scan + commit), {dt_s*1e3:.0f} ms each",
+            "per_node_state_scan": {"value": nodes / dt2_s, "unit": "tree-nodes/s",
+                                    "sample": f"{reps2} full-size steps with the oracle's per-node-state scan "
+                                              f"in place of the path-unrolled one, {dt2_s*1e3:.0f} ms each"}}
 
 
 if __name__ == "__main__":
