@@ -175,3 +175,19 @@ def commit(parent, accepted, x, dt, A, Bm, h0=None, xbc_pre=None, conv_state=Non
     if st:
         raise ValueError("invalid tree or accepted index")
     return h_out, cs_out
+
+
+def gate_norm(y, z, w, ngroups: int, eps: float = 1e-5):
+    """Output gate and grouped RMS norm of the Mamba2 block behind the scan:
+    out = rmsnorm_per_group(y * silu(z)) * w.  y, z [..., H, P] (or [..., d]); w [d];
+    groups are ngroups runs of d / ngroups consecutive channels.  Returns y's shape."""
+    y, z, w = map(_f64, (y, z, w))
+    d = w.shape[0]
+    rows = y.size // d
+    assert y.shape == z.shape and y.size == rows * d
+    out = np.full((rows, d), np.nan)
+    st = lib().orc_gate_norm(C.c_int(rows), C.c_int(d), C.c_int(ngroups), _p(y.reshape(rows, d)),
+                             _p(z.reshape(rows, d)), _p(w), C.c_double(eps), _p(out))
+    if st:
+        raise ValueError("ngroups does not divide the channel count")
+    return out.reshape(y.shape)

@@ -37,6 +37,10 @@
  *   orc_commit            state after the accepted path + conv tail; pinned by
  *                         orc_linear_scan on the extracted path and by
  *                         commit-then-continue == grafted tree.
+ *   orc_gate_norm         output gate and grouped RMS norm behind the scan (the
+ *                         Mamba2 block that the SSM of Sec. 3 sits in; not in
+ *                         the paper): pinned by torch's silu and rms_norm, by
+ *                         a hand-worked 2 x 4 example and by closed forms.
  *
  * Layouts (all contiguous, fp64 unless noted):
  *   parent int32 [B,N] (root -1, parent[i] < i)    x  [B,N,H,P]
@@ -373,6 +377,37 @@ int orc_commit(int B, int N, int H, int P, int S, int G, int W, int Cc, const in
                 memcpy(conv_state_out + ((size_t)b * (W - 1) + r) * Cc, row, sizeof(double) * (size_t)Cc);
             }
             free(path);
+        }
+    }
+    return 0;
+}
+
+/*
+ * Output gate and grouped RMS norm of the Mamba2 block behind the SSM (not in
+ * the paper; the block the scan of Sec. 3 sits in): per node, with the d = H*P
+ * channels split into G groups of gs = d / G consecutive channels,
+ *   v_c   = y_c * z_c * sigmoid(z_c)                       (gate: y * silu(z))
+ *   out_c = v_c / sqrt(mean_{c' in group(c)} v_{c'}^2 + eps) * w_c
+ * y, z, out [rows, d]; w [d].  Returns 1 when G does not divide d.
+ */
+int orc_gate_norm(int rows, int d, int G, const double *y, const double *z, const double *w, double eps,
+                  double *out) {
+    if (G < 1 || d % G != 0) return 1;
+    const int gs = d / G;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < rows; ++r) {
+        for (int g = 0; g < G; ++g) {
+            const double *yr = y + (size_t)r * d + (size_t)g * gs;
+            const double *zr = z + (size_t)r * d + (size_t)g * gs;
+            double *o = out + (size_t)r * d + (size_t)g * gs;
+            double ss = 0.0;
+            for (int c = 0; c < gs; ++c) {
+                const double v = yr[c] * (zr[c] / (1.0 + exp(-zr[c])));
+                o[c] = v;
+                ss += v * v;
+            }
+            const double scale = 1.0 / sqrt(ss / gs + eps);
+            for (int c = 0; c < gs; ++c) o[c] = o[c] * scale * w[g * gs + c];
         }
     }
     return 0;

@@ -384,3 +384,64 @@ def test_prefix_in_chunks_equals_one_scan(oracle):
         sl = slice(c * chunk, (c + 1) * chunk)
         h, _ = oracle.commit(synth.chain_tree(chunk), [chunk - 1], x[:, sl], dt[:, sl], A, Bm[:, sl], h)
     assert np.array_equal(h, hf)
+
+
+# --------------------------------------------------------------------------- #
+# output gate + grouped RMS norm behind the scan (the Mamba2 block; not in the paper)
+# --------------------------------------------------------------------------- #
+def test_gate_norm_hand_worked_example(oracle):
+    """tests/golden/gate_norm_example.txt: 2 rows x 4 channels, 2 groups, worked by hand."""
+    rows, w = [], None
+    for line in open(os.path.join(GOLDEN, "gate_norm_example.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        f = line.split()
+        if f[0] == "w":
+            w = np.array([float(v) for v in f[1:]])
+        else:
+            rows.append([float(v) for v in f[1:]])
+    rows = np.array(rows)
+    y, z, want = rows[:, :4], rows[:, 4:8] * np.log(3.0), rows[:, 8:]
+    got = oracle.gate_norm(y, z, w, 2, 0.0)
+    assert np.allclose(got, want, rtol=0, atol=5e-10)
+
+
+def test_gate_norm_against_torch_silu_and_rms_norm(oracle):
+    """The two library routines the step is made of: silu, then rms_norm on each group."""
+    import torch
+    import torch.nn.functional as F
+    rng = np.random.default_rng(70)
+    for (rows, H, P, G, eps) in ((5, 4, 8, 1, 1e-5), (3, 6, 4, 3, 1e-6), (2, 8, 16, 8, 0.0), (4, 2, 3, 2, 1e-5)):
+        d = H * P
+        y = rng.standard_normal((rows, H, P)); z = 2.0 * rng.standard_normal((rows, H, P)); w = rng.uniform(0.5, 1.5, d)
+        v = torch.from_numpy(y) * F.silu(torch.from_numpy(z))
+        vg = v.reshape(rows, G, d // G)
+        want = F.rms_norm(vg, (d // G,), eps=eps).reshape(rows, d) * torch.from_numpy(w)
+        got = oracle.gate_norm(y, z, w, G, eps)
+        assert got.shape == y.shape
+        _close(got.reshape(rows, d), want.numpy(), 1e-13)
+
+
+def test_gate_norm_closed_forms(oracle):
+    rng = np.random.default_rng(71)
+    rows, d, G = 4, 24, 3
+    y = rng.standard_normal((rows, d)); z = rng.standard_normal((rows, d)); w = rng.uniform(0.5, 1.5, d)
+    base = oracle.gate_norm(y, z, w, G, 0.0)
+    # without eps the norm forgets the scale of y; each group has unit mean square before the weight
+    _close(oracle.gate_norm(7.5 * y, z, w, G, 0.0), base, 1e-13)
+    ms = np.mean((base / w).reshape(rows, G, d // G) ** 2, axis=-1)
+    assert np.allclose(ms, 1.0, rtol=1e-12)
+    # a group only sees its own channels
+    y2 = y.copy(); y2[:, : d // G] *= -3.0
+    other = oracle.gate_norm(y2, z, w, G, 0.0)
+    assert np.array_equal(other[:, d // G:], base[:, d // G:]) and not np.allclose(other[:, : d // G], base[:, : d // G])
+    # z = 0 closes the gate: silu(0) = 0, and with eps > 0 the output is exactly zero
+    assert not oracle.gate_norm(y, np.zeros_like(z), w, G, 1e-5).any()
+    # large z opens it: silu(z) -> z, so y * silu(z) -> y z
+    zz = np.full_like(z, 40.0)
+    v = y * 40.0
+    want = v / np.sqrt(np.mean(v.reshape(rows, G, -1) ** 2, axis=-1, keepdims=True)).repeat(d // G, -1).reshape(rows, d) * w
+    _close(oracle.gate_norm(y, zz, w, G, 0.0), want, 1e-12)
+    with pytest.raises(ValueError):
+        oracle.gate_norm(y, z, w, 5, 0.0)
