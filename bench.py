@@ -154,6 +154,8 @@ def main():
         s["y"] = torch.empty((B, N, H, P), dtype=torch.bfloat16, device=dev)
         s["h_out"] = torch.empty((B, H, P, S), dtype=torch.float32, device=dev)
         s["cs_out"] = torch.empty_like(s["conv_state"])
+        s["z"] = torch.randn((B, N, H, P), device=dev).to(torch.bfloat16)     # gate input (random: not part of the step)
+        s["yn"] = torch.empty((B, N, H, P), dtype=torch.bfloat16, device=dev)
         s["x"] = s["xbc"][:, :, : H * P].unflatten(2, (H, P))
         s["Bm"] = s["xbc"][:, :, H * P: H * P + G * S].unflatten(2, (G, S))
         s["Cm"] = s["xbc"][:, :, H * P + G * S:].unflatten(2, (G, S))
@@ -169,6 +171,11 @@ def main():
     def commit(s):
         st.stree_commit_state(s["parent"], s["accepted"], s["x"], s["dt"], A, s["Bm"], s["h0"], h_out=s["h_out"],
                               xbc_pre=s["xbc_pre"], conv_state=s["conv_state"], conv_state_out=s["cs_out"])
+
+    norm_w = torch.ones(H * P, dtype=torch.bfloat16, device=dev)
+
+    def gate_norm(s):        # the block's output gate + grouped RMS norm behind the scan (timed on its own)
+        st.stree_gate_norm(s["y"], s["z"], norm_w, G, 1e-5, out=s["yn"])
 
     def step(s):
         conv(s)
@@ -270,6 +277,7 @@ def main():
     _, ms_fused = timed(fused, K, Wm)
     _, ms_tail = timed(conv_replay, K, Wm)
     ms_cs, _ = timed(conv_ssd, K, Wm)
+    _, ms_gn = timed(gate_norm, K, Wm)
     # one buffer set only: inputs stay in the 256 MB Infinity Cache
     keep = sets
     sets = [keep[0]] * N_SETS
@@ -291,6 +299,8 @@ def main():
     log(f"[bench]   tree_ssd: {alg_bytes/1e6:.2f} MB algorithmic -> {achieved:.0f} GB/s "
         f"({achieved/HBM_PEAK_GBS*100:.1f}% of 8 TB/s); {alg_flops/ (ms_ssd*1e-3)/1e12:.1f} TFLOP/s bf16 MFMA "
         f"(dense-masked count); scan-only {nodes/(ms_ssd*1e-3)/1e6:.1f} M nodes/s")
+    log(f"[bench]   gate + RMS norm behind the scan {ms_gn*1e3:.2f} us "
+        f"({(3 * B * N * H * P * 2) / (ms_gn * 1e-3) / 1e9:.0f} GB/s)")
     log(f"[bench] fused:    step {ms_fstep*1e3:.1f} us wall ({ms_fstep_ev*1e3:.1f} us events)")
     log(f"[bench]   conv (tail folded in) {ms_tail*1e3:.2f} us | replay+scan {ms_fused*1e3:.2f} us")
     log(f"[bench]   replay+scan: {alg_bytes_f/1e6:.2f} MB algorithmic -> {achieved_f:.0f} GB/s "
@@ -333,7 +343,11 @@ def main():
         "nodes_per_s": {"tree_ssd": nodes / (ms_ssd * 1e-3), "conv+ssd": nodes / (ms_cs * 1e-3),
                         "conv+ssd+commit": nodes / (ms_best * 1e-3)},
         "kernels_us": {"tree_conv": ms_conv * 1e3, "tree_ssd": ms_ssd * 1e3, "commit_state": ms_commit * 1e3,
-                       "tree_conv_replay": ms_tail * 1e3, "tree_ssd_replay": ms_fused * 1e3},
+                       "tree_conv_replay": ms_tail * 1e3, "tree_ssd_replay": ms_fused * 1e3,
+                       "gate_norm": ms_gn * 1e3},
+        # the output gate + RMS norm behind the scan: y and z read, out written (not part of the timed step)
+        "gate_norm": {"us": ms_gn * 1e3, "algorithmic_bytes": 3 * B * N * H * P * 2 + H * P * 2,
+                      "GBps": (3 * B * N * H * P * 2 + H * P * 2) / (ms_gn * 1e-3) / 1e9},
     }
     del sets, keep
     torch.cuda.empty_cache()

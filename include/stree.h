@@ -249,6 +249,27 @@ int stree_tree_step(const stree_dims *dims, const stree_replay *prev, const void
                     void *y, int32_t *tree_status, int32_t *replay_status, void *hip_stream);
 
 /*
+ * Output gate and grouped RMS norm behind the scan (the Mamba2 block that the SSM of
+ * Sec. 3 sits in -- Eq. in_proj names its projections; the paper does not print the
+ * gate and the norm, they follow public Mamba2 practice): per node, the d = H*P
+ * channels of y split into ngroups runs of d / ngroups consecutive channels,
+ *   v   = y * z * sigmoid(z)
+ *   out = v / sqrt(mean over the channel's group of v^2 + eps) * norm_w
+ *   y      io [B,N,H,P] dense: the scan's output
+ *   z      io [B,N,H,P] with token stride z_stride_n elements (0 = dense), so that z may
+ *          be a column range of the input projection's output
+ *   norm_w io [H*P];  eps >= 0
+ *   out    io [B,N,H,P] dense, MAY alias y
+ * fp32 arithmetic, one rounding of the result.  16-byte aligned pointers, a stride and a
+ * group size that are multiples of 8 (bf16) or 4 (fp32) elements, and groups of at most
+ * 8192 (bf16) / 4096 (fp32) channels take the single-pass kernel (y and z read once);
+ * anything else a plain two-pass kernel with the same result.  No tree is involved, so
+ * there is no tree_status.
+ */
+int stree_gate_norm(const stree_dims *dims, const void *y, const void *z, int64_t z_stride_n,
+                    const void *norm_w, float eps, void *out, void *hip_stream);
+
+/*
  * Linear prefix scan: the ordinary causal Mamba2 scan of T tokens per sequence (the
  * chain case of the tree mask, Sec. 3: a lower-triangular L is Mamba2 with an
  * initial state), chunked, with the state carried from chunk to chunk on chip.  It

@@ -70,6 +70,8 @@ def load() -> C.CDLL:
         lib.stree_tree_step.argtypes = [dp, C.POINTER(StreeReplay)] + [_VP] * 17
         lib.stree_linear_ssd.argtypes = [dp] + [_VP] * 10
         lib.stree_linear_ssd.restype = C.c_int
+        lib.stree_gate_norm.argtypes = [dp, _VP, _VP, C.c_int64, _VP, C.c_float, _VP, _VP]
+        lib.stree_gate_norm.restype = C.c_int
         for f in (lib.stree_tree_index, lib.stree_tree_conv, lib.stree_tree_ssd, lib.stree_commit_state,
                   lib.stree_tree_ssd_replay, lib.stree_tree_conv_replay, lib.stree_tree_step):
             f.restype = C.c_int
@@ -291,6 +293,19 @@ def stree_tree_step(prev_parent, prev_accepted, prev_xbc_pre, prev_xbc_out, prev
                                   _ptr(dt), _ptr(A), _ptr(D), _ptr(h0), _ptr(h_out), _ptr(out), _ptr(status),
                                   _ptr(replay_status), _stream()), "stree_tree_step")
     return out, h_out, xbc_out, conv_state_out
+
+
+def stree_gate_norm(y, z, norm_w, ngroups: int, eps: float = 1e-5, out: Optional[torch.Tensor] = None):
+    """Output gate and grouped RMS norm: y [B,N,H,P] dense, z [B,N,H,P] (may be a column view with its
+    own token stride), norm_w [H*P] -> out [B,N,H,P]; out may be y itself."""
+    B, N, H, P = y.shape
+    assert y.is_contiguous() and z.shape == y.shape and z.dtype == y.dtype and norm_w.numel() == H * P
+    if out is None:
+        out = torch.empty_like(y)
+    d = make_dims(B, N, H, P, 1, ngroups, 0, _io_code(y))
+    _check(load().stree_gate_norm(C.byref(d), _ptr(y), _ptr(z), _token_stride(z, N), _ptr(norm_w), C.c_float(eps),
+                                  _ptr(out), _stream()), "stree_gate_norm")
+    return out
 
 
 def stree_linear_ssd(x, dt, A, Bm, Cm=None, D=None, h0=None, want_y: bool = True,

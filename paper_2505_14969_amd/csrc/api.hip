@@ -227,6 +227,20 @@ int stree_tree_step(const stree_dims *dims, const stree_replay *prev, const void
                                  y, tree_status, replay_status, hip_stream);
 }
 
+int stree_gate_norm(const stree_dims *dims, const void *y, const void *z, int64_t z_stride_n, const void *norm_w,
+                    float eps, void *out, void *hip_stream) {
+    int rc = check_dims(dims, kNoConv);
+    if (rc) return rc;
+    if (!y || !z || !norm_w || !out) return STREE_ERR_NULL_ARG;
+    const int64_t d = (int64_t)dims->nheads * dims->headdim;
+    if (z_stride_n == 0) z_stride_n = d;
+    if (z_stride_n < d) return STREE_ERR_BAD_STRIDE;
+    if (!(eps >= 0.f)) return STREE_ERR_BAD_SHAPE;
+    if ((int64_t)dims->batch * dims->nnodes * dims->ngroups > 0x7fffffffLL) return STREE_ERR_BAD_SHAPE;
+    if (dims->batch == 0) return STREE_OK;
+    return hip_status(stree::launch_gate_norm(*dims, y, z, (long)z_stride_n, norm_w, eps, out, (hipStream_t)hip_stream));
+}
+
 int stree_linear_ssd(const stree_dims *dims, const void *x, const float *dt, const float *A, const void *Bm,
                      const void *Cm, const float *D, const float *h0, void *y, float *h_out, void *hip_stream) {
     if (!dims) return STREE_ERR_NULL_ARG;

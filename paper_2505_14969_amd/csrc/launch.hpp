@@ -60,6 +60,10 @@ bool linear_ssd_supported(const stree_dims &d, const void *x, const void *Bm, co
 hipError_t launch_linear_ssd(const stree_dims &d, const void *x, const float *dt, const float *A, const void *Bm,
                              const void *Cm, const float *D, const float *h0, void *y, float *h_out, hipStream_t st);
 
+// output gate + grouped RMS norm behind the scan; z_sn = token stride of z in elements
+hipError_t launch_gate_norm(const stree_dims &d, const void *y, const void *z, long z_sn, const void *w, float eps,
+                            void *out, hipStream_t st);
+
 // h_out == NULL: conv tail only
 hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const int32_t *accepted,
                                const void *x, const float *dt, const float *A, const void *Bm,
