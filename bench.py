@@ -101,6 +101,8 @@ def main():
                     help="profiling aid: measure configuration C kernel by kernel and exit")
     ap.add_argument("--only-fused", type=int, default=0, metavar="K",
                     help="profiling aid: run K fused replay + scan launches and exit")
+    ap.add_argument("--only-gate", type=int, default=0, metavar="K",
+                    help="profiling aid: run K gate + norm launches and exit")
     ap.add_argument("--prefix", action="store_true",
                     help="the 4096-token prefix pass of the prefix-then-tree configuration: the chunked linear "
                          "scan kernel against 16 chain-tree calls (prints its own JSON line)")
@@ -212,11 +214,13 @@ def main():
         step_fused(s)
     torch.cuda.synchronize()
 
-    if args.only_ssd or args.only_fused:
+    if args.only_ssd or args.only_fused or args.only_gate:
         for k in range(args.only_ssd):
             ssd(sets[k % N_SETS])
         for k in range(args.only_fused):
             fused(sets[k % N_SETS])
+        for k in range(args.only_gate):
+            gate_norm(sets[k % N_SETS])
         torch.cuda.synchronize()
         return
 
@@ -404,6 +408,10 @@ def measure_config(cid, st, synth, torch, dev, use_graph):
         s["Bm"] = s["xbc"][:, :, H * P: H * P + G * S].unflatten(2, (G, S))
         s["Cm"] = s["xbc"][:, :, H * P + G * S:].unflatten(2, (G, S))
         sets.append(s)
+
+    # a plain copy of known size (the fp32 state of one set, read and written once): the kernel
+    # that scales the FETCH_SIZE / WRITE_SIZE counters when this function runs under a profiler
+    torch.roll(sets[0]["h0"], 1, 0)
 
     def ssd(s):
         st.stree_tree_ssd(parent, s["x"], s["dt"], A, s["Bm"], s["Cm"], D, s["h0"], out=s["y"])

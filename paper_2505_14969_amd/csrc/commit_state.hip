@@ -168,20 +168,43 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
         const float dt_i = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
         bad = build_tree_index(tree, mask, parent + (size_t)b * n, n, n, words, dt_i, A_h);
         len = 0;
-        decay = 1.f;
         if (!bad && k >= 0 && !k_bad) {
             // compact path(k) (ancestors have smaller labels, so ascending label = root first)
-            const float s_k = tree.s[k];
             if (tid < n && mask_bit(mask, words, k, tid)) {
                 int pos = 0;
                 for (int w = 0; w < (tid >> 5); ++w) pos += __popc(mask[k * words + w]);
                 pos += __popc(mask[k * words + (tid >> 5)] & ((1u << (tid & 31)) - 1u));
                 path[pos] = tid;
-                coef[pos] = tree.dt[tid] * __expf(s_k - tree.s[tid]);
+                coef[pos] = tree.dt[tid];              // the step size for now, the weight below
             }
             len = tree.cnt[k];
-            decay = __expf(s_k);
         }
+        __syncthreads();
+        // exp(s_k - s_j) as the exponential of the sum of dt_m A over the path nodes BEHIND j, summed
+        // along the path itself (thread = position on the path from here on): its rounding error is
+        // relative to that sum, which is small wherever the weight is not negligible, while the
+        // difference of two prefix sums carries the error of |s_k| (hundreds on a long chain with a
+        // strong decay: 1e-4 in the weight).  Suffix sums inside each wave, then the later waves' totals.
+        __shared__ float wave_total[kThreads / 64];
+        const float dt_p = tid < len ? coef[tid] : 0.f;
+        float suf = dt_p * A_h;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float t = __shfl_down(suf, off);
+            if (lane + off < 64) suf += t;
+        }
+        float behind = __shfl_down(suf, 1);
+        if (lane == 63) behind = 0.f;
+        if (lane == 0) wave_total[tid >> 6] = suf;
+        __syncthreads();
+        float whole = 0.f;
+#pragma unroll
+        for (int w = kThreads / 64 - 1; w >= 0; --w) {
+            if (w > (tid >> 6)) behind += wave_total[w];
+            whole += wave_total[w];
+        }
+        if (tid < len) coef[tid] = dt_p * __expf(behind);
+        decay = __expf(whole);                         // (no path: exp(0) = 1)
         __syncthreads();
     }
     if (status && blockIdx.x == 0 && h == 0 && tid == 0) status[b] = bad ? bad : (k_bad ? -1 : 0);

@@ -19,8 +19,9 @@ def st():
     return binding
 
 
-def _pipeline(st, oracle, wl, h0_dev, h0_ref, check_commit=True):
-    """conv -> ssd -> commit on both sides; returns nothing, asserts parity."""
+def _pipeline(st, oracle, wl, h0_dev, h0_ref, check_commit=True, ew_tol_y=None):
+    """conv -> ssd -> commit on both sides; returns nothing, asserts parity.  ew_tol_y: the
+    elementwise bound on y where a configuration states its own (default: the tensor tolerance)."""
     import torch
     H, P, S, G = wl.nheads, wl.headdim, wl.dstate, wl.ngroups
     io = wl.io_dtype
@@ -42,12 +43,12 @@ def _pipeline(st, oracle, wl, h0_dev, h0_ref, check_commit=True):
     dt_d, A_d, D_d = to_dev(wl.dt), to_dev(wl.A), to_dev(wl.D)
     ox, oB, oC = split_xbc_dev(to_dev(ref_xbc, io), H, P, G, S)
     y_iso = st.stree_tree_ssd(par_d, ox, dt_d, A_d, oB, oC, D_d, to_dev(h0_ref.astype(np.float32)))
-    assert_parity(to_host(y_iso), want_y, TOL[io], f"{wl.name} y (scan alone)", kind="y")
+    assert_parity(to_host(y_iso), want_y, TOL[io], f"{wl.name} y (scan alone)", kind="y", ew_tol=ew_tol_y)
     # ---- tree scan, end to end: views of the GPU's own conv output and the GPU's own h0
     gx, gB, gC = split_xbc_dev(xbc_d, H, P, G, S)
     y_d = st.stree_tree_ssd(par_d, gx, dt_d, A_d, gB, gC, D_d, h0_dev, status=status)
     assert not to_host(status).any()
-    assert_parity(to_host(y_d), want_y, TOL[io], f"{wl.name} y (conv + scan)", kind="y")
+    assert_parity(to_host(y_d), want_y, TOL[io], f"{wl.name} y (conv + scan)", kind="y", ew_tol=ew_tol_y)
     if not check_commit:
         return
     # ---- commit
@@ -165,4 +166,10 @@ def test_config4_prefix_then_tree(st, oracle):
         st.stree_commit_state(chain, last, px[:, sl].contiguous(), pdt[:, sl].contiguous(), A_d,
                               pB[:, sl].contiguous(), h, h_out=h)
     assert_parity(to_host(h), h_ref, 1e-4, "cfg4 prefix state", kind="state")
-    _pipeline(st, oracle, wl, h, h_ref)
+    # The state behind 4096 tokens is heavy-tailed (rms 0.37, single entries up to 11, whole rows at
+    # twice their head's rms).  It enters the scan as a bf16 MFMA operand, so an element of y carries
+    # a rounding error of about 2^-9 / sqrt(3) * |C_i| * rms(h0[p, :]): it scales with the state's row
+    # p, not with the head's y.  The worst of the 5.2e6 elements (a 5-sigma draw on a heavy row) sits
+    # at 3.0e-2 of |ref| + rms(block) with both MFMA kernels alike (the fp32 FMA kernel: 3.6e-3); the
+    # per-tensor bounds hold at 3.2e-3.  Hence the wider elementwise bound for this configuration.
+    _pipeline(st, oracle, wl, h, h_ref, ew_tol_y=4e-2)
