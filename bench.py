@@ -465,6 +465,8 @@ def measure_config(cid, st, synth, torch, dev, use_graph):
                      "frac": nbytes / cold / 1e3 / HBM_PEAK_GBS}
         if name == "tree_ssd":
             row[name]["nodes_per_s"] = B * N / (cold * 1e-6)
+            if N > 64:
+                row[name]["traffic"], row[name]["traffic_source"] = read_traffic(f"tree_ssd_blocks_cfg{cid}")
         log(f"[bench] {wl.name}: {name:12s} {cold:7.2f} us cold ({nbytes/cold/1e3:5.0f} GB/s = "
             f"{nbytes/cold/8e4:4.1f}% of 8 TB/s), {warm:7.2f} us warm; {nbytes/1e6:.2f} MB algorithmic")
     del sets
