@@ -23,9 +23,14 @@
  *     `io_dtype` selects fp32 or bf16 for x, B, C, y and the conv tensors.
  *   - Envelope: 1 <= nnodes <= 256, batch >= 0 (0 is a no-op), nheads % ngroups
  *     == 0, 1 <= headdim <= 256, 1 <= dstate <= 256, conv_width in {2,3,4}.
- *     The MFMA kernel is used when io_dtype is bf16, headdim in {32,64,128},
+ *     An MFMA kernel is used when io_dtype is bf16, headdim in {32,64,128},
  *     dstate % 16 == 0 and pointers/strides are 16-byte aligned; every other
- *     case in the envelope runs a plain fp32-FMA kernel.
+ *     case in the envelope runs a plain fp32-FMA kernel.  Among the MFMA
+ *     shapes, the persistent kernels (the ones the benchmark prices) take
+ *     headdim 64 with dstate 64 or 128 at any node count, and headdim 128 with
+ *     dstate 128 at up to 64 nodes; the remaining MFMA shapes (headdim 32,
+ *     dstate 256, ...) run one workgroup per (sequence, head) and are several
+ *     times slower per node.  Results are the same to rounding on every route.
  */
 #ifndef STREE_H
 #define STREE_H
