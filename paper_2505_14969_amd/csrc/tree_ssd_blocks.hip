@@ -123,7 +123,9 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
     };
 
     // ---- prefetch registers and their loaders ---------------------------------------------------
-    // Rows past the tree are read from row n-1 (valid memory) and zeroed when staged: no branches.
+    // Rows past the tree are read from row n-1 (valid memory): no branches, and nothing to zero when
+    // they are staged -- as columns j >= n they have no ancestor bit and u_j = +inf (weight 0, removed
+    // by the select), as rows i >= n they only reach outputs that are never stored.
     // One register array serves both roles (a thread is either Y or G for its whole life):
     //   Y threads  pre[0 .. NH)          state tile of the next unit (fp32 bits)
     //   G threads  pre[0 .. NC)          B tile of the next pass        pre[NC .. 2 NC)   C tile of the next row block
@@ -148,7 +150,8 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
     };
     auto load_rows = [&](int r0, const bf16_t *base, long sn, int b, int g, int blk) {
         const char *rb = reinterpret_cast<const char *>(base + (size_t)b * n * sn + (size_t)g * S);
-        const int t = opaque(rt), rc0 = t / (S / 8), cc0 = t % (S / 8);
+        const uint32_t t = (uint32_t)opaque(rt);
+        const int rc0 = (int)(t / (S / 8)), cc0 = (int)(t % (S / 8));
 #pragma unroll
         for (int q = 0; q < NC; ++q) {
             const int rr = min(blk * kBk + rc0 + q * kRowsC, n - 1);
@@ -159,7 +162,8 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
     auto load_C = [&](const PassId &p) { load_rows(kPreC, Cm, c_sn, p.b, p.h / hpg, p.ib); };
     auto load_X = [&](const PassId &p) {
         const char *xb = reinterpret_cast<const char *>(x + (size_t)p.b * n * x_sn + (size_t)p.h * P);
-        const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
+        const uint32_t t = (uint32_t)opaque(rt);
+        const int rx0 = (int)(t / (P / 8)), cx0 = (int)(t % (P / 8));
 #pragma unroll
         for (int q = 0; q < NX; ++q)
             pre[kPreX + q] = *reinterpret_cast<const uint4 *>(
@@ -175,32 +179,25 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
         }
     };
     // ---- registers -> LDS -------------------------------------------------------------------------
-    auto stage_rows = [&](int r0, bf16_t *tile, int blk) {
-        const int t = opaque(rt), rc0 = t / (S / 8), cc0 = t % (S / 8);
+    auto stage_rows = [&](int r0, bf16_t *tile) {
+        const uint32_t t = (uint32_t)opaque(rt);
+        const int rc0 = (int)(t / (S / 8)), cc0 = (int)(t % (S / 8));
 #pragma unroll
-        for (int q = 0; q < NC; ++q) {
-            const int rr = rc0 + q * kRowsC;
-            const uint32_t keep = blk * kBk + rr < n ? 0xffffffffu : 0u;   // zero the rows beyond the tree
-            *reinterpret_cast<uint4 *>(&tile[rr * SP + cc0 * 8]) =
-                make_uint4(pre[r0 + q].x & keep, pre[r0 + q].y & keep, pre[r0 + q].z & keep, pre[r0 + q].w & keep);
-        }
+        for (int q = 0; q < NC; ++q)
+            *reinterpret_cast<uint4 *>(&tile[(rc0 + q * kRowsC) * SP + cc0 * 8]) = pre[r0 + q];
     };
-    auto stage_X = [&](int blk) {
-        const int t = opaque(rt), rx0 = t / (P / 8), cx0 = t % (P / 8);
+    auto stage_X = [&]() {
+        const uint32_t t = (uint32_t)opaque(rt);
+        const int rx0 = (int)(t / (P / 8)), cx0 = (int)(t % (P / 8));
 #pragma unroll
-        for (int q = 0; q < NX; ++q) {
-            const int rr = rx0 + q * kRowsX;
-            const uint32_t keep = blk * kBk + rr < n ? 0xffffffffu : 0u;
-            const uint4 xq = pre[kPreX + q];
-            store_transposed_pair<P / 8>(sXT, kNPk, rr, cx0 * 8,
-                                         make_uint4(xq.x & keep, xq.y & keep, xq.z & keep, xq.w & keep), opaque(lane));
-        }
+        for (int q = 0; q < NX; ++q)
+            store_transposed_pair<P / 8>(sXT, kNPk, rx0 + q * kRowsX, cx0 * 8, pre[kPreX + q], opaque(lane));
     };
     auto stage_H = [&]() {
-        const int t = opaque(rt);
+        const uint32_t t = (uint32_t)opaque(rt);
 #pragma unroll
         for (int q = 0; q < NH; ++q) {
-            const int e = (t + q * kHalf) * 4, p = e / S, sidx = e % S;
+            const uint32_t e = (t + q * kHalf) * 4u, p = e / S, sidx = e % S;
             bf16x4 o;
             o[0] = (bf16_t)__uint_as_float(pre[q].x); o[1] = (bf16_t)__uint_as_float(pre[q].y);
             o[2] = (bf16_t)__uint_as_float(pre[q].z); o[3] = (bf16_t)__uint_as_float(pre[q].w);
@@ -466,9 +463,9 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
         load_B(cur);
         load_X(cur);
         if (isT) build_index(cur.b, cur.h, true);
-        stage_rows(kPreC, sC, 0);
-        stage_rows(kPreB, sB, 0);
-        stage_X(0);
+        stage_rows(kPreC, sC);
+        stage_rows(kPreB, sB);
+        stage_X();
         while (true) {
             // the next pass's tiles: in flight for this whole pass
             // the next unit's parents and steps (tree wave): in flight for this whole unit
@@ -542,9 +539,9 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
             __syncthreads();                                  // barrier (a): X^T and the y scratch in the B tile are dead
             // ---- the one wait of this role: the next pass's tiles registers -> LDS ----------------------
             if (!v1) break;
-            stage_rows(kPreB, sB, n1.jb);
-            stage_X(n1.jb);
-            if (n1.jb == 0) stage_rows(kPreC, sC, n1.ib);
+            stage_rows(kPreB, sB);
+            stage_X();
+            if (n1.jb == 0) stage_rows(kPreC, sC);
             cur = n1;
             n1 = next_pass(n1);
         }
