@@ -228,18 +228,46 @@ __device__ __forceinline__ unsigned long long wave_read(unsigned long long v, in
     return ((unsigned long long)hi << 32) | lo;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (no LDS
+// round trips): shifts by 1, 2, 4, 8 inside each row of 16 lanes (zeros shifted in), then lane 15
+// of rows 0 and 2 broadcast to rows 1 and 3, then lane 31 to the upper half.
+template <int CTRL, int ROW_MASK, bool BOUND>
+__device__ __forceinline__ float dpp_move(float a) {     // lanes the move does not reach read 0
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(a), CTRL, ROW_MASK, 0xf, BOUND));
+}
+__device__ __forceinline__ float wave_inclusive_sum(float v) {
+    v += dpp_move<0x111, 0xf, true>(v);    // row_shr:1
+    v += dpp_move<0x112, 0xf, true>(v);    // row_shr:2
+    v += dpp_move<0x114, 0xf, true>(v);    // row_shr:4
+    v += dpp_move<0x118, 0xf, true>(v);    // row_shr:8
+    v += dpp_move<0x142, 0xa, false>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_move<0x143, 0xc, false>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // Transposing store of one 16-byte row piece (8 bf16 of row r, columns c8 .. c8+7) into an LDS
 // tile laid out [column][row] with `ld` elements per column.  Two-byte scatter writes would put
 // two lanes into every LDS word and serialise; instead the lanes holding rows r and r^1 of the
 // same columns (lane ^ VPR, VPR = 16-byte pieces per row) swap half of their data, and each
 // writes four full words (row pair, one column each).  Every lane of the wave must call it.
-template <int VPR>
+//
+// SWZ: the tile's 16-byte groups of a column (8 rows each) are permuted by the column's group of 8,
+//   group g of column c lies at group g ^ ((c >> 3) & 7)       (transposed_at() below),
+// because without it the lanes of a wave that hold the same rows of different column groups all
+// write to the same banks (8 columns x ld elements is a multiple of 32 words whatever the padding):
+// 8- to 16-way conflicts on every transposing store.  Readers of a swizzled tile address it
+// through transposed_at(); a 16-byte read of 8 consecutive rows stays one aligned group.
+template <bool SWZ>
+__device__ __forceinline__ int transposed_at(int ld, int c, int r) {     // element index of (column c, row r)
+    return c * ld + (SWZ ? ((((r >> 3) ^ (c >> 3)) & 7) << 3) | (r & ~63) | (r & 7) : r);
+}
+template <int VPR, bool SWZ = false>
 __device__ __forceinline__ void store_transposed_pair(unsigned short *tile, int ld, int r, int c8, uint4 v, int lane) {
     const bool odd = r & 1;
     const uint32_t r0 = wave_read(odd ? v.x : v.z, lane ^ VPR), r1 = wave_read(odd ? v.y : v.w, lane ^ VPR);
     // even row: columns c8..c8+3, own values low; odd row: columns c8+4..c8+7, own values high
     const uint32_t lo0 = odd ? r0 : v.x, lo1 = odd ? r1 : v.y, hi0 = odd ? v.z : r0, hi1 = odd ? v.w : r1;
-    uint32_t *dst = reinterpret_cast<uint32_t *>(tile + (c8 + (odd ? 4 : 0)) * ld + (r & ~1));
+    uint32_t *dst = reinterpret_cast<uint32_t *>(tile + transposed_at<SWZ>(ld, c8 + (odd ? 4 : 0), r & ~1));
     const int ldw = ld / 2;
     dst[0] = (lo0 & 0xffffu) | (hi0 << 16);
     dst[ldw] = (lo0 >> 16) | (hi0 & 0xffff0000u);

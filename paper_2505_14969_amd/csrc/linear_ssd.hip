@@ -125,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
         for (int q = 0; q < NC; ++q) {
             const int r = rc0 + q * kRowsC;
             const uint32_t keep = (c0 + r < T) ? 0xffffffffu : 0u;
-            store_transposed_pair<S / 8>(sBT, kCP, r, cc0 * 8,
+            store_transposed_pair<S / 8, true>(sBT, kCP, r, cc0 * 8,
                                          make_uint4(rb[q].x & keep, rb[q].y & keep, rb[q].z & keep, rb[q].w & keep), lane);
         }
     };
@@ -149,17 +149,13 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
         for (int q = 0; q < NX; ++q) {
             const int r = rx0 + q * kRowsX;
             const uint32_t keep = (c0 + r < T) ? 0xffffffffu : 0u;
-            store_transposed_pair<P / 8>(sXT, kCP, r, cx0 * 8,
+            store_transposed_pair<P / 8, true>(sXT, kCP, r, cx0 * 8,
                                          make_uint4(rx[q].x & keep, rx[q].y & keep, rx[q].z & keep, rx[q].w & keep), lane);
         }
-        if (tid < kChunk) {   // wave 0: inclusive scan of dt * A over the chunk's tokens
-            float s2 = rdt * A2;
-#pragma unroll
-            for (int off = 1; off < kChunk; off <<= 1) {
-                const float up = wave_read(s2, max(lane - off, 0));
-                if (lane >= off) s2 += up;
-            }
-            const float last = wave_read(s2, kChunk - 1);
+        if (tid < kChunk) {   // wave 0: inclusive scan of dt * A over the chunk's tokens (on the
+            // chunk's critical path: every other wave waits for it at the barrier below)
+            const float s2 = wave_inclusive_sum(rdt * A2);
+            const float last = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s2), kChunk - 1));
             const float u = s2 - __log2f(rdt);                 // dt = 0 -> +inf -> weight 0
             sS2[lane] = s2;
             sU[lane] = u;
@@ -245,13 +241,14 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
                 for (int rg = 0; rg < 4; ++rg)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        xv[4 * rg + e] = __uint_as_float((uint32_t)sXT[(pt * 32 + 8 * rg + 4 * lh + e) * kCP + il] << 16);
-                const bf16_t *ap = reinterpret_cast<const bf16_t *>(sXT) + (pt * 32 + l32) * kCP + 8 * lh;
+                        xv[4 * rg + e] = __uint_as_float((uint32_t)sXT[transposed_at<true>(kCP, pt * 32 + 8 * rg + 4 * lh + e, il)] << 16);
+                const bf16_t *xt = reinterpret_cast<const bf16_t *>(sXT);
                 const bf16_t *bp = &sM[il * kCP + 8 * lh];
                 const int ksteps = it ? 4 : 2;
                 for (int j = 0; j < ksteps; ++j)
-                    acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(ap + 16 * j),
-                                                                     *reinterpret_cast<const bf16x8 *>(bp + 16 * j), acc[q], 0, 0, 0);
+                    acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        *reinterpret_cast<const bf16x8 *>(xt + transposed_at<true>(kCP, pt * 32 + l32, 8 * lh + 16 * j)),
+                        *reinterpret_cast<const bf16x8 *>(bp + 16 * j), acc[q], 0, 0, 0);
                 // row r of the wave's tile keeps its 16-byte chunk c at slot c ^ ((r >> 2) & 3)
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg) {
@@ -286,7 +283,7 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
                 const float4 w0 = *reinterpret_cast<const float4 *>(&sW[k0 + 8 * lh]);
                 const float4 w1 = *reinterpret_cast<const float4 *>(&sW[k0 + 8 * lh + 4]);
                 const float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-                const uint4 xr = *reinterpret_cast<const uint4 *>(&sXT[(pt * 32 + l32) * kCP + 8 * lh + k0]);
+                const uint4 xr = *reinterpret_cast<const uint4 *>(&sXT[transposed_at<true>(kCP, pt * 32 + l32, 8 * lh + k0)]);
                 const float xf[8] = {bf16_lo(xr.x), bf16_hi(xr.x), bf16_lo(xr.y), bf16_hi(xr.y),
                                      bf16_lo(xr.z), bf16_hi(xr.z), bf16_lo(xr.w), bf16_hi(xr.w)};
                 bf16x8 t0, t1;
@@ -299,7 +296,7 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
 #pragma unroll
                 for (int q = 0; q < TQ; ++q) {
                     const int st = (wave % WPP) * TQ + q;
-                    const bf16x8 bt = *reinterpret_cast<const bf16x8 *>(&sBT[(st * 32 + l32) * kCP + 8 * lh + k0]);
+                    const bf16x8 bt = *reinterpret_cast<const bf16x8 *>(&sBT[transposed_at<true>(kCP, st * 32 + l32, 8 * lh + k0)]);
                     hacc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bt, t0, hacc[q], 0, 0, 0);
                     hacc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bt, t1, hacc[q], 0, 0, 0);
                 }
