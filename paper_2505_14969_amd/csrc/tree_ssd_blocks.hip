@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
         const int rx0 = (int)(t / (P / 8)), cx0 = (int)(t % (P / 8));
 #pragma unroll
         for (int q = 0; q < NX; ++q)
-            store_transposed_pair<P / 8>(sXT, kNPk, rx0 + q * kRowsX, cx0 * 8, pre[kPreX + q], opaque(lane));
+            store_transposed_pair<P / 8, true>(sXT, kNPk, rx0 + q * kRowsX, cx0 * 8, pre[kPreX + q], opaque(lane));
     };
     auto stage_H = [&]() {
         const uint32_t t = (uint32_t)opaque(rt);
@@ -377,13 +377,14 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
                 for (int q = 0; q < YQ; ++q) {
                     const int pt = (opaque(wave) + 4 * q) >> 1;
                     if (!bad) {
-                        const bf16_t *ap = reinterpret_cast<const bf16_t *>(sXT) + (pt * 32 + l32) * kNPk + 8 * lh;
+                        const bf16_t *xt = reinterpret_cast<const bf16_t *>(sXT);   // (swizzled: transposed_at)
                         const bf16_t *bp = &sM[il * kNPk + 8 * lh];
                         if (it || !diag) {
                             bf16x8 a[4], bb[4];
 #pragma unroll
                             for (int j = 0; j < 4; ++j) {
-                                a[j] = *reinterpret_cast<const bf16x8 *>(ap + 16 * j);
+                                a[j] = *reinterpret_cast<const bf16x8 *>(
+                                    xt + transposed_at<true>(kNPk, pt * 32 + l32, 8 * lh + 16 * j));
                                 bb[j] = *reinterpret_cast<const bf16x8 *>(bp + 16 * j);
                             }
 #pragma unroll
@@ -393,7 +394,8 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
                             bf16x8 a[2], bb[2];
 #pragma unroll
                             for (int j = 0; j < 2; ++j) {
-                                a[j] = *reinterpret_cast<const bf16x8 *>(ap + 16 * j);
+                                a[j] = *reinterpret_cast<const bf16x8 *>(
+                                    xt + transposed_at<true>(kNPk, pt * 32 + l32, 8 * lh + 16 * j));
                                 bb[j] = *reinterpret_cast<const bf16x8 *>(bp + 16 * j);
                             }
 #pragma unroll
@@ -410,7 +412,7 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 const float xv =
-                                    __uint_as_float((uint32_t)sXT[(pt * 32 + 8 * rg + 4 * lh + e) * kNPk + il] << 16);
+                                    __uint_as_float((uint32_t)sXT[transposed_at<true>(kNPk, pt * 32 + 8 * rg + 4 * lh + e, il)] << 16);
                                 o[e] = bad ? (bf16_t)0.f : (bf16_t)fmaf(D_h, xv, acc[q][4 * rg + e]);
                             }
                             yreg[q][rg] = o;
