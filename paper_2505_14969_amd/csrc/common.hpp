@@ -245,6 +245,23 @@ __device__ __forceinline__ float wave_inclusive_sum(float v) {
     return v;
 }
 
+// Sum of the lanes ABOVE each lane (exclusive suffix sum), same moves in the other direction: shifts
+// towards lower lanes inside each row of 16, the totals of the rows above added from scalars, then
+// one shift of the whole wave.  `total` = the sum over all 64 lanes.
+__device__ __forceinline__ float wave_exclusive_suffix_sum(float v, float &total) {
+    v += dpp_move<0x101, 0xf, true>(v);    // row_shl:1
+    v += dpp_move<0x102, 0xf, true>(v);    // row_shl:2
+    v += dpp_move<0x104, 0xf, true>(v);    // row_shl:4
+    v += dpp_move<0x108, 0xf, true>(v);    // row_shl:8
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    const int row = (int)(__lane_id() >> 4);
+    v += row == 0 ? r1 + (r2 + r3) : row == 1 ? r2 + r3 : row == 2 ? r3 : 0.f;
+    total = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    return dpp_move<0x130, 0xf, true>(v);  // wave_shl:1: lane l reads lane l + 1, lane 63 reads 0
+}
+
 // Transposing store of one 16-byte row piece (8 bf16 of row r, columns c8 .. c8+7) into an LDS
 // tile laid out [column][row] with `ld` elements per column.  Two-byte scatter writes would put
 // two lanes into every LDS word and serialise; instead the lanes holding rows r and r^1 of the

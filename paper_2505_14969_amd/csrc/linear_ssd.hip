@@ -155,12 +155,17 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
         if (tid < kChunk) {   // wave 0: inclusive scan of dt * A over the chunk's tokens (on the
             // chunk's critical path: every other wave waits for it at the barrier below)
             const float s2 = wave_inclusive_sum(rdt * A2);
-            const float last = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s2), kChunk - 1));
-            const float u = s2 - __log2f(rdt);                 // dt = 0 -> +inf -> weight 0
+            // The state's weights dt_j exp(s_last - s_j) from the sum of the steps BEHIND token j, taken
+            // on its own: its rounding error is relative to that sum -- small wherever the weight is
+            // not negligible -- while s_last - s_j as a difference of prefix sums carries the error of
+            // |s_last| (a strong decay over 64 tokens: 1e-4 in the weight, the whole error budget of
+            // the state).
+            float whole;
+            const float behind = wave_exclusive_suffix_sum(rdt * A2, whole);
             sS2[lane] = s2;
-            sU[lane] = u;
-            sW[lane] = __builtin_amdgcn_exp2f(last - u);       // dt_j exp(s_last - s_j)
-            if (lane == 0) *sDecay = __builtin_amdgcn_exp2f(last);
+            sU[lane] = s2 - __log2f(rdt);                      // dt = 0 -> +inf -> weight 0
+            sW[lane] = rdt * __builtin_amdgcn_exp2f(behind);
+            if (lane == 0) *sDecay = __builtin_amdgcn_exp2f(whole);
         }
         if constexpr (!WY) write_bt(c0);                      // no B rows needed: B^T at once
         if (c0 + kChunk < T) {

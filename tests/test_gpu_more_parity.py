@@ -166,3 +166,75 @@ def test_seeded_shape_sweep(st, oracle):
                                        H, P, S, G, silu=True))
         bound = (2.0 ** -8 if io == "bf16" else 2e-5) * np.abs(want_c) + 1e-5
         assert np.all(np.abs(c - want_c) <= bound), "conv, " + tag
+
+
+@pytest.mark.parametrize("N,kw", [(64, {}), (64, dict(force_fma=True)), (128, {}), (200, {}),
+                                  (200, dict(general_mfma=True))])
+def test_scan_with_extreme_decay_and_mixed_heads(st, oracle, N, kw):
+    """dt A = -50 per node on some heads: every ancestor's contribution and the initial state vanish
+    (exp(-50)), y_i = dt_i <C_i,B_i> x_i + D x_i (a closed form the oracle is pinned to), while for
+    NON-ancestor pairs exp(s_i - s_j) overflows to +inf after a few levels -- which must be removed by
+    the select, never multiplied by zero.  The other heads keep ordinary decays, and some of their
+    steps are large (dt = 8: decay factors down to exp(-59))."""
+    B, H, P, S, G = 3, 4, 64, 128, 2
+    parent = _trees(480 + N, B, N)
+    parent[1] = synth.chain_tree(N)
+    x, dt, A, Bm, Cm, D, h0 = _rand(481 + N, "bf16", B, N, H, P, S, G)
+    A[0] = A[2] = -100.0
+    dt[:, :, 0] = dt[:, :, 2] = 0.5
+    dt[:, ::5, 1] = 8.0
+    want = oracle.ssd_paths(parent, x, dt, A, Bm, Cm, D, h0)
+    f8 = np.float64
+    closed = (dt.astype(f8)[:, :, [0, 2], None] * np.einsum("bngs,bngs->bng", Cm.astype(f8), Bm.astype(f8))[:, :, [0, 1], None]
+              + D.astype(f8)[[0, 2]][None, None, :, None]) * x.astype(f8)[:, :, [0, 2]]
+    assert np.allclose(want[:, :, [0, 2]], closed, rtol=1e-9, atol=1e-15)
+    got = _run_ssd(st, "bf16", parent, x, dt, A, Bm, Cm, D, h0, **kw)
+    assert np.isfinite(got).all()
+    assert_parity(got, want, TOL["bf16"], f"scan with extreme decays, N={N} {kw}", kind="y")
+
+
+def test_commit_replay_and_prefix_scan_with_extreme_decay(st, oracle):
+    """The same for the state: on a head with dt A = -50 per node the committed state is dt_k x_k
+    (outer) B_k of the accepted node alone, through the commit kernel (both sizes), the fused replay
+    and the chunked prefix scan.  (The prefix scan's chunk sums reach 4600 in log2 units there: as a
+    difference of prefix sums its weights would be off by 2e-4.)"""
+    import torch
+    H, P, S, G = 4, 64, 128, 2
+    for N in (48, 150):
+        B = 3
+        parent = _trees(490 + N, B, N)
+        x, dt, A, Bm, Cm, D, h0 = _rand(491 + N, "bf16", B, N, H, P, S, G)
+        A[1] = -100.0
+        dt[:, :, 1] = 0.5
+        acc = np.array([N - 1, 0, N // 2], dtype=np.int32)
+        want_h, _ = oracle.commit(parent, acc, x, dt, A, Bm, h0, None, None)
+        bidx = np.arange(B)
+        closed = (dt.astype(np.float64)[bidx, acc, 1][:, None, None] * x.astype(np.float64)[bidx, acc, 1][:, :, None]
+                  * Bm.astype(np.float64)[bidx, acc, 0][:, None, :])
+        assert np.allclose(want_h[:, 1], closed, rtol=1e-9, atol=1e-15)
+        h, _ = st.stree_commit_state(to_dev(parent), to_dev(acc), to_dev(x, "bf16"), to_dev(dt), to_dev(A),
+                                     to_dev(Bm, "bf16"), to_dev(h0))
+        got = to_host(h)
+        assert np.isfinite(got).all()
+        assert_parity(got, want_h, 1e-4, f"commit with an extreme decay, N={N}", kind="state")
+        if N <= 64:      # the fused replay + scan of a following tree from that state
+            parent2 = _trees(495, B, 40)
+            x2, dt2, _, B2, C2, _, _ = _rand(496, "bf16", B, 40, H, P, S, G)
+            want_y = oracle.ssd_paths(parent2, x2, dt2, A, B2, C2, D, want_h)
+            y, h2 = st.stree_tree_ssd_replay(to_dev(parent), to_dev(acc), to_dev(x, "bf16"), to_dev(dt),
+                                             to_dev(Bm, "bf16"), to_dev(parent2), to_dev(x2, "bf16"), to_dev(dt2),
+                                             to_dev(A), to_dev(B2, "bf16"), to_dev(C2, "bf16"), to_dev(D), to_dev(h0))
+            assert_parity(to_host(h2), want_h, 1e-4, "fused replay with an extreme decay: state", kind="state")
+            assert_parity(to_host(y), want_y, TOL["bf16"], "fused replay with an extreme decay: y", kind="y")
+    # prefix scan: 300 tokens, one head with dt A = -50 per token, one with large steps
+    B, T = 2, 300
+    x, dt, A, Bm, Cm, D, h0 = _rand(499, "bf16", B, T, H, P, S, G)
+    A[3] = -100.0
+    dt[:, :, 3] = 0.5
+    dt[:, ::7, 0] = 8.0
+    want_y, want_h = oracle.linear_scan(x, dt, A, Bm, Cm, D, h0)
+    y, h = st.stree_linear_ssd(to_dev(x, "bf16"), to_dev(dt), to_dev(A), to_dev(Bm, "bf16"), to_dev(Cm, "bf16"),
+                               to_dev(D), to_dev(h0))
+    assert np.isfinite(to_host(y)).all() and np.isfinite(to_host(h)).all()
+    assert_parity(to_host(h), want_h, 1e-4, "prefix scan with extreme decays: state", kind="state")
+    assert_parity(to_host(y), want_y, TOL["bf16"], "prefix scan with extreme decays: y", kind="y")
