@@ -167,6 +167,19 @@ __device__ __forceinline__ void store_through16(void *p, uint4 v) {
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_store_rsrc(void *base, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)bytes, 0x00020000);
 }
+// A read-only array as a raw buffer: loads at byte offsets >= `bytes` return zeros (and a null
+// array with bytes = 0 reads as all zeros).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void *base, size_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)(uint32_t)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t off) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ int buffer_load4(__amdgpu_buffer_rsrc_t rsrc, uint32_t off) {
+    return (int)__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)off, 0, 0);
+}
 __device__ __forceinline__ void buffer_store_through16(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, uint4 v) {
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
     const u32x4 vv = {v.x, v.y, v.z, v.w};

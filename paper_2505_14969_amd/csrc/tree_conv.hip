@@ -62,44 +62,74 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
     constexpr int VEC = Vec16<T>::N;
     extern __shared__ __align__(16) uint4 rows[];      // [n + W - 1][kConvVecs]; row n + m - 1 = m rows above the root
     __shared__ int par[kMaxNodes];
-    __shared__ int bad_s, pbad_s;
+    __shared__ __align__(16) uint4 wsh[(4 + 1) * kConvVecs];   // weight pieces 0 .. W-1 and the bias of each channel vector
+    __shared__ int bad_w[kThreads / 64], pbad_w[kThreads / 64];   // first bad node + 1 per wave, or INT_MAX
     const int tid = threadIdx.x, v = tid % kConvVecs, g = tid / kConvVecs;
     const int cblocks = (Cc / VEC + kConvVecs - 1) / kConvVecs;
     const int cblk = blockIdx.x % cblocks, b = blockIdx.x / cblocks;
     const int c0 = (cblk * kConvVecs + v) * VEC;
     const bool has_c = c0 < Cc;
 
-    if (tid == 0) {
-        bad_s = 0x7fffffff;
-        pbad_s = 0x7fffffff;
-    }
-    // Every global load of the kernel is issued up front, before anything is waited for: the
-    // tree's rows, weights and bias, the old conv state rows and (replay) the path rows.
+    // Every global load of the kernel is issued up front, before anything is waited for: both trees'
+    // parents, the tree's rows, weights and bias, the old conv state rows and (replay) the path rows
+    // -- and no more requests than can be used: the kernel's phases run in step across the chip, and
+    // every request a wave issues, also one whose lanes all read nothing, showed in its duration.
+    // They are raw buffer loads: a uniform descriptor of the array (this sequence's part of it) plus a
+    // 32-bit byte offset per lane, and a lane that has nothing to fetch -- a row past the tree, a
+    // channel past the last one, a node lane without a state row -- passes an offset past the end and
+    // reads zeros: no branch around any load, so the compiler knows how many requests are behind the
+    // one it waits for and a wait for an early one (the previous tree's parents, below) is not a
+    // wait for them all.
     const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
-    // (no ?: between a loaded and a constant uint4: that selects between addresses and parks the
-    // constant, and with it every array it is assigned to, in scratch memory)
-    auto ld16 = [&](const T *ptr, bool on) {
-        uint4 r = make_uint4(0u, 0u, 0u, 0u);
-        if (on) r = *reinterpret_cast<const uint4 *>(ptr);
-        return r;
-    };
-    auto ld_row = [&](int i) { return ld16(xbc_pre + ((size_t)b * n + min(i, n - 1)) * Cc + c0, has_c && i < n); };
+    constexpr uint32_t kNone = 0xffffffffu, kE = (uint32_t)sizeof(T);
+    auto ld16 = [&](__amdgpu_buffer_rsrc_t rsrc, uint32_t off, bool on) { return buffer_load16(rsrc, on ? off : kNone); };
+    const __amdgpu_buffer_rsrc_t r_pre = make_buffer(xbc_pre + (size_t)b * n * Cc, (size_t)n * Cc * kE);
+    const __amdgpu_buffer_rsrc_t r_w = make_buffer(w, (size_t)Cc * W * kE);
+    const __amdgpu_buffer_rsrc_t r_b = make_buffer(bias, bias ? (size_t)Cc * kE : 0);
+    const __amdgpu_buffer_rsrc_t r_cs = make_buffer(conv_state + (size_t)b * (W - 1) * Cc, (size_t)(W - 1) * Cc * kE);
+    auto ld_row = [&](int i) { return ld16(r_pre, ((uint32_t)i * (uint32_t)Cc + (uint32_t)c0) * kE, has_c); };
+    // replay, previous trees of at most 64 nodes: every wave holds that tree's parents, one per lane
+    // (requested first: the walk below needs them before anything else is needed)
+    int pparent_lane = -1, pparent_mine = -1;
+    if constexpr (RP)
+        pparent_lane = buffer_load4(make_buffer(R.parent + (size_t)b * R.pn, (size_t)R.pn * 4), (uint32_t)(tid & 63) * 4u);
+    // both trees' parents, one entry per thread (the envelope has at most kThreads nodes): requested
+    // with everything else, so that validating them costs no round trip of its own later
+    static_assert(kMaxNodes <= kThreads, "one parent entry per thread");
+    const int parent_mine = buffer_load4(make_buffer(parent + (size_t)b * n, (size_t)n * 4), (uint32_t)tid * 4u);
+    if constexpr (RP) {
+        if (R.pn > 64)      // (smaller previous trees are validated on the per-wave copy above)
+            pparent_mine = buffer_load4(make_buffer(R.parent + (size_t)b * R.pn, (size_t)R.pn * 4), (uint32_t)tid * 4u);
+    }
     // the first four rows of this thread (all of them for trees of up to 4 * kConvLanes nodes)
-    const uint4 t0 = ld_row(g), t1 = ld_row(g + kConvLanes), t2 = ld_row(g + 2 * kConvLanes),
-                t3 = ld_row(g + 3 * kConvLanes);
-    uint4 wq[W], bq = zero4;
-#pragma unroll
-    for (int q = 0; q < W; ++q) wq[q] = ld16(w + (size_t)c0 * W + q * VEC, has_c);
-    if (bias) bq = ld16(bias + c0, has_c);
+    const uint4 t0 = ld_row(g), t1 = ld_row(g + kConvLanes);
+    uint4 t2 = zero4, t3 = zero4;
+    if (n > 2 * kConvLanes) {                 // (uniform: a request that reads nothing still costs its issue)
+        t2 = ld_row(g + 2 * kConvLanes);
+        t3 = ld_row(g + 3 * kConvLanes);
+    }
+    // weights and bias of this thread's channel vector: W + 1 sixteen-byte pieces that all node lanes
+    // need -- node lane q fetches piece q (lane W the bias) in ONE request and they are handed out
+    // through LDS behind the barrier below, instead of W + 1 requests by every lane
+    const uint4 wpc = ld16(r_w, (uint32_t)(c0 * W + min(g, W - 1) * VEC) * kE, has_c && g < W);
+    const uint4 bpc = ld16(r_b, (uint32_t)c0 * kE, has_c && g == W);
     // rows above the root, m = 1 (newest) .. W-1, one per node lane g = m - 1
     const int m = g + 1;
     const bool is_state_lane = g < W - 1 && has_c;
-    uint4 old[W - 1], prow = zero4;            // old[r]: conv_state row r (oldest first)
-#pragma unroll
-    for (int r = 0; r < W - 1; ++r)
-        old[r] = ld16(conv_state + ((size_t)b * (W - 1) + r) * Cc + c0, is_state_lane);
-    // Replay: walk up from the accepted node of the previous tree (uniform, scalar loads; each
-    // step checked on its own so that a corrupt parent array cannot send the walk out of bounds).
+    // lane m's candidates (no arrays, no select between loaded values: a lane that does not need a
+    // candidate reads zeros, and the two it can need after a valid walk are OR-ed):
+    //   keep_row  conv_state row W-1-m: nothing accepted, or the previous tree is invalid
+    //   old_row   conv_state row W-1-(m-L), L = nodes found on the walk, if the path is shorter than m
+    //   prow      the pre-conv row of the (m-1)-th node of the walk otherwise
+    // (each is requested only where the walk's outcome -- uniform -- can make some lane use it: a
+    // request that reads nothing still costs its issue in every wave)
+    const uint32_t keep_off = (uint32_t)((W - 1 - min(m, W - 1)) * Cc + c0) * kE;
+    uint4 keep_row = zero4, old_row = zero4, prow = zero4;
+    if constexpr (!RP) keep_row = ld16(r_cs, keep_off, is_state_lane);
+    // Replay: walk up from the accepted node of the previous tree (uniform; each step checked on its
+    // own so that a corrupt parent array cannot send the walk out of bounds): through the parents
+    // held in the lanes where that tree has at most 64 nodes -- one round trip for the whole walk --
+    // else by scalar loads, one dependent round trip per step.
     // anc_ok = nodes found on the walk, at most W-1; lane m needs the (m-1)-th of them.
     int k_prev = -1, anc_ok = 0;
     bool k_bad = false;
@@ -112,27 +142,46 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
             if (cur >= 0) {
                 ++anc_ok;
                 if (sstep == m - 1) mine = cur;
-                const int pz = R.parent[(size_t)b * R.pn + cur];
+                const int pz = R.pn <= 64 ? __builtin_amdgcn_readlane(pparent_lane, cur)
+                                          : R.parent[(size_t)b * R.pn + cur];
                 cur = (cur > 0 && pz >= 0 && pz < cur) ? pz : -1;
             }
         }
-        prow = ld16(reinterpret_cast<const T *>(R.xbc_pre) + ((size_t)b * R.pn + max(mine, 0)) * Cc + c0,
-                    is_state_lane && mine >= 0);
+        const __amdgpu_buffer_rsrc_t r_pp =
+            make_buffer(reinterpret_cast<const T *>(R.xbc_pre) + (size_t)b * R.pn * Cc, (size_t)R.pn * Cc * kE);
+        if (anc_ok > 0)
+            prow = ld16(r_pp, ((uint32_t)max(mine, 0) * (uint32_t)Cc + (uint32_t)c0) * kE, is_state_lane && mine >= 0);
+        if (anc_ok > 0 && anc_ok < W - 1)
+            old_row = ld16(r_cs, (uint32_t)(max((W - 1) - (m - anc_ok), 0) * Cc + c0) * kE, is_state_lane && m > anc_ok);
+        if (anc_ok == 0) keep_row = ld16(r_cs, keep_off, is_state_lane);
     }
-    __syncthreads();
-    for (int i = tid; i < n; i += kThreads) {
-        const int pz = parent[(size_t)b * n + i];
-        const bool ok = (i == 0) ? (pz == -1) : (pz >= 0 && pz < i);
-        if (!ok) atomicMin(&bad_s, i + 1);
-        par[i] = ok ? pz : -1;
+    // Tree validity: every thread checks its own node, a wave reports its first bad one (no LDS
+    // atomics, nothing to initialise: no barrier in front of this).  A previous tree of at most 64
+    // nodes is also checked by every wave on its own copy, so that the rows above the root can be
+    // placed before the one barrier below instead of behind a second one.
+    auto node_ok = [](int node, int pz) { return (node == 0) ? (pz == -1) : (pz >= 0 && pz < node); };
+    auto first_bad = [&](bool ok, int base) {       // (uniform per wave) base + lane + 1 of the first bad lane
+        const unsigned long long bm = __ballot(!ok);
+        return bm ? base + (int)__ffsll((long long)bm) : 0x7fffffff;
+    };
+    {
+        const bool ok = tid >= n || node_ok(tid, parent_mine);
+        const int fb = first_bad(ok, tid & ~63);
+        if ((tid & 63) == 0) bad_w[tid >> 6] = fb;
+        if (tid < n) par[tid] = ok ? parent_mine : -1;
     }
+    int pbad_own = 0;
+    const bool early_state = !RP;
     if constexpr (RP) {
-        for (int i = tid; i < R.pn; i += kThreads) {
-            const int pz = R.parent[(size_t)b * R.pn + i];
-            const bool ok = (i == 0) ? (pz == -1) : (pz >= 0 && pz < i);
-            if (!ok) atomicMin(&pbad_s, i + 1);
+        if (R.pn <= 64) {
+            const int ln = tid & 63, f = first_bad(ln >= R.pn || node_ok(ln, pparent_lane), 0);
+            pbad_own = f == 0x7fffffff ? 0 : f;
+        } else {
+            const int fb = first_bad(tid >= R.pn || node_ok(tid, pparent_mine), tid & ~63);
+            if ((tid & 63) == 0) pbad_w[tid >> 6] = fb;
         }
     }
+    if (g <= W) wsh[g * kConvVecs + v] = make_uint4(wpc.x | bpc.x, wpc.y | bpc.y, wpc.z | bpc.z, wpc.w | bpc.w);
     if (g < n) rows[g * kConvVecs + v] = t0;
     if (g + kConvLanes < n) rows[(g + kConvLanes) * kConvVecs + v] = t1;
     if (g + 2 * kConvLanes < n) rows[(g + 2 * kConvLanes) * kConvVecs + v] = t2;
@@ -145,26 +194,20 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
         if (i0 + 2 * kConvLanes < n) rows[(i0 + 2 * kConvLanes) * kConvVecs + v] = u2;
         if (i0 + 3 * kConvLanes < n) rows[(i0 + 3 * kConvLanes) * kConvVecs + v] = u3;
     }
-    __syncthreads();
-    const int bad = bad_s == 0x7fffffff ? 0 : bad_s;
-    if (status && cblk == 0 && tid == 0) status[b] = bad;
-    if (g < W - 1) {
-        // the m-th newest row of [conv_state ; path rows]: a path row if the path has at least m
-        // nodes, else the (m - L)-th newest old row, L = nodes on the path (0: nothing accepted,
-        // or the previous tree / the accepted index is invalid)
-        int L = 0;
+    // the m-th newest row of [conv_state ; path rows]: a path row if the path has at least m nodes,
+    // else the (m - L)-th newest old row, L = nodes on the path (0: nothing accepted, or the previous
+    // tree / the accepted index is invalid)
+    auto place_state_rows = [&](int pbad) {
+        if (g >= W - 1) return;
         if constexpr (RP) {
-            const int pbad = pbad_s == 0x7fffffff ? 0 : pbad_s;
             if (R.status && cblk == 0 && tid == 0) R.status[b] = pbad ? pbad : (k_bad ? -1 : 0);
-            L = pbad ? 0 : anc_ok;
         }
-        uint4 r = prow;
-        if (m > L) {
-            const int idx = (W - 1) - (m - L);
-            r = old[0];
-#pragma unroll
-            for (int q = 1; q < W - 1; ++q)
-                if (idx == q) r = old[q];
+        uint4 r = make_uint4(keep_row.x | old_row.x | prow.x, keep_row.y | old_row.y | prow.y,
+                             keep_row.z | old_row.z | prow.z, keep_row.w | old_row.w | prow.w);   // (one of them was read)
+        if constexpr (RP) {
+            // an invalid previous tree accepts nothing after all: the old row, fetched only now
+            if (pbad && anc_ok > 0 && has_c)
+                r = *reinterpret_cast<const uint4 *>(conv_state + ((size_t)b * (W - 1) + (W - 1 - m)) * Cc + c0);
         }
         rows[(n + m - 1) * kConvVecs + v] = r;
         if constexpr (RP) {   // the new conv state, oldest first: row W-1-m
@@ -172,14 +215,37 @@ __global__ __launch_bounds__(kThreads) void tree_conv_kernel(
                 store_written_through16(reinterpret_cast<T *>(R.conv_state_out) +
                                             ((size_t)b * (W - 1) + (W - 1 - m)) * Cc + c0, r);
         }
-    }
+    };
+    if (early_state) place_state_rows(pbad_own);
     __syncthreads();
+    int bad = 0x7fffffff;
+#pragma unroll
+    for (int q = 0; q < kThreads / 64; ++q) bad = min(bad, bad_w[q]);
+    bad = bad == 0x7fffffff ? 0 : bad;
+    if (status && cblk == 0 && tid == 0) status[b] = bad;
+    if constexpr (RP) {
+        if (!early_state) {
+            int pbad = pbad_own;
+            if (R.pn > 64) {
+                pbad = 0x7fffffff;
+#pragma unroll
+                for (int q = 0; q < kThreads / 64; ++q) pbad = min(pbad, pbad_w[q]);
+                pbad = pbad == 0x7fffffff ? 0 : pbad;
+            }
+            place_state_rows(pbad);
+            __syncthreads();
+        }
+    }
     if (!has_c) return;
     if (bad) {
         for (int i = g; i < n; i += kConvLanes)
             *reinterpret_cast<uint4 *>(out + ((size_t)b * n + i) * Cc + c0) = make_uint4(0u, 0u, 0u, 0u);
         return;
     }
+    uint4 wq[W];
+#pragma unroll
+    for (int q = 0; q < W; ++q) wq[q] = wsh[q * kConvVecs + v];
+    const uint4 bq = wsh[W * kConvVecs + v];
     float wv[W][VEC];  // flat [e*W + j] = w[c0+e][j]
 #pragma unroll
     for (int q = 0; q < W; ++q) Vec16<T>::unpack(wq[q], wv[q]);
