@@ -15,16 +15,19 @@
 //                   in LDS and stored as row pieces; on a unit's last pass the next unit's state
 //                   tile registers -> LDS (bf16), request the state tile of the unit after that
 //     G waves:      the next pass's B_J (and C_I when it starts a row block) registers -> LDS,
-//                   request the tiles of the pass after that; on a unit's last pass wave 6 builds
-//                   the next unit's tree index and requests the parents / steps of the unit after
+//                   request the tiles of the pass after that; wave 6 builds the tree index of the
+//                   next block of 64 nodes of this unit (in the unit's last pass: of the first
+//                   block of the next unit)
 //
 // so that every tile is in flight for a whole pass and the fp32 state tile for a whole unit.  The
 // bf16 state tile stays in LDS for all row blocks of its unit (read from memory once), the tree
-// index is built once per unit (the ancestor bit rows once per sequence), by one wave, with
-// pointer doubling through LDS: lane l owns nodes l, l + 64, ...
+// index is built block by block, each before the first pass that needs it (the ancestor bit rows
+// once per sequence), by one wave, with pointer doubling through LDS: lane l owns nodes l, l + 64, ...
 //
 // Same products, operand layouts and accumulator layouts as tree_ssd_mfma64.hip: every product is
 // formed transposed, so that a lane owns one node i in all accumulators.
+#include <type_traits>
+
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -207,18 +210,90 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
     };
 
     // ---- tree index of a unit, by one wave (Sec. 3: depth-ordered packing, Eq. a_tree) --------------
-    // Lane l owns nodes l + 64 slot.  Pointer doubling in place through LDS: every node keeps a jump
-    // pointer (in sU, as integer bits) and the aggregate -- log-decay sum in sS2, ancestor bits in its
-    // mask row -- of the path segment from itself up to, not including, the jump target; a round merges
-    // the target's segment and takes over its pointer.  A wave's LDS operations complete in order, so
-    // no barrier is needed.  The bit rows depend on the sequence only: rebuilt when it changes.
-    // Outputs are in log2 units so that the decay is one v_exp_f32 per element:
+    // Lane l owns nodes l + 64 slot.  The index is built one block of 64 nodes (slot) at a time, each
+    // just before the first pass that needs it -- block 0 in front of the unit, block s while the Y
+    // waves are in phase 3 of the unit's pass number s - 1 -- so that a unit does not wait for the
+    // whole tree's index before its first pass.  Within a slot: pointer doubling in place through
+    // LDS over the parents that lie in the same slot -- every node keeps a jump pointer (in sU, as
+    // integer bits) and the aggregate (log-decay sum in sS2, ancestor bits in its mask row) of the
+    // path segment from itself up to, not including, the jump target; a round merges the target's
+    // segment and takes over its pointer -- and then one merge with the first ancestor in a lower
+    // slot, whose own aggregate is complete.  A wave's LDS operations complete in order and a round
+    // reads before it writes, so no barrier is needed.  The bit rows depend on the sequence only:
+    // rebuilt when it changes.  In log2 units so that the decay is one v_exp_f32 per element:
     //   s2[i] = log2(e) s_i      u[j] = s2[j] - log2(dt_j)      exp(s_i - s_j) dt_j = exp2(s2[i] - u[j])
-    auto build_index = [&](int b, int h, bool newb) {
+    int cpar[NB];                        // the unit's parents and steps, copied out of the load registers
+    float cdt[NB];                       // (reading those again later would wait for whatever is in flight)
+    bool unit_newb = true;
+    float unit_A2 = 0.f;                 // log2(e) A_h of the unit (fetched once, in front of slot 0)
+#pragma unroll
+    for (int s = 0; s < NB; ++s) {
+        cpar[s] = -1;
+        cdt[s] = 0.f;
+    }
+    auto build_slot = [&](auto slc, bool newb) {
+        constexpr int sl = decltype(slc)::value;
+        const int ln = opaque(lane), node = ln + 64 * sl, lo = 64 * sl;
+        const float A2 = unit_A2;
+        int j = node < n ? cpar[sl] : -1;
+        float s = node < n ? cdt[sl] * A2 : 0.f;
+        uint2 *own = reinterpret_cast<uint2 *>(&sMask[kBk * sl * (sl + 1) + ln * 2 * (sl + 1)]);
+        if (newb) {
+#pragma unroll
+            for (int w = 0; w <= sl; ++w)
+                own[w] = make_uint2((node < n && 2 * w == (node >> 5)) ? (1u << (node & 31)) : 0u,
+                                    (node < n && 2 * w + 1 == (node >> 5)) ? (1u << (node & 31)) : 0u);
+        }
+        sS2[node] = s;
+        sU[node] = __int_as_float(j);
+        for (int round = 0; round < 6; ++round) {   // chains inside a slot are at most 64 long
+            const bool in = j >= lo;
+            if (!__any(in)) break;
+            const int q = in ? j : node;            // (a lane with nothing to merge reads its own entry)
+            const float rs = sS2[q];
+            const int rj = __float_as_int(sU[q]);
+            if (newb) {
+                const uint2 *tgt = reinterpret_cast<const uint2 *>(&sMask[kBk * sl * (sl + 1) + (q & 63) * 2 * (sl + 1)]);
+                uint2 add[sl + 1];
+#pragma unroll
+                for (int w = 0; w <= sl; ++w) add[w] = tgt[w];
+                // (another lane may read this row already merged while the owner's jump pointer in LDS is
+                // still the old one: the extra bits are ancestors all the same, OR-ing them again in a
+                // later round changes nothing)
+#pragma unroll
+                for (int w = 0; w <= sl; ++w) {
+                    const uint2 o = own[w];
+                    own[w] = in ? make_uint2(o.x | add[w].x, o.y | add[w].y) : o;
+                }
+            }
+            if (in) {
+                s += rs;
+                j = rj;
+            }
+            sS2[node] = s;
+            sU[node] = __int_as_float(j);
+        }
+        if constexpr (sl > 0) {                     // the first ancestor below this slot: its aggregate is final
+            const bool has = j >= 0;
+            const int q = has ? j : 0, qb = q >> 6;
+            const float rs = sS2[q];
+            if (newb) {
+                const uint2 *tgt = reinterpret_cast<const uint2 *>(&sMask[kBk * qb * (qb + 1) + (q & 63) * 2 * (qb + 1)]);
+#pragma unroll
+                for (int w = 0; w < sl; ++w) {      // (the target's row has qb + 1 <= sl pairs of words)
+                    const uint2 t = tgt[min(w, qb)];
+                    const uint2 o = own[w];
+                    own[w] = (has && w <= qb) ? make_uint2(o.x | t.x, o.y | t.y) : o;
+                }
+            }
+            if (has) s += rs;
+        }
+        sS2[node] = s;
+        sU[node] = s - __log2f(node < n ? cdt[sl] : 0.f);   // dt = 0 (and nodes past the tree): u = +inf, weight 0
+    };
+    // validation of the whole tree, the copies of its parents and steps, and slot 0
+    auto build_first = [&](int b, int h, bool newb) {
         const int ln = opaque(lane);
-        const float A_h = A[__builtin_amdgcn_readfirstlane(h)];
-        int jump[NB];
-        float s[NB];
         int bad = 0;
 #pragma unroll
         for (int sl = NB - 1; sl >= 0; --sl) {      // (descending: the smallest bad label wins)
@@ -227,78 +302,24 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
             const bool ok = node >= n || ((node == 0) ? (p == -1) : (p >= 0 && p < node));
             const unsigned long long bm = __ballot(!ok);
             if (bm) bad = (int)__ffsll((long long)bm) + 64 * sl;
-            jump[sl] = (node < n && ok) ? p : -1;
-            s[sl] = node < n ? rdt[sl] * A_h : 0.f;
+            cpar[sl] = p;
+            cdt[sl] = rdt[sl];
         }
         if (ln == 0) {
             *sBad = bad;
             if (status && h == 0) status[b] = bad;
         }
+        unit_newb = newb;
+        unit_A2 = A[__builtin_amdgcn_readfirstlane(h)] * 1.44269504088896340736f;
         if (bad) return;
-#pragma unroll
-        for (int sl = 0; sl < NB; ++sl) {
-            const int node = ln + 64 * sl;
-            sS2[node] = s[sl];
-            sU[node] = __int_as_float(jump[sl]);
-            if (newb) {
-                uint32_t *row = &sMask[kBk * sl * (sl + 1) + ln * 2 * (sl + 1)];
-#pragma unroll
-                for (int w = 0; w < 2 * (sl + 1); ++w)
-                    row[w] = (node < n && w == (node >> 5)) ? (1u << (node & 31)) : 0u;
-            }
-        }
-        for (int round = 0; round < 8; ++round) {   // depth < 256
-            bool more = false;
-#pragma unroll
-            for (int sl = 0; sl < NB; ++sl) more |= jump[sl] >= 0;
-            if (!__any(more)) break;
-            float rs[NB];
-            int rj[NB];
-#pragma unroll
-            for (int sl = 0; sl < NB; ++sl) {       // all reads of a round first: the round sees one snapshot
-                const int q = max(jump[sl], 0);
-                rs[sl] = sS2[q];
-                rj[sl] = __float_as_int(sU[q]);
-            }
-            if (newb) {
-#pragma unroll
-                for (int sl = 0; sl < NB; ++sl) {
-                    const int q = max(jump[sl], 0), qb = q >> 6;
-                    uint2 *own = reinterpret_cast<uint2 *>(&sMask[kBk * sl * (sl + 1) + ln * 2 * (sl + 1)]);
-                    const uint2 *tgt = reinterpret_cast<const uint2 *>(&sMask[kBk * qb * (qb + 1) + (q & 63) * 2 * (qb + 1)]);
-                    uint2 add[NB];
-#pragma unroll
-                    for (int w = 0; w <= sl; ++w) add[w] = (jump[sl] >= 0 && w <= qb) ? tgt[min(w, qb)] : make_uint2(0u, 0u);
-#pragma unroll
-                    for (int w = 0; w <= sl; ++w) {
-                        const uint2 o = own[w];
-                        add[w].x |= o.x;
-                        add[w].y |= o.y;
-                    }
-                    // (a later slot may read this row already merged while the owner's jump pointer in LDS
-                    // is still the old one: the extra bits are ancestors all the same, and OR-ing them
-                    // again in a later round changes nothing)
-#pragma unroll
-                    for (int w = 0; w <= sl; ++w) own[w] = add[w];
-                }
-            }
-#pragma unroll
-            for (int sl = 0; sl < NB; ++sl) {
-                if (jump[sl] >= 0) {
-                    s[sl] += rs[sl];
-                    jump[sl] = rj[sl];
-                }
-                const int node = ln + 64 * sl;
-                sS2[node] = s[sl];
-                sU[node] = __int_as_float(jump[sl]);
-            }
-        }
-#pragma unroll
-        for (int sl = 0; sl < NB; ++sl) {
-            const int node = ln + 64 * sl;
-            const float s2 = s[sl] * 1.44269504088896340736f;
-            sS2[node] = s2;
-            sU[node] = s2 - __log2f(node < n ? rdt[sl] : 0.f);   // dt = 0 (and nodes past the tree): u = +inf, weight 0
+        build_slot(std::integral_constant<int, 0>{}, newb);
+    };
+    auto build_later = [&](int sl) {                 // slot sl >= 1 of the current unit
+        if (*sBad) return;
+        if (sl == 1) build_slot(std::integral_constant<int, 1>{}, unit_newb);
+        if constexpr (NB > 2) {
+            if (sl == 2) build_slot(std::integral_constant<int, 2>{}, unit_newb);
+            if (sl == 3) build_slot(std::integral_constant<int, 3>{}, unit_newb);
         }
     };
 
@@ -464,7 +485,7 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
         load_C(cur);
         load_B(cur);
         load_X(cur);
-        if (isT) build_index(cur.b, cur.h, true);
+        if (isT) build_first(cur.b, cur.h, true);
         stage_rows(kPreC, sC);
         stage_rows(kPreB, sB);
         stage_X();
@@ -536,8 +557,13 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
             __syncthreads();                                  // barrier 2: M is ready; B, C and the tree arrays are dead
             const bool last_of_unit = diag && cur.ib == nblk - 1;
             const bool more_units = cur.k + 1 < nU;
-            // the next unit's tree index, while the Y waves are in phase 3
-            if (isT && last_of_unit && more_units) build_index(n1.b, n1.h, n1.b != cur.b);
+            // the tree index while the Y waves are in phase 3: the current unit's next block of nodes, or,
+            // in its last pass, the next unit's first
+            if (isT) {
+                const int pidx = cur.ib * (cur.ib + 1) / 2 + cur.jb;      // number of this pass within its unit
+                if (pidx + 1 < nblk) build_later(pidx + 1);
+                else if (last_of_unit && more_units) build_first(n1.b, n1.h, n1.b != cur.b);
+            }
             __syncthreads();                                  // barrier (a): X^T and the y scratch in the B tile are dead
             // ---- the one wait of this role: the next pass's tiles registers -> LDS ----------------------
             if (!v1) break;
