@@ -191,3 +191,14 @@ def gate_norm(y, z, w, ngroups: int, eps: float = 1e-5):
     if st:
         raise ValueError("ngroups does not divide the channel count")
     return out.reshape(y.shape)
+
+
+def step_size(raw, bias=None):
+    """Step size from the raw projection: softplus(raw + bias[h]) in fp64.  raw [..., H]; bias [H] or None."""
+    raw = _f64(raw)
+    H = raw.shape[-1]
+    bias = None if bias is None else _f64(bias)
+    assert bias is None or bias.shape == (H,)
+    out = np.full(raw.shape, np.nan)
+    lib().orc_step_size(C.c_int(raw.size // H), C.c_int(H), _p(raw), _p(bias), _p(out))
+    return out

@@ -41,6 +41,11 @@
  *                         Mamba2 block that the SSM of Sec. 3 sits in; not in
  *                         the paper): pinned by torch's silu and rms_norm, by
  *                         a hand-worked 2 x 4 example and by closed forms.
+ *   orc_step_size         step size from the raw projection, softplus(raw +
+ *                         bias) (Mamba2's discretisation; the paper leaves the
+ *                         step size out): pinned by ln 2 at zero, by
+ *                         softplus(v) - softplus(-v) = v, by both tails and by
+ *                         torch's softplus.
  *
  * Layouts (all contiguous, fp64 unless noted):
  *   parent int32 [B,N] (root -1, parent[i] < i)    x  [B,N,H,P]
@@ -411,4 +416,20 @@ int orc_gate_norm(int rows, int d, int G, const double *y, const double *z, cons
         }
     }
     return 0;
+}
+
+/*
+ * Step size of the discretised recurrence from the raw projection (Mamba2
+ * practice; the paper's Eq. ssm carries no step size at all): per token and
+ * head,
+ *   dt = softplus(raw + bias_h) = log(1 + exp(raw + bias_h)),
+ * written so that neither tail overflows or cancels.  raw, out [rows, H];
+ * bias [H] or NULL (zero).
+ */
+void orc_step_size(int rows, int H, const double *raw, const double *bias, double *out) {
+    for (int r = 0; r < rows; ++r)
+        for (int h = 0; h < H; ++h) {
+            const double v = raw[(size_t)r * H + h] + (bias ? bias[h] : 0.0);
+            out[(size_t)r * H + h] = v > 0.0 ? v + log1p(exp(-v)) : log1p(exp(v));
+        }
 }

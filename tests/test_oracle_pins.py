@@ -445,3 +445,22 @@ def test_gate_norm_closed_forms(oracle):
     _close(oracle.gate_norm(y, zz, w, G, 0.0), want, 1e-12)
     with pytest.raises(ValueError):
         oracle.gate_norm(y, z, w, 5, 0.0)
+
+
+def test_step_size_closed_forms_and_library_softplus(oracle):
+    """softplus(raw + bias): ln 2 at zero, softplus(v) - softplus(-v) = v, both tails, the bias is per head
+    (last index), and torch's softplus (its threshold switched off) on random values."""
+    import torch
+    assert oracle.step_size(np.zeros((1, 1)))[0, 0] == pytest.approx(math.log(2.0), rel=1e-15)
+    v = np.linspace(-30, 30, 61).reshape(-1, 1)
+    assert np.allclose(oracle.step_size(v) - oracle.step_size(-v), v, rtol=0, atol=1e-13)
+    assert oracle.step_size(np.array([[50.0]]))[0, 0] == pytest.approx(50.0, rel=1e-15)
+    assert oracle.step_size(np.array([[800.0]]))[0, 0] == 800.0                      # no overflow
+    assert oracle.step_size(np.array([[-40.0]]))[0, 0] == pytest.approx(math.exp(-40.0), rel=1e-12)
+    # bias indexed by head, added before the softplus: softplus(0 + b_h) with b = (0, ln(e - 1)) gives (ln 2, 1)
+    got = oracle.step_size(np.zeros((3, 2)), np.array([0.0, math.log(math.e - 1.0)]))
+    assert np.allclose(got, np.array([[math.log(2.0), 1.0]] * 3), rtol=1e-14, atol=0)
+    rng = np.random.default_rng(77)
+    raw, bias = rng.standard_normal((5, 7, 6)) * 4, rng.standard_normal(6)
+    want = torch.nn.functional.softplus(torch.from_numpy(raw + bias), threshold=1e9).numpy()
+    assert np.allclose(oracle.step_size(raw, bias), want, rtol=1e-13, atol=0)
