@@ -58,6 +58,8 @@ enum stree_dtype { STREE_F32 = 0, STREE_BF16 = 1 };
 
 enum stree_flags {
     STREE_FLAG_CONV_SILU = 1,    /* tree_conv applies z * sigmoid(z) */
+    STREE_FLAG_DT_SOFTPLUS = 2,  /* every `dt` argument (and prev->dt) holds the RAW projection; the kernels use
+                                    softplus(dt + dt_bias[h]) as the step size (see stree_dims.dt_bias) */
     STREE_FLAG_FORCE_FMA = 256,    /* tree_ssd: use the plain fp32-FMA kernel even where MFMA applies */
     STREE_FLAG_GENERAL_MFMA = 1024 /* tree_ssd: trees of more than 64 nodes take the one-workgroup-per-(b,h) MFMA
                                       kernel even where the persistent one applies (same results to rounding) */
@@ -79,6 +81,12 @@ typedef struct stree_dims {
      * x | B | C be column ranges of one conv output buffer [B,N,H*P+2*G*S].  The
      * batch stride is nnodes * token stride. */
     int64_t x_stride_n, b_stride_n, c_stride_n;
+    /* DEVICE pointer, f32 [H]: the per-head bias in front of the softplus.  Read only when
+     * STREE_FLAG_DT_SOFTPLUS is set, and required then (STREE_ERR_NULL_ARG otherwise); pass zeros
+     * for a plain softplus.  The paper's Eq. ssm has no step size; this is Mamba2's discretisation,
+     * dt = log(1 + exp(raw + bias_h)), evaluated in fp32 where dt is loaded (values above 20 pass
+     * through, the difference being below fp32 resolution).  Without the flag `dt` is the step size itself. */
+    const float *dt_bias;
 } stree_dims;
 
 int stree_version(void);
@@ -134,7 +142,8 @@ int stree_tree_conv(const stree_dims *dims, const int32_t *parent, const void *x
  *   y_i  = exp(s_i) * h0 C_i
  *        + sum_{j on path(i)} exp(s_i - s_j) * dt[j] * <C_i,B_j> * x_j
  *        + D[h] * x_i
- *   x   io  [B,N,H,P] (token stride x_stride_n)    dt  f32 [B,N,H], already softplus'ed
+ *   x   io  [B,N,H,P] (token stride x_stride_n)    dt  f32 [B,N,H]: the step size (>= 0), or, with
+ *                                                  STREE_FLAG_DT_SOFTPLUS, the raw projection
  *   A   f32 [H], negative                          Bm, Cm io [B,N,G,S] (strides b/c_stride_n)
  *   D   f32 [H] or NULL                            h0  f32 [B,H,P,S] or NULL (zero state)
  *   y   io  [B,N,H,P] dense

@@ -13,6 +13,7 @@ int check_dims(const stree_dims *d, int need_conv) {
     if (!d) return STREE_ERR_NULL_ARG;
     if (d->io_dtype != STREE_F32 && d->io_dtype != STREE_BF16) return STREE_ERR_BAD_DTYPE;
     if (d->state_dtype != STREE_F32) return STREE_ERR_BAD_DTYPE;
+    if ((d->flags & STREE_FLAG_DT_SOFTPLUS) && !d->dt_bias) return STREE_ERR_NULL_ARG;
     if (d->batch < 0 || d->batch > 65535) return STREE_ERR_BAD_SHAPE;
     if (d->nnodes < 1 || d->nnodes > STREE_MAX_NODES) return STREE_ERR_BAD_SHAPE;
     if (d->nheads < 1 || d->nheads > 65535 || d->ngroups < 1 || d->nheads % d->ngroups != 0)

@@ -85,11 +85,11 @@ struct ConvTailArgs {      // conv part folded into the state kernel's grid (cbl
 // two pieces the kernel needs under 102 registers, i.e. five workgroups per CU: at 80 heads x
 // batch 16 every workgroup of the launch is resident at once.  (Forcing that budget on the compiler
 // where it does not come by itself is worse than four per CU: the spills wait on the state loads.)
-template <typename T, bool WAVE, int NS>
+template <typename T, bool WAVE, int NS, bool SPL>
 __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     const int32_t *__restrict__ parent, const int32_t *__restrict__ accepted, int n, int H, int P, int S,
-    int G, const T *__restrict__ x, long x_sn, const float *__restrict__ dt, const float *__restrict__ A,
-    const T *__restrict__ Bm, long b_sn, const float *h0, float *h_out, int32_t *__restrict__ status,
+    int G, const T *__restrict__ x, long x_sn, const float *__restrict__ dt, const float *__restrict__ dt_bias,
+    const float *__restrict__ A, const T *__restrict__ Bm, long b_sn, const float *h0, float *h_out, int32_t *__restrict__ status,
     int slabs, ConvTailArgs ct) {
     constexpr bool FAST = NS > 0;
     constexpr int kStageMax = NS ? NS : 1;
@@ -148,6 +148,8 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     const int k = accepted[b];
     const bool k_bad = (k < -1) || (k >= n);
     const float A_h = A[h];
+    float bias_h = 0.f;
+    if constexpr (SPL) bias_h = dt_bias[h];
     int bad, len = 0;
     float decay = 1.f;
     if constexpr (WAVE) {
@@ -155,6 +157,7 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
         // their loads stay where they were issued, ahead of the state); wave 0 publishes it
         int pos;
         float cf;
+        if constexpr (SPL) dt_j = softplus_step(dt_j + bias_h);      // raw projection -> step size
         bad = wave_path(lane, n, (k >= 0 && !k_bad) ? k : 0, par_j, dt_j, A_h, pos, cf, len, decay);
         if (tid < 64 && bad == 0 && pos >= 0) {
             path[pos] = lane;
@@ -165,7 +168,8 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
         __shared__ TreeLds tree;
         __shared__ uint32_t mask[kMaxNodes * kMaxWords];
         const int words = (n + 31) / 32;
-        const float dt_i = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
+        const float dt_raw = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
+        const float dt_i = (SPL && tid < n) ? softplus_step(dt_raw + bias_h) : dt_raw;
         bad = build_tree_index(tree, mask, parent + (size_t)b * n, n, n, words, dt_i, A_h);
         len = 0;
         if (!bad && k >= 0 && !k_bad) {
@@ -351,10 +355,16 @@ hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const
     ConvTailArgs ct = {xbc_pre, conv_state, conv_state_out, Cc, d.conv_width, cblocks, d.batch, state_z};
     const dim3 grid(gx, gy, state_z + tail_z);
     const size_t lds = (size_t)kPathChunk * (d.headdim + d.dstate) * sizeof(float);
-#define STREE_COMMIT_LAUNCH(TT, WV, NS)                                                                      \
-    hipLaunchKernelGGL((commit_h_kernel<TT, WV, NS>), grid, dim3(kThreads), lds, st, parent, accepted, d.nnodes, \
-                       d.nheads, d.headdim, d.dstate, d.ngroups, (const TT *)x, (long)d.x_stride_n, dt, A,      \
-                       (const TT *)Bm, (long)d.b_stride_n, h0, h_out, status, slabs, ct)
+    // (the in-kernel softplus is a variant of its own: compiled into the common one, even unused, it costs time)
+#define STREE_COMMIT_LAUNCH_SP(TT, WV, NS, SPL)                                                                  \
+    hipLaunchKernelGGL((commit_h_kernel<TT, WV, NS, SPL>), grid, dim3(kThreads), lds, st, parent, accepted,      \
+                       d.nnodes, d.nheads, d.headdim, d.dstate, d.ngroups, (const TT *)x, (long)d.x_stride_n,    \
+                       dt, step_bias(d), A, (const TT *)Bm, (long)d.b_stride_n, h0, h_out, status, slabs, ct)
+#define STREE_COMMIT_LAUNCH(TT, WV, NS)                         \
+    do {                                                        \
+        if (step_bias(d)) STREE_COMMIT_LAUNCH_SP(TT, WV, NS, true); \
+        else STREE_COMMIT_LAUNCH_SP(TT, WV, NS, false);         \
+    } while (0)
     const bool wave = d.nnodes <= 64;
     const int ns = slabs > 0 ? commit_fast_shape(d, x, Bm, h0, h_out) : 0;
 #define STREE_COMMIT_NS(TT, WV)                                 \
@@ -372,6 +382,7 @@ hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const
     }
 #undef STREE_COMMIT_NS
 #undef STREE_COMMIT_LAUNCH
+#undef STREE_COMMIT_LAUNCH_SP
     return hipGetLastError();
 }
 

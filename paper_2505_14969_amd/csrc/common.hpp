@@ -22,6 +22,22 @@ __device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
 __device__ __forceinline__ void from_f32(float v, float &o) { o = v; }
 __device__ __forceinline__ void from_f32(float v, bf16_t &o) { o = (bf16_t)v; }  // round to nearest even
 
+// Step size of a token from the raw projection, softplus(raw + bias_h): Mamba2's discretisation of the
+// recurrence of Eq. ssm, used by the kernel variants that the caller selects with a bias vector.
+//   softplus(v) = max(v, 0) + log1p(exp(-|v|)),   log1p(t) = log(1 + t) * t / ((1 + t) - 1)
+// (the quotient restores what the rounding of 1 + t lost; 1 + t == 1: log1p(t) = t).  A dozen instructions,
+// no branch, hardware exp2 / log2 / reciprocal: a few ulp, far inside the tolerance of the state (1e-4) --
+// it sits on the chain parents -> path -> rows -> state that the commit kernels are bound by.
+__device__ __forceinline__ float softplus_step(float v) {
+    const float t = __expf(-fabsf(v));
+    const float u = 1.f + t;
+    const float l = (u == 1.f) ? t : __logf(u) * __fdividef(t, u - 1.f);
+    return fmaxf(v, 0.f) + l;
+}
+__device__ __forceinline__ float step_size(float raw, const float *__restrict__ bias, int h) {
+    return bias ? softplus_step(raw + bias[h]) : raw;
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 

@@ -7,6 +7,11 @@
 
 namespace stree {
 
+// the per-head bias of the in-kernel softplus, or null when `dt` already holds step sizes
+inline const float *step_bias(const stree_dims &d) {
+    return (d.flags & STREE_FLAG_DT_SOFTPLUS) ? d.dt_bias : nullptr;
+}
+
 hipError_t launch_tree_index(const stree_dims &d, const int32_t *parent, int32_t *depth_out,
                              uint32_t *mask_out, int32_t *anc_out, int32_t *status, hipStream_t st);
 

@@ -34,7 +34,7 @@ constexpr int kCP = kChunk + 8;    // padded row of a [.. x 64] bf16 LDS tile
 template <int P, int S, bool WY>
 __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
     int T, int H, int G, const bf16_t *__restrict__ x, long x_sn, const float *__restrict__ dt,
-    const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn, const bf16_t *__restrict__ Cm,
+    const float *__restrict__ dt_bias, const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn, const bf16_t *__restrict__ Cm,
     long c_sn, const float *__restrict__ D, const float *__restrict__ h0, bf16_t *__restrict__ y,
     float *__restrict__ h_out) {
     constexpr int SP = S + 8;
@@ -58,6 +58,7 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
     const int h = blockIdx.x, b = blockIdx.y, g = h / (H / G);
     const float A2 = A[h] * 1.44269504088896340736f;          // log2 domain
+    const float bias_h = dt_bias ? dt_bias[h] : 0.f;
     const float D_h = D ? D[h] : 0.f;
     const char *xb = reinterpret_cast<const char *>(x + (size_t)b * T * x_sn + (size_t)h * P);
     const char *Bb = reinterpret_cast<const char *>(Bm + (size_t)b * T * b_sn + (size_t)g * S);
@@ -154,6 +155,7 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
         }
         if (tid < kChunk) {   // wave 0: inclusive scan of dt * A over the chunk's tokens (on the
             // chunk's critical path: every other wave waits for it at the barrier below)
+            if (dt_bias) rdt = (c0 + lane < T) ? softplus_step(rdt + bias_h) : 0.f;   // raw projection -> step size
             const float s2 = wave_inclusive_sum(rdt * A2);
             // The state's weights dt_j exp(s_last - s_j) from the sum of the steps BEHIND token j, taken
             // on its own: its rounding error is relative to that sum -- small wherever the weight is
@@ -326,12 +328,12 @@ hipError_t launch_ps(const stree_dims &d, const void *x, const float *dt, const 
                      const void *Cm, const float *D, const float *h0, void *y, float *h_out, hipStream_t st) {
     if (y)
         hipLaunchKernelGGL((linear_ssd_kernel<P, S, true>), dim3(d.nheads, d.batch), dim3(kThreads), 0, st, d.nnodes,
-                           d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A, (const bf16_t *)Bm,
-                           (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0, (bf16_t *)y, h_out);
+                           d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d), A,
+                           (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0, (bf16_t *)y, h_out);
     else
         hipLaunchKernelGGL((linear_ssd_kernel<P, S, false>), dim3(d.nheads, d.batch), dim3(kThreads), 0, st, d.nnodes,
-                           d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A, (const bf16_t *)Bm,
-                           (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0, (bf16_t *)y, h_out);
+                           d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d), A,
+                           (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0, (bf16_t *)y, h_out);
     return hipGetLastError();
 }
 

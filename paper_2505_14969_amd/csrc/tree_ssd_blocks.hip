@@ -60,7 +60,8 @@ struct PassId {                    // unit k of the workgroup's run = (b, h); pa
 template <int P, int S, int NB, int WPE>
 __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void tree_ssd_blocks_kernel(
     const int32_t *__restrict__ parent, int n, int nbatch, int H, int G, const bf16_t *__restrict__ x, long x_sn,
-    const float *__restrict__ dt, const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn,
+    const float *__restrict__ dt, const float *__restrict__ dt_bias, const float *__restrict__ A,
+    const bf16_t *__restrict__ Bm, long b_sn,
     const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
     bf16_t *__restrict__ y, int32_t *__restrict__ status) {
     constexpr int SP = S + 8;
@@ -294,6 +295,7 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
     // validation of the whole tree, the copies of its parents and steps, and slot 0
     auto build_first = [&](int b, int h, bool newb) {
         const int ln = opaque(lane);
+        const float bias_h = dt_bias ? dt_bias[__builtin_amdgcn_readfirstlane(h)] : 0.f;
         int bad = 0;
 #pragma unroll
         for (int sl = NB - 1; sl >= 0; --sl) {      // (descending: the smallest bad label wins)
@@ -304,6 +306,7 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
             if (bm) bad = (int)__ffsll((long long)bm) + 64 * sl;
             cpar[sl] = p;
             cdt[sl] = rdt[sl];
+            if (dt_bias) cdt[sl] = node < n ? softplus_step(rdt[sl] + bias_h) : 0.f;   // raw projection -> step size
         }
         if (ln == 0) {
             *sBad = bad;
@@ -587,8 +590,8 @@ hipError_t launch_blocks_ps(const stree_dims &d, const int32_t *parent, const vo
     const int cap = 256 * (WPE == 4 ? 2 : 1);
     if (grid > cap) grid = cap;
     hipLaunchKernelGGL((tree_ssd_blocks_kernel<P, S, NB, WPE>), dim3(grid), dim3(kTk), 0, st, parent, d.nnodes, d.batch,
-                       d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A, (const bf16_t *)Bm,
-                       (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0, (bf16_t *)y, status);
+                       d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d), A,
+                       (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0, (bf16_t *)y, status);
     return hipGetLastError();
 }
 

@@ -26,7 +26,8 @@ __host__ __device__ constexpr size_t fma_lds_floats(int P, int S) {
 template <typename T>
 __global__ __launch_bounds__(kThreads) void tree_ssd_fma_kernel(
     const int32_t *__restrict__ parent, int n, int H, int P, int S, int G, const T *__restrict__ x,
-    long x_sn, const float *__restrict__ dt, const float *__restrict__ A, const T *__restrict__ Bm,
+    long x_sn, const float *__restrict__ dt, const float *__restrict__ dt_bias, const float *__restrict__ A,
+    const T *__restrict__ Bm,
     long b_sn, const T *__restrict__ Cm, long c_sn, const float *__restrict__ D,
     const float *__restrict__ h0, T *__restrict__ y, int32_t *__restrict__ status) {
     extern __shared__ __align__(16) float dyn[];
@@ -37,7 +38,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_fma_kernel(
     const int g = h / (H / G);
     const int words = (n + 31) / 32;
     const float A_h = A[h];
-    const float dt_i = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
+    const float dt_i = tid < n ? step_size(dt[((size_t)b * n + tid) * H + h], dt_bias, h) : 0.f;
     const int bad = build_tree_index(tree, mask, parent + (size_t)b * n, n, n, words, dt_i, A_h);
     if (status && h == 0 && tid == 0) status[b] = bad;
     T *yb = y + (size_t)b * n * H * P + (size_t)h * P;
@@ -137,8 +138,8 @@ static hipError_t launch_fma_t(const stree_dims &d, const int32_t *parent, const
         if (raised != hipSuccess) return raised;
     }
     hipLaunchKernelGGL(tree_ssd_fma_kernel<T>, dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
-                       d.nheads, d.headdim, d.dstate, d.ngroups, (const T *)x, (long)d.x_stride_n, dt, A,
-                       (const T *)Bm, (long)d.b_stride_n, (const T *)Cm, (long)d.c_stride_n, D, h0, (T *)y, status);
+                       d.nheads, d.headdim, d.dstate, d.ngroups, (const T *)x, (long)d.x_stride_n, dt, step_bias(d),
+                       A, (const T *)Bm, (long)d.b_stride_n, (const T *)Cm, (long)d.c_stride_n, D, h0, (T *)y, status);
     return hipGetLastError();
 }
 

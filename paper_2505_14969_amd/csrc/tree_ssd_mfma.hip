@@ -69,7 +69,8 @@ constexpr int kH0Batch = 8;      // float4 pieces of h0 per thread requested ahe
 template <int P, bool SH>
 __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kernel(
     const int32_t *__restrict__ parent, int n, int H, int S, int G, const bf16_t *__restrict__ x, long x_sn,
-    const float *__restrict__ dt, const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn,
+    const float *__restrict__ dt, const float *__restrict__ dt_bias, const float *__restrict__ A,
+    const bf16_t *__restrict__ Bm, long b_sn,
     const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
     bf16_t *__restrict__ y, int32_t *__restrict__ status) {
     constexpr int YT = (P / 32) * 2;          // 32x32 tiles of Yt[p][i] per node block
@@ -174,7 +175,8 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
     //      in order, and the tree index needs only these), then h0 and the tiles of pair (0, 0) ----
     const float A_h = A[h];
     const float D_h = D ? D[h] : 0.f;          // (asked for here: after the tree index its latency is exposed)
-    const float dt_i = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
+    const float bias_h = dt_bias ? dt_bias[h] : 0.f;
+    const float dt_raw = tid < n ? dt[((size_t)b * n + tid) * H + h] : 0.f;
     const int parent_i = tid < n ? parent[(size_t)b * n + tid] : -1;
     if (h0) {
 #pragma unroll
@@ -189,6 +191,7 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
 
     // ---- tree index: depth, mask rows L_i, s_i = (A_tree)_i ---------------------------------
     if (tid == 0) nz_bits = 0u;
+    const float dt_i = (dt_bias && tid < n) ? softplus_step(dt_raw + bias_h) : dt_raw;
     const int bad = build_tree_index(tree, mask, parent_i, n, npad, words, dt_i, A_h);
     if (status && h == 0 && tid == 0) status[b] = bad;
     bf16_t *yb = y + (size_t)b * n * H * P + (size_t)h * P;
@@ -429,8 +432,8 @@ static hipError_t launch_p(const stree_dims &d, const int32_t *parent, const voi
         }
     }
     hipLaunchKernelGGL((tree_ssd_mfma_kernel<P, SH>), dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
-                       d.nheads, d.dstate, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A,
-                       (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,
+                       d.nheads, d.dstate, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d),
+                       A, (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,
                        (bf16_t *)y, status);
     return hipGetLastError();
 }

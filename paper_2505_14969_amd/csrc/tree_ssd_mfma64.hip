@@ -119,10 +119,11 @@ __device__ __forceinline__ int wave_tree_index(int lane, int n, int parent_i, fl
 // where it puts them into LDS; one more barrier per unit (c) separates that from the FMAs of the
 // threads that carry the unit.  Longer paths read the remaining rows from
 // global memory.  Each thread owns one 4-wide piece of the state index and NH consecutive rows.
-template <int P, int S, int WPE, bool RP>
+template <int P, int S, int WPE, bool RP, bool SPL>
 __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void tree_ssd_mfma64_kernel(
     const int32_t *__restrict__ parent, int n, int nbatch, int H, int G, const bf16_t *__restrict__ x, long x_sn,
-    const float *__restrict__ dt, const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn,
+    const float *__restrict__ dt, const float *__restrict__ dt_bias, const float *__restrict__ A,
+    const bf16_t *__restrict__ Bm, long b_sn,
     const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
     bf16_t *__restrict__ y, int32_t *__restrict__ status, ReplayArgs R) {
     using L = Lds64<P, S>;
@@ -355,7 +356,9 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     };
     auto stage_T = [&](int h) {
         const int ln = opaque(lane);   // LDS addresses re-derived here, not carried across the loop
-        const int bad = wave_tree_index(ln, n, rpar, rdt, A[h], sS2, sU, sMask);
+        float dt_i = rdt;
+        if constexpr (SPL) dt_i = softplus_step(rdt + dt_bias[h]);               // raw projection -> step size
+        const int bad = wave_tree_index(ln, n, rpar, dt_i, A[h], sS2, sU, sMask);
         if (ln == 0) *sBad = bad;
     };
 
@@ -383,10 +386,12 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         // waiting for it would wait for the whole h0 prefetch)
         const int rk = R.accepted[__builtin_amdgcn_readfirstlane(b)];
         const float rRA = A[__builtin_amdgcn_readfirstlane(h)];
+        float pdt_i = rpdt;
+        if constexpr (SPL) pdt_i = softplus_step(rpdt + dt_bias[__builtin_amdgcn_readfirstlane(h)]);
         const bool kbad = rk < -1 || rk >= pn;
         int pos = -1, len = 0;
         float cf = 0.f, dc = 1.f;
-        const int st = wave_path(ln, pn, (rk >= 0 && !kbad) ? rk : 0, rpp, rpdt, rRA, pos, cf, len, dc);
+        const int st = wave_path(ln, pn, (rk >= 0 && !kbad) ? rk : 0, rpp, pdt_i, rRA, pos, cf, len, dc);
         if (st != 0 || rk < 0 || kbad) {   // nothing to replay: the state passes through
             pos = -1;
             len = 0;
@@ -793,10 +798,15 @@ hipError_t launch64_ps(const stree_dims &d, const int32_t *parent, const void *x
     int grid = (n_units + 7) / 8 * 8;
     const int cap = 256 * (per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu));
     if (grid > cap) grid = cap;
-    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE, RP>), dim3(grid), dim3(kT64), 0, st, parent, d.nnodes,
-                       d.batch, d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, A,
-                       (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,
-                       (bf16_t *)y, status, R);
+    // (the in-kernel softplus is a variant of its own: compiled into the common one, even unused, it costs time)
+#define STREE_LAUNCH64(SPL)                                                                                          \
+    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE, RP, SPL>), dim3(grid), dim3(kT64), 0, st, parent, d.nnodes, \
+                       d.batch, d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d), A,     \
+                       (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,        \
+                       (bf16_t *)y, status, R)
+    if (step_bias(d)) STREE_LAUNCH64(true);
+    else STREE_LAUNCH64(false);
+#undef STREE_LAUNCH64
     return hipGetLastError();
 }
 

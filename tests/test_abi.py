@@ -10,6 +10,7 @@ import pytest
 from paper_2505_14969_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "stree.h")
 
 
 @pytest.fixture(scope="module")
@@ -34,10 +35,28 @@ def test_header_symbols_are_exported(lib):
         assert hasattr(lib, n), f"{n} declared in include/stree.h but not exported"
 
 
-def test_dims_struct_matches_header_layout():
-    # 10 int32 + 3 int64, naturally aligned
-    assert C.sizeof(binding.StreeDims) == 10 * 4 + 3 * 8
-    assert binding.StreeDims.x_stride_n.offset == 40
+def test_dims_struct_matches_header_layout(tmp_path):
+    """Sizes and field offsets of the two argument structs: the ctypes mirror against the header itself,
+    as the host C compiler lays it out."""
+    import subprocess
+    fields = {"stree_dims": ["batch", "flags", "x_stride_n", "c_stride_n", "dt_bias"],
+              "stree_replay": ["nnodes", "parent", "accepted", "x", "dt", "Bm", "x_stride_n", "b_stride_n"]}
+    src = ['#include <stdio.h>', '#include <stddef.h>', f'#include "{HEADER}"', 'int main(void) {']
+    for st, fs in fields.items():
+        src.append(f'printf("%zu\\n", sizeof({st}));')
+        src += [f'printf("%zu\\n", offsetof({st}, {f}));' for f in fs]
+    src += ['return 0; }']
+    (tmp_path / "layout.c").write_text("\n".join(src))
+    subprocess.run(["gcc", "-o", str(tmp_path / "layout"), str(tmp_path / "layout.c")], check=True)
+    got = [int(v) for v in subprocess.run([str(tmp_path / "layout")], check=True, capture_output=True,
+                                          text=True).stdout.split()]
+    want = []
+    for st, cls in (("stree_dims", binding.StreeDims), ("stree_replay", binding.StreeReplay)):
+        want.append(C.sizeof(cls))
+        want += [getattr(cls, f).offset for f in fields[st]]
+    assert got == want
+    # 10 int32 + 3 int64 + 1 pointer, naturally aligned
+    assert C.sizeof(binding.StreeDims) == 10 * 4 + 3 * 8 + 8 and binding.StreeDims.dt_bias.offset == 64
 
 
 def test_version_and_status_strings(lib):
@@ -86,6 +105,8 @@ def test_tree_ssd_rejects_bad_arguments(lib):
     assert _ssd(lib, d) == 3
     assert _ssd(lib, binding.make_dims(**ok, x_stride_n=8)) == 4
     assert _ssd(lib, binding.make_dims(**ok, b_stride_n=64)) == 4
+    # the in-kernel softplus needs its bias vector
+    assert _ssd(lib, binding.make_dims(**ok, flags=binding.FLAG_DT_SOFTPLUS)) == 1
     # batch 0 is a valid no-op and launches nothing
     assert _ssd(lib, binding.make_dims(**{**ok, "batch": 0})) == 0
 
