@@ -43,17 +43,18 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes_tree_ssd(B, N, H, P, S, G):
-    """Each operand once: x, y (bf16), B, C (bf16), dt (f32), h0 (f32), parent."""
-    per_seq = N * H * P * 2 * 2 + 2 * N * G * S * 2 + N * H * 4 + H * P * S * 4 + N * 4
+def algorithmic_bytes_tree_ssd(B, N, H, P, S, G, se=4):
+    """Each operand once: x, y (bf16), B, C (bf16), dt (f32), h0 (se bytes per element: f32, or the bf16
+    variant of the state), parent."""
+    per_seq = N * H * P * 2 * 2 + 2 * N * G * S * 2 + N * H * 4 + H * P * S * se + N * 4
     return B * per_seq + 2 * H * 4
 
 
-def algorithmic_bytes_replay(B, N, Np, H, P, S, G, path_nodes):
+def algorithmic_bytes_replay(B, N, Np, H, P, S, G, path_nodes, se=4):
     """The scan's operands plus the replayed state written once, the previous tree's parent /
     accepted / dt, and the x and B rows of the accepted paths (path_nodes = their total length)."""
-    extra = B * H * P * S * 4 + B * (Np * 4 + 4 + Np * H * 4) + path_nodes * (H * P + G * S) * 2
-    return algorithmic_bytes_tree_ssd(B, N, H, P, S, G) + extra
+    extra = B * H * P * S * se + B * (Np * 4 + 4 + Np * H * 4) + path_nodes * (H * P + G * S) * 2
+    return algorithmic_bytes_tree_ssd(B, N, H, P, S, G, se) + extra
 
 
 def algorithmic_bytes_conv(B, N, H, P, S, G, W, e=2):
@@ -62,12 +63,12 @@ def algorithmic_bytes_conv(B, N, H, P, S, G, W, e=2):
     return B * (2 * N * Cc + (W - 1) * Cc) * e + Cc * (W + 1) * e
 
 
-def algorithmic_bytes_commit(B, N, H, P, S, G, W, path_nodes, e=2):
+def algorithmic_bytes_commit(B, N, H, P, S, G, W, path_nodes, e=2, se=4):
     """State read and written once, parent / accepted / dt, the x and B rows of the accepted paths,
     and (W > 0) the conv tail: W-1 rows read and written per sequence."""
     Cc = H * P + 2 * G * S
     tail = B * 2 * (W - 1) * Cc * e if W else 0
-    return 2 * B * H * P * S * 4 + B * (N * 4 + 4 + N * H * 4) + path_nodes * (H * P + G * S) * e + tail
+    return 2 * B * H * P * S * se + B * (N * 4 + 4 + N * H * 4) + path_nodes * (H * P + G * S) * e + tail
 
 
 def algorithmic_flops_tree_ssd(B, N, H, P, S, G):
@@ -208,10 +209,35 @@ def main():
         conv_replay(s)
         fused(s)
 
+    # the variant with the state kept in bf16 (reported on its own, never as `value`)
+    for s in sets:
+        s["h0b"] = s["h0"].to(torch.bfloat16)
+        s["h_outb"] = torch.empty_like(s["h0b"])
+
+    def ssd_b(s):
+        st.stree_tree_ssd(s["parent"], s["x"], s["dt"], A, s["Bm"], s["Cm"], D, s["h0b"], out=s["y"])
+
+    def commit_b(s):
+        st.stree_commit_state(s["parent"], s["accepted"], s["x"], s["dt"], A, s["Bm"], s["h0b"], h_out=s["h_outb"],
+                              xbc_pre=s["xbc_pre"], conv_state=s["conv_state"], conv_state_out=s["cs_out"])
+
+    def fused_b(s):
+        q = s["prev"]
+        st.stree_tree_ssd_replay(q["parent"], q["accepted"], q["x"], q["dt"], q["Bm"], s["parent"], s["x"], s["dt"],
+                                 A, s["Bm"], s["Cm"], D, s["h0b"], h_out=s["h_outb"], out=s["y"])
+
+    def step_fused_b(s):
+        conv_replay(s)
+        fused_b(s)
+
     for s in sets:           # first launches (also sets the kernel's LDS attribute) outside any capture
         step(s)
     for s in sets:
         step_fused(s)
+    for s in sets:
+        ssd_b(s)
+        commit_b(s)
+        step_fused_b(s)
     torch.cuda.synchronize()
 
     if args.only_ssd or args.only_fused or args.only_gate:
@@ -282,6 +308,10 @@ def main():
     _, ms_tail = timed(conv_replay, K, Wm)
     ms_cs, _ = timed(conv_ssd, K, Wm)
     _, ms_gn = timed(gate_norm, K, Wm)
+    _, ms_ssd_b = timed(ssd_b, K, Wm)
+    _, ms_commit_b = timed(commit_b, K, Wm)
+    _, ms_fused_b = timed(fused_b, K, Wm)
+    ms_fstep_b, _ = timed(step_fused_b, K, Wm)
     # one buffer set only: inputs stay in the 256 MB Infinity Cache
     keep = sets
     sets = [keep[0]] * N_SETS
@@ -310,6 +340,12 @@ def main():
     log(f"[bench]   replay+scan: {alg_bytes_f/1e6:.2f} MB algorithmic -> {achieved_f:.0f} GB/s "
         f"({achieved_f/HBM_PEAK_GBS*100:.1f}% of 8 TB/s)")
 
+    ab_b = {"tree_ssd": algorithmic_bytes_tree_ssd(B, N, H, P, S, G, se=2),
+            "tree_ssd_replay": algorithmic_bytes_replay(B, N, N, H, P, S, G, path_nodes, se=2),
+            "commit_state": algorithmic_bytes_commit(B, N, H, P, S, G, W, path_nodes, se=2)}
+    us_b = {"tree_ssd": ms_ssd_b * 1e3, "tree_ssd_replay": ms_fused_b * 1e3, "commit_state": ms_commit_b * 1e3}
+    log(f"[bench] bf16 state (variant): tree_ssd {us_b['tree_ssd']:.2f} us | replay+scan {us_b['tree_ssd_replay']:.2f} us | "
+        f"commit {us_b['commit_state']:.2f} us | fused step {ms_fstep_b*1e3:.1f} us")
     steps = {"separate": ms_step, "fused": ms_fstep}
     best = min(steps, key=steps.get)
     ms_best = steps[best]
@@ -350,6 +386,12 @@ def main():
                        "tree_conv_replay": ms_tail * 1e3, "tree_ssd_replay": ms_fused * 1e3,
                        "gate_norm": ms_gn * 1e3},
         # the output gate + RMS norm behind the scan: y and z read, out written (not part of the timed step)
+        # the same workload with the SSM state kept in bf16 (state_dtype): half the state traffic, one rounding
+        # of the state per iteration; a variant, not the headline configuration (whose state is fp32)
+        "state_bf16": {"kernels": {k: {"us": us_b[k], "algorithmic_bytes": ab_b[k],
+                                       "GBps": ab_b[k] / (us_b[k] * 1e-6) / 1e9,
+                                       "frac": ab_b[k] / (us_b[k] * 1e-6) / 1e9 / HBM_PEAK_GBS} for k in us_b},
+                       "fused_step_us": ms_fstep_b * 1e3, "nodes_per_s": nodes / (ms_fstep_b * 1e-3)},
         "gate_norm": {"us": ms_gn * 1e3, "algorithmic_bytes": 3 * B * N * H * P * 2 + H * P * 2,
                       "GBps": (3 * B * N * H * P * 2 + H * P * 2) / (ms_gn * 1e-3) / 1e9},
     }

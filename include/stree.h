@@ -19,7 +19,8 @@
  *     or (index of the first bad node) + 1, and that sequence's outputs are
  *     zero-filled (commit: state copied through unchanged).
  *   - Layouts are row-major with the last index contiguous.  Head h reads group
- *     g = h / (nheads / ngroups).  dt, A, D and the SSM state are always fp32;
+ *     g = h / (nheads / ngroups).  dt, A, D are always fp32; the SSM state (h0, h_out:
+ *     "st" below) is fp32, or bf16 with state_dtype = STREE_BF16;
  *     `io_dtype` selects fp32 or bf16 for x, B, C, y and the conv tensors.
  *   - Envelope: 1 <= nnodes <= 256, batch >= 0 (0 is a no-op), nheads % ngroups
  *     == 0, 1 <= headdim <= 256, 1 <= dstate <= 256, conv_width in {2,3,4}.
@@ -75,7 +76,10 @@ typedef struct stree_dims {
     int32_t ngroups;     /* G */
     int32_t conv_width;  /* W (ignored by tree_ssd; 0 allowed there) */
     int32_t io_dtype;    /* enum stree_dtype */
-    int32_t state_dtype; /* STREE_F32 only */
+    int32_t state_dtype; /* type of h0 / h_out: STREE_F32, or STREE_BF16 (only with io_dtype = STREE_BF16).
+                          * A bf16 state is widened exactly when read, all arithmetic stays fp32, and a new
+                          * state is rounded to nearest even once, when written: every iteration adds that
+                          * rounding (at most 2^-8 relative) to the state -- the caller's trade for half the traffic. */
     int32_t flags;       /* enum stree_flags */
     /* token strides in ELEMENTS of x, B, C (0 = dense: H*P, G*S, G*S).  They let
      * x | B | C be column ranges of one conv output buffer [B,N,H*P+2*G*S].  The
@@ -145,14 +149,14 @@ int stree_tree_conv(const stree_dims *dims, const int32_t *parent, const void *x
  *   x   io  [B,N,H,P] (token stride x_stride_n)    dt  f32 [B,N,H]: the step size (>= 0), or, with
  *                                                  STREE_FLAG_DT_SOFTPLUS, the raw projection
  *   A   f32 [H], negative                          Bm, Cm io [B,N,G,S] (strides b/c_stride_n)
- *   D   f32 [H] or NULL                            h0  f32 [B,H,P,S] or NULL (zero state)
+ *   D   f32 [H] or NULL                            h0  st  [B,H,P,S] or NULL (zero state)
  *   y   io  [B,N,H,P] dense
  * bf16 mode: products on the bf16 MFMA units with fp32 accumulation; the state
  * and the decay-weighted mask are rounded to bf16 as MFMA operands.
  */
 int stree_tree_ssd(const stree_dims *dims, const int32_t *parent, const void *x, const float *dt,
                    const float *A, const void *Bm, const void *Cm, const float *D,
-                   const float *h0, void *y, int32_t *tree_status, void *hip_stream);
+                   const void *h0, void *y, int32_t *tree_status, void *hip_stream);
 
 /*
  * State commit (the "activation replay" of Sec. 3 "Implementation" / Alg. 1: the
@@ -163,7 +167,7 @@ int stree_tree_ssd(const stree_dims *dims, const int32_t *parent, const void *x,
  * accepted[b] == -1 copies the state through.  An accepted index outside
  * [-1, N) sets tree_status[b] = -1 and copies the state through.
  *   accepted int32 [B]; x, dt, A, Bm as in stree_tree_ssd
- *   h0 f32 [B,H,P,S] or NULL; h_out f32 [B,H,P,S], MAY alias h0
+ *   h0 st [B,H,P,S] or NULL; h_out st [B,H,P,S], MAY alias h0
  *   xbc_pre, conv_state, conv_state_out: all three NULL to skip the conv part;
  *   conv_state_out MAY alias conv_state.
  *   x, dt, A, Bm, h0, h_out: all six NULL to skip the state part (conv tail only,
@@ -172,7 +176,7 @@ int stree_tree_ssd(const stree_dims *dims, const int32_t *parent, const void *x,
  */
 int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int32_t *accepted,
                        const void *x, const float *dt, const float *A, const void *Bm,
-                       const float *h0, float *h_out, const void *xbc_pre,
+                       const void *h0, void *h_out, const void *xbc_pre,
                        const void *conv_state, void *conv_state_out, int32_t *tree_status,
                        void *hip_stream);
 
@@ -200,7 +204,7 @@ typedef struct stree_replay {
  * current tree would do, reading the state once instead of twice:
  *   h_out = state after the accepted path of `prev` starting from h0   (commit formula)
  *   y     = tree scan of the current tree starting from h_out          (scan formula)
- *   h0    f32 [B,H,P,S], required; h_out f32 [B,H,P,S], required, MAY alias h0
+ *   h0    st [B,H,P,S], required; h_out st [B,H,P,S], required, MAY alias h0
  *   replay_status int32 [B] or NULL: 0, (first bad node of the previous tree) + 1,
  *                 or -1 for an accepted index outside [-1, prev->nnodes); in the
  *                 last two cases the state passes through unchanged
@@ -212,7 +216,7 @@ typedef struct stree_replay {
  */
 int stree_tree_ssd_replay(const stree_dims *dims, const stree_replay *prev, const int32_t *parent,
                           const void *x, const float *dt, const float *A, const void *Bm,
-                          const void *Cm, const float *D, const float *h0, float *h_out, void *y,
+                          const void *Cm, const float *D, const void *h0, void *h_out, void *y,
                           int32_t *tree_status, int32_t *replay_status, void *hip_stream);
 
 /*
@@ -241,7 +245,7 @@ int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, con
  *                  C = the last G*S, each with token stride Cc (the strides in dims
  *                  are ignored)
  *   conv_state_out io [B,W-1,Cc], must NOT alias conv_state
- *   h_out          f32 [B,H,P,S], MAY alias h0;  y io [B,N,H,P] dense
+ *   h_out          st [B,H,P,S], MAY alias h0;   y io [B,N,H,P] dense
  *   prev           the previous tree; prev->x and prev->Bm are the x and B columns of
  *                  the previous step's xbc_out (strides in prev), prev_xbc_pre its
  *                  pre-conv rows [B, prev->nnodes, Cc]
@@ -259,7 +263,7 @@ int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, con
 int stree_tree_step(const stree_dims *dims, const stree_replay *prev, const void *prev_xbc_pre,
                     const int32_t *parent, const void *xbc_pre, const void *conv_state,
                     const void *conv_w, const void *conv_b, void *xbc_out, void *conv_state_out,
-                    const float *dt, const float *A, const float *D, const float *h0, float *h_out,
+                    const float *dt, const float *A, const float *D, const void *h0, void *h_out,
                     void *y, int32_t *tree_status, int32_t *replay_status, void *hip_stream);
 
 /*
@@ -292,7 +296,7 @@ int stree_gate_norm(const stree_dims *dims, const void *y, const void *z, int64_
  *   dims->nnodes = T, any T >= 1 (not limited to STREE_MAX_NODES); conv_width ignored
  *   x, dt, A, Bm, Cm, D, h0 as in stree_tree_ssd with T in place of N
  *   y      io [B,T,H,P] or NULL: state only (then Cm and D may be NULL too)
- *   h_out  f32 [B,H,P,S] state after token T-1, required, MAY alias h0
+ *   h_out  st [B,H,P,S] state after token T-1, required, MAY alias h0
  * Shapes: bf16 io, (headdim, dstate) in {(64,64), (64,128), (128,128)}, 16-byte
  * aligned pointers and strides; anything else returns STREE_ERR_BAD_SHAPE
  * (a chain tree through stree_tree_ssd / stree_commit_state covers it, 256
@@ -302,8 +306,8 @@ int stree_gate_norm(const stree_dims *dims, const void *y, const void *z, int64_
  * rounded to bf16.
  */
 int stree_linear_ssd(const stree_dims *dims, const void *x, const float *dt, const float *A,
-                     const void *Bm, const void *Cm, const float *D, const float *h0, void *y,
-                     float *h_out, void *hip_stream);
+                     const void *Bm, const void *Cm, const float *D, const void *h0, void *y,
+                     void *h_out, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -88,12 +88,20 @@ def _stream() -> _VP:
     return _VP(torch.cuda.current_stream().cuda_stream)
 
 
-def _io_code(t: torch.Tensor) -> int:
-    if t.dtype == torch.float32:
+def _io_code(t) -> int:
+    dt = t.dtype if isinstance(t, torch.Tensor) else t
+    if dt == torch.float32:
         return F32
-    if t.dtype == torch.bfloat16:
+    if dt == torch.bfloat16:
         return BF16
-    raise TypeError(f"unsupported io dtype {t.dtype}")
+    raise TypeError(f"unsupported dtype {dt}")
+
+
+def _state_code(*states) -> int:
+    """Type code of the SSM state from the state tensors of a call (those that are given must agree)."""
+    dts = {t.dtype for t in states if t is not None}
+    assert len(dts) <= 1, "h0 and h_out must have the same dtype"
+    return _io_code(next(iter(dts))) if dts else F32
 
 
 def _token_stride(t: torch.Tensor, nnodes: int) -> int:
@@ -108,13 +116,14 @@ def _token_stride(t: torch.Tensor, nnodes: int) -> int:
 
 
 def make_dims(batch, nnodes, nheads, headdim, dstate, ngroups, conv_width=0, io_dtype=BF16, flags=0,
-              x_stride_n=0, b_stride_n=0, c_stride_n=0, dt_bias: Optional[torch.Tensor] = None) -> StreeDims:
+              x_stride_n=0, b_stride_n=0, c_stride_n=0, dt_bias: Optional[torch.Tensor] = None,
+              state_dtype=F32) -> StreeDims:
     """`dt_bias` (f32 [H] on the GPU) switches the in-kernel softplus on: the dt arguments of the call are
     then the raw projection and the step size is softplus(dt + dt_bias[h])."""
     if dt_bias is not None:
         assert dt_bias.dtype == torch.float32 and dt_bias.is_contiguous() and dt_bias.numel() == nheads
         flags |= FLAG_DT_SOFTPLUS
-    return StreeDims(batch, nnodes, nheads, headdim, dstate, ngroups, conv_width, io_dtype, F32, flags,
+    return StreeDims(batch, nnodes, nheads, headdim, dstate, ngroups, conv_width, io_dtype, state_dtype, flags,
                      x_stride_n, b_stride_n, c_stride_n, None if dt_bias is None else dt_bias.data_ptr())
 
 
@@ -162,7 +171,7 @@ def stree_tree_conv(parent, xbc_pre, conv_state, conv_w, conv_b, nheads, headdim
 def stree_tree_ssd(parent, x, dt, A, Bm, Cm, D=None, h0=None, out: Optional[torch.Tensor] = None,
                    status: Optional[torch.Tensor] = None, force_fma: bool = False, general_mfma: bool = False,
                    dt_bias: Optional[torch.Tensor] = None):
-    """x [B,N,H,P], dt [B,N,H] f32, A [H] f32, Bm/Cm [B,N,G,S], D [H]|None, h0 [B,H,P,S] f32|None
+    """x [B,N,H,P], dt [B,N,H] f32, A [H] f32, Bm/Cm [B,N,G,S], D [H]|None, h0 [B,H,P,S] f32 or bf16|None
     -> y [B,N,H,P].  x, Bm, Cm may be column views of one [B,N,Cc] buffer.  With dt_bias [H] f32, dt is
     the raw projection and the kernels take softplus(dt + dt_bias[h]) as the step size (here and in
     every function below that has this argument)."""
@@ -172,7 +181,7 @@ def stree_tree_ssd(parent, x, dt, A, Bm, Cm, D=None, h0=None, out: Optional[torc
         out = torch.empty((B, N, H, P), dtype=x.dtype, device=x.device)
     d = make_dims(B, N, H, P, S, G, 0, _io_code(x),
                   (FLAG_FORCE_FMA if force_fma else 0) | (FLAG_GENERAL_MFMA if general_mfma else 0),
-                  _token_stride(x, N), _token_stride(Bm, N), _token_stride(Cm, N), dt_bias)
+                  _token_stride(x, N), _token_stride(Bm, N), _token_stride(Cm, N), dt_bias, _state_code(h0))
     assert dt.is_contiguous() and dt.dtype == torch.float32 and out.is_contiguous()
     _check(load().stree_tree_ssd(C.byref(d), _ptr(parent), _ptr(x), _ptr(dt), _ptr(A), _ptr(Bm), _ptr(Cm),
                                  _ptr(D), _ptr(h0), _ptr(out), _ptr(status), _stream()), "stree_tree_ssd")
@@ -183,7 +192,7 @@ def stree_commit_state(parent, accepted, x, dt, A, Bm, h0=None, h_out: Optional[
                        xbc_pre=None, conv_state=None, conv_state_out: Optional[torch.Tensor] = None,
                        status: Optional[torch.Tensor] = None, dims: Optional[tuple] = None,
                        dt_bias: Optional[torch.Tensor] = None):
-    """-> (h_out [B,H,P,S] f32, conv_state_out [B,W-1,Cc] | None).  h_out may be h0 itself
+    """-> (h_out [B,H,P,S] in the dtype of h0, conv_state_out [B,W-1,Cc] | None).  h_out may be h0 itself
     (in place), conv_state_out may be conv_state itself.  With x, dt, A, Bm all None only the conv
     tail is updated; `dims` = (H, P, S, G) then names the head shapes."""
     if x is None:
@@ -200,13 +209,14 @@ def stree_commit_state(parent, accepted, x, dt, A, Bm, h0=None, h_out: Optional[
     B, N, H, P = x.shape
     G, S = Bm.shape[2], Bm.shape[3]
     if h_out is None:
-        h_out = torch.empty((B, H, P, S), dtype=torch.float32, device=x.device)
+        h_out = torch.empty((B, H, P, S), dtype=torch.float32 if h0 is None else h0.dtype, device=x.device)
     W = 0
     if xbc_pre is not None:
         W = conv_state.shape[1] + 1
         if conv_state_out is None:
             conv_state_out = torch.empty_like(conv_state)
-    d = make_dims(B, N, H, P, S, G, W, _io_code(x), 0, _token_stride(x, N), _token_stride(Bm, N), 0, dt_bias)
+    d = make_dims(B, N, H, P, S, G, W, _io_code(x), 0, _token_stride(x, N), _token_stride(Bm, N), 0, dt_bias,
+                  _state_code(h0, h_out))
     _check(load().stree_commit_state(C.byref(d), _ptr(parent), _ptr(accepted), _ptr(x), _ptr(dt), _ptr(A),
                                      _ptr(Bm), _ptr(h0), _ptr(h_out), _ptr(xbc_pre), _ptr(conv_state),
                                      _ptr(conv_state_out), _ptr(status), _stream()), "stree_commit_state")
@@ -218,7 +228,7 @@ def stree_tree_ssd_replay(prev_parent, prev_accepted, prev_x, prev_dt, prev_Bm, 
                           status: Optional[torch.Tensor] = None, replay_status: Optional[torch.Tensor] = None,
                           force_fma: bool = False, dt_bias: Optional[torch.Tensor] = None):
     """Commit of the previous tree's accepted path fused with the scan of the current tree.
-    -> (y [B,N,H,P], h_out [B,H,P,S] f32).  h_out may be h0 itself (in place)."""
+    -> (y [B,N,H,P], h_out [B,H,P,S] in the dtype of h0).  h_out may be h0 itself (in place)."""
     B, N, H, P = x.shape
     G, S = Bm.shape[2], Bm.shape[3]
     Np = prev_x.shape[1]
@@ -230,7 +240,7 @@ def stree_tree_ssd_replay(prev_parent, prev_accepted, prev_x, prev_dt, prev_Bm, 
     if h_out is None:
         h_out = torch.empty_like(h0)
     d = make_dims(B, N, H, P, S, G, 0, _io_code(x), FLAG_FORCE_FMA if force_fma else 0,
-                  _token_stride(x, N), _token_stride(Bm, N), _token_stride(Cm, N), dt_bias)
+                  _token_stride(x, N), _token_stride(Bm, N), _token_stride(Cm, N), dt_bias, _state_code(h0, h_out))
     r = StreeReplay(Np, 0, prev_parent.data_ptr(), prev_accepted.data_ptr(), prev_x.data_ptr(), prev_dt.data_ptr(),
                     prev_Bm.data_ptr(), _token_stride(prev_x, Np), _token_stride(prev_Bm, Np))
     _check(load().stree_tree_ssd_replay(C.byref(d), C.byref(r), _ptr(parent), _ptr(x), _ptr(dt), _ptr(A), _ptr(Bm),
@@ -274,7 +284,7 @@ def stree_tree_step(prev_parent, prev_accepted, prev_xbc_pre, prev_xbc_out, prev
     """One decoding step in one call: tree conv (seeded by the conv state after the previous tree's
     accepted path), state replay along that path and tree scan.  prev_xbc_out is the previous step's
     conv output [B,Np,Cc] (its x and B columns are replayed; it must not be xbc_out).
-    -> (y [B,N,H,P], h_out [B,H,P,S] f32, xbc_out [B,N,Cc], conv_state_out [B,W-1,Cc])."""
+    -> (y [B,N,H,P], h_out [B,H,P,S] in the dtype of h0, xbc_out [B,N,Cc], conv_state_out [B,W-1,Cc])."""
     B, N, Cc = xbc_pre.shape
     W = conv_w.shape[1]
     Np = prev_xbc_pre.shape[1]
@@ -294,7 +304,7 @@ def stree_tree_step(prev_parent, prev_accepted, prev_xbc_pre, prev_xbc_out, prev
     assert xbc_out.is_contiguous() and out.is_contiguous() and h_out.is_contiguous()
     assert conv_state_out.data_ptr() != conv_state.data_ptr()
     flags = (FLAG_CONV_SILU if silu else 0) | (FLAG_FORCE_FMA if force_fma else 0)
-    d = make_dims(B, N, H, P, S, G, W, _io_code(xbc_pre), flags, dt_bias=dt_bias)
+    d = make_dims(B, N, H, P, S, G, W, _io_code(xbc_pre), flags, dt_bias=dt_bias, state_dtype=_state_code(h0, h_out))
     prev_B = prev_xbc_out[:, :, H * P:H * P + G * S]
     r = StreeReplay(Np, 0, prev_parent.data_ptr(), prev_accepted.data_ptr(), prev_xbc_out.data_ptr(),
                     prev_dt.data_ptr(), prev_B.data_ptr(), Cc, Cc)
@@ -322,16 +332,16 @@ def stree_linear_ssd(x, dt, A, Bm, Cm=None, D=None, h0=None, want_y: bool = True
                      out: Optional[torch.Tensor] = None, h_out: Optional[torch.Tensor] = None,
                      dt_bias: Optional[torch.Tensor] = None):
     """Causal scan of T tokens per sequence: x [B,T,H,P], dt [B,T,H] f32, Bm/Cm [B,T,G,S].
-    -> (y [B,T,H,P] or None, h_out [B,H,P,S] f32).  h_out may be h0 itself."""
+    -> (y [B,T,H,P] or None, h_out [B,H,P,S] in the dtype of h0).  h_out may be h0 itself."""
     B, T, H, P = x.shape
     G, S = Bm.shape[2], Bm.shape[3]
     assert dt.is_contiguous() and dt.dtype == torch.float32 and dt.shape == (B, T, H)
     if want_y and out is None:
         out = torch.empty((B, T, H, P), dtype=x.dtype, device=x.device)
     if h_out is None:
-        h_out = torch.empty((B, H, P, S), dtype=torch.float32, device=x.device)
+        h_out = torch.empty((B, H, P, S), dtype=torch.float32 if h0 is None else h0.dtype, device=x.device)
     d = make_dims(B, T, H, P, S, G, 0, _io_code(x), 0, _token_stride(x, T), _token_stride(Bm, T),
-                  _token_stride(Cm, T) if Cm is not None else 0, dt_bias)
+                  _token_stride(Cm, T) if Cm is not None else 0, dt_bias, _state_code(h0, h_out))
     _check(load().stree_linear_ssd(C.byref(d), _ptr(x), _ptr(dt), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(D), _ptr(h0),
                                    _ptr(out) if want_y else None, _ptr(h_out), _stream()), "stree_linear_ssd")
     return (out if want_y else None), h_out

@@ -12,7 +12,8 @@ enum ConvCheck { kNoConv = 0, kConvWidth = 1, kConvChannels = 2 };
 int check_dims(const stree_dims *d, int need_conv) {
     if (!d) return STREE_ERR_NULL_ARG;
     if (d->io_dtype != STREE_F32 && d->io_dtype != STREE_BF16) return STREE_ERR_BAD_DTYPE;
-    if (d->state_dtype != STREE_F32) return STREE_ERR_BAD_DTYPE;
+    if (d->state_dtype != STREE_F32 && !(d->state_dtype == STREE_BF16 && d->io_dtype == STREE_BF16))
+        return STREE_ERR_BAD_DTYPE;                 // (a bf16 state goes with bf16 io only)
     if ((d->flags & STREE_FLAG_DT_SOFTPLUS) && !d->dt_bias) return STREE_ERR_NULL_ARG;
     if (d->batch < 0 || d->batch > 65535) return STREE_ERR_BAD_SHAPE;
     if (d->nnodes < 1 || d->nnodes > STREE_MAX_NODES) return STREE_ERR_BAD_SHAPE;
@@ -99,7 +100,7 @@ int stree_tree_conv(const stree_dims *dims, const int32_t *parent, const void *x
 }
 
 int stree_tree_ssd(const stree_dims *dims, const int32_t *parent, const void *x, const float *dt,
-                   const float *A, const void *Bm, const void *Cm, const float *D, const float *h0, void *y,
+                   const float *A, const void *Bm, const void *Cm, const float *D, const void *h0, void *y,
                    int32_t *tree_status, void *hip_stream) {
     int rc = check_dims(dims, kNoConv);
     if (rc) return rc;
@@ -115,7 +116,7 @@ int stree_tree_ssd(const stree_dims *dims, const int32_t *parent, const void *x,
 }
 
 int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int32_t *accepted, const void *x,
-                       const float *dt, const float *A, const void *Bm, const float *h0, float *h_out,
+                       const float *dt, const float *A, const void *Bm, const void *h0, void *h_out,
                        const void *xbc_pre, const void *conv_state, void *conv_state_out,
                        int32_t *tree_status, void *hip_stream) {
     const bool conv = xbc_pre || conv_state || conv_state_out;
@@ -138,7 +139,7 @@ int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int3
 
 int stree_tree_ssd_replay(const stree_dims *dims, const stree_replay *prev, const int32_t *parent,
                           const void *x, const float *dt, const float *A, const void *Bm, const void *Cm,
-                          const float *D, const float *h0, float *h_out, void *y, int32_t *tree_status,
+                          const float *D, const void *h0, void *h_out, void *y, int32_t *tree_status,
                           int32_t *replay_status, void *hip_stream) {
     int rc = check_dims(dims, kNoConv);
     if (rc) return rc;
@@ -189,7 +190,7 @@ int stree_tree_conv_replay(const stree_dims *dims, const stree_replay *prev, con
 int stree_tree_step(const stree_dims *dims, const stree_replay *prev, const void *prev_xbc_pre,
                     const int32_t *parent, const void *xbc_pre, const void *conv_state, const void *conv_w,
                     const void *conv_b, void *xbc_out, void *conv_state_out, const float *dt, const float *A,
-                    const float *D, const float *h0, float *h_out, void *y, int32_t *tree_status,
+                    const float *D, const void *h0, void *h_out, void *y, int32_t *tree_status,
                     int32_t *replay_status, void *hip_stream) {
     int rc = check_dims(dims, kConvChannels);
     if (rc) return rc;
@@ -243,7 +244,7 @@ int stree_gate_norm(const stree_dims *dims, const void *y, const void *z, int64_
 }
 
 int stree_linear_ssd(const stree_dims *dims, const void *x, const float *dt, const float *A, const void *Bm,
-                     const void *Cm, const float *D, const float *h0, void *y, float *h_out, void *hip_stream) {
+                     const void *Cm, const float *D, const void *h0, void *y, void *h_out, void *hip_stream) {
     if (!dims) return STREE_ERR_NULL_ARG;
     stree_dims d = *dims;
     const int T = d.nnodes;

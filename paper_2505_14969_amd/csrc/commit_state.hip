@@ -85,12 +85,12 @@ struct ConvTailArgs {      // conv part folded into the state kernel's grid (cbl
 // two pieces the kernel needs under 102 registers, i.e. five workgroups per CU: at 80 heads x
 // batch 16 every workgroup of the launch is resident at once.  (Forcing that budget on the compiler
 // where it does not come by itself is worse than four per CU: the spills wait on the state loads.)
-template <typename T, bool WAVE, int NS, bool SPL>
+template <typename T, typename HT, bool WAVE, int NS, bool SPL>
 __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     const int32_t *__restrict__ parent, const int32_t *__restrict__ accepted, int n, int H, int P, int S,
     int G, const T *__restrict__ x, long x_sn, const float *__restrict__ dt, const float *__restrict__ dt_bias,
-    const float *__restrict__ A, const T *__restrict__ Bm, long b_sn, const float *h0, float *h_out, int32_t *__restrict__ status,
-    int slabs, ConvTailArgs ct) {
+    const float *__restrict__ A, const T *__restrict__ Bm, long b_sn, const HT *h0, HT *h_out,
+    int32_t *__restrict__ status, int slabs, ConvTailArgs ct) {
     constexpr bool FAST = NS > 0;
     constexpr int kStageMax = NS ? NS : 1;
     if ((int)blockIdx.z >= ct.state_z) {               // the conv-tail slices at the end of the grid
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     const bool owner = FAST || tid < RP * S4;          // S/4 need not divide the thread count
     const size_t sbase = ((size_t)b * H + h) * P * S + (size_t)s4 * 4;
     const size_t ubase = ((size_t)b * H + h) * P * S;              // FAST: the head's state, uniform
-    const uint32_t loff = (uint32_t)(p0 * S + s4 * 4) * 4u;       //       and this thread's place in it, bytes
+    const uint32_t loff = (uint32_t)(p0 * S + s4 * 4) * (uint32_t)sizeof(HT);   // and this thread's place in it, bytes
     // n <= 64: every wave asks for the parents and step sizes (wave 0 uses them), ahead of the state
     int par_j = -1;
     float dt_j = 0.f;
@@ -126,22 +126,19 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     // as for the store of the result below)
     float4 acc[kQ];
     if constexpr (FAST) {
-        const float *src = h0 ? h0 : h_out;           // no initial state: any readable rows, zeroed below
+        const HT *src = h0 ? h0 : h_out;              // no initial state: any readable rows, zeroed below
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
             // (uniform row pointer + one 32-bit lane offset: one address register for all kQ rows)
-            const uint4 v = load_stream16(reinterpret_cast<const char *>(src + ubase + (size_t)q * S) + loff);
-            acc[q] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+            acc[q] = load_state4(reinterpret_cast<const HT *>(
+                reinterpret_cast<const char *>(src + ubase + (size_t)q * S) + loff));
         }
     } else {
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
             const int p = p0 + q;
             acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (h0 && owner && p < P) {
-                const uint4 v = load_stream16(h0 + sbase + (size_t)p * S);
-                acc[q] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
-            }
+            if (h0 && owner && p < P) acc[q] = load_state4(h0 + sbase + (size_t)p * S);
         }
     }
 
@@ -305,17 +302,12 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
     if constexpr (FAST) {
 #pragma unroll
         for (int q = 0; q < kQ; ++q)
-            store_stream16(reinterpret_cast<char *>(h_out + ubase + (size_t)q * S) + loff,
-                           make_uint4(__float_as_uint(acc[q].x), __float_as_uint(acc[q].y),
-                                      __float_as_uint(acc[q].z), __float_as_uint(acc[q].w)));
+            store_state4(reinterpret_cast<HT *>(reinterpret_cast<char *>(h_out + ubase + (size_t)q * S) + loff), acc[q]);
     } else if (owner) {
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
             const int p = p0 + q;
-            if (p < P)
-                store_stream16(h_out + sbase + (size_t)p * S,
-                               make_uint4(__float_as_uint(acc[q].x), __float_as_uint(acc[q].y),
-                                          __float_as_uint(acc[q].z), __float_as_uint(acc[q].w)));
+            if (p < P) store_state4(h_out + sbase + (size_t)p * S, acc[q]);
         }
     }
 }
@@ -323,8 +315,8 @@ __global__ __launch_bounds__(kThreads) void commit_h_kernel(
 // Shapes of the unpredicated kernel: the threads tile the state exactly (S/4 divides the workgroup,
 // its kQ-row slabs divide P), x and B rows are whole 16-byte pieces at 16-byte addresses, and a
 // chunk of path rows is at most four pieces per thread.  Returns that number of pieces (2 or 4), or 0.
-static int commit_fast_shape(const stree_dims &d, const void *x, const void *Bm, const float *h0,
-                              const float *h_out) {
+static int commit_fast_shape(const stree_dims &d, const void *x, const void *Bm, const void *h0,
+                              const void *h_out) {
     const int S4 = d.dstate / 4;
     if (d.dstate % 4 != 0 || S4 > kThreads || kThreads % S4 != 0) return 0;
     const int rows_wg = kQ * (kThreads / S4);
@@ -339,7 +331,7 @@ static int commit_fast_shape(const stree_dims &d, const void *x, const void *Bm,
 
 hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const int32_t *accepted,
                                const void *x, const float *dt, const float *A, const void *Bm,
-                               const float *h0, float *h_out, const void *xbc_pre, const void *conv_state,
+                               const void *h0, void *h_out, const void *xbc_pre, const void *conv_state,
                                void *conv_state_out, int32_t *status, hipStream_t st) {
     const int rows_wg = kQ * (kThreads / (d.dstate / 4));   // state rows per workgroup
     const int slabs = h_out ? (d.headdim + rows_wg - 1) / rows_wg : 0;
@@ -356,30 +348,36 @@ hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const
     const dim3 grid(gx, gy, state_z + tail_z);
     const size_t lds = (size_t)kPathChunk * (d.headdim + d.dstate) * sizeof(float);
     // (the in-kernel softplus is a variant of its own: compiled into the common one, even unused, it costs time)
-#define STREE_COMMIT_LAUNCH_SP(TT, WV, NS, SPL)                                                                  \
-    hipLaunchKernelGGL((commit_h_kernel<TT, WV, NS, SPL>), grid, dim3(kThreads), lds, st, parent, accepted,      \
+#define STREE_COMMIT_LAUNCH_SP(TT, HT, WV, NS, SPL)                                                              \
+    hipLaunchKernelGGL((commit_h_kernel<TT, HT, WV, NS, SPL>), grid, dim3(kThreads), lds, st, parent, accepted,  \
                        d.nnodes, d.nheads, d.headdim, d.dstate, d.ngroups, (const TT *)x, (long)d.x_stride_n,    \
-                       dt, step_bias(d), A, (const TT *)Bm, (long)d.b_stride_n, h0, h_out, status, slabs, ct)
-#define STREE_COMMIT_LAUNCH(TT, WV, NS)                         \
-    do {                                                        \
-        if (step_bias(d)) STREE_COMMIT_LAUNCH_SP(TT, WV, NS, true); \
-        else STREE_COMMIT_LAUNCH_SP(TT, WV, NS, false);         \
+                       dt, step_bias(d), A, (const TT *)Bm, (long)d.b_stride_n, (const HT *)h0, (HT *)h_out,     \
+                       status, slabs, ct)
+#define STREE_COMMIT_LAUNCH(TT, HT, WV, NS)                             \
+    do {                                                                \
+        if (step_bias(d)) STREE_COMMIT_LAUNCH_SP(TT, HT, WV, NS, true); \
+        else STREE_COMMIT_LAUNCH_SP(TT, HT, WV, NS, false);             \
     } while (0)
     const bool wave = d.nnodes <= 64;
     const int ns = slabs > 0 ? commit_fast_shape(d, x, Bm, h0, h_out) : 0;
-#define STREE_COMMIT_NS(TT, WV)                                 \
-    do {                                                        \
-        if (ns == 2) STREE_COMMIT_LAUNCH(TT, WV, 2);            \
-        else if (ns == 4) STREE_COMMIT_LAUNCH(TT, WV, 4);       \
-        else STREE_COMMIT_LAUNCH(TT, WV, 0);                    \
+#define STREE_COMMIT_NS(TT, HT, WV)                                 \
+    do {                                                            \
+        if (ns == 2) STREE_COMMIT_LAUNCH(TT, HT, WV, 2);            \
+        else if (ns == 4) STREE_COMMIT_LAUNCH(TT, HT, WV, 4);       \
+        else STREE_COMMIT_LAUNCH(TT, HT, WV, 0);                    \
+    } while (0)
+#define STREE_COMMIT_WV(TT, HT)                 \
+    do {                                        \
+        if (wave) STREE_COMMIT_NS(TT, HT, true); \
+        else STREE_COMMIT_NS(TT, HT, false);    \
     } while (0)
     if (d.io_dtype == STREE_BF16) {
-        if (wave) STREE_COMMIT_NS(bf16_t, true);
-        else STREE_COMMIT_NS(bf16_t, false);
+        if (d.state_dtype == STREE_BF16) STREE_COMMIT_WV(bf16_t, bf16_t);   // (a bf16 state goes with bf16 io only)
+        else STREE_COMMIT_WV(bf16_t, float);
     } else {
-        if (wave) STREE_COMMIT_NS(float, true);
-        else STREE_COMMIT_NS(float, false);
+        STREE_COMMIT_WV(float, float);
     }
+#undef STREE_COMMIT_WV
 #undef STREE_COMMIT_NS
 #undef STREE_COMMIT_LAUNCH
 #undef STREE_COMMIT_LAUNCH_SP

@@ -161,6 +161,39 @@ __device__ __forceinline__ void store_stream16(void *p, uint4 v) {
     __builtin_nontemporal_store(vv, reinterpret_cast<u32x4 *>(p));
 }
 
+// Four consecutive values of the recurrent state, which is kept in fp32 (16 bytes) or in bf16 (8 bytes):
+// read once and written once per call, both with the streaming hint.  A bf16 state is widened exactly
+// on the way in and rounded to nearest even on the way out.
+__device__ __forceinline__ uint2 load_stream8(const void *p) {
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
+    return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ void store_stream8(void *p, uint2 v) {
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 vv = {v.x, v.y};
+    __builtin_nontemporal_store(vv, reinterpret_cast<u32x2 *>(p));
+}
+__device__ __forceinline__ uint2 pack_bf16x4(float a, float b, float c, float d) {
+    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+    bf16x4_t o;
+    o[0] = (__bf16)a; o[1] = (__bf16)b; o[2] = (__bf16)c; o[3] = (__bf16)d;
+    return __builtin_bit_cast(uint2, o);
+}
+__device__ __forceinline__ float4 load_state4(const float *p) {
+    const uint4 v = load_stream16(p);
+    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+__device__ __forceinline__ float4 load_state4(const __bf16 *p) {
+    const uint2 v = load_stream8(p);
+    return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+                       __uint_as_float(v.y & 0xffff0000u));
+}
+__device__ __forceinline__ void store_state4(float *p, float4 v) {
+    store_stream16(p, make_uint4(__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)));
+}
+__device__ __forceinline__ void store_state4(__bf16 *p, float4 v) { store_stream8(p, pack_bf16x4(v.x, v.y, v.z, v.w)); }
+
 // Output stores that write through L2 (system scope) with the streaming hint: y and the replayed
 // state are never read again by this kernel, and lines left dirty in the eight L2s would all be
 // written back at once when the kernel ends.  (Measured on the 64-node / 80-head / batch-16 shape:
@@ -173,6 +206,13 @@ __device__ __forceinline__ void store_through16(void *p, uint4 v) {
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
     const u32x4 vv = {v.x, v.y, v.z, v.w};
     asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(vv) : "memory");
+}
+
+// The 8-byte form (a state kept in bf16).  A store of at most 8 bytes needs no wait states behind it.
+__device__ __forceinline__ void store_through8(void *p, uint2 v) {
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 vv = {v.x, v.y};
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1 nt" ::"v"(p), "v"(vv) : "memory");
 }
 
 // The same store as a raw buffer store, the cache bits riding on an instruction the compiler knows.

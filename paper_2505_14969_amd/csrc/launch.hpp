@@ -28,42 +28,42 @@ hipError_t launch_tree_conv_replay(const stree_dims &d, int prev_nnodes, const i
 
 hipError_t launch_tree_ssd_fma(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                const float *A, const void *Bm, const void *Cm, const float *D,
-                               const float *h0, void *y, int32_t *status, hipStream_t st);
+                               const void *h0, void *y, int32_t *status, hipStream_t st);
 
 // true when the MFMA kernel covers these dims / alignments
 bool tree_ssd_mfma_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm,
-                             const float *h0, const void *y);
+                             const void *h0, const void *y);
 hipError_t launch_tree_ssd_mfma(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                 const float *A, const void *Bm, const void *Cm, const float *D,
-                                const float *h0, void *y, int32_t *status, hipStream_t st);
+                                const void *h0, void *y, int32_t *status, hipStream_t st);
 
 // single node block (n <= 64), persistent and software-pipelined
 bool tree_ssd_mfma64_supported(const stree_dims &d);
 hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                   const float *A, const void *Bm, const void *Cm, const float *D,
-                                  const float *h0, void *y, int32_t *status, hipStream_t st);
+                                  const void *h0, void *y, int32_t *status, hipStream_t st);
 
 // 65 .. 256 nodes: the persistent kernel over (row block, column block) pairs
 bool tree_ssd_blocks_supported(const stree_dims &d);
 hipError_t launch_tree_ssd_blocks(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
-                                  const float *A, const void *Bm, const void *Cm, const float *D, const float *h0,
+                                  const float *A, const void *Bm, const void *Cm, const float *D, const void *h0,
                                   void *y, int32_t *status, hipStream_t st);
 
 // fused replay + scan: `dp` describes the previous tree (its node count and strides)
 bool tree_ssd_replay_fused_supported(const stree_dims &d, const stree_dims &dp, const void *px, const void *pB,
-                                     const void *x, const void *Bm, const void *Cm, const void *y, const float *h0,
-                                     const float *h_out);
+                                     const void *x, const void *Bm, const void *Cm, const void *y, const void *h0,
+                                     const void *h_out);
 hipError_t launch_tree_ssd_replay_fused(const stree_dims &d, const stree_dims &dp, const int32_t *pparent,
                                         const int32_t *paccepted, const void *px, const float *pdt, const void *pB,
                                         const int32_t *parent, const void *x, const float *dt, const float *A,
-                                        const void *Bm, const void *Cm, const float *D, const float *h0,
-                                        float *h_out, void *y, int32_t *status, int32_t *rstatus, hipStream_t st);
+                                        const void *Bm, const void *Cm, const float *D, const void *h0,
+                                        void *h_out, void *y, int32_t *status, int32_t *rstatus, hipStream_t st);
 
 // chunked causal scan of a long sequence (d.nnodes = T tokens)
 bool linear_ssd_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm, const void *y,
-                          const float *h0, const float *h_out);
+                          const void *h0, const void *h_out);
 hipError_t launch_linear_ssd(const stree_dims &d, const void *x, const float *dt, const float *A, const void *Bm,
-                             const void *Cm, const float *D, const float *h0, void *y, float *h_out, hipStream_t st);
+                             const void *Cm, const float *D, const void *h0, void *y, void *h_out, hipStream_t st);
 
 // output gate + grouped RMS norm behind the scan; z_sn = token stride of z in elements
 hipError_t launch_gate_norm(const stree_dims &d, const void *y, const void *z, long z_sn, const void *w, float eps,
@@ -72,7 +72,7 @@ hipError_t launch_gate_norm(const stree_dims &d, const void *y, const void *z, l
 // h_out == NULL: conv tail only
 hipError_t launch_commit_state(const stree_dims &d, const int32_t *parent, const int32_t *accepted,
                                const void *x, const float *dt, const float *A, const void *Bm,
-                               const float *h0, float *h_out, const void *xbc_pre, const void *conv_state,
+                               const void *h0, void *h_out, const void *xbc_pre, const void *conv_state,
                                void *conv_state_out, int32_t *status, hipStream_t st);
 
 }  // namespace stree

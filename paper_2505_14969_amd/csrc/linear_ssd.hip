@@ -31,12 +31,12 @@ constexpr int kChunk = 64;
 constexpr int kCP = kChunk + 8;    // padded row of a [.. x 64] bf16 LDS tile
 
 // WY = false: state only (no y, no C): a third of the LDS, so more workgroups per CU
-template <int P, int S, bool WY>
+template <int P, int S, bool WY, typename HT>
 __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
     int T, int H, int G, const bf16_t *__restrict__ x, long x_sn, const float *__restrict__ dt,
     const float *__restrict__ dt_bias, const float *__restrict__ A, const bf16_t *__restrict__ Bm, long b_sn, const bf16_t *__restrict__ Cm,
-    long c_sn, const float *__restrict__ D, const float *__restrict__ h0, bf16_t *__restrict__ y,
-    float *__restrict__ h_out) {
+    long c_sn, const float *__restrict__ D, const HT *__restrict__ h0, bf16_t *__restrict__ y,
+    HT *__restrict__ h_out) {
     constexpr int SP = S + 8;
     constexpr int YT = (P / 32) * 2, YQ = YT / 4;            // Yt tiles [p][i], per wave
     // state tiles h^T[s][p]: a wave owns one p tile and TQ consecutive s tiles, so that the weighted
@@ -73,7 +73,15 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (h0) v = *reinterpret_cast<const float4 *>(h0 + ((size_t)b * H + h) * P * S + (size_t)(pt * 32 + l32) * S + st * 32 + 8 * rg + 4 * lh);
+            if (h0) {
+                const HT *src = h0 + ((size_t)b * H + h) * P * S + (size_t)(pt * 32 + l32) * S + st * 32 + 8 * rg + 4 * lh;
+                if constexpr (sizeof(HT) == 4) {
+                    v = *reinterpret_cast<const float4 *>(src);
+                } else {                                  // a bf16 state: widened exactly
+                    const uint2 w = *reinterpret_cast<const uint2 *>(src);
+                    v = make_float4(bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y));
+                }
+            }
             hacc[q][4 * rg] = v.x; hacc[q][4 * rg + 1] = v.y; hacc[q][4 * rg + 2] = v.z; hacc[q][4 * rg + 3] = v.w;
         }
     }
@@ -317,30 +325,45 @@ __global__ __launch_bounds__(kThreads) void linear_ssd_kernel(
     for (int q = 0; q < TQ; ++q) {
         const int st = (wave % WPP) * TQ + q, pt = wave / WPP;
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg)
-            *reinterpret_cast<float4 *>(h_out + ((size_t)b * H + h) * P * S + (size_t)(pt * 32 + l32) * S + st * 32 + 8 * rg + 4 * lh) =
-                make_float4(hacc[q][4 * rg], hacc[q][4 * rg + 1], hacc[q][4 * rg + 2], hacc[q][4 * rg + 3]);
+        for (int rg = 0; rg < 4; ++rg) {
+            HT *dst = h_out + ((size_t)b * H + h) * P * S + (size_t)(pt * 32 + l32) * S + st * 32 + 8 * rg + 4 * lh;
+            if constexpr (sizeof(HT) == 4)
+                *reinterpret_cast<float4 *>(dst) =
+                    make_float4(hacc[q][4 * rg], hacc[q][4 * rg + 1], hacc[q][4 * rg + 2], hacc[q][4 * rg + 3]);
+            else                                          // a bf16 state: rounded to nearest even once, here
+                *reinterpret_cast<uint2 *>(dst) =
+                    pack_bf16x4(hacc[q][4 * rg], hacc[q][4 * rg + 1], hacc[q][4 * rg + 2], hacc[q][4 * rg + 3]);
+        }
     }
 }
 
-template <int P, int S>
+template <int P, int S, typename HT>
 hipError_t launch_ps(const stree_dims &d, const void *x, const float *dt, const float *A, const void *Bm,
-                     const void *Cm, const float *D, const float *h0, void *y, float *h_out, hipStream_t st) {
+                     const void *Cm, const float *D, const void *h0, void *y, void *h_out, hipStream_t st) {
     if (y)
-        hipLaunchKernelGGL((linear_ssd_kernel<P, S, true>), dim3(d.nheads, d.batch), dim3(kThreads), 0, st, d.nnodes,
+        hipLaunchKernelGGL((linear_ssd_kernel<P, S, true, HT>), dim3(d.nheads, d.batch), dim3(kThreads), 0, st, d.nnodes,
                            d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d), A,
-                           (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0, (bf16_t *)y, h_out);
+                           (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D,
+                           (const HT *)h0, (bf16_t *)y, (HT *)h_out);
     else
-        hipLaunchKernelGGL((linear_ssd_kernel<P, S, false>), dim3(d.nheads, d.batch), dim3(kThreads), 0, st, d.nnodes,
+        hipLaunchKernelGGL((linear_ssd_kernel<P, S, false, HT>), dim3(d.nheads, d.batch), dim3(kThreads), 0, st, d.nnodes,
                            d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d), A,
-                           (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0, (bf16_t *)y, h_out);
+                           (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D,
+                           (const HT *)h0, (bf16_t *)y, (HT *)h_out);
     return hipGetLastError();
+}
+
+template <int P, int S>
+hipError_t launch_p(const stree_dims &d, const void *x, const float *dt, const float *A, const void *Bm,
+                    const void *Cm, const float *D, const void *h0, void *y, void *h_out, hipStream_t st) {
+    if (d.state_dtype == STREE_BF16) return launch_ps<P, S, bf16_t>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
+    return launch_ps<P, S, float>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
 }
 
 }  // namespace
 
 bool linear_ssd_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm, const void *y,
-                          const float *h0, const float *h_out) {
+                          const void *h0, const void *h_out) {
     if (d.io_dtype != STREE_BF16) return false;
     const int P = d.headdim, S = d.dstate;
     if (!((P == 64 && (S == 128 || S == 64)) || (P == 128 && S == 128))) return false;
@@ -350,11 +373,11 @@ bool linear_ssd_supported(const stree_dims &d, const void *x, const void *Bm, co
 }
 
 hipError_t launch_linear_ssd(const stree_dims &d, const void *x, const float *dt, const float *A, const void *Bm,
-                             const void *Cm, const float *D, const float *h0, void *y, float *h_out, hipStream_t st) {
+                             const void *Cm, const float *D, const void *h0, void *y, void *h_out, hipStream_t st) {
     const int P = d.headdim, S = d.dstate;
-    if (P == 64 && S == 128) return launch_ps<64, 128>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
-    if (P == 64 && S == 64) return launch_ps<64, 64>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
-    if (P == 128 && S == 128) return launch_ps<128, 128>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
+    if (P == 64 && S == 128) return launch_p<64, 128>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
+    if (P == 64 && S == 64) return launch_p<64, 64>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
+    if (P == 128 && S == 128) return launch_p<128, 128>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
     return hipErrorInvalidValue;
 }
 

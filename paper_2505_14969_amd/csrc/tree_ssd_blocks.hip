@@ -57,12 +57,13 @@ struct PassId {                    // unit k of the workgroup's run = (b, h); pa
 
 // NB = node blocks the LDS tree arrays are sized for (2: trees of at most 128 nodes, 4: 256).
 // WPE = waves per SIMD the register budget is sized for: 4 when two workgroups fit a CU's LDS.
-template <int P, int S, int NB, int WPE>
+// HT = type the state is kept in (fp32, or bf16: then h0 is the MFMA operand as it comes).
+template <int P, int S, int NB, int WPE, typename HT>
 __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void tree_ssd_blocks_kernel(
     const int32_t *__restrict__ parent, int n, int nbatch, int H, int G, const bf16_t *__restrict__ x, long x_sn,
     const float *__restrict__ dt, const float *__restrict__ dt_bias, const float *__restrict__ A,
     const bf16_t *__restrict__ Bm, long b_sn,
-    const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
+    const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const HT *__restrict__ h0,
     bf16_t *__restrict__ y, int32_t *__restrict__ status) {
     constexpr int SP = S + 8;
     constexpr int kHalf = kTk / 2;                  // threads per role group
@@ -148,9 +149,15 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
     auto load_H = [&](int b, int h) {
         if (D) rD = D[h + (opaque(lane) & 0)];   // (a vector load: it queues with the state chunks)
         const char *hb = reinterpret_cast<const char *>(h0 + ((size_t)b * H + h) * P * S);
-        const uint32_t off = (uint32_t)opaque(rt) * 16u;
+        if constexpr (sizeof(HT) == 4) {
+            const uint32_t off = (uint32_t)opaque(rt) * 16u;
 #pragma unroll
-        for (int q = 0; q < NH; ++q) pre[q] = load_stream16(hb + q * (kHalf * 16) + off);
+            for (int q = 0; q < NH; ++q) pre[q] = load_stream16(hb + q * (kHalf * 16) + off);
+        } else {                                   // a bf16 state: eight values per 16-byte chunk, half as many chunks
+            const uint32_t off = (uint32_t)opaque(rt) * 16u;
+#pragma unroll
+            for (int q = 0; q < NH / 2; ++q) pre[q] = load_stream16(hb + q * (kHalf * 16) + off);
+        }
     };
     auto load_rows = [&](int r0, const bf16_t *base, long sn, int b, int g, int blk) {
         const char *rb = reinterpret_cast<const char *>(base + (size_t)b * n * sn + (size_t)g * S);
@@ -200,12 +207,17 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
     auto stage_H = [&]() {
         const uint32_t t = (uint32_t)opaque(rt);
 #pragma unroll
-        for (int q = 0; q < NH; ++q) {
-            const uint32_t e = (t + q * kHalf) * 4u, p = e / S, sidx = e % S;
-            bf16x4 o;
-            o[0] = (bf16_t)__uint_as_float(pre[q].x); o[1] = (bf16_t)__uint_as_float(pre[q].y);
-            o[2] = (bf16_t)__uint_as_float(pre[q].z); o[3] = (bf16_t)__uint_as_float(pre[q].w);
-            *reinterpret_cast<bf16x4 *>(&sH[p * SP + sidx]) = o;
+        for (int q = 0; q < (sizeof(HT) == 4 ? NH : NH / 2); ++q) {
+            if constexpr (sizeof(HT) == 4) {
+                const uint32_t e = (t + q * kHalf) * 4u, p = e / S, sidx = e % S;
+                bf16x4 o;
+                o[0] = (bf16_t)__uint_as_float(pre[q].x); o[1] = (bf16_t)__uint_as_float(pre[q].y);
+                o[2] = (bf16_t)__uint_as_float(pre[q].z); o[3] = (bf16_t)__uint_as_float(pre[q].w);
+                *reinterpret_cast<bf16x4 *>(&sH[p * SP + sidx]) = o;
+            } else {                               // already the MFMA operand: copied as it came
+                const uint32_t e = (t + q * kHalf) * 8u, p = e / S, sidx = e % S;
+                *reinterpret_cast<uint4 *>(&sH[p * SP + sidx]) = pre[q];
+            }
         }
         if (rt == 0) *sDh = rD;      // D of that unit, for the Y waves
     };
@@ -581,7 +593,7 @@ __global__ __launch_bounds__(kTk) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 
 template <int P, int S, int NB>
 hipError_t launch_blocks_ps(const stree_dims &d, const int32_t *parent, const void *x, const float *dt, const float *A,
-                            const void *Bm, const void *Cm, const float *D, const float *h0, void *y,
+                            const void *Bm, const void *Cm, const float *D, const void *h0, void *y,
                             int32_t *status, hipStream_t st) {
     constexpr size_t lds = LdsBlocks<P, S, NB>::total;        // static LDS (upper bound)
     constexpr int WPE = (2 * (lds + 64) <= 160 * 1024) ? 4 : 2;
@@ -589,9 +601,14 @@ hipError_t launch_blocks_ps(const stree_dims &d, const int32_t *parent, const vo
     int grid = (n_units + 7) / 8 * 8;
     const int cap = 256 * (WPE == 4 ? 2 : 1);
     if (grid > cap) grid = cap;
-    hipLaunchKernelGGL((tree_ssd_blocks_kernel<P, S, NB, WPE>), dim3(grid), dim3(kTk), 0, st, parent, d.nnodes, d.batch,
-                       d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d), A,
-                       (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0, (bf16_t *)y, status);
+#define STREE_LAUNCH_BLOCKS(HT)                                                                                       \
+    hipLaunchKernelGGL((tree_ssd_blocks_kernel<P, S, NB, WPE, HT>), dim3(grid), dim3(kTk), 0, st, parent, d.nnodes,   \
+                       d.batch, d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d), A,      \
+                       (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D,             \
+                       (const HT *)h0, (bf16_t *)y, status)
+    if (d.state_dtype == STREE_BF16) STREE_LAUNCH_BLOCKS(bf16_t);
+    else STREE_LAUNCH_BLOCKS(float);
+#undef STREE_LAUNCH_BLOCKS
     return hipGetLastError();
 }
 
@@ -604,7 +621,7 @@ bool tree_ssd_blocks_supported(const stree_dims &d) {
 }
 
 hipError_t launch_tree_ssd_blocks(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
-                                  const float *A, const void *Bm, const void *Cm, const float *D, const float *h0,
+                                  const float *A, const void *Bm, const void *Cm, const float *D, const void *h0,
                                   void *y, int32_t *status, hipStream_t st) {
     const bool small = d.nnodes <= 2 * kBk;
     if (d.dstate == 128)

@@ -23,13 +23,13 @@ __host__ __device__ constexpr size_t fma_lds_floats(int P, int S) {
     return rows + (rows > piece ? rows : piece) + (size_t)kFmaRows * P;
 }
 
-template <typename T>
+template <typename T, typename HT>
 __global__ __launch_bounds__(kThreads) void tree_ssd_fma_kernel(
     const int32_t *__restrict__ parent, int n, int H, int P, int S, int G, const T *__restrict__ x,
     long x_sn, const float *__restrict__ dt, const float *__restrict__ dt_bias, const float *__restrict__ A,
     const T *__restrict__ Bm,
     long b_sn, const T *__restrict__ Cm, long c_sn, const float *__restrict__ D,
-    const float *__restrict__ h0, T *__restrict__ y, int32_t *__restrict__ status) {
+    const HT *__restrict__ h0, T *__restrict__ y, int32_t *__restrict__ status) {
     extern __shared__ __align__(16) float dyn[];
     __shared__ TreeLds tree;
     __shared__ uint32_t mask[kMaxNodes * kMaxWords];
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_fma_kernel(
     const T *xb = x + (size_t)b * n * x_sn + (size_t)h * P;
     const T *Bb = Bm + (size_t)b * n * b_sn + (size_t)g * S;
     const T *Cb = Cm + (size_t)b * n * c_sn + (size_t)g * S;
-    const float *hb = h0 ? h0 + ((size_t)b * H + h) * P * S : nullptr;
+    const HT *hb = h0 ? h0 + ((size_t)b * H + h) * P * S : nullptr;
     const float D_h = D ? D[h] : 0.f;
     const int SP1 = S + 1, HP1 = kFmaSC + 1;
     float *sCt = dyn, *sBH = dyn + kFmaRows * SP1;
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_fma_kernel(
                 __syncthreads();                          // the B rows / the last piece consumed
                 for (int idx = tid; idx < P * kFmaSC; idx += kThreads) {
                     const int p = idx / kFmaSC, sidx = idx - p * kFmaSC;
-                    if (sidx < sc) sBH[p * HP1 + sidx] = hb[(size_t)p * S + sc0 + sidx];
+                    if (sidx < sc) sBH[p * HP1 + sidx] = to_f32(hb[(size_t)p * S + sc0 + sidx]);
                 }
                 __syncthreads();
                 for (int idx = tid; idx < rows * P; idx += kThreads) {
@@ -125,30 +125,34 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_fma_kernel(
     }
 }
 
-template <typename T>
+template <typename T, typename HT>
 static hipError_t launch_fma_t(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
-                               const float *A, const void *Bm, const void *Cm, const float *D, const float *h0,
+                               const float *A, const void *Bm, const void *Cm, const float *D, const void *h0,
                                void *y, int32_t *status, hipStream_t st) {
     const size_t lds = fma_lds_floats(d.headdim, d.dstate) * sizeof(float);
     if (lds > 48 * 1024) {   // beyond the default cap on dynamic LDS: raise it once, to what headdim = dstate = 256 need
         static const hipError_t raised =
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_fma_kernel<T>),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_fma_kernel<T, HT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)(fma_lds_floats(256, 256) * sizeof(float)));
         if (raised != hipSuccess) return raised;
     }
-    hipLaunchKernelGGL(tree_ssd_fma_kernel<T>, dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
+    hipLaunchKernelGGL((tree_ssd_fma_kernel<T, HT>), dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
                        d.nheads, d.headdim, d.dstate, d.ngroups, (const T *)x, (long)d.x_stride_n, dt, step_bias(d),
-                       A, (const T *)Bm, (long)d.b_stride_n, (const T *)Cm, (long)d.c_stride_n, D, h0, (T *)y, status);
+                       A, (const T *)Bm, (long)d.b_stride_n, (const T *)Cm, (long)d.c_stride_n, D,
+                       (const HT *)h0, (T *)y, status);
     return hipGetLastError();
 }
 
 hipError_t launch_tree_ssd_fma(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                const float *A, const void *Bm, const void *Cm, const float *D,
-                               const float *h0, void *y, int32_t *status, hipStream_t st) {
-    if (d.io_dtype == STREE_BF16)
-        return launch_fma_t<bf16_t>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
-    return launch_fma_t<float>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+                               const void *h0, void *y, int32_t *status, hipStream_t st) {
+    if (d.io_dtype == STREE_BF16) {                 // (a bf16 state goes with bf16 io only)
+        if (d.state_dtype == STREE_BF16)
+            return launch_fma_t<bf16_t, bf16_t>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+        return launch_fma_t<bf16_t, float>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+    }
+    return launch_fma_t<float, float>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
 }
 
 }  // namespace stree

@@ -66,12 +66,12 @@ constexpr int kMaxS32 = 8;       // dstate <= 256: at most 8 16-byte pieces of a
 constexpr int kH0Batch = 8;      // float4 pieces of h0 per thread requested ahead of the tree index
 
 // (for headdim <= 64 two workgroups fit the LDS of a CU: the register budget is held to that)
-template <int P, bool SH>
+template <int P, bool SH, typename HT>
 __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kernel(
     const int32_t *__restrict__ parent, int n, int H, int S, int G, const bf16_t *__restrict__ x, long x_sn,
     const float *__restrict__ dt, const float *__restrict__ dt_bias, const float *__restrict__ A,
     const bf16_t *__restrict__ Bm, long b_sn,
-    const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
+    const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const HT *__restrict__ h0,
     bf16_t *__restrict__ y, int32_t *__restrict__ status) {
     constexpr int YT = (P / 32) * 2;          // 32x32 tiles of Yt[p][i] per node block
     constexpr int YQ = (YT + 3) / 4;          // tiles per wave
@@ -99,7 +99,16 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
     const bf16_t *xb = x + (size_t)b * n * x_sn + (size_t)h * P;
     const bf16_t *Bb = Bm + (size_t)b * n * b_sn + (size_t)g * S;
     const bf16_t *Cb = Cm + (size_t)b * n * c_sn + (size_t)g * S;
-    const float *hb = h0 ? h0 + ((size_t)b * H + h) * P * S : nullptr;
+    const HT *hb = h0 ? h0 + ((size_t)b * H + h) * P * S : nullptr;
+    // four consecutive state values, widened exactly when the state is kept in bf16
+    auto load_h4 = [&](int idx) -> float4 {
+        if constexpr (sizeof(HT) == 4) {
+            return *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4);
+        } else {
+            const uint2 w = *reinterpret_cast<const uint2 *>(hb + (size_t)idx * 4);
+            return make_float4(bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y));
+        }
+    };
     const int s8 = S / 8;
     const int cb_items = kBlk * s8;           // 16-byte pieces of a C or B tile
     const int h_items = P * S / 4;            // float4 pieces of h0
@@ -182,7 +191,7 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
 #pragma unroll
         for (int q = 0; q < kH0Batch; ++q) {
             const int idx = min(q * kThreads + tid, h_items - 1);
-            hreg[q] = *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4);
+            hreg[q] = load_h4(idx);
         }
     }
     load_rows(creg, Cb, c_sn, 0);
@@ -253,7 +262,7 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
 #pragma unroll
                     for (int q = 0; q < kH0Batch; ++q) {
                         const int idx = min(q * kThreads + opaque(tid), h_items - 1);
-                        hreg[q] = *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4);
+                        hreg[q] = load_h4(idx);
                     }
                 }
 #pragma unroll
@@ -262,7 +271,7 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
                     if (idx < h_items) store_h(idx, hreg[q], one);
                 }
                 for (int idx = kH0Batch * kThreads + tid; idx < h_items; idx += kThreads)
-                    store_h(idx, *reinterpret_cast<const float4 *>(hb + (size_t)idx * 4), one);
+                    store_h(idx, load_h4(idx), one);
             }
             __syncthreads();
 #pragma unroll
@@ -402,7 +411,7 @@ __global__ __launch_bounds__(kThreads, P <= 64 ? 2 : 1) void tree_ssd_mfma_kerne
 }
 
 bool tree_ssd_mfma_supported(const stree_dims &d, const void *x, const void *Bm, const void *Cm,
-                             const float *h0, const void *y) {
+                             const void *h0, const void *y) {
     if (d.io_dtype != STREE_BF16) return false;
     if (!(d.headdim == 32 || d.headdim == 64 || d.headdim == 128)) return false;
     if (d.dstate % 16 != 0 || d.dstate < 16) return false;
@@ -413,10 +422,10 @@ bool tree_ssd_mfma_supported(const stree_dims &d, const void *x, const void *Bm,
     return mfma_lds_plan(d.headdim, d.dstate, npad, (d.nnodes + 31) / 32).total + sizeof(TreeLds) <= 160 * 1024;
 }
 
-template <int P, bool SH>
-static hipError_t launch_p(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
-                           const float *A, const void *Bm, const void *Cm, const float *D, const float *h0,
-                           void *y, int32_t *status, hipStream_t st) {
+template <int P, bool SH, typename HT>
+static hipError_t launch_pt(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
+                           const float *A, const void *Bm, const void *Cm, const float *D, const void *h0,
+                            void *y, int32_t *status, hipStream_t st) {
     const int npad = (d.nnodes + kBlk - 1) / kBlk * kBlk;
     const size_t lds = mfma_lds_plan(P, d.dstate, npad, (d.nnodes + 31) / 32).total;
     {   // raise the dynamic-LDS limit of this instantiation (64 KB is the default cap).  The limit only
@@ -425,22 +434,30 @@ static hipError_t launch_p(const stree_dims &d, const int32_t *parent, const voi
         static size_t lds_set = 0;
         std::lock_guard<std::mutex> hold(mu);
         if (lds > lds_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_mfma_kernel<P, SH>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_mfma_kernel<P, SH, HT>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             lds_set = lds;
         }
     }
-    hipLaunchKernelGGL((tree_ssd_mfma_kernel<P, SH>), dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
+    hipLaunchKernelGGL((tree_ssd_mfma_kernel<P, SH, HT>), dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
                        d.nheads, d.dstate, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d),
-                       A, (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,
-                       (bf16_t *)y, status);
+                       A, (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D,
+                       (const HT *)h0, (bf16_t *)y, status);
     return hipGetLastError();
+}
+
+template <int P, bool SH>
+static hipError_t launch_p(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
+                           const float *A, const void *Bm, const void *Cm, const float *D, const void *h0,
+                           void *y, int32_t *status, hipStream_t st) {
+    if (d.state_dtype == STREE_BF16) return launch_pt<P, SH, bf16_t>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+    return launch_pt<P, SH, float>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
 }
 
 hipError_t launch_tree_ssd_mfma(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                 const float *A, const void *Bm, const void *Cm, const float *D,
-                                const float *h0, void *y, int32_t *status, hipStream_t st) {
+                                const void *h0, void *y, int32_t *status, hipStream_t st) {
     if (tree_ssd_mfma64_supported(d))
         return launch_tree_ssd_mfma64(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
     if (tree_ssd_blocks_supported(d) && !(d.flags & STREE_FLAG_GENERAL_MFMA))

@@ -63,7 +63,7 @@ struct ReplayArgs {
     const float *dt;                    // [B, pn, H]
     long x_sn, b_sn;
     int pn;
-    float *h_out;                       // [B, H, P, S]: the replayed state
+    void *h_out;                        // [B, H, P, S]: the replayed state, in the type the state is kept in
     int32_t *status;                    // [B] or null
 };
 
@@ -119,12 +119,14 @@ __device__ __forceinline__ int wave_tree_index(int lane, int n, int parent_i, fl
 // where it puts them into LDS; one more barrier per unit (c) separates that from the FMAs of the
 // threads that carry the unit.  Longer paths read the remaining rows from
 // global memory.  Each thread owns one 4-wide piece of the state index and NH consecutive rows.
-template <int P, int S, int WPE, bool RP, bool SPL>
+// HT = type the state is kept in: fp32, or bf16 (then h0 is the MFMA operand as it comes, and the replayed
+// state is rounded once, to the value that is both written back and scanned from).
+template <int P, int S, int WPE, bool RP, bool SPL, typename HT>
 __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void tree_ssd_mfma64_kernel(
     const int32_t *__restrict__ parent, int n, int nbatch, int H, int G, const bf16_t *__restrict__ x, long x_sn,
     const float *__restrict__ dt, const float *__restrict__ dt_bias, const float *__restrict__ A,
     const bf16_t *__restrict__ Bm, long b_sn,
-    const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const float *__restrict__ h0,
+    const bf16_t *__restrict__ Cm, long c_sn, const float *__restrict__ D, const HT *__restrict__ h0,
     bf16_t *__restrict__ y, int32_t *__restrict__ status, ReplayArgs R) {
     using L = Lds64<P, S>;
     constexpr int SP = L::SP;
@@ -136,6 +138,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     constexpr int kRowsC = kHalf / (S / 8), kRowsX = kHalf / (P / 8);
     static_assert(NC >= 1 && NX >= 1 && NH >= 1 && YQ >= 1, "tile too small for this thread count");
     static_assert(!RP || NH % 4 == 0, "replay reads a thread's x values four at a time");
+    static_assert(NH % 2 == 0 && S % 8 == 0, "a bf16 state is moved eight values at a time");
     // separate LDS objects (not slices of one array), so that the compiler knows that a write to
     // one tile cannot alias a read of another and does not serialise them
     __shared__ __align__(16) bf16_t sC[kB64 * SP];
@@ -219,15 +222,29 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
         // queue as the h0 chunks instead of forcing a scalar-cache wait in the hot window
         if (D) rD = D[h + (opaque(lane) & 0)];
         const char *hb = reinterpret_cast<const char *>(h0 + ((size_t)b * H + h) * P * S);
+        constexpr uint32_t HB = sizeof(HT);    // a bf16 state: the same four values per chunk, in 8 bytes
+        auto chunk = [&](int q, const char *src) {
+            if constexpr (HB == 4) {
+                pre[q] = load_stream16(src);
+            } else {
+                const uint2 v = load_stream8(src);
+                pre[q].x = v.x;
+                pre[q].y = v.y;
+            }
+        };
         if constexpr (RP) {
             const int t = opaque(rt);
-            const uint32_t off = (uint32_t)(((t / S4) * NH) * S + (t % S4) * 4) * 4u;
+            const uint32_t off = (uint32_t)(((t / S4) * NH) * S + (t % S4) * 4) * HB;
 #pragma unroll
-            for (int q = 0; q < NH; ++q) pre[q] = load_stream16(hb + off + q * (S * 4));
-        } else {
+            for (int q = 0; q < NH; ++q) chunk(q, hb + off + q * (S * HB));
+        } else if constexpr (HB == 4) {
             const uint32_t off = (uint32_t)opaque(rt) * 16u;
 #pragma unroll
             for (int q = 0; q < NH; ++q) pre[q] = load_stream16(hb + q * (kHalf * 16) + off);
+        } else {                               // no replay, bf16 state: eight values per 16-byte chunk, half as many chunks
+            const uint32_t off = (uint32_t)opaque(rt) * 16u;
+#pragma unroll
+            for (int q = 0; q < NH / 2; ++q) pre[q] = load_stream16(hb + q * (kHalf * 16) + off);
         }
     };
     // C and B tiles of a unit: global -> registers -> LDS in one go (G threads).  Runs only when
@@ -278,8 +295,13 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
             float hv[NH][4];
 #pragma unroll
             for (int q = 0; q < NH; ++q) {
-                hv[q][0] = dec * __uint_as_float(pre[q].x); hv[q][1] = dec * __uint_as_float(pre[q].y);
-                hv[q][2] = dec * __uint_as_float(pre[q].z); hv[q][3] = dec * __uint_as_float(pre[q].w);
+                if constexpr (sizeof(HT) == 4) {
+                    hv[q][0] = dec * __uint_as_float(pre[q].x); hv[q][1] = dec * __uint_as_float(pre[q].y);
+                    hv[q][2] = dec * __uint_as_float(pre[q].z); hv[q][3] = dec * __uint_as_float(pre[q].w);
+                } else {
+                    hv[q][0] = dec * bf16_lo(pre[q].x); hv[q][1] = dec * bf16_hi(pre[q].x);
+                    hv[q][2] = dec * bf16_lo(pre[q].y); hv[q][3] = dec * bf16_hi(pre[q].y);
+                }
             }
             auto rank1 = [&](float cf, uint2 b4, const uint32_t (&xw)[NH / 2]) {
                 const float bv[4] = {cf * bf16_lo(b4.x), cf * bf16_hi(b4.x), cf * bf16_lo(b4.y), cf * bf16_hi(b4.y)};
@@ -320,17 +342,20 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 }
             }
             // the replayed state: written once, through L2 (never read again by this kernel)
-            char *ob = reinterpret_cast<char *>(R.h_out + ((size_t)b * H + h) * P * S);
+            char *ob = reinterpret_cast<char *>(reinterpret_cast<HT *>(R.h_out) + ((size_t)b * H + h) * P * S);
 #pragma unroll
             for (int q = 0; q < NH; ++q) {
-                store_through16(ob + (uint32_t)((prow + q) * S + s4 * 4) * 4u,
-                                make_uint4(__float_as_uint(hv[q][0]), __float_as_uint(hv[q][1]),
-                                           __float_as_uint(hv[q][2]), __float_as_uint(hv[q][3])));
                 bf16x4 o;
                 o[0] = (bf16_t)hv[q][0]; o[1] = (bf16_t)hv[q][1]; o[2] = (bf16_t)hv[q][2]; o[3] = (bf16_t)hv[q][3];
+                if constexpr (sizeof(HT) == 4)
+                    store_through16(ob + (uint32_t)((prow + q) * S + s4 * 4) * 4u,
+                                    make_uint4(__float_as_uint(hv[q][0]), __float_as_uint(hv[q][1]),
+                                               __float_as_uint(hv[q][2]), __float_as_uint(hv[q][3])));
+                else
+                    store_through8(ob + (uint32_t)((prow + q) * S + s4 * 4) * 2u, __builtin_bit_cast(uint2, o));
                 *reinterpret_cast<bf16x4 *>(&sH[(prow + q) * SP + s4 * 4]) = o;
             }
-        } else {
+        } else if constexpr (sizeof(HT) == 4) {
 #pragma unroll
             for (int q = 0; q < NH; ++q) {
                 const int e = (t + q * kHalf) * 4, p = e / S, sidx = e % S;
@@ -338,6 +363,12 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 o[0] = (bf16_t)__uint_as_float(pre[q].x); o[1] = (bf16_t)__uint_as_float(pre[q].y);
                 o[2] = (bf16_t)__uint_as_float(pre[q].z); o[3] = (bf16_t)__uint_as_float(pre[q].w);
                 *reinterpret_cast<bf16x4 *>(&sH[p * SP + sidx]) = o;
+            }
+        } else {                                   // already the MFMA operand: copied as it came
+#pragma unroll
+            for (int q = 0; q < NH / 2; ++q) {
+                const int e = (t + q * kHalf) * 8, p = e / S, sidx = e % S;
+                *reinterpret_cast<uint4 *>(&sH[p * SP + sidx]) = pre[q];
             }
         }
         if (rt == 0) *sDh = rD;      // D of that unit, for the Y waves
@@ -789,7 +820,7 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
 
 template <int P, int S, bool RP>
 hipError_t launch64_ps(const stree_dims &d, const int32_t *parent, const void *x, const float *dt, const float *A,
-                       const void *Bm, const void *Cm, const float *D, const float *h0, void *y,
+                       const void *Bm, const void *Cm, const float *D, const void *h0, void *y,
                        int32_t *status, const ReplayArgs &R, hipStream_t st) {
     constexpr size_t lds = RP ? Lds64<P, S>::total_replay : Lds64<P, S>::total;   // static LDS (upper bound)
     constexpr int WPE = (2 * (lds + 64) <= 160 * 1024) ? 4 : 2;
@@ -799,20 +830,26 @@ hipError_t launch64_ps(const stree_dims &d, const int32_t *parent, const void *x
     const int cap = 256 * (per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu));
     if (grid > cap) grid = cap;
     // (the in-kernel softplus is a variant of its own: compiled into the common one, even unused, it costs time)
-#define STREE_LAUNCH64(SPL)                                                                                          \
-    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE, RP, SPL>), dim3(grid), dim3(kT64), 0, st, parent, d.nnodes, \
-                       d.batch, d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d), A,     \
-                       (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D, h0,        \
-                       (bf16_t *)y, status, R)
-    if (step_bias(d)) STREE_LAUNCH64(true);
-    else STREE_LAUNCH64(false);
+#define STREE_LAUNCH64(SPL, HT)                                                                                     \
+    hipLaunchKernelGGL((tree_ssd_mfma64_kernel<P, S, WPE, RP, SPL, HT>), dim3(grid), dim3(kT64), 0, st, parent,     \
+                       d.nnodes, d.batch, d.nheads, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt,           \
+                       step_bias(d), A, (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm,                 \
+                       (long)d.c_stride_n, D, (const HT *)h0, (bf16_t *)y, status, R)
+    const bool hb = d.state_dtype == STREE_BF16;
+    if (step_bias(d)) {
+        if (hb) STREE_LAUNCH64(true, bf16_t);
+        else STREE_LAUNCH64(true, float);
+    } else {
+        if (hb) STREE_LAUNCH64(false, bf16_t);
+        else STREE_LAUNCH64(false, float);
+    }
 #undef STREE_LAUNCH64
     return hipGetLastError();
 }
 
 template <bool RP>
 hipError_t launch64(const stree_dims &d, const int32_t *parent, const void *x, const float *dt, const float *A,
-                    const void *Bm, const void *Cm, const float *D, const float *h0, void *y, int32_t *status,
+                    const void *Bm, const void *Cm, const float *D, const void *h0, void *y, int32_t *status,
                     const ReplayArgs &R, hipStream_t st) {
     const int P = d.headdim, S = d.dstate;
     if (P == 64 && S == 128) return launch64_ps<64, 128, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
@@ -830,8 +867,8 @@ bool tree_ssd_mfma64_supported(const stree_dims &d) {
 }
 
 bool tree_ssd_replay_fused_supported(const stree_dims &d, const stree_dims &dp, const void *px, const void *pB,
-                                     const void *x, const void *Bm, const void *Cm, const void *y, const float *h0,
-                                     const float *h_out) {
+                                     const void *x, const void *Bm, const void *Cm, const void *y, const void *h0,
+                                     const void *h_out) {
     if (d.io_dtype != STREE_BF16 || !tree_ssd_mfma64_supported(d) || dp.nnodes > kB64) return false;
     if ((d.x_stride_n | d.b_stride_n | d.c_stride_n | dp.x_stride_n | dp.b_stride_n) % 8 != 0) return false;
     const uintptr_t bits = (uintptr_t)x | (uintptr_t)Bm | (uintptr_t)Cm | (uintptr_t)y | (uintptr_t)px | (uintptr_t)pB |
@@ -842,8 +879,8 @@ bool tree_ssd_replay_fused_supported(const stree_dims &d, const stree_dims &dp, 
 hipError_t launch_tree_ssd_replay_fused(const stree_dims &d, const stree_dims &dp, const int32_t *pparent,
                                         const int32_t *paccepted, const void *px, const float *pdt, const void *pB,
                                         const int32_t *parent, const void *x, const float *dt, const float *A,
-                                        const void *Bm, const void *Cm, const float *D, const float *h0,
-                                        float *h_out, void *y, int32_t *status, int32_t *rstatus, hipStream_t st) {
+                                        const void *Bm, const void *Cm, const float *D, const void *h0,
+                                        void *h_out, void *y, int32_t *status, int32_t *rstatus, hipStream_t st) {
     const ReplayArgs R = {pparent, paccepted, (const bf16_t *)px, (const bf16_t *)pB, pdt,
                           (long)dp.x_stride_n, (long)dp.b_stride_n, dp.nnodes, h_out, rstatus};
     return launch64<true>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
@@ -851,7 +888,7 @@ hipError_t launch_tree_ssd_replay_fused(const stree_dims &d, const stree_dims &d
 
 hipError_t launch_tree_ssd_mfma64(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                   const float *A, const void *Bm, const void *Cm, const float *D,
-                                  const float *h0, void *y, int32_t *status, hipStream_t st) {
+                                  const void *h0, void *y, int32_t *status, hipStream_t st) {
     return launch64<false>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, ReplayArgs{}, st);
 }
 

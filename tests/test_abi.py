@@ -101,7 +101,10 @@ def test_tree_ssd_rejects_bad_arguments(lib):
     assert _ssd(lib, binding.make_dims(**{**ok, "batch": -1})) == 2
     assert _ssd(lib, binding.make_dims(**ok, io_dtype=7)) == 3
     d = binding.make_dims(**ok)
-    d.state_dtype = 1
+    d.state_dtype = 7
+    assert _ssd(lib, d) == 3
+    d = binding.make_dims(**ok, io_dtype=binding.F32)      # a bf16 state goes with bf16 io only
+    d.state_dtype = binding.BF16
     assert _ssd(lib, d) == 3
     assert _ssd(lib, binding.make_dims(**ok, x_stride_n=8)) == 4
     assert _ssd(lib, binding.make_dims(**ok, b_stride_n=64)) == 4
