@@ -12,15 +12,15 @@ namespace stree {
 hipError_t launch_tree_index(const stree_dims &, const int32_t *, int32_t *, uint32_t *, int32_t *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
 hipError_t launch_tree_conv(const stree_dims &, const int32_t *, const void *, const void *, const void *, const void *, void *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
 hipError_t launch_tree_conv_replay(const stree_dims &, int, const int32_t *, const int32_t *, const void *, const int32_t *, const void *, const void *, const void *, const void *, void *, void *, int32_t *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
-hipError_t launch_tree_ssd_fma(const stree_dims &, const int32_t *, const void *, const float *, const float *, const void *, const void *, const float *, const float *, void *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
-bool tree_ssd_mfma_supported(const stree_dims &, const void *, const void *, const void *, const float *, const void *) { return true; }
-hipError_t launch_tree_ssd_mfma(const stree_dims &, const int32_t *, const void *, const float *, const float *, const void *, const void *, const float *, const float *, void *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
-bool tree_ssd_replay_fused_supported(const stree_dims &, const stree_dims &, const void *, const void *, const void *, const void *, const void *, const void *, const float *, const float *) { return true; }
-hipError_t launch_tree_ssd_replay_fused(const stree_dims &, const stree_dims &, const int32_t *, const int32_t *, const void *, const float *, const void *, const int32_t *, const void *, const float *, const float *, const void *, const void *, const float *, const float *, float *, void *, int32_t *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
-bool linear_ssd_supported(const stree_dims &d, const void *, const void *, const void *, const void *, const float *, const float *) { return d.headdim == 64; }
-hipError_t launch_linear_ssd(const stree_dims &, const void *, const float *, const float *, const void *, const void *, const float *, const float *, void *, float *, hipStream_t) { ++launches; return hipSuccess; }
+hipError_t launch_tree_ssd_fma(const stree_dims &, const int32_t *, const void *, const float *, const float *, const void *, const void *, const float *, const void *, void *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
+bool tree_ssd_mfma_supported(const stree_dims &, const void *, const void *, const void *, const void *, const void *) { return true; }
+hipError_t launch_tree_ssd_mfma(const stree_dims &, const int32_t *, const void *, const float *, const float *, const void *, const void *, const float *, const void *, void *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
+bool tree_ssd_replay_fused_supported(const stree_dims &, const stree_dims &, const void *, const void *, const void *, const void *, const void *, const void *, const void *, const void *) { return true; }
+hipError_t launch_tree_ssd_replay_fused(const stree_dims &, const stree_dims &, const int32_t *, const int32_t *, const void *, const float *, const void *, const int32_t *, const void *, const float *, const float *, const void *, const void *, const float *, const void *, void *, void *, int32_t *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
+bool linear_ssd_supported(const stree_dims &d, const void *, const void *, const void *, const void *, const void *, const void *) { return d.headdim == 64; }
+hipError_t launch_linear_ssd(const stree_dims &, const void *, const float *, const float *, const void *, const void *, const float *, const void *, void *, void *, hipStream_t) { ++launches; return hipSuccess; }
 hipError_t launch_gate_norm(const stree_dims &, const void *, const void *, long, const void *, float, void *, hipStream_t) { ++launches; return hipSuccess; }
-hipError_t launch_commit_state(const stree_dims &, const int32_t *, const int32_t *, const void *, const float *, const float *, const void *, const float *, float *, const void *, const void *, void *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
+hipError_t launch_commit_state(const stree_dims &, const int32_t *, const int32_t *, const void *, const float *, const float *, const void *, const void *, void *, const void *, const void *, void *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
 }  // namespace stree
 
 static int fails = 0;
@@ -46,6 +46,11 @@ int main() {
     d = ok; d.ngroups = 3; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_SHAPE);
     d = ok; d.io_dtype = 9; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_DTYPE);
     d = ok; d.x_stride_n = 8; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_STRIDE);
+    d = ok; d.state_dtype = 9; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_DTYPE);
+    d = ok; d.io_dtype = STREE_F32; d.state_dtype = STREE_BF16;   // a bf16 state goes with bf16 io only
+    EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_DTYPE);
+    d = ok; d.flags = STREE_FLAG_DT_SOFTPLUS;                     // the softplus needs its bias vector
+    EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_NULL_ARG);
     d = ok; d.batch = 0; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_OK);
     d = ok; d.conv_width = 5; EXPECT(stree_tree_conv(&d, ip, p, p, p, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_SHAPE);
     EXPECT(stree_tree_conv(&ok, ip, p, p, p, nullptr, nullptr, nullptr, nullptr), STREE_ERR_NULL_ARG);
