@@ -351,13 +351,13 @@ def main():
     ms_best = steps[best]
     tr_scan, src_scan = read_traffic("tree_ssd_mfma_cfg2")
     tr_fused, src_fused = read_traffic("tree_ssd_replay_cfg2")
-    roof_scan = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,false,false>", "achieved": achieved,
+    roof_scan = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,false,false,float>", "achieved": achieved,
                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                  "traffic": tr_scan, "traffic_source": src_scan,
                  "algorithmic_bytes": alg_bytes, "avg_launch_us": ms_ssd * 1e3,
                  "cache_warm_us": ms_ssd_warm * 1e3,
                  "mfma_tflops": alg_flops / (ms_ssd * 1e-3) / 1e12}
-    roof_fused = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,true,false>", "achieved": achieved_f,
+    roof_fused = {"bound": "hbm", "kernel": "tree_ssd_mfma64_kernel<64,128,4,true,false,float>", "achieved": achieved_f,
                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_f / HBM_PEAK_GBS,
                   "traffic": tr_fused, "traffic_source": src_fused,
                   "algorithmic_bytes": alg_bytes_f, "avg_launch_us": ms_fused * 1e3}
