@@ -79,7 +79,8 @@ typedef struct stree_dims {
     int32_t state_dtype; /* type of h0 / h_out: STREE_F32, or STREE_BF16 (only with io_dtype = STREE_BF16).
                           * A bf16 state is widened exactly when read, all arithmetic stays fp32, and a new
                           * state is rounded to nearest even once, when written: every iteration adds that
-                          * rounding (at most 2^-8 relative) to the state -- the caller's trade for half the traffic. */
+                          * rounding (at most 2^-8 relative) to the state -- the caller's trade for half the traffic.
+                          * bf16 state arrays start on 16-byte boundaries (STREE_ERR_BAD_SHAPE otherwise). */
     int32_t flags;       /* enum stree_flags */
     /* token strides in ELEMENTS of x, B, C (0 = dense: H*P, G*S, G*S).  They let
      * x | B | C be column ranges of one conv output buffer [B,N,H*P+2*G*S].  The

@@ -41,6 +41,11 @@ int resolve_strides(stree_dims &d) {
     return STREE_OK;
 }
 
+// a state kept in bf16 is moved 8 or 16 bytes at a time by every kernel: its arrays start on 16-byte boundaries
+bool state_aligned(const stree_dims &d, const void *h0, const void *h_out) {
+    return d.state_dtype != STREE_BF16 || (((uintptr_t)h0 | (uintptr_t)h_out) % 16) == 0;
+}
+
 int hip_status(hipError_t e) { return e == hipSuccess ? STREE_OK : STREE_ERR_HIP; }
 
 // true when the byte ranges [a, a + na) and [b, b + nb) share a byte
@@ -108,6 +113,7 @@ int stree_tree_ssd(const stree_dims *dims, const int32_t *parent, const void *x,
     stree_dims d = *dims;
     rc = resolve_strides(d);
     if (rc) return rc;
+    if (!state_aligned(d, h0, nullptr)) return STREE_ERR_BAD_SHAPE;
     if (d.batch == 0) return STREE_OK;
     hipStream_t st = (hipStream_t)hip_stream;
     if (!(d.flags & STREE_FLAG_FORCE_FMA) && stree::tree_ssd_mfma_supported(d, x, Bm, Cm, h0, y))
@@ -131,6 +137,7 @@ int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int3
     stree_dims d = *dims;
     rc = resolve_strides(d);
     if (rc) return rc;
+    if (!state_aligned(d, h0, h_out)) return STREE_ERR_BAD_SHAPE;
     if (d.batch == 0) return STREE_OK;
     return hip_status(stree::launch_commit_state(d, parent, accepted, x, dt, A, Bm, h0, h_out, xbc_pre,
                                                  conv_state, conv_state_out, tree_status,
@@ -149,6 +156,7 @@ int stree_tree_ssd_replay(const stree_dims *dims, const stree_replay *prev, cons
     stree_dims d = *dims;
     rc = resolve_strides(d);
     if (rc) return rc;
+    if (!state_aligned(d, h0, h_out)) return STREE_ERR_BAD_SHAPE;
     // the previous tree as a problem of its own: same heads and dtypes, its own node count and strides
     stree_dims dp = *dims;
     dp.nnodes = prev->nnodes;
@@ -210,6 +218,7 @@ int stree_tree_step(const stree_dims *dims, const stree_replay *prev, const void
     dp.c_stride_n = 0;
     rc = resolve_strides(dp);
     if (rc) return rc;
+    if (!state_aligned(d, h0, h_out)) return STREE_ERR_BAD_SHAPE;      // (before the conv is launched)
     if (d.batch == 0) return STREE_OK;
     {   // the conv overwrites xbc_out before the replay reads the previous step's x / B rows
         const size_t e = d.io_dtype == STREE_BF16 ? 2 : 4;

@@ -31,7 +31,7 @@ static int fails = 0;
     } while (0)
 
 int main() {
-    char buf[64];
+    alignas(16) char buf[64];
     void *p = buf;                       // never dereferenced by the validation
     const int32_t *ip = reinterpret_cast<const int32_t *>(buf);
     const float *fp = reinterpret_cast<const float *>(buf);
@@ -49,6 +49,9 @@ int main() {
     d = ok; d.state_dtype = 9; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_DTYPE);
     d = ok; d.io_dtype = STREE_F32; d.state_dtype = STREE_BF16;   // a bf16 state goes with bf16 io only
     EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_DTYPE);
+    d = ok; d.state_dtype = STREE_BF16;                           // a bf16 state starts on a 16-byte boundary
+    EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, buf + 2, p, nullptr, nullptr), STREE_ERR_BAD_SHAPE);
+    EXPECT(stree_commit_state(&d, ip, ip, p, fp, fp, p, nullptr, buf + 8, nullptr, nullptr, nullptr, nullptr, nullptr), STREE_ERR_BAD_SHAPE);
     d = ok; d.flags = STREE_FLAG_DT_SOFTPLUS;                     // the softplus needs its bias vector
     EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_NULL_ARG);
     d = ok; d.batch = 0; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_OK);

@@ -173,3 +173,22 @@ def test_bf16_state_needs_bf16_io(st):
     with pytest.raises(Exception, match="dtype"):
         st.stree_tree_ssd(parent, to_dev(x), to_dev(dt), to_dev(A), to_dev(Bm), to_dev(Cm), to_dev(D),
                           to_dev(synth.round_to_bf16(h0), "bf16"))
+
+
+def test_bf16_state_must_start_on_a_16_byte_boundary(st):
+    """Every kernel moves a bf16 state 8 or 16 bytes at a time: a view that starts elsewhere is refused on the
+    host, before anything is launched (the output keeps its fill)."""
+    from paper_2505_14969_amd.binding import StreeError
+    B, N, H, P, S, G = 1, 20, 2, 64, 64, 1
+    parent = to_dev(_trees(9900, B, N))
+    x, dt, A, Bm, Cm, D, h0 = _inputs(9901, B, N, H, P, S, G)
+    flat = torch.zeros(B * H * P * S + 1, dtype=torch.bfloat16, device="cuda")
+    flat[1:] = to_dev(h0, "bf16").reshape(-1)
+    h_view = flat[1:].view(B, H, P, S)                       # 2 bytes off
+    out = torch.full((B, N, H, P), 7.0, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(StreeError) as e:
+        st.stree_tree_ssd(parent, to_dev(x, "bf16"), to_dev(dt), to_dev(A), to_dev(Bm, "bf16"), to_dev(Cm, "bf16"),
+                          to_dev(D), h_view, out=out)
+    assert e.value.code == 2
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
