@@ -23,7 +23,9 @@
  *     "st" below) is fp32, or bf16 with state_dtype = STREE_BF16;
  *     `io_dtype` selects fp32 or bf16 for x, B, C, y and the conv tensors.
  *   - Envelope: 1 <= nnodes <= 256, batch >= 0 (0 is a no-op), nheads % ngroups
- *     == 0, 1 <= headdim <= 256, 1 <= dstate <= 256, conv_width in {2,3,4}.
+ *     == 0, 1 <= headdim <= 256, 1 <= dstate <= 256, conv_width in {2,3,4};
+ *     batch * nnodes * nheads < 2^31 and nnodes * (token stride) <= 2^29 elements
+ *     (32-bit offsets inside the kernels).
  *     An MFMA kernel is used when io_dtype is bf16, headdim in {32,64,128},
  *     dstate % 16 == 0 and pointers/strides are 16-byte aligned; every other
  *     case in the envelope runs a plain fp32-FMA kernel.  Among the MFMA

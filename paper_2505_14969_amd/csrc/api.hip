@@ -20,6 +20,10 @@ int check_dims(const stree_dims *d, int need_conv) {
     if (d->nheads < 1 || d->nheads > 65535 || d->ngroups < 1 || d->nheads % d->ngroups != 0)
         return STREE_ERR_BAD_SHAPE;
     if (d->headdim < 1 || d->headdim > 256 || d->dstate < 1 || d->dstate > 256) return STREE_ERR_BAD_SHAPE;
+    // the kernels index dt, and the rows of one sequence, with 32-bit offsets
+    if ((int64_t)d->batch * d->nnodes * d->nheads > 0x7fffffffLL) return STREE_ERR_BAD_SHAPE;
+    if ((int64_t)d->nnodes * ((int64_t)d->nheads * d->headdim + 2 * (int64_t)d->ngroups * d->dstate) > (1LL << 29))
+        return STREE_ERR_BAD_SHAPE;
     if (need_conv) {
         if (d->conv_width < 2 || d->conv_width > 4) return STREE_ERR_BAD_SHAPE;
     }
@@ -38,6 +42,11 @@ int resolve_strides(stree_dims &d) {
     if (d.x_stride_n < (int64_t)d.nheads * d.headdim) return STREE_ERR_BAD_STRIDE;
     if (d.b_stride_n < (int64_t)d.ngroups * d.dstate) return STREE_ERR_BAD_STRIDE;
     if (d.c_stride_n < (int64_t)d.ngroups * d.dstate) return STREE_ERR_BAD_STRIDE;
+    // a tree's rows are addressed with 32-bit byte offsets from the sequence's first row (the prefix scan,
+    // whose sequences are longer than a tree, uses 64-bit ones)
+    const int64_t widest = d.x_stride_n > d.b_stride_n ? (d.x_stride_n > d.c_stride_n ? d.x_stride_n : d.c_stride_n)
+                                                       : (d.b_stride_n > d.c_stride_n ? d.b_stride_n : d.c_stride_n);
+    if (d.nnodes <= STREE_MAX_NODES && (int64_t)d.nnodes * widest > (1LL << 29)) return STREE_ERR_BAD_STRIDE;
     return STREE_OK;
 }
 

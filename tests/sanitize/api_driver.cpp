@@ -46,6 +46,10 @@ int main() {
     d = ok; d.ngroups = 3; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_SHAPE);
     d = ok; d.io_dtype = 9; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_DTYPE);
     d = ok; d.x_stride_n = 8; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_STRIDE);
+    d = ok; d.x_stride_n = 1LL << 28;                             // 64 nodes x 2^28 elements: beyond 32-bit offsets
+    EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_STRIDE);
+    d = ok; d.batch = 65535; d.nnodes = 256; d.nheads = 65535;    // dt index beyond 32 bits
+    EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_SHAPE);
     d = ok; d.state_dtype = 9; EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_DTYPE);
     d = ok; d.io_dtype = STREE_F32; d.state_dtype = STREE_BF16;   // a bf16 state goes with bf16 io only
     EXPECT(stree_tree_ssd(&d, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_BAD_DTYPE);
