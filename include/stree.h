@@ -100,6 +100,16 @@ int stree_version(void);
 const char *stree_status_string(int status);
 
 /*
+ * Optional set-up for callers that capture the entry points into a HIP graph (or cannot afford a slow
+ * first call).  Two of the kernels -- the one-workgroup-per-(sequence, head) MFMA kernel and the fp32-FMA
+ * kernel, i.e. the shapes outside the persistent kernels -- need more dynamic LDS than the default limit
+ * and raise it with hipFuncSetAttribute at their first launch that needs it.  This call raises every such
+ * limit at once, on the CURRENT device (call it once per device used): afterwards no entry point calls
+ * anything but kernel launches.  Launches nothing, allocates nothing.  Returns STREE_OK or STREE_ERR_HIP.
+ */
+int stree_prepare(void);
+
+/*
  * Device scratch that the entry points below would need for a problem of these sizes
  * (the problem statement of Sec. 3 "Formalization" fixes the operands; this call sizes
  * what the library needs beyond them).  Every intermediate of every kernel -- the tree

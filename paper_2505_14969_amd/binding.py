@@ -60,6 +60,8 @@ def load() -> C.CDLL:
         lib.stree_status_string.restype = C.c_char_p
         lib.stree_status_string.argtypes = [C.c_int]
         lib.stree_workspace_bytes.restype = C.c_size_t
+        lib.stree_prepare.restype = C.c_int
+        lib.stree_prepare.argtypes = []
         lib.stree_workspace_bytes.argtypes = [C.POINTER(StreeDims)]
         dp = C.POINTER(StreeDims)
         lib.stree_tree_index.argtypes = [dp] + [_VP] * 6
@@ -125,6 +127,12 @@ def make_dims(batch, nnodes, nheads, headdim, dstate, ngroups, conv_width=0, io_
         flags |= FLAG_DT_SOFTPLUS
     return StreeDims(batch, nnodes, nheads, headdim, dstate, ngroups, conv_width, io_dtype, state_dtype, flags,
                      x_stride_n, b_stride_n, c_stride_n, None if dt_bias is None else dt_bias.data_ptr())
+
+
+def stree_prepare() -> None:
+    """Raise, on the current device, the dynamic-LDS limits that two of the kernels otherwise raise at their
+    first launch: afterwards every entry point only launches kernels (what a stream capture wants)."""
+    _check(load().stree_prepare(), "stree_prepare")
 
 
 def stree_workspace_bytes(d: StreeDims) -> int:

@@ -79,6 +79,12 @@ size_t stree_workspace_bytes(const stree_dims *dims) {
     return check_dims(dims, kNoConv) == STREE_OK ? 0 : (size_t)-1;
 }
 
+int stree_prepare(void) {
+    hipError_t e = stree::prepare_tree_ssd_mfma();
+    if (e == hipSuccess) e = stree::prepare_tree_ssd_fma();
+    return hip_status(e);
+}
+
 const char *stree_status_string(int status) {
     switch (status) {
         case STREE_OK: return "ok";

@@ -3,6 +3,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "../../include/stree.h"
 
 namespace stree {
@@ -11,6 +13,32 @@ namespace stree {
 inline const float *step_bias(const stree_dims &d) {
     return (d.flags & STREE_FLAG_DT_SOFTPLUS) ? d.dt_bias : nullptr;
 }
+
+// The dynamic-LDS limit of one kernel (64 KB unless raised), raised on demand with hipFuncSetAttribute.
+// The limit only ever grows, under a lock, so a launch from another host thread never finds it lowered;
+// it is tracked per device, each device holding its own copy of the kernel and of its attributes.
+struct LdsLimit {
+    static constexpr int kDevices = 64;
+    std::mutex mu;
+    size_t set[kDevices] = {};
+    hipError_t raise(const void *kernel, size_t bytes) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kDevices) return hipErrorInvalidDevice;
+        std::lock_guard<std::mutex> hold(mu);
+        if (bytes > set[dev]) {
+            e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e != hipSuccess) return e;
+            set[dev] = bytes;
+        }
+        return hipSuccess;
+    }
+};
+
+// raise, on the current device, every limit that a launcher below would otherwise raise at its first launch
+hipError_t prepare_tree_ssd_mfma();
+hipError_t prepare_tree_ssd_fma();
 
 hipError_t launch_tree_index(const stree_dims &d, const int32_t *parent, int32_t *depth_out,
                              uint32_t *mask_out, int32_t *anc_out, int32_t *status, hipStream_t st);

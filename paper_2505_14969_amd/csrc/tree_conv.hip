@@ -299,18 +299,12 @@ static hipError_t launch_conv_t(const stree_dims &d, const int32_t *parent, cons
     const int Cc = d.nheads * d.headdim + 2 * d.ngroups * d.dstate;
     const int cblocks = (Cc / VEC + kConvVecs - 1) / kConvVecs;
     const dim3 grid(cblocks * d.batch);
+    // (at most (256 + 3) rows of 128 bytes: inside the default limit on dynamic LDS)
     const size_t lds = (size_t)(d.nnodes + d.conv_width - 1) * kConvVecs * sizeof(uint4);
+    static_assert((kMaxNodes + 3) * kConvVecs * sizeof(uint4) <= 48 * 1024, "the conv rows outgrow the default LDS limit");
     const int silu = (d.flags & STREE_FLAG_CONV_SILU) ? 1 : 0;
 #define STREE_CONV_CASE(WW)                                                                                   \
     case WW:                                                                                                  \
-        if (lds > 48 * 1024) { /* beyond the default cap on dynamic LDS: raise it for this kernel, once,   */ \
-            /* to the most any tree in the envelope needs (thread-safe: a function-local static)          */ \
-            static const hipError_t raised = hipFuncSetAttribute(                                             \
-                reinterpret_cast<const void *>(&tree_conv_kernel<T, WW, RP>),                                 \
-                hipFuncAttributeMaxDynamicSharedMemorySize,                                                   \
-                (int)((kMaxNodes + WW - 1) * kConvVecs * sizeof(uint4)));                                     \
-            if (raised != hipSuccess) return raised;                                                          \
-        }                                                                                                     \
         hipLaunchKernelGGL((tree_conv_kernel<T, WW, RP>), grid, dim3(kThreads), lds, st, parent, d.nnodes, Cc, \
                            silu, (const T *)xbc_pre, (const T *)conv_state, (const T *)conv_w,                \
                            (const T *)conv_b, (T *)xbc_out, status, R);                                       \

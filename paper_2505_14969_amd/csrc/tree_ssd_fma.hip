@@ -126,22 +126,39 @@ __global__ __launch_bounds__(kThreads) void tree_ssd_fma_kernel(
 }
 
 template <typename T, typename HT>
+static LdsLimit &fma_lds_limit() {
+    static LdsLimit lim;
+    return lim;
+}
+
+template <typename T, typename HT>
+static hipError_t prepare_fma_t() {
+    return fma_lds_limit<T, HT>().raise(reinterpret_cast<const void *>(&tree_ssd_fma_kernel<T, HT>),
+                                        fma_lds_floats(256, 256) * sizeof(float));
+}
+
+template <typename T, typename HT>
 static hipError_t launch_fma_t(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                const float *A, const void *Bm, const void *Cm, const float *D, const void *h0,
                                void *y, int32_t *status, hipStream_t st) {
     const size_t lds = fma_lds_floats(d.headdim, d.dstate) * sizeof(float);
-    if (lds > 48 * 1024) {   // beyond the default cap on dynamic LDS: raise it once, to what headdim = dstate = 256 need
-        static const hipError_t raised =
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_fma_kernel<T, HT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(fma_lds_floats(256, 256) * sizeof(float)));
-        if (raised != hipSuccess) return raised;
+    if (lds > 48 * 1024) {   // beyond the default cap on dynamic LDS: raised once, to what headdim = dstate = 256 need
+        const hipError_t e = fma_lds_limit<T, HT>().raise(reinterpret_cast<const void *>(&tree_ssd_fma_kernel<T, HT>),
+                                                          fma_lds_floats(256, 256) * sizeof(float));
+        if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((tree_ssd_fma_kernel<T, HT>), dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
                        d.nheads, d.headdim, d.dstate, d.ngroups, (const T *)x, (long)d.x_stride_n, dt, step_bias(d),
                        A, (const T *)Bm, (long)d.b_stride_n, (const T *)Cm, (long)d.c_stride_n, D,
                        (const HT *)h0, (T *)y, status);
     return hipGetLastError();
+}
+
+hipError_t prepare_tree_ssd_fma() {
+    hipError_t e = prepare_fma_t<bf16_t, bf16_t>();
+    if (e == hipSuccess) e = prepare_fma_t<bf16_t, float>();
+    if (e == hipSuccess) e = prepare_fma_t<float, float>();
+    return e;
 }
 
 hipError_t launch_tree_ssd_fma(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,

@@ -423,23 +423,31 @@ bool tree_ssd_mfma_supported(const stree_dims &d, const void *x, const void *Bm,
 }
 
 template <int P, bool SH, typename HT>
+static LdsLimit &mfma_lds_limit() {
+    static LdsLimit lim;
+    return lim;
+}
+
+// the most dynamic LDS this instantiation can be launched with: what the CU has less the kernel's static part
+template <int P, bool SH, typename HT>
+static hipError_t prepare_pt() {
+    hipFuncAttributes attr;
+    const void *k = reinterpret_cast<const void *>(&tree_ssd_mfma_kernel<P, SH, HT>);
+    hipError_t e = hipFuncGetAttributes(&attr, k);
+    if (e != hipSuccess) return e;
+    return mfma_lds_limit<P, SH, HT>().raise(k, 160 * 1024 - attr.sharedSizeBytes);
+}
+
+template <int P, bool SH, typename HT>
 static hipError_t launch_pt(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                            const float *A, const void *Bm, const void *Cm, const float *D, const void *h0,
                             void *y, int32_t *status, hipStream_t st) {
     const int npad = (d.nnodes + kBlk - 1) / kBlk * kBlk;
     const size_t lds = mfma_lds_plan(P, d.dstate, npad, (d.nnodes + 31) / 32).total;
-    {   // raise the dynamic-LDS limit of this instantiation (64 KB is the default cap).  The limit only
-        // ever grows, under a lock, so a launch from another host thread never finds it lowered.
-        static std::mutex mu;
-        static size_t lds_set = 0;
-        std::lock_guard<std::mutex> hold(mu);
-        if (lds > lds_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_ssd_mfma_kernel<P, SH, HT>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            lds_set = lds;
-        }
-    }
+    // the dynamic-LDS limit of this instantiation (64 KB by default)
+    const hipError_t e = mfma_lds_limit<P, SH, HT>().raise(
+        reinterpret_cast<const void *>(&tree_ssd_mfma_kernel<P, SH, HT>), lds);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((tree_ssd_mfma_kernel<P, SH, HT>), dim3(d.nheads, d.batch), dim3(kThreads), lds, st, parent, d.nnodes,
                        d.nheads, d.dstate, d.ngroups, (const bf16_t *)x, (long)d.x_stride_n, dt, step_bias(d),
                        A, (const bf16_t *)Bm, (long)d.b_stride_n, (const bf16_t *)Cm, (long)d.c_stride_n, D,
@@ -453,6 +461,21 @@ static hipError_t launch_p(const stree_dims &d, const int32_t *parent, const voi
                            void *y, int32_t *status, hipStream_t st) {
     if (d.state_dtype == STREE_BF16) return launch_pt<P, SH, bf16_t>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
     return launch_pt<P, SH, float>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+}
+
+hipError_t prepare_tree_ssd_mfma() {
+    hipError_t e = hipSuccess;
+#define STREE_PREP(P, SH)                                            \
+    if (e == hipSuccess) e = prepare_pt<P, SH, float>();             \
+    if (e == hipSuccess) e = prepare_pt<P, SH, bf16_t>()
+    STREE_PREP(32, true);
+    STREE_PREP(32, false);
+    STREE_PREP(64, true);
+    STREE_PREP(64, false);
+    STREE_PREP(128, true);
+    STREE_PREP(128, false);
+#undef STREE_PREP
+    return e;
 }
 
 hipError_t launch_tree_ssd_mfma(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,

@@ -19,6 +19,8 @@ bool tree_ssd_replay_fused_supported(const stree_dims &, const stree_dims &, con
 hipError_t launch_tree_ssd_replay_fused(const stree_dims &, const stree_dims &, const int32_t *, const int32_t *, const void *, const float *, const void *, const int32_t *, const void *, const float *, const float *, const void *, const void *, const float *, const void *, void *, void *, int32_t *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
 bool linear_ssd_supported(const stree_dims &d, const void *, const void *, const void *, const void *, const void *, const void *) { return d.headdim == 64; }
 hipError_t launch_linear_ssd(const stree_dims &, const void *, const float *, const float *, const void *, const void *, const float *, const void *, void *, void *, hipStream_t) { ++launches; return hipSuccess; }
+hipError_t prepare_tree_ssd_mfma() { return hipSuccess; }
+hipError_t prepare_tree_ssd_fma() { return hipSuccess; }
 hipError_t launch_gate_norm(const stree_dims &, const void *, const void *, long, const void *, float, void *, hipStream_t) { ++launches; return hipSuccess; }
 hipError_t launch_commit_state(const stree_dims &, const int32_t *, const int32_t *, const void *, const float *, const float *, const void *, const void *, void *, const void *, const void *, void *, int32_t *, hipStream_t) { ++launches; return hipSuccess; }
 }  // namespace stree
@@ -39,6 +41,7 @@ int main() {
     stree_dims ok = {2, 64, 8, 64, 128, 1, 4, STREE_BF16, STREE_F32, 0, 0, 0, 0};
     stree_dims d = ok;
     EXPECT(stree_workspace_bytes(&ok), 0);
+    EXPECT(stree_prepare(), STREE_OK);
     EXPECT(stree_workspace_bytes(nullptr), (size_t)-1);
     d = ok; d.nnodes = 257; EXPECT(stree_workspace_bytes(&d), (size_t)-1);
     EXPECT(stree_tree_ssd(nullptr, ip, p, fp, fp, p, p, nullptr, nullptr, p, nullptr, nullptr), STREE_ERR_NULL_ARG);

@@ -142,3 +142,35 @@ def test_graph_replays_of_the_large_tree_kernel_and_gate_norm(st, oracle):
             want_n = oracle.gate_norm(got_y.reshape(B * N, H * P), z.reshape(B * N, H * P), nw, G, 1e-5)
             got_n = to_host(graphed["yn"]).reshape(B * N, H * P)
             assert np.all(np.abs(got_n - want_n) <= 2.0 ** -8 * np.abs(want_n) + 1e-5)
+
+
+def test_capture_without_a_first_call_after_prepare(st, oracle):
+    """stree_prepare raises the dynamic-LDS limits of the two kernels that would otherwise raise them at their
+    first launch: after it their very first launch may sit inside a stream capture (run on its own, this test
+    is that first launch).  The fp32 kernel at headdim = dstate = 256, its largest LDS tile, and the
+    one-workgroup-per-(sequence, head) MFMA kernel on a 256-node tree with headdim 128."""
+    from test_gpu_parity import _rand
+    st.stree_prepare()
+    cases = []
+    for io, B, N, H, P, S, G in (("f32", 1, 40, 2, 256, 256, 1), ("bf16", 1, 256, 2, 128, 128, 1)):
+        parent = _trees(406 + N, B, N)
+        x, dt, A, Bm, Cm, D, h0 = _rand(407 + N, io, B, N, H, P, S, G)
+        dev = [to_dev(parent), to_dev(x, io), to_dev(dt), to_dev(A), to_dev(Bm, io), to_dev(Cm, io), to_dev(D),
+               to_dev(h0)]
+        out = torch.zeros((B, N, H, P), dtype=dev[1].dtype, device="cuda")
+        cases.append((io, parent, (x, dt, A, Bm, Cm, D, h0), dev, out))
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):             # no launch of these kernels before this capture
+        for _, _, _, dev, out in cases:
+            st.stree_tree_ssd(*dev, out=out)
+    torch.cuda.synchronize()
+    for replay in range(2):
+        for _, _, _, _, out in cases:
+            out.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for io, parent, (x, dt, A, Bm, Cm, D, h0), _, out in cases:
+            want = oracle.ssd_paths(parent, x, dt, A, Bm, Cm, D, h0)
+            assert_parity(to_host(out), want, TOL[io], f"captured first launch ({io}), replay {replay}", kind="y")
