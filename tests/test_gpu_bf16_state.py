@@ -192,3 +192,26 @@ def test_bf16_state_must_start_on_a_16_byte_boundary(st):
     assert e.value.code == 2
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
+
+
+@pytest.mark.parametrize("Np,N", [(50, 64), (90, 140)])
+def test_bf16_state_together_with_the_in_kernel_step_size(st, oracle, Np, N):
+    """Both variants at once (raw dt + bias, state in bf16) through the fused replay + scan: one kernel for
+    trees of at most 64 nodes, commit followed by the scan kernel of larger trees otherwise."""
+    B, H, P, S, G = 2, 4, 64, 128, 1
+    io = "bf16"
+    rng = np.random.default_rng(9950 + N)
+    pparent, parent = _trees(9951 + Np, B, Np), _trees(9952 + N, B, N)
+    px, _, A, pB, _, D, h0 = _inputs(9953 + Np, B, Np, H, P, S, G)
+    x, _, _, Bm, Cm, _, _ = _inputs(9954 + N, B, N, H, P, S, G)
+    praw = rng.standard_normal((B, Np, H)).astype(np.float32)
+    raw = rng.standard_normal((B, N, H)).astype(np.float32)
+    bias = rng.uniform(-3.0, -1.0, H).astype(np.float32)
+    acc = np.array([Np - 1, Np // 2], dtype=np.int32)
+    h_want, _ = oracle.commit(pparent, acc, px, oracle.step_size(praw, bias), A, pB, h0)
+    y, h = st.stree_tree_ssd_replay(to_dev(pparent), to_dev(acc), to_dev(px, io), to_dev(praw), to_dev(pB, io),
+                                    to_dev(parent), to_dev(x, io), to_dev(raw), to_dev(A), to_dev(Bm, io),
+                                    to_dev(Cm, io), to_dev(D), to_dev(h0, io), dt_bias=to_dev(bias))
+    _assert_rounded_state(to_host(h), h_want, f"replayed bf16 state, raw dt, {Np}->{N}")
+    y_want = oracle.ssd_paths(parent, x, oracle.step_size(raw, bias), A, Bm, Cm, D, to_host(h))
+    assert_parity(to_host(y), y_want, TOL[io], f"y, bf16 state and raw dt, {Np}->{N}", kind="y")
