@@ -217,6 +217,10 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     // chunk q of a thread: without replay element (t + q*kHalf)*4 of the P x S tile; with replay
     // row (t / S4) * NH + q, piece t % S4, so that a thread's rows are consecutive
     constexpr int S4 = S / 4;
+    // replay on a state kept in bf16: a thread owns NH/2 rows of EIGHT columns, so that the state moves in
+    // 16-byte pieces as the fp32 one does (where its x values still come four at a time; otherwise the
+    // fp32 map with 8-byte pieces)
+    constexpr bool kWide = RP && sizeof(HT) == 2 && (NH / 2) % 4 == 0;
     auto load_H = [&](int b, int h) {       // the role group that carries this unit
         // the lane-dependent zero keeps this a vector load: it then sits in the same in-order
         // queue as the h0 chunks instead of forcing a scalar-cache wait in the hot window
@@ -232,7 +236,12 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
                 pre[q].y = v.y;
             }
         };
-        if constexpr (RP) {
+        if constexpr (kWide) {                 // replay on a bf16 state: NH/2 rows of eight columns per thread
+            const int t = opaque(rt);
+            const uint32_t off = (uint32_t)(((t / (S / 8)) * (NH / 2)) * S + (t % (S / 8)) * 8) * 2u;
+#pragma unroll
+            for (int q = 0; q < NH / 2; ++q) pre[q] = load_stream16(hb + off + q * (S * 2));
+        } else if constexpr (RP) {
             const int t = opaque(rt);
             const uint32_t off = (uint32_t)(((t / S4) * NH) * S + (t % S4) * 4) * HB;
 #pragma unroll
@@ -288,7 +297,71 @@ __global__ __launch_bounds__(kT64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))
     // rbuf: the LDS rows of the replayed path (x rows [kRC][P], then B rows [kRC][S]); b, h: the unit
     auto stage_H = [&]([[maybe_unused]] const char *rbuf, [[maybe_unused]] int b, [[maybe_unused]] int h) {
         const int t = opaque(rt);
-        if constexpr (RP) {
+        if constexpr (kWide) {
+            constexpr int S8 = S / 8, NR = NH / 2;
+            const int prow = (t / S8) * NR, s8 = t % S8;
+            const int len = *sRlen;
+            const float dec = *sRdec;
+            float hv[NR][8];
+#pragma unroll
+            for (int q = 0; q < NR; ++q) {
+                const uint32_t w4[4] = {pre[q].x, pre[q].y, pre[q].z, pre[q].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    hv[q][2 * e] = dec * bf16_lo(w4[e]);
+                    hv[q][2 * e + 1] = dec * bf16_hi(w4[e]);
+                }
+            }
+            auto rank1 = [&](float cf, uint4 b8, const uint32_t (&xw)[NR / 2]) {
+                const float bv[8] = {cf * bf16_lo(b8.x), cf * bf16_hi(b8.x), cf * bf16_lo(b8.y), cf * bf16_hi(b8.y),
+                                     cf * bf16_lo(b8.z), cf * bf16_hi(b8.z), cf * bf16_lo(b8.w), cf * bf16_hi(b8.w)};
+#pragma unroll
+                for (int q = 0; q < NR; ++q) {
+                    const float xv = (q & 1) ? bf16_hi(xw[q >> 1]) : bf16_lo(xw[q >> 1]);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) hv[q][e] = fmaf(xv, bv[e], hv[q][e]);
+                }
+            };
+            const int nl = min(len, kRC);
+            for (int j = 0; j < nl; ++j) {
+                const uint4 b8 = *reinterpret_cast<const uint4 *>(rbuf + (kRC * P + j * S + s8 * 8) * 2);
+                uint32_t xw[NR / 2];
+#pragma unroll
+                for (int w = 0; w < NR / 2; w += 2) {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(rbuf + (j * P + prow + 2 * w) * 2);
+                    xw[w] = v.x;
+                    xw[w + 1] = v.y;
+                }
+                rank1(sRcoef[j], b8, xw);
+            }
+            if (len > kRC) {   // the rest of a long path: rows straight from global memory
+                const int g = h / hpg;
+                const char *xb = reinterpret_cast<const char *>(R.x + (size_t)b * R.pn * R.x_sn + (size_t)h * P + prow);
+                const char *Bb = reinterpret_cast<const char *>(R.Bm + (size_t)b * R.pn * R.b_sn + (size_t)g * S + s8 * 8);
+                for (int j = kRC; j < len; ++j) {
+                    const int node = sRnode[j];
+                    const uint4 b8 = *reinterpret_cast<const uint4 *>(Bb + (size_t)node * R.b_sn * 2);
+                    uint32_t xw[NR / 2];
+#pragma unroll
+                    for (int w = 0; w < NR / 2; w += 2) {
+                        const uint2 v = *reinterpret_cast<const uint2 *>(xb + ((size_t)node * R.x_sn + 2 * w) * 2);
+                        xw[w] = v.x;
+                        xw[w + 1] = v.y;
+                    }
+                    rank1(sRcoef[j], b8, xw);
+                }
+            }
+            // the replayed state, rounded once: the value written back (through L2) is the MFMA operand
+            char *ob = reinterpret_cast<char *>(reinterpret_cast<HT *>(R.h_out) + ((size_t)b * H + h) * P * S);
+#pragma unroll
+            for (int q = 0; q < NR; ++q) {
+                const uint2 lo = pack_bf16x4(hv[q][0], hv[q][1], hv[q][2], hv[q][3]);
+                const uint2 hi = pack_bf16x4(hv[q][4], hv[q][5], hv[q][6], hv[q][7]);
+                const uint4 o = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                store_through16(ob + (uint32_t)((prow + q) * S + s8 * 8) * 2u, o);
+                *reinterpret_cast<uint4 *>(&sH[(prow + q) * SP + s8 * 8]) = o;
+            }
+        } else if constexpr (RP) {
             const int prow = (t / S4) * NH, s4 = t % S4;
             const int len = *sRlen;
             const float dec = *sRdec;
