@@ -174,3 +174,36 @@ def test_capture_without_a_first_call_after_prepare(st, oracle):
         for io, parent, (x, dt, A, Bm, Cm, D, h0), _, out in cases:
             want = oracle.ssd_paths(parent, x, dt, A, Bm, Cm, D, h0)
             assert_parity(to_host(out), want, TOL[io], f"captured first launch ({io}), replay {replay}", kind="y")
+
+
+def test_entry_points_run_on_the_callers_stream(st, oracle):
+    """The kernels are enqueued on the stream handed over (here torch's current stream, a non-blocking side
+    stream of default priority): their inputs are finished by a long chain of small kernels on that same
+    stream, so a launch anywhere else would read them half done."""
+    from test_gpu_parity import _rand
+    io, B, N, H, P, S, G = "bf16", 4, 64, 8, 64, 128, 1
+    parent = _trees(430, B, N)
+    x, dt, A, Bm, Cm, D, h0 = _rand(431, io, B, N, H, P, S, G)
+    acc = np.array([N - 1, 3, -1, 20], dtype=np.int32)
+    want_y = oracle.ssd_paths(parent, x, dt, A, Bm, Cm, D, h0)
+    want_h, _ = oracle.commit(parent, acc, x, dt, A, Bm, h0)
+    par, accd, Ad, Dd = to_dev(parent), to_dev(acc), to_dev(A), to_dev(D)
+    xd, Bd, Cd = to_dev(x, io), to_dev(Bm, io), to_dev(Cm, io)
+    steps = 400
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        # a chain of small kernels first; dt and h0 become valid only behind it (h0 even depends on its result)
+        dtd = torch.zeros((B, N, H), dtype=torch.float32, device="cuda")
+        h0d = torch.zeros((B, H, P, S), dtype=torch.float32, device="cuda")
+        junk = torch.zeros_like(h0d)
+        for _ in range(steps):
+            junk.add_(1.0)
+        dtd.copy_(to_dev(dt))             # the inputs become valid only behind the chain
+        h0d.copy_(to_dev(h0))
+        h0d.add_(junk.sub_(float(steps)))  # + 0 exactly, once the chain is through
+        y = st.stree_tree_ssd(par, xd, dtd, Ad, Bd, Cd, Dd, h0d)
+        h, _ = st.stree_commit_state(par, accd, xd, dtd, Ad, Bd, h0d)
+    side.synchronize()
+    assert_parity(to_host(y), want_y, TOL[io], "scan on a side stream", kind="y")
+    assert_parity(to_host(h), want_h, 1e-4, "commit on a side stream", kind="state")
