@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--batches", action="store_true",
                     help="the scan and the replay + scan kernels at batch 8 .. 128 of the headline shape: how far "
                          "the fill and drain of a 2-3 unit run are from the steady state (prints its own JSON line)")
+    ap.add_argument("--latency", action="store_true",
+                    help="the step at batch 1, 2, 4 on the paper's tree sizes (single-sequence decoding)")
     ap.add_argument("--sweep", action="store_true",
                     help="second workload: the paper's tree shapes, packed tree scan against the same scan on the "
                          "tree unrolled into one chain per leaf (prints its own JSON line)")
@@ -129,6 +131,8 @@ def main():
         return sweep(st, synth, torch, dev)
     if args.prefix:
         return prefix(st, synth, torch, dev)
+    if args.latency:
+        return latency(st, synth, torch, dev)
     if args.batches:
         return batches(st, synth, torch, dev)
     if args.only_config >= 0:
@@ -585,6 +589,66 @@ def unroll_paths(parent):
             v = int(parent[v])
         paths.append(p[::-1])
     return paths
+
+
+def latency(st, synth, torch, dev):
+    """Single-sequence decoding, the paper's setting: the fused step (conv + conv tail, replay + scan, one call)
+    and the scan alone at batch 1, 2, 4 on full binary trees of 15 / 31 / 63 nodes and a 64-node random tree,
+    80 heads x 64, dstate 128.  HIP graph of six buffer sets, HIP-event time per call."""
+    H, P, S, G, W = 80, 64, 128, 1, 4
+    Cc = H * P + 2 * G * S
+    n_sets, reps = 6, 200
+    rng = np.random.default_rng(3)
+    A, D = -torch.rand(H, device=dev) - 0.5, torch.randn(H, device=dev)
+    cw, cb = torch.randn((Cc, W), device=dev).to(torch.bfloat16), torch.randn(Cc, device=dev).to(torch.bfloat16)
+    rows = []
+    for B in (1, 2, 4):
+        for N in (15, 31, 63, 64):
+            one = synth.full_binary_tree({15: 4, 31: 5, 63: 6}[N]) if N < 64 else synth.gen_tree(N, 6, 4, rng)
+            parent = torch.from_numpy(np.stack([one] * B).astype(np.int32)).to(dev)
+            acc = torch.full((B,), N // 2, dtype=torch.int32, device=dev)
+            sets = [dict(pre=torch.randn((B, N, Cc), device=dev).to(torch.bfloat16),
+                         pout=torch.randn((B, N, Cc), device=dev).to(torch.bfloat16),
+                         cs=torch.randn((B, W - 1, Cc), device=dev).to(torch.bfloat16),
+                         dt=torch.rand((B, N, H), device=dev) * 0.1 + 0.01,
+                         h0=torch.randn((B, H, P, S), device=dev) * 0.1, h1=torch.empty((B, H, P, S), device=dev),
+                         xbc=torch.empty((B, N, Cc), dtype=torch.bfloat16, device=dev),
+                         cso=torch.empty((B, W - 1, Cc), dtype=torch.bfloat16, device=dev),
+                         y=torch.empty((B, N, H, P), dtype=torch.bfloat16, device=dev)) for _ in range(n_sets)]
+
+            def step(s):
+                st.stree_tree_step(parent, acc, s["pre"], s["pout"], s["dt"], parent, s["pre"], s["cs"], cw, cb, s["dt"],
+                                   A, D, s["h0"], H, P, S, G, xbc_out=s["xbc"], conv_state_out=s["cso"], h_out=s["h1"],
+                                   out=s["y"])
+
+            def scan(s):
+                xbc = s["xbc"]
+                st.stree_tree_ssd(parent, xbc[:, :, :H * P].unflatten(2, (H, P)), s["dt"], A,
+                                  xbc[:, :, H * P:H * P + G * S].unflatten(2, (G, S)),
+                                  xbc[:, :, H * P + G * S:].unflatten(2, (G, S)), D, s["h0"], out=s["y"])
+
+            us = []
+            for fn in (step, scan):
+                for s in sets:
+                    fn(s)
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for s in sets:
+                        fn(s)
+                for _ in range(3):
+                    g.replay()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                us.append(e0.elapsed_time(e1) / (reps * n_sets) * 1e3)
+            log(f"[latency] batch {B} x {N:2d} nodes: step {us[0]:6.2f} us   scan alone {us[1]:5.2f} us")
+            rows.append({"batch": B, "nnodes": N, "step_us": us[0], "scan_us": us[1]})
+    print(json.dumps({"latency": rows}), flush=True)
 
 
 def batches(st, synth, torch, dev):
