@@ -111,6 +111,40 @@ def test_config2_fused_sequence(st, oracle):
     assert_parity(to_host(y), want_y, TOL[io], "cfg2 fused: y", kind="y")
 
 
+def test_config2_fused_scan_with_raw_dt_and_bf16_state(st, oracle):
+    """The headline shape at full size with both variants of the boundary switched on: `dt` handed over as the
+    raw projection (the kernels take softplus(dt + bias)) and the state kept in bf16 (what the fused kernel
+    writes back is one rounding away from the oracle's commit, and is the state it scans from)."""
+    wl = synth.config(2)
+    H, P, S, G = wl.nheads, wl.headdim, wl.dstate, wl.ngroups
+    io = wl.io_dtype
+    roll = lambda a: np.roll(a, 1, axis=0)
+    pparent, pacc, pxbc_pre = roll(wl.parent), roll(wl.accepted), roll(wl.xbc_pre)
+    pxbc = synth.round_to_bf16(oracle.tree_conv(pparent, pxbc_pre, roll(wl.conv_state), wl.conv_w, wl.conv_b,
+                                                True).astype(np.float32))
+    xbc = synth.round_to_bf16(oracle.tree_conv(wl.parent, wl.xbc_pre, wl.conv_state, wl.conv_w, wl.conv_b,
+                                               True).astype(np.float32))
+    px, pB, _ = split_xbc(pxbc, H, P, G, S)
+    x, Bm, Cm = split_xbc(xbc, H, P, G, S)
+    # raw values whose softplus (with the bias) is the configuration's step size, up to their fp32 rounding
+    bias = np.linspace(-3.0, -1.0, H).astype(np.float32)
+    raw = (np.log(np.expm1(wl.dt.astype(np.float64))) - bias).astype(np.float32)
+    praw = roll(raw)
+    dt_eff, pdt_eff = oracle.step_size(raw, bias), oracle.step_size(praw, bias)
+    assert np.allclose(dt_eff, wl.dt, rtol=1e-5, atol=0)
+    h0 = synth.round_to_bf16(wl.h0)
+    want_h, _ = oracle.commit(pparent, pacc, px, pdt_eff, wl.A, pB, h0)
+    dx, dB, dC = split_xbc_dev(to_dev(xbc, io), H, P, G, S)
+    qx, qB, _ = split_xbc_dev(to_dev(pxbc, io), H, P, G, S)
+    y, h = st.stree_tree_ssd_replay(to_dev(pparent), to_dev(pacc), qx, to_dev(praw), qB, to_dev(wl.parent), dx,
+                                    to_dev(raw), to_dev(wl.A), dB, dC, to_dev(wl.D), to_dev(h0, "bf16"),
+                                    dt_bias=to_dev(bias))
+    got_h = to_host(h).astype(np.float64)
+    assert np.all(np.abs(got_h - want_h) <= 2.0 ** -8 * np.abs(want_h) * 1.001 + 1e-4 * np.max(np.abs(want_h)))
+    want_y = oracle.ssd_paths(wl.parent, x, dt_eff, wl.A, Bm, Cm, wl.D, got_h)
+    assert_parity(to_host(y), want_y, TOL[io], "cfg2 fused, raw dt and bf16 state: y", kind="y")
+
+
 def test_config2_direct_inputs_scan_only(st, oracle):
     """The variant the benchmark's roofline is quoted on: x,B,C ~ N(0,1) directly."""
     wl = synth.direct_xbc(synth.config(2))
