@@ -30,9 +30,9 @@
  *     dstate % 16 == 0 and pointers/strides are 16-byte aligned; every other
  *     case in the envelope runs a plain fp32-FMA kernel.  Among the MFMA
  *     shapes, the persistent kernels (the ones the benchmark prices) take
- *     headdim 64 with dstate 64 or 128 at any node count, and headdim 128 with
- *     dstate 128 at up to 64 nodes; the remaining MFMA shapes (headdim 32,
- *     dstate 256, ...) run one workgroup per (sequence, head) and are several
+ *     headdim 64 with dstate 64, 128 or 256 at any node count, and headdim 128
+ *     with dstate 128 at up to 64 nodes; the remaining MFMA shapes (headdim 32,
+ *     other dstates, ...) run one workgroup per (sequence, head) and are several
  *     times slower per node.  Results are the same to rounding on every route.
  */
 #ifndef STREE_H
@@ -310,7 +310,7 @@ int stree_gate_norm(const stree_dims *dims, const void *y, const void *z, int64_
  *   x, dt, A, Bm, Cm, D, h0 as in stree_tree_ssd with T in place of N
  *   y      io [B,T,H,P] or NULL: state only (then Cm and D may be NULL too)
  *   h_out  st [B,H,P,S] state after token T-1, required, MAY alias h0
- * Shapes: bf16 io, (headdim, dstate) in {(64,64), (64,128), (128,128)}, 16-byte
+ * Shapes: bf16 io, (headdim, dstate) in {(64,64), (64,128), (64,256), (128,128)}, 16-byte
  * aligned pointers and strides; anything else returns STREE_ERR_BAD_SHAPE
  * (a chain tree through stree_tree_ssd / stree_commit_state covers it, 256
  * tokens at a time).  The state is carried in fp32 (the weighted inputs enter

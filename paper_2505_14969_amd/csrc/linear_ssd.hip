@@ -366,7 +366,7 @@ bool linear_ssd_supported(const stree_dims &d, const void *x, const void *Bm, co
                           const void *h0, const void *h_out) {
     if (d.io_dtype != STREE_BF16) return false;
     const int P = d.headdim, S = d.dstate;
-    if (!((P == 64 && (S == 128 || S == 64)) || (P == 128 && S == 128))) return false;
+    if (!((P == 64 && (S == 128 || S == 64 || S == 256)) || (P == 128 && S == 128))) return false;
     if ((d.x_stride_n | d.b_stride_n | d.c_stride_n) % 8 != 0) return false;
     // (the state is read and written 16 bytes at a time, like the rows)
     return (((uintptr_t)x | (uintptr_t)Bm | (uintptr_t)Cm | (uintptr_t)y | (uintptr_t)h0 | (uintptr_t)h_out) % 16) == 0;
@@ -377,6 +377,7 @@ hipError_t launch_linear_ssd(const stree_dims &d, const void *x, const float *dt
     const int P = d.headdim, S = d.dstate;
     if (P == 64 && S == 128) return launch_p<64, 128>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
     if (P == 64 && S == 64) return launch_p<64, 64>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
+    if (P == 64 && S == 256) return launch_p<64, 256>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
     if (P == 128 && S == 128) return launch_p<128, 128>(d, x, dt, A, Bm, Cm, D, h0, y, h_out, st);
     return hipErrorInvalidValue;
 }

@@ -617,7 +617,7 @@ hipError_t launch_blocks_ps(const stree_dims &d, const int32_t *parent, const vo
 // bf16, 65 .. 256 nodes, the head shapes below; alignment is checked by the caller (tree_ssd_mfma_supported)
 bool tree_ssd_blocks_supported(const stree_dims &d) {
     if (d.nnodes <= kBk || d.nnodes > 4 * kBk) return false;
-    return d.headdim == 64 && (d.dstate == 128 || d.dstate == 64);
+    return d.headdim == 64 && (d.dstate == 128 || d.dstate == 64 || d.dstate == 256);
 }
 
 hipError_t launch_tree_ssd_blocks(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
@@ -627,6 +627,9 @@ hipError_t launch_tree_ssd_blocks(const stree_dims &d, const int32_t *parent, co
     if (d.dstate == 128)
         return small ? launch_blocks_ps<64, 128, 2>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st)
                      : launch_blocks_ps<64, 128, 4>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
+    if (d.dstate == 256)
+        return small ? launch_blocks_ps<64, 256, 2>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st)
+                     : launch_blocks_ps<64, 256, 4>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
     return small ? launch_blocks_ps<64, 64, 2>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st)
                  : launch_blocks_ps<64, 64, 4>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
 }

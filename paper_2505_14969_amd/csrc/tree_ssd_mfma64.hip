@@ -927,6 +927,7 @@ hipError_t launch64(const stree_dims &d, const int32_t *parent, const void *x, c
     const int P = d.headdim, S = d.dstate;
     if (P == 64 && S == 128) return launch64_ps<64, 128, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
     if (P == 64 && S == 64) return launch64_ps<64, 64, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
+    if (P == 64 && S == 256) return launch64_ps<64, 256, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
     if (P == 128 && S == 128) return launch64_ps<128, 128, RP>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, R, st);
     return hipErrorInvalidValue;
 }
@@ -936,7 +937,7 @@ hipError_t launch64(const stree_dims &d, const int32_t *parent, const void *x, c
 bool tree_ssd_mfma64_supported(const stree_dims &d) {
     if (d.nnodes > kB64) return false;
     const int P = d.headdim, S = d.dstate;
-    return (P == 64 && (S == 128 || S == 64)) || (P == 128 && S == 128);
+    return (P == 64 && (S == 128 || S == 64 || S == 256)) || (P == 128 && S == 128);
 }
 
 bool tree_ssd_replay_fused_supported(const stree_dims &d, const stree_dims &dp, const void *px, const void *pB,

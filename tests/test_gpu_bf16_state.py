@@ -37,6 +37,8 @@ SCAN_CASES = [
     (2, 200, 4, 64, 128, 1, {"general_mfma": True}),    # one workgroup per (sequence, head)
     (2, 50, 3, 32, 64, 1, {}),
     (2, 150, 2, 128, 128, 1, {}),
+    (2, 64, 3, 64, 256, 1, {}),                         # dstate 256 on the persistent kernels
+    (2, 180, 3, 64, 256, 1, {}),
     (2, 90, 3, 64, 128, 1, {"force_fma": True}),        # fp32 FMA kernel
     (2, 30, 3, 24, 40, 1, {}),                          # (a shape only the FMA kernel takes)
 ]
@@ -81,7 +83,7 @@ def test_commit_into_a_bf16_state(st, oracle, B, N, H, P, S, G):
 
 
 @pytest.mark.parametrize("Np,N,P,S", [(64, 64, 64, 128), (23, 50, 64, 64), (40, 33, 128, 128), (100, 40, 64, 128),
-                                      (30, 130, 64, 128)])
+                                      (30, 130, 64, 128), (50, 60, 64, 256), (40, 140, 64, 256)])
 def test_replay_and_step_with_a_bf16_state(st, oracle, Np, N, P, S):
     """Fused replay + scan (one kernel when both trees have at most 64 nodes, otherwise two): the state it
     writes is the oracle's commit within one rounding, and y is the scan FROM THAT ROUNDED STATE (the value
@@ -132,7 +134,7 @@ def test_replay_and_step_with_a_bf16_state(st, oracle, Np, N, P, S):
 
 
 @pytest.mark.parametrize("P,S,T,with_h0,want_y", [(64, 128, 300, True, True), (64, 64, 129, False, True),
-                                                  (128, 128, 64, True, False)])
+                                                  (128, 128, 64, True, False), (64, 256, 200, True, True)])
 def test_linear_scan_with_a_bf16_state(st, oracle, P, S, T, with_h0, want_y):
     B, H, G = 2, 3, 1
     x, dt, A, Bm, Cm, D, h0 = _inputs(9600 + T, B, T, H, P, S, G)

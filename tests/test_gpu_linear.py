@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("B,T,H,P,S,G,with_h0", [(2, 1, 2, 64, 128, 1, True), (2, 63, 4, 64, 128, 2, False),
                                                   (1, 64, 2, 64, 128, 1, True), (3, 65, 4, 64, 64, 1, True),
-                                                  (2, 200, 2, 128, 128, 2, True), (2, 1000, 3, 64, 128, 1, True)])
+                                                  (2, 200, 2, 128, 128, 2, True), (2, 1000, 3, 64, 128, 1, True),
+                                                  (2, 300, 2, 64, 256, 1, True), (1, 130, 4, 64, 256, 2, False)])
 def test_linear_scan_against_oracle(st, oracle, B, T, H, P, S, G, with_h0):
     io = "bf16"
     x, dt, A, Bm, Cm, D, h0 = _rand(300 + T, io, B, T, H, P, S, G, h0=with_h0)

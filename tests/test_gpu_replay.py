@@ -41,7 +41,7 @@ def _run(st, io, pp, acc, prev, p, cur, A, D, h_io=None, **kw):
 # units per workgroup, and shapes that take the two-kernel route
 SHAPES = [("bf16", 5, 40, 64, 6, 64, 128, 2), ("bf16", 3, 64, 30, 4, 64, 64, 1), ("bf16", 2, 20, 64, 3, 128, 128, 1),
           ("bf16", 16, 33, 57, 80, 64, 128, 1), ("bf16", 2, 100, 64, 4, 64, 128, 1), ("bf16", 2, 30, 130, 4, 64, 128, 2),
-          ("f32", 2, 25, 31, 3, 24, 20, 1)]
+          ("f32", 2, 25, 31, 3, 24, 20, 1), ("bf16", 4, 64, 64, 6, 64, 256, 2), ("bf16", 3, 17, 40, 3, 64, 256, 1)]
 
 
 @pytest.mark.parametrize("io,B,Np,N,H,P,S,G", SHAPES)
