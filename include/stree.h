@@ -30,10 +30,10 @@
  *     dstate % 16 == 0 and pointers/strides are 16-byte aligned; every other
  *     case in the envelope runs a plain fp32-FMA kernel.  Among the MFMA
  *     shapes, the persistent kernels (the ones the benchmark prices) take
- *     headdim 64 with dstate 64, 128 or 256 at any node count, and headdim 128
- *     with dstate 128 at up to 64 nodes; the remaining MFMA shapes (headdim 32,
- *     other dstates, ...) run one workgroup per (sequence, head) and are several
- *     times slower per node.  Results are the same to rounding on every route.
+ *     headdim 64 with dstate 64, 128 or 256, and headdim 128 with dstate 128,
+ *     at any node count; the remaining MFMA shapes (headdim 32, other dstates,
+ *     ...) run one workgroup per (sequence, head) and are several times slower
+ *     per node.  Results are the same to rounding on every route.
  */
 #ifndef STREE_H
 #define STREE_H

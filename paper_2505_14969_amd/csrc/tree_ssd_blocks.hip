@@ -617,13 +617,17 @@ hipError_t launch_blocks_ps(const stree_dims &d, const int32_t *parent, const vo
 // bf16, 65 .. 256 nodes, the head shapes below; alignment is checked by the caller (tree_ssd_mfma_supported)
 bool tree_ssd_blocks_supported(const stree_dims &d) {
     if (d.nnodes <= kBk || d.nnodes > 4 * kBk) return false;
-    return d.headdim == 64 && (d.dstate == 128 || d.dstate == 64 || d.dstate == 256);
+    return (d.headdim == 64 && (d.dstate == 128 || d.dstate == 64 || d.dstate == 256)) ||
+           (d.headdim == 128 && d.dstate == 128);
 }
 
 hipError_t launch_tree_ssd_blocks(const stree_dims &d, const int32_t *parent, const void *x, const float *dt,
                                   const float *A, const void *Bm, const void *Cm, const float *D, const void *h0,
                                   void *y, int32_t *status, hipStream_t st) {
     const bool small = d.nnodes <= 2 * kBk;
+    if (d.headdim == 128)
+        return small ? launch_blocks_ps<128, 128, 2>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st)
+                     : launch_blocks_ps<128, 128, 4>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);
     if (d.dstate == 128)
         return small ? launch_blocks_ps<64, 128, 2>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st)
                      : launch_blocks_ps<64, 128, 4>(d, parent, x, dt, A, Bm, Cm, D, h0, y, status, st);

@@ -11,10 +11,13 @@ from test_gpu_parity import _rand, _run_ssd, _trees, st  # noqa: F401  (fixture)
 pytestmark = pytest.mark.gpu
 
 # (B, N, H, P, S, G): one and several units per workgroup run (the grid stops at 512 workgroups),
-# runs that cross a sequence and a group boundary, ragged last blocks, both state sizes
+# runs that cross a sequence and a group boundary, ragged last blocks, every head shape the kernel takes
 SHAPES = [(3, 65, 2, 64, 128, 1), (2, 100, 6, 64, 128, 3), (3, 128, 4, 64, 64, 2), (2, 129, 3, 64, 128, 1),
           (2, 192, 4, 64, 128, 2), (3, 255, 2, 64, 64, 1), (2, 256, 8, 64, 128, 8),
-          (9, 70, 64, 64, 128, 4), (5, 130, 120, 64, 128, 1)]
+          (9, 70, 64, 64, 128, 4), (5, 130, 120, 64, 128, 1),
+          # the wide tiles (one workgroup per CU): dstate 256, headdim 128; more units than workgroups
+          (2, 100, 3, 64, 256, 1), (2, 256, 4, 64, 256, 2), (3, 129, 2, 128, 128, 1), (2, 250, 4, 128, 128, 2),
+          (5, 70, 60, 128, 128, 2)]
 
 
 @pytest.mark.parametrize("B,N,H,P,S,G", SHAPES)
