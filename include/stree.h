@@ -89,7 +89,8 @@ typedef struct stree_dims {
      * batch stride is nnodes * token stride. */
     int64_t x_stride_n, b_stride_n, c_stride_n;
     /* DEVICE pointer, f32 [H]: the per-head bias in front of the softplus.  Read only when
-     * STREE_FLAG_DT_SOFTPLUS is set, and required then (STREE_ERR_NULL_ARG otherwise); pass zeros
+     * STREE_FLAG_DT_SOFTPLUS is set, and required then by every entry point that takes dt
+     * (STREE_ERR_NULL_ARG otherwise); pass zeros
      * for a plain softplus.  The paper's Eq. ssm has no step size; this is Mamba2's discretisation,
      * dt = log(1 + exp(raw + bias_h)), evaluated in fp32 where dt is loaded (values above 20 pass
      * through, the difference being below fp32 resolution).  Without the flag `dt` is the step size itself. */

@@ -14,7 +14,6 @@ int check_dims(const stree_dims *d, int need_conv) {
     if (d->io_dtype != STREE_F32 && d->io_dtype != STREE_BF16) return STREE_ERR_BAD_DTYPE;
     if (d->state_dtype != STREE_F32 && !(d->state_dtype == STREE_BF16 && d->io_dtype == STREE_BF16))
         return STREE_ERR_BAD_DTYPE;                 // (a bf16 state goes with bf16 io only)
-    if ((d->flags & STREE_FLAG_DT_SOFTPLUS) && !d->dt_bias) return STREE_ERR_NULL_ARG;
     if (d->batch < 0 || d->batch > 65535) return STREE_ERR_BAD_SHAPE;
     if (d->nnodes < 1 || d->nnodes > STREE_MAX_NODES) return STREE_ERR_BAD_SHAPE;
     if (d->nheads < 1 || d->nheads > 65535 || d->ngroups < 1 || d->nheads % d->ngroups != 0)
@@ -49,6 +48,9 @@ int resolve_strides(stree_dims &d) {
     if (d.nnodes <= STREE_MAX_NODES && (int64_t)d.nnodes * widest > (1LL << 29)) return STREE_ERR_BAD_STRIDE;
     return STREE_OK;
 }
+
+// entry points that read dt: the in-kernel softplus needs its bias vector
+bool step_bias_missing(const stree_dims *d) { return (d->flags & STREE_FLAG_DT_SOFTPLUS) && !d->dt_bias; }
 
 // a state kept in bf16 is moved 8 or 16 bytes at a time by every kernel: its arrays start on 16-byte boundaries
 bool state_aligned(const stree_dims &d, const void *h0, const void *h_out) {
@@ -124,7 +126,7 @@ int stree_tree_ssd(const stree_dims *dims, const int32_t *parent, const void *x,
                    int32_t *tree_status, void *hip_stream) {
     int rc = check_dims(dims, kNoConv);
     if (rc) return rc;
-    if (!parent || !x || !dt || !A || !Bm || !Cm || !y) return STREE_ERR_NULL_ARG;
+    if (!parent || !x || !dt || !A || !Bm || !Cm || !y || step_bias_missing(dims)) return STREE_ERR_NULL_ARG;
     stree_dims d = *dims;
     rc = resolve_strides(d);
     if (rc) return rc;
@@ -145,7 +147,7 @@ int stree_commit_state(const stree_dims *dims, const int32_t *parent, const int3
     if (rc) return rc;
     const bool no_state = !x && !dt && !A && !Bm && !h0 && !h_out;   // conv tail only
     if (!parent || !accepted) return STREE_ERR_NULL_ARG;
-    if (!no_state && (!x || !dt || !A || !Bm || !h_out)) return STREE_ERR_NULL_ARG;
+    if (!no_state && (!x || !dt || !A || !Bm || !h_out || step_bias_missing(dims))) return STREE_ERR_NULL_ARG;
     if (no_state && !conv) return STREE_ERR_NULL_ARG;
     if (conv && (!xbc_pre || !conv_state || !conv_state_out)) return STREE_ERR_NULL_ARG;
     if (dims->dstate % 4 != 0) return STREE_ERR_BAD_SHAPE;
@@ -166,7 +168,8 @@ int stree_tree_ssd_replay(const stree_dims *dims, const stree_replay *prev, cons
     int rc = check_dims(dims, kNoConv);
     if (rc) return rc;
     if (!prev || !prev->parent || !prev->accepted || !prev->x || !prev->dt || !prev->Bm) return STREE_ERR_NULL_ARG;
-    if (!parent || !x || !dt || !A || !Bm || !Cm || !y || !h0 || !h_out) return STREE_ERR_NULL_ARG;
+    if (!parent || !x || !dt || !A || !Bm || !Cm || !y || !h0 || !h_out || step_bias_missing(dims))
+        return STREE_ERR_NULL_ARG;
     if (prev->nnodes < 1 || prev->nnodes > STREE_MAX_NODES || dims->dstate % 4 != 0) return STREE_ERR_BAD_SHAPE;
     stree_dims d = *dims;
     rc = resolve_strides(d);
@@ -220,7 +223,7 @@ int stree_tree_step(const stree_dims *dims, const stree_replay *prev, const void
     if (!prev || !prev->parent || !prev->accepted || !prev->x || !prev->dt || !prev->Bm || !prev_xbc_pre)
         return STREE_ERR_NULL_ARG;
     if (!parent || !xbc_pre || !conv_state || !conv_w || !xbc_out || !conv_state_out) return STREE_ERR_NULL_ARG;
-    if (!dt || !A || !h0 || !h_out || !y) return STREE_ERR_NULL_ARG;
+    if (!dt || !A || !h0 || !h_out || !y || step_bias_missing(dims)) return STREE_ERR_NULL_ARG;
     if (prev->nnodes < 1 || prev->nnodes > STREE_MAX_NODES || dims->dstate % 4 != 0) return STREE_ERR_BAD_SHAPE;
     // x, B, C of the scan: column ranges of the conv output
     stree_dims d = *dims;
@@ -277,7 +280,7 @@ int stree_linear_ssd(const stree_dims *dims, const void *x, const float *dt, con
     if (rc) return rc;
     if (T < 1 || T > (1 << 24)) return STREE_ERR_BAD_SHAPE;
     d.nnodes = T;
-    if (!x || !dt || !A || !Bm || !h_out || (y && !Cm)) return STREE_ERR_NULL_ARG;
+    if (!x || !dt || !A || !Bm || !h_out || (y && !Cm) || step_bias_missing(dims)) return STREE_ERR_NULL_ARG;
     rc = resolve_strides(d);
     if (rc) return rc;
     if (!stree::linear_ssd_supported(d, x, Bm, Cm, y, h0, h_out)) return STREE_ERR_BAD_SHAPE;
